@@ -1,0 +1,286 @@
+"""CPU oracle for the Switch FFN layer -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes front end over ``switch_oracle.c`` (plain fp64 C, written from the
+paper) plus ``dense_onehot.py`` (the paper's dense dispatch/combine-tensor
+formulation in numpy, for tiny inputs).  Only the tests, the smoke check and
+the benchmark's ``cpu_baseline`` leg may import this package; the GPU library
+never does, and nothing here imports the GPU library.
+
+Tensors go in as numpy float32 arrays holding the exact values given to the
+GPU (bf16 widens to float32 without rounding); all arithmetic is fp64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "switch_oracle.c")
+_LIB = os.path.join(_HERE, "libswitch_oracle.so")
+_LIB_F64IN = os.path.join(_HERE, "libswitch_oracle_f64in.so")
+
+# Storage dtype of the tensors handed to C.  float32 holds every bf16 / fp32
+# value exactly and is what parity tests use.  The finite-difference tests switch
+# to float64 storage (second build of the same C file) so that inputs can be
+# perturbed by 1e-6; see use_f64_inputs().
+_in_dtype = np.float32
+
+_c_f32p = ctypes.c_void_p
+_c_f64p = ctypes.POINTER(ctypes.c_double)
+_c_i32p = ctypes.POINTER(ctypes.c_int32)
+_c_i64p = ctypes.POINTER(ctypes.c_int64)
+_c_u8p = ctypes.POINTER(ctypes.c_uint8)
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no fast-math: fp64 semantics stay IEEE)."""
+    for lib, extra in ((_LIB, []), (_LIB_F64IN, ["-DSWO_IN_T=double"])):
+        stale = (not os.path.exists(lib)) or os.path.getmtime(lib) < os.path.getmtime(_SRC)
+        if force or stale:
+            cmd = ["gcc", "-O3", "-fopenmp", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
+                   *extra, "-o", lib, _SRC, "-lm"]
+            subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_libs = {}
+
+
+def use_f64_inputs(on: bool) -> None:
+    """Switch the storage dtype of tensors handed to C (float32 <-> float64)."""
+    global _in_dtype
+    _in_dtype = np.float64 if on else np.float32
+
+
+def _load():
+    key = np.dtype(_in_dtype).name
+    if key in _libs:
+        return _libs[key]
+    build()
+    lib = ctypes.CDLL(_LIB if _in_dtype is np.float32 else _LIB_F64IN)
+    i64, f64 = ctypes.c_int64, ctypes.c_double
+    lib.swo_capacity.restype = i64
+    lib.swo_capacity.argtypes = [i64, i64, f64]
+    lib.swo_logits.restype = None
+    lib.swo_logits.argtypes = [i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f64p]
+    lib.swo_softmax.restype = None
+    lib.swo_softmax.argtypes = [i64, i64, _c_f64p, _c_f64p]
+    lib.swo_top1.restype = None
+    lib.swo_top1.argtypes = [i64, i64, _c_f64p, _c_f64p, _c_i32p, _c_f64p]
+    lib.swo_aux_loss.restype = f64
+    lib.swo_aux_loss.argtypes = [i64, i64, _c_i32p, _c_f64p, f64, _c_i64p, _c_f64p, _c_f64p]
+    lib.swo_positions.restype = None
+    lib.swo_positions.argtypes = [i64, i64, i64, _c_i32p, _c_i32p, _c_u8p, _c_i64p]
+    lib.swo_expert_ffn.restype = None
+    lib.swo_expert_ffn.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_i32p,
+                                   _c_u8p, _c_f64p, _c_u8p, _c_f64p]
+    lib.swo_backward.restype = None
+    lib.swo_backward.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f32p,
+                                 _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, _c_i64p,
+                                 _c_i32p, _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p,
+                                 _c_f64p, _c_f64p]
+    _libs[key] = lib
+    return lib
+
+
+def _f32(a) -> np.ndarray:
+    """Contiguous array in the current input storage dtype (float32 by default)."""
+    return np.ascontiguousarray(a, dtype=_in_dtype)
+
+
+def _ptr(a: Optional[np.ndarray], ctype):
+    if a is None:
+        return None
+    if ctype is ctypes.c_void_p:
+        return ctypes.c_void_p(a.ctypes.data)
+    return a.ctypes.data_as(ctype)
+
+
+def set_threads(n: int) -> None:
+    """Cap the OpenMP thread count used by the C oracle."""
+    os.environ["OMP_NUM_THREADS"] = str(n)
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+        omp.omp_set_num_threads(int(n))
+    except OSError:
+        pass
+
+
+def max_threads() -> int:
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+        return int(omp.omp_get_max_threads())
+    except OSError:
+        return 1
+
+
+# --------------------------------------------------------------------------
+# step-level wrappers (one per oracle step)
+# --------------------------------------------------------------------------
+def capacity(T: int, E: int, capacity_factor: float) -> int:
+    """Eq. 3 with floor rounding."""
+    return int(_load().swo_capacity(T, E, float(capacity_factor)))
+
+
+def logits(x, W_r, b_r=None) -> np.ndarray:
+    """h = x W_r (+ b_r), fp64 (Sec. 2.1)."""
+    x, W_r = _f32(x), _f32(W_r)
+    T, d = x.shape
+    E = W_r.shape[1]
+    assert W_r.shape[0] == d
+    b = None if b_r is None else _f32(b_r)
+    h = np.empty((T, E), dtype=np.float64)
+    _load().swo_logits(T, d, E, _ptr(x, _c_f32p), _ptr(W_r, _c_f32p), _ptr(b, _c_f32p),
+                       _ptr(h, _c_f64p))
+    return h
+
+
+def softmax(h) -> np.ndarray:
+    """Eq. 1."""
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    p = np.empty_like(h)
+    _load().swo_softmax(h.shape[0], h.shape[1], _ptr(h, _c_f64p), _ptr(p, _c_f64p))
+    return p
+
+
+def top1(h, p):
+    """Expert index (arg max, lowest index on ties) and its gate value."""
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    T, E = h.shape
+    e = np.empty(T, dtype=np.int32)
+    g = np.empty(T, dtype=np.float64)
+    _load().swo_top1(T, E, _ptr(h, _c_f64p), _ptr(p, _c_f64p), _ptr(e, _c_i32p), _ptr(g, _c_f64p))
+    return e, g
+
+
+def aux_loss(expert_index, p, alpha: float):
+    """Eqs. 4-6.  Returns (loss, counts[E], f[E], P[E])."""
+    e = np.ascontiguousarray(expert_index, dtype=np.int32)
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    T, E = p.shape
+    counts = np.empty(E, dtype=np.int64)
+    f = np.empty(E, dtype=np.float64)
+    P = np.empty(E, dtype=np.float64)
+    loss = _load().swo_aux_loss(T, E, _ptr(e, _c_i32p), _ptr(p, _c_f64p), float(alpha),
+                                _ptr(counts, _c_i64p), _ptr(f, _c_f64p), _ptr(P, _c_f64p))
+    return float(loss), counts, f, P
+
+
+def positions(expert_index, E: int, C: int):
+    """Sequence-order rank within the chosen expert, dropped mask, kept counts."""
+    e = np.ascontiguousarray(expert_index, dtype=np.int32)
+    T = e.shape[0]
+    pos = np.empty(T, dtype=np.int32)
+    dropped = np.empty(T, dtype=np.uint8)
+    kept = np.empty(E, dtype=np.int64)
+    _load().swo_positions(T, E, C, _ptr(e, _c_i32p), _ptr(pos, _c_i32p), _ptr(dropped, _c_u8p),
+                          _ptr(kept, _c_i64p))
+    return pos, dropped, kept
+
+
+def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None) -> np.ndarray:
+    """y_t = gate_t * ReLU(x_t W_in[e_t]) W_out[e_t] for kept tokens, 0 for dropped."""
+    x, W_in, W_out = _f32(x), _f32(W_in), _f32(W_out)
+    T, d = x.shape
+    E, d2, f = W_in.shape
+    assert d2 == d and W_out.shape == (E, f, d)
+    e = np.ascontiguousarray(expert_index, dtype=np.int32)
+    dr = np.ascontiguousarray(dropped, dtype=np.uint8)
+    g = np.ascontiguousarray(gate, dtype=np.float64)
+    sel = None
+    if expert_sel is not None:
+        sel = np.zeros(E, dtype=np.uint8)
+        sel[list(expert_sel)] = 1
+    y = np.empty((T, d), dtype=np.float64)
+    _load().swo_expert_ffn(T, d, f, E, _ptr(x, _c_f32p), _ptr(W_in, _c_f32p), _ptr(W_out, _c_f32p),
+                           _ptr(e, _c_i32p), _ptr(dr, _c_u8p), _ptr(g, _c_f64p),
+                           _ptr(sel, _c_u8p), _ptr(y, _c_f64p))
+    return y
+
+
+# --------------------------------------------------------------------------
+# whole layer
+# --------------------------------------------------------------------------
+def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
+            logits_override=None, expert_index_override=None,
+            expert_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False) -> Dict:
+    """Whole forward pass.
+
+    logits_override: use these logits (e.g. another implementation's fp32
+        logits, widened) instead of computing them -- for the routing-stage
+        comparison, which is defined on identical logits.
+    expert_index_override: keep this module's probabilities but force the
+        routing decision (used when a near-tie arg max legitimately differs,
+        so that one flipped token does not shift every later position).
+    expert_sel: evaluate the expert FFN only for these experts.
+    """
+    x32 = _f32(x)
+    T, d = x32.shape
+    E = np.asarray(W_r).shape[1]
+    C = capacity(T, E, capacity_factor)
+    if logits_override is None:
+        h = logits(x32, W_r, b_r)
+    else:
+        h = np.ascontiguousarray(logits_override, dtype=np.float64)
+    p = softmax(h)
+    e, g = top1(h, p)
+    if expert_index_override is not None:
+        e = np.ascontiguousarray(expert_index_override, dtype=np.int32)
+        g = p[np.arange(T), e].copy()
+    loss, counts, f_vec, P_vec = aux_loss(e, p, alpha)
+    pos, dropped, kept = positions(e, E, C)
+    out = dict(capacity=C, logits=h, probs=p, expert_index=e, gate=g, aux_loss=loss,
+               expert_counts=counts, f=f_vec, P=P_vec, position_in_expert=pos,
+               dropped=dropped, kept_counts=kept)
+    if not skip_ffn:
+        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel)
+    return out
+
+
+def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.0,
+             expert_sel: Optional[Sequence[int]] = None) -> Dict:
+    """Whole backward pass for L = sum <dy, y> + d_aux * aux_loss.
+
+    With expert_sel, weight gradients are returned only for those experts
+    (stacked in the given order); dx rows of other experts' tokens are NaN and
+    their gate gradient is taken as 0 in dW_r / db_r (exact only if dy is zero
+    on those tokens).
+    """
+    x32, W_r32, W_in32, W_out32, dy32 = _f32(x), _f32(W_r), _f32(W_in), _f32(W_out), _f32(dy)
+    T, d = x32.shape
+    E, _, f = W_in32.shape
+    e = np.ascontiguousarray(fwd["expert_index"], dtype=np.int32)
+    dr = np.ascontiguousarray(fwd["dropped"], dtype=np.uint8)
+    g = np.ascontiguousarray(fwd["gate"], dtype=np.float64)
+    p = np.ascontiguousarray(fwd["probs"], dtype=np.float64)
+    counts = np.ascontiguousarray(fwd["expert_counts"], dtype=np.int64)
+    if expert_sel is None:
+        sel_slot = None
+        nsel = E
+    else:
+        expert_sel = list(expert_sel)
+        sel_slot = np.full(E, -1, dtype=np.int32)
+        for s, ex in enumerate(expert_sel):
+            sel_slot[ex] = s
+        nsel = len(expert_sel)
+    dx = np.empty((T, d), dtype=np.float64)
+    dW_r = np.empty((d, E), dtype=np.float64)
+    db_r = np.empty(E, dtype=np.float64)
+    dW_in = np.empty((nsel, d, f), dtype=np.float64)
+    dW_out = np.empty((nsel, f, d), dtype=np.float64)
+    dgate = np.empty(T, dtype=np.float64)
+    dlog = np.empty((T, E), dtype=np.float64)
+    _load().swo_backward(T, d, f, E, _ptr(x32, _c_f32p), _ptr(W_r32, _c_f32p),
+                         _ptr(W_in32, _c_f32p), _ptr(W_out32, _c_f32p), _ptr(dy32, _c_f32p),
+                         float(d_aux), float(alpha), _ptr(e, _c_i32p), _ptr(dr, _c_u8p),
+                         _ptr(g, _c_f64p), _ptr(p, _c_f64p), _ptr(counts, _c_i64p),
+                         _ptr(sel_slot, _c_i32p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
+                         _ptr(db_r, _c_f64p), _ptr(dW_in, _c_f64p), _ptr(dW_out, _c_f64p),
+                         _ptr(dgate, _c_f64p), _ptr(dlog, _c_f64p))
+    return dict(dx=dx, dW_r=dW_r, db_r=db_r, dW_in=dW_in, dW_out=dW_out, dgate=dgate,
+                dlogits=dlog)

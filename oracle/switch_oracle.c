@@ -1,0 +1,323 @@
+/*
+ * Switch FFN layer -- CPU oracle (TEST INFRASTRUCTURE, not a product path).
+ *
+ * A plain, slow, fp64 evaluation of the layer's definition, written from the
+ * paper (arXiv 2101.03961): one routing group holding all T tokens.  It is the
+ * thing the GPU library is compared against; it shares no code, header or
+ * table with that library and must never be called from it.
+ *
+ * Conventions
+ *   - Tensors arrive as float arrays holding the exact values the GPU sees
+ *     (bf16 and fp32 both widen to float without rounding); every arithmetic
+ *     step is done in double.  Integer routing results are int32 / uint8.
+ *   - Row-major:  x[T][d], W_r[d][E], W_in[E][d][f], W_out[E][f][d].
+ *   - Loops run in the order the definition is written (k ascending inside a
+ *     dot product, tokens in sequence order); there is no blocking or fusion.
+ *     OpenMP is used only across independent tokens / experts / output rows,
+ *     which does not change any summation order.
+ *
+ * Readings of the paper taken here (each also listed in the design notes):
+ *   - capacity = floor(T / E * capacity_factor), evaluated in double (Eq. 3
+ *     leaves the rounding open).
+ *   - position_in_expert is the 0-based count of earlier tokens (sequence
+ *     order) that chose the same expert; a token is kept iff position <
+ *     capacity, so an expert keeps exactly min(count, capacity) tokens
+ *     (Fig. 3; the appendix listing's 1-based cumsum with a strict compare
+ *     would keep capacity-1 and is read as an off-by-one).
+ *   - arg max ties go to the lowest expert index.
+ *   - f_i in the auxiliary loss counts arg max decisions over ALL tokens,
+ *     before any capacity truncation (Eq. 5), and is a constant under
+ *     differentiation; P_i is differentiable (Sec. 2.2).
+ *   - the residual connection is outside the layer: a dropped token's output
+ *     row is zero.
+ *   - ReLU'(0) = 0.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* Storage type of the incoming tensors.  float by default (holds every bf16 and
+ * fp32 value exactly).  The finite-difference tests build a second copy of this
+ * file with -DSWO_IN_T=double so that inputs can be perturbed by 1e-6; the
+ * arithmetic below is the same either way (every operand is widened to double
+ * before use). */
+#ifndef SWO_IN_T
+#define SWO_IN_T float
+#endif
+typedef SWO_IN_T in_t;
+
+/* ---- Eq. 3: expert capacity -------------------------------------------- */
+int64_t swo_capacity(int64_t T, int64_t E, double capacity_factor) {
+    double c = (double)T / (double)E * capacity_factor;
+    return (int64_t)floor(c);
+}
+
+/* ---- Sec. 2.1: router logits h(x) = W_r . x (+ optional bias) ----------- */
+void swo_logits(int64_t T, int64_t d, int64_t E, const in_t *x, const in_t *W_r,
+                const in_t *b_r /* may be NULL */, double *h /* [T][E] */) {
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t i = 0; i < E; ++i) {
+            double s = 0.0;
+            for (int64_t k = 0; k < d; ++k)
+                s += (double)x[t * d + k] * (double)W_r[k * E + i];
+            if (b_r) s += (double)b_r[i];
+            h[t * E + i] = s;
+        }
+    }
+}
+
+/* ---- Eq. 1: p_i = exp(h_i) / sum_j exp(h_j), max-shifted ---------------- */
+void swo_softmax(int64_t T, int64_t E, const double *h, double *p) {
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const double *ht = h + t * E;
+        double m = ht[0];
+        for (int64_t i = 1; i < E; ++i)
+            if (ht[i] > m) m = ht[i];
+        double z = 0.0;
+        for (int64_t i = 0; i < E; ++i) z += exp(ht[i] - m);
+        for (int64_t i = 0; i < E; ++i) p[t * E + i] = exp(ht[i] - m) / z;
+    }
+}
+
+/* ---- Switch routing (k = 1): expert = arg max, gate = its probability --- */
+void swo_top1(int64_t T, int64_t E, const double *h, const double *p,
+              int32_t *expert_index, double *gate) {
+    for (int64_t t = 0; t < T; ++t) {
+        int64_t best = 0;
+        for (int64_t i = 1; i < E; ++i)
+            if (h[t * E + i] > h[t * E + best]) best = i; /* strict: lowest index wins ties */
+        expert_index[t] = (int32_t)best;
+        gate[t] = p[t * E + best];
+    }
+}
+
+/* ---- Eqs. 4-6: loss = alpha * N * sum_i f_i P_i -------------------------- */
+double swo_aux_loss(int64_t T, int64_t E, const int32_t *expert_index, const double *p,
+                    double alpha, int64_t *counts /* [E] */, double *f_out /* [E] or NULL */,
+                    double *P_out /* [E] or NULL */) {
+    double loss = 0.0;
+    for (int64_t i = 0; i < E; ++i) counts[i] = 0;
+    for (int64_t t = 0; t < T; ++t) counts[expert_index[t]] += 1;
+    for (int64_t i = 0; i < E; ++i) {
+        double f_i = (double)counts[i] / (double)T;
+        double P_i = 0.0;
+        for (int64_t t = 0; t < T; ++t) P_i += p[t * E + i];
+        P_i /= (double)T;
+        if (f_out) f_out[i] = f_i;
+        if (P_out) P_out[i] = P_i;
+        loss += f_i * P_i;
+    }
+    return alpha * (double)E * loss;
+}
+
+/* ---- position in expert, sequence order; overflow is dropped ------------- */
+void swo_positions(int64_t T, int64_t E, int64_t C, const int32_t *expert_index,
+                   int32_t *position_in_expert, uint8_t *dropped, int64_t *kept /* [E] */) {
+    int64_t *seen = (int64_t *)calloc((size_t)E, sizeof(int64_t));
+    for (int64_t i = 0; i < E; ++i) kept[i] = 0;
+    for (int64_t t = 0; t < T; ++t) {
+        int32_t e = expert_index[t];
+        int64_t pos = seen[e]++;
+        position_in_expert[t] = (int32_t)pos;
+        dropped[t] = (uint8_t)(pos >= C);
+        if (pos < C) kept[e] += 1;
+    }
+    free(seen);
+}
+
+/* One token through one expert: h = x W_in, a = ReLU(h), o = a W_out (Sec. 5,
+ * review of the FFN layer). */
+static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, const in_t *Wo,
+                      double *hpre, double *a, double *o) {
+    for (int64_t j = 0; j < f; ++j) hpre[j] = 0.0;
+    for (int64_t k = 0; k < d; ++k) {
+        double xk = (double)xt[k];
+        const in_t *row = Wi + k * f;
+        for (int64_t j = 0; j < f; ++j) hpre[j] += xk * (double)row[j];
+    }
+    for (int64_t j = 0; j < f; ++j) a[j] = hpre[j] > 0.0 ? hpre[j] : 0.0;
+    for (int64_t i = 0; i < d; ++i) o[i] = 0.0;
+    for (int64_t j = 0; j < f; ++j) {
+        double aj = a[j];
+        const in_t *row = Wo + j * d;
+        for (int64_t i = 0; i < d; ++i) o[i] += aj * (double)row[i];
+    }
+}
+
+/* ---- layer output: y_t = gate_t * FFN_{e_t}(x_t) for kept tokens, 0 for
+ * dropped ones (Fig. 2 caption; Sec. 2.2 on dropped tokens).
+ * expert_sel (may be NULL = all): experts with expert_sel[e] == 0 are skipped
+ * and their tokens' rows are filled with NaN ("not computed"). */
+void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
+                    const in_t *W_in, const in_t *W_out, const int32_t *expert_index,
+                    const uint8_t *dropped, const double *gate, const uint8_t *expert_sel,
+                    double *y /* [T][d] */) {
+#pragma omp parallel
+    {
+        double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
+        double *a = (double *)malloc(sizeof(double) * (size_t)f);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t t = 0; t < T; ++t) {
+            int32_t e = expert_index[t];
+            double *yt = y + t * d;
+            if (expert_sel && !expert_sel[e]) {
+                for (int64_t i = 0; i < d; ++i) yt[i] = NAN;
+                continue;
+            }
+            if (dropped[t]) {
+                for (int64_t i = 0; i < d; ++i) yt[i] = 0.0;
+                continue;
+            }
+            ffn_token(d, f, x + t * d, W_in + (int64_t)e * d * f, W_out + (int64_t)e * f * d,
+                      hpre, a, o);
+            for (int64_t i = 0; i < d; ++i) yt[i] = gate[t] * o[i];
+        }
+        free(hpre);
+        free(a);
+        free(o);
+    }
+    (void)E;
+}
+
+/* ---- backward ------------------------------------------------------------
+ * Scalar objective  L = sum_t <dy_t, y_t> + d_aux * aux_loss.
+ * Chain rule through y_t = k_t g_t o_t, o = a W_out, a = ReLU(h), h = x W_in,
+ * g_t = p[t, e_t], p = softmax(x W_r + b_r), aux = alpha E sum_i f_i P_i with f
+ * held constant:
+ *   do_t  = k_t g_t dy_t                 dg_t = k_t <dy_t, o_t>
+ *   dW_out[e] += a_t^T do_t              da_t = do_t W_out[e]^T
+ *   dh_t  = da_t * 1[h_t > 0]            dW_in[e] += x_t^T dh_t
+ *   dx_t  = dh_t W_in[e]^T  (expert part)
+ *   dp[t,i]  = dg_t 1[i = e_t] + d_aux alpha E f_i / T
+ *   dl[t,j]  = p[t,j] (dp[t,j] - sum_i p[t,i] dp[t,i])         (softmax)
+ *   dW_r = x^T dl,  db_r = sum_t dl_t,  dx_t += dl_t W_r^T
+ *
+ * sel_slot[e] >= 0 selects expert e; its weight gradients go to slot
+ * sel_slot[e] of dW_in_sel / dW_out_sel.  sel_slot == NULL selects all experts
+ * with slot e.  Tokens of unselected experts get dgate = 0 in the router part
+ * (only meaningful when dy is zero there) and NaN rows in dx_expert.
+ */
+void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, const in_t *W_r,
+                  const in_t *W_in, const in_t *W_out, const in_t *dy, double d_aux,
+                  double alpha, const int32_t *expert_index, const uint8_t *dropped,
+                  const double *gate, const double *p /* [T][E] */, const int64_t *counts,
+                  const int32_t *sel_slot /* [E] or NULL */,
+                  double *dx /* [T][d] */, double *dW_r /* [d][E] */, double *db_r /* [E] */,
+                  double *dW_in_sel /* [nsel][d][f] */, double *dW_out_sel /* [nsel][f][d] */,
+                  double *dgate /* [T] */, double *dlogits /* [T][E] */) {
+    /* expert part: one thread owns one expert and walks its tokens in order */
+#pragma omp parallel
+    {
+        double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
+        double *a = (double *)malloc(sizeof(double) * (size_t)f);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        double *dout = (double *)malloc(sizeof(double) * (size_t)d);
+        double *dh = (double *)malloc(sizeof(double) * (size_t)f);
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t e = 0; e < E; ++e) {
+            int64_t slot = sel_slot ? sel_slot[e] : e;
+            const in_t *Wi = W_in + e * d * f;
+            const in_t *Wo = W_out + e * f * d;
+            double *gWi = slot >= 0 ? dW_in_sel + slot * d * f : NULL;
+            double *gWo = slot >= 0 ? dW_out_sel + slot * f * d : NULL;
+            if (slot >= 0) {
+                for (int64_t q = 0; q < d * f; ++q) gWi[q] = 0.0;
+                for (int64_t q = 0; q < d * f; ++q) gWo[q] = 0.0;
+            }
+            for (int64_t t = 0; t < T; ++t) {
+                if (expert_index[t] != e) continue;
+                double *dxt = dx + t * d;
+                if (slot < 0) {
+                    dgate[t] = 0.0;
+                    for (int64_t k = 0; k < d; ++k) dxt[k] = NAN;
+                    continue;
+                }
+                if (dropped[t]) {
+                    dgate[t] = 0.0;
+                    for (int64_t k = 0; k < d; ++k) dxt[k] = 0.0;
+                    continue;
+                }
+                const in_t *xt = x + t * d;
+                const in_t *dyt = dy + t * d;
+                ffn_token(d, f, xt, Wi, Wo, hpre, a, o);
+                double dg = 0.0;
+                for (int64_t i = 0; i < d; ++i) {
+                    dout[i] = gate[t] * (double)dyt[i];
+                    dg += (double)dyt[i] * o[i];
+                }
+                dgate[t] = dg;
+                for (int64_t j = 0; j < f; ++j) {
+                    const in_t *row = Wo + j * d;
+                    double *grow = gWo + j * d;
+                    double aj = a[j], s = 0.0;
+                    for (int64_t i = 0; i < d; ++i) {
+                        grow[i] += aj * dout[i];
+                        s += dout[i] * (double)row[i];
+                    }
+                    dh[j] = hpre[j] > 0.0 ? s : 0.0;
+                }
+                for (int64_t k = 0; k < d; ++k) {
+                    const in_t *row = Wi + k * f;
+                    double *grow = gWi + k * f;
+                    double xk = (double)xt[k], s = 0.0;
+                    for (int64_t j = 0; j < f; ++j) {
+                        grow[j] += xk * dh[j];
+                        s += dh[j] * (double)row[j];
+                    }
+                    dxt[k] = s;
+                }
+            }
+        }
+        free(hpre);
+        free(a);
+        free(o);
+        free(dout);
+        free(dh);
+    }
+
+    /* router part: softmax backward per token */
+#pragma omp parallel
+    {
+        double *dp = (double *)malloc(sizeof(double) * (size_t)E);
+#pragma omp for schedule(static)
+        for (int64_t t = 0; t < T; ++t) {
+            const double *pt = p + t * E;
+            double s = 0.0;
+            for (int64_t i = 0; i < E; ++i) {
+                double f_i = (double)counts[i] / (double)T;
+                dp[i] = d_aux * alpha * (double)E * f_i / (double)T;
+                if (i == expert_index[t]) dp[i] += dgate[t];
+                s += pt[i] * dp[i];
+            }
+            for (int64_t j = 0; j < E; ++j) dlogits[t * E + j] = pt[j] * (dp[j] - s);
+            double *dxt = dx + t * d;
+            for (int64_t k = 0; k < d; ++k) {
+                double r = 0.0;
+                for (int64_t j = 0; j < E; ++j) r += dlogits[t * E + j] * (double)W_r[k * E + j];
+                dxt[k] += r;
+            }
+        }
+        free(dp);
+    }
+    /* dW_r[k][j] = sum_t x[t][k] dl[t][j], t ascending for every element; a
+     * thread owns whole rows k, so no element is shared between threads. */
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < d; ++k) {
+        double *row = dW_r + k * E;
+        for (int64_t j = 0; j < E; ++j) row[j] = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            double xk = (double)x[t * d + k];
+            const double *dl = dlogits + t * E;
+            for (int64_t j = 0; j < E; ++j) row[j] += xk * dl[j];
+        }
+    }
+    for (int64_t j = 0; j < E; ++j) {
+        double s = 0.0;
+        for (int64_t t = 0; t < T; ++t) s += dlogits[t * E + j];
+        db_r[j] = s;
+    }
+}

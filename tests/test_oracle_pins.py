@@ -1,0 +1,415 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the
+mathematics fix, never against itself.
+
+  capacity          hand-worked products (golden file, Eq. 3)
+  logits            numpy fp64 matmul (library routine)
+  softmax / gate    scipy softmax; closed forms (E=1, W_r=0)
+  arg max           lowest-index tie-break on exact ties
+  aux loss          alpha under uniform routing (golden file, text after Eq. 6),
+                    stronger closed forms, appendix (mean-based) form
+  positions / drop  the O(T^2) definition by brute force over all E^T
+                    assignments for tiny T, E, C
+  expert FFN        numpy dense FFN (E=1), token-by-token numpy
+  whole layer       the paper's dense dispatch/combine-tensor formulation
+  backward          central finite differences (fp64 inputs), torch autograd
+                    on an independently written fp64 forward, closed forms
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+import oracle
+from oracle import dense_onehot
+from synth_inputs import CONFIGS, SwitchShape, make_inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if line:
+                out.append(line.split())
+    return out
+
+
+def _np_inputs(shape, seed=None):
+    t = make_inputs(shape, "cpu", seed=seed)
+    return {k: (None if v is None else v.float().numpy()) for k, v in t.items()}
+
+
+# ------------------------------------------------------------------ capacity
+def test_capacity_golden():
+    for T, E, cf, C in _rows("capacity_cases.txt"):
+        assert oracle.capacity(int(T), int(E), float(cf)) == int(C), (T, E, cf)
+
+
+def test_capacity_matches_configs():
+    want = {"tiny": 80, "base_cf1.0": 512, "base_cf1.25": 640, "base_zipf": 512,
+            "large": 640, "xxl": 320, "c_share": 512}
+    for name, C in want.items():
+        s = CONFIGS[name]
+        assert oracle.capacity(s.T, s.E, s.capacity_factor) == C
+
+
+# -------------------------------------------------------------------- router
+def test_logits_against_numpy_matmul():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((37, 19)).astype(np.float32)
+    W = rng.standard_normal((19, 7)).astype(np.float32)
+    b = rng.standard_normal(7).astype(np.float32)
+    ref = x.astype(np.float64) @ W.astype(np.float64)
+    np.testing.assert_allclose(oracle.logits(x, W), ref, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.logits(x, W, b), ref + b.astype(np.float64), rtol=0, atol=1e-13)
+
+
+def test_softmax_against_scipy_and_invariants():
+    rng = np.random.default_rng(2)
+    h = rng.standard_normal((50, 9)) * 5.0
+    h[3] += 700.0          # would overflow exp() without the max shift
+    p = oracle.softmax(h)
+    np.testing.assert_allclose(p, scipy.special.softmax(h, axis=1), rtol=1e-13, atol=1e-300)
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, rtol=0, atol=1e-14)
+    e, g = oracle.top1(h, p)
+    assert np.array_equal(e, h.argmax(axis=1))
+    assert np.all(g >= 1.0 / 9 - 1e-15)
+    np.testing.assert_array_equal(g, p[np.arange(50), e])
+
+
+def test_single_expert_gate_is_exactly_one():
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((20, 1)) * 10
+    p = oracle.softmax(h)
+    e, g = oracle.top1(h, p)
+    assert np.all(g == 1.0) and np.all(e == 0)
+
+
+def test_zero_router_gives_uniform_probs_and_expert_zero():
+    x = np.random.default_rng(4).standard_normal((16, 8)).astype(np.float32)
+    W = np.zeros((8, 4), dtype=np.float32)
+    h = oracle.logits(x, W)
+    p = oracle.softmax(h)
+    assert np.all(p == 0.25)
+    e, g = oracle.top1(h, p)
+    assert np.all(e == 0) and np.all(g == 0.25)
+
+
+def test_argmax_tie_goes_to_lowest_index():
+    h = np.array([[1.0, 3.0, 3.0, 2.0], [5.0, 5.0, 5.0, 5.0], [0.0, -1.0, 0.0, -1.0],
+                  [-2.0, -2.0, -1.0, -1.0]])
+    e, _ = oracle.top1(h, oracle.softmax(h))
+    assert e.tolist() == [1, 0, 0, 2]
+
+
+# ------------------------------------------------------------------ aux loss
+def test_aux_loss_uniform_routing_golden():
+    """f_i = P_i = 1/N  =>  loss = alpha (text after Eq. 6)."""
+    for N, alpha, want in _rows("aux_loss_uniform.txt"):
+        N, alpha, want = int(N), float(alpha), float(want)
+        T = 4 * N
+        e = np.arange(T, dtype=np.int32) % N
+        p = np.full((T, N), 1.0 / N)
+        loss, counts, f, P = oracle.aux_loss(e, p, alpha)
+        assert abs(loss - want) <= 1e-15 * max(1.0, N)
+        assert np.all(counts == 4)
+
+
+def test_aux_loss_stronger_closed_forms():
+    rng = np.random.default_rng(5)
+    N, T, alpha = 8, 64, 0.01
+    p = scipy.special.softmax(rng.standard_normal((T, N)) * 3, axis=1)
+    # uniform f, any p  (sum_i P_i = 1)
+    e = np.arange(T, dtype=np.int32) % N
+    assert abs(oracle.aux_loss(e, p, alpha)[0] - alpha) < 1e-15
+    # uniform P, any routing
+    e2 = rng.integers(0, N, T).astype(np.int32)
+    assert abs(oracle.aux_loss(e2, np.full((T, N), 1.0 / N), alpha)[0] - alpha) < 1e-15
+    # collapse onto one expert with probability -> 1: upper bound alpha * N
+    p3 = np.full((T, N), 1e-12)
+    p3[:, 5] = 1.0 - 7e-12
+    e3 = np.full(T, 5, dtype=np.int32)
+    assert abs(oracle.aux_loss(e3, p3, alpha)[0] - alpha * N) < 1e-10
+    # a hand-worked non-uniform case: N = 2, f = (3/4, 1/4), P = (0.6, 0.4)
+    e4 = np.array([0, 0, 0, 1], dtype=np.int32)
+    p4 = np.array([[0.9, 0.1], [0.7, 0.3], [0.6, 0.4], [0.2, 0.8]])
+    want = 0.5 * 2 * (0.75 * 0.6 + 0.25 * 0.4)
+    assert abs(oracle.aux_loss(e4, p4, 0.5)[0] - want) < 1e-15
+
+
+def test_aux_loss_matches_appendix_mean_form():
+    rng = np.random.default_rng(6)
+    N, T, alpha = 5, 40, 0.01
+    p = scipy.special.softmax(rng.standard_normal((T, N)) * 2, axis=1)
+    e = p.argmax(axis=1).astype(np.int32)
+    mask = np.eye(N)[e]
+    appendix = alpha * np.mean(p.mean(axis=0) * mask.mean(axis=0)) * N ** 2
+    assert abs(oracle.aux_loss(e, p, alpha)[0] - appendix) < 1e-16
+
+
+def test_aux_loss_independent_of_capacity_factor():
+    s = SwitchShape("t", 96, 16, 32, 4, 1.0, dtype="f32", seed_index=11)
+    inp = _np_inputs(s)
+    a = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.25, 0.01, skip_ffn=True)
+    b = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 4.0, 0.01, skip_ffn=True)
+    assert a["aux_loss"] == b["aux_loss"]
+    assert a["dropped"].sum() > 0 and b["dropped"].sum() == 0
+
+
+# ------------------------------------------------------- positions / dropping
+def _positions_by_definition(e, C):
+    T = len(e)
+    pos = [sum(1 for s in range(t) if e[s] == e[t]) for t in range(T)]
+    return pos, [int(p >= C) for p in pos]
+
+
+@pytest.mark.parametrize("T,E", [(1, 1), (4, 2), (6, 3), (8, 2), (7, 3)])
+def test_positions_bruteforce_all_assignments(T, E):
+    for assign in itertools.product(range(E), repeat=T):
+        e = np.array(assign, dtype=np.int32)
+        for C in range(0, T + 1):
+            pos, dropped, kept = oracle.positions(e, E, C)
+            wpos, wdrop = _positions_by_definition(assign, C)
+            assert pos.tolist() == wpos and dropped.tolist() == wdrop
+            counts = np.bincount(e, minlength=E)
+            assert kept.tolist() == np.minimum(counts, C).tolist()
+
+
+def test_position_invariants_random():
+    rng = np.random.default_rng(7)
+    T, E, C = 500, 7, 60
+    e = rng.integers(0, E, T).astype(np.int32)
+    pos, dropped, kept = oracle.positions(e, E, C)
+    counts = np.bincount(e, minlength=E)
+    assert kept.sum() == np.minimum(counts, C).sum() == (dropped == 0).sum()
+    pairs = {(int(a), int(b)) for a, b, k in zip(e, pos, dropped) if not k}
+    assert len(pairs) == kept.sum()                       # kept (expert, slot) pairs unique
+    for i in range(E):                                    # the dropped ones are the latest ones
+        toks = np.nonzero(e == i)[0]
+        assert np.array_equal(pos[toks], np.arange(len(toks)))
+        assert np.array_equal(dropped[toks], (np.arange(len(toks)) >= C).astype(np.uint8))
+
+
+def test_single_expert_keeps_first_floor_T_cf_tokens():
+    T, cf = 37, 0.6
+    C = oracle.capacity(T, 1, cf)
+    assert C == 22
+    pos, dropped, kept = oracle.positions(np.zeros(T, dtype=np.int32), 1, C)
+    assert dropped.tolist() == [0] * 22 + [1] * 15
+
+
+# ---------------------------------------------------------------- expert FFN
+def test_single_expert_is_dense_ffn():
+    s = SwitchShape("t", 40, 24, 48, 1, 1.0, dtype="f32", seed_index=12)
+    inp = _np_inputs(s)
+    out = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, 0.01)
+    x, Wi, Wo = (inp[k].astype(np.float64) for k in ("x", "W_in", "W_out"))
+    dense = np.maximum(x @ Wi[0], 0.0) @ Wo[0]
+    assert np.all(out["gate"] == 1.0) and out["dropped"].sum() == 0
+    np.testing.assert_allclose(out["y"], dense, rtol=1e-12, atol=1e-13)
+    assert abs(out["aux_loss"] - 0.01) < 1e-16
+
+
+def test_no_drop_token_by_token():
+    s = SwitchShape("t", 60, 16, 40, 5, 5.0, dtype="f32", seed_index=13)
+    inp = _np_inputs(s)
+    out = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 5.0, 0.01)
+    assert out["dropped"].sum() == 0
+    x, Wr, Wi, Wo = (inp[k].astype(np.float64) for k in ("x", "W_r", "W_in", "W_out"))
+    p = scipy.special.softmax(x @ Wr, axis=1)
+    for t in range(s.T):
+        e = int(p[t].argmax())
+        want = p[t, e] * (np.maximum(x[t] @ Wi[e], 0.0) @ Wo[e])
+        np.testing.assert_allclose(out["y"][t], want, rtol=1e-12, atol=1e-14)
+
+
+def test_dropped_rows_are_positive_zero_and_linear_in_W_out():
+    s = SwitchShape("t", 64, 16, 32, 4, 0.5, dtype="f32", seed_index=14)
+    inp = _np_inputs(s)
+    out = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.5, 0.01)
+    drop = out["dropped"].astype(bool)
+    assert drop.any()
+    rows = out["y"][drop]
+    assert np.all(rows == 0.0) and not np.any(np.signbit(rows))
+    out2 = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], 2.0 * inp["W_out"], 0.5, 0.01)
+    np.testing.assert_allclose(out2["y"], 2.0 * out["y"], rtol=1e-15, atol=0)
+
+
+def test_swapping_two_tokens_of_different_experts_swaps_rows():
+    s = SwitchShape("t", 32, 8, 16, 4, 8.0, dtype="f32", seed_index=15)
+    inp = _np_inputs(s)
+    out = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 8.0, 0.01)
+    e = out["expert_index"]
+    i = 0
+    j = int(np.nonzero(e != e[0])[0][0])
+    x2 = inp["x"].copy()
+    x2[[i, j]] = x2[[j, i]]
+    out2 = oracle.forward(x2, inp["W_r"], inp["W_in"], inp["W_out"], 8.0, 0.01)
+    np.testing.assert_array_equal(out2["y"][i], out["y"][j])
+    np.testing.assert_array_equal(out2["y"][j], out["y"][i])
+    mask = np.ones(s.T, bool)
+    mask[[i, j]] = False
+    np.testing.assert_array_equal(out2["y"][mask], out["y"][mask])
+
+
+# ------------------------------------------ whole layer vs dense formulation
+@pytest.mark.parametrize("cf", [0.5, 1.0, 1.25, 4.0])
+def test_index_oracle_equals_dense_onehot_formulation(cf):
+    s = CONFIGS["tiny"].with_(capacity_factor=cf)
+    inp = _np_inputs(s)
+    a = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], cf, s.alpha)
+    b = dense_onehot.switch_layer_dense(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"],
+                                        a["capacity"], s.alpha)
+    assert np.array_equal(a["expert_index"], b["expert_index"])
+    assert np.array_equal(a["dropped"], b["dropped"])
+    np.testing.assert_allclose(a["y"], b["y"], rtol=1e-12, atol=1e-14)
+    assert abs(a["aux_loss"] - b["aux_loss"]) < 1e-15
+    # each expert holds exactly min(count, C) tokens, one per slot
+    per_slot = b["dispatch"].sum(axis=0)
+    assert per_slot.max() <= 1
+    assert np.array_equal(per_slot.sum(axis=1), a["kept_counts"])
+
+
+def test_dense_formulation_with_bias_and_skew():
+    s = SwitchShape("t", 128, 16, 32, 8, 1.0, dtype="f32", zipf_bias=True, seed_index=16)
+    inp = _np_inputs(s)
+    a = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, 0.01, b_r=inp["b_r"])
+    b = dense_onehot.switch_layer_dense(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"],
+                                        a["capacity"], 0.01, b_r=inp["b_r"])
+    assert a["dropped"].sum() > 0
+    assert np.array_equal(a["dropped"], b["dropped"])
+    np.testing.assert_allclose(a["y"], b["y"], rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------ backward
+def _torch_layer_loss(x, W_r, b_r, W_in, W_out, dy, C, alpha, d_aux):
+    """Independent fp64 forward in torch, differentiated by autograd."""
+    T, d = x.shape
+    E = W_r.shape[1]
+    h = x @ W_r
+    if b_r is not None:
+        h = h + b_r
+    p = torch.softmax(h, dim=1)
+    e = torch.argmax(h, dim=1)
+    onehot = torch.nn.functional.one_hot(e, E).to(torch.float64)
+    pos = ((torch.cumsum(onehot, 0) - 1) * onehot).sum(1)
+    kept = (pos < C).to(torch.float64)
+    gate = (p * onehot).sum(1)
+    hid = torch.relu(torch.einsum("td,tdf->tf", x, W_in[e]))
+    o = torch.einsum("tf,tfd->td", hid, W_out[e])
+    y = (kept * gate)[:, None] * o
+    f_vec = onehot.mean(0).detach()
+    aux = alpha * E * (f_vec * p.mean(0)).sum()
+    return (y * dy).sum() + d_aux * aux, y, aux
+
+
+@pytest.mark.parametrize("cf,bias", [(1.25, False), (0.5, True)])
+def test_backward_against_torch_autograd(cf, bias):
+    s = SwitchShape("t", 96, 24, 40, 4, cf, dtype="f32", zipf_bias=bias, seed_index=17)
+    inp = _np_inputs(s)
+    d_aux = 1.7
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], cf, s.alpha, b_r=inp["b_r"])
+    bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd,
+                          s.alpha, d_aux)
+    tt = {k: (None if v is None else torch.tensor(v, dtype=torch.float64,
+                                                   requires_grad=(k != "dy")))
+          for k, v in inp.items()}
+    loss, y, aux = _torch_layer_loss(tt["x"], tt["W_r"], tt["b_r"], tt["W_in"], tt["W_out"],
+                                     tt["dy"], fwd["capacity"], s.alpha, d_aux)
+    loss.backward()
+    np.testing.assert_allclose(fwd["y"], y.detach().numpy(), rtol=1e-12, atol=1e-14)
+    assert abs(fwd["aux_loss"] - float(aux.detach())) < 1e-15
+    for name in ("x", "W_r", "W_in", "W_out"):
+        g = tt[name].grad.numpy()
+        np.testing.assert_allclose(bwd["d" + name], g, rtol=1e-10,
+                                   atol=1e-12 * max(1.0, np.abs(g).max()), err_msg=name)
+    if bias:
+        np.testing.assert_allclose(bwd["db_r"], tt["b_r"].grad.numpy(), rtol=1e-10, atol=1e-13)
+        assert fwd["dropped"].sum() > 0
+
+
+def test_backward_against_central_finite_differences():
+    """Perturb fp64-stored inputs by 1e-6; routing and ReLU pattern must not move."""
+    s = SwitchShape("t", 24, 6, 10, 3, 0.75, dtype="f32", seed_index=18)
+    inp = {k: (None if v is None else v.astype(np.float64)) for k, v in _np_inputs(s).items()}
+    alpha, d_aux, cf, eps = 0.3, 0.9, 0.75, 1e-6
+    oracle.use_f64_inputs(True)
+    try:
+        def loss_of(**over):
+            a = dict(inp, **over)
+            f = oracle.forward(a["x"], a["W_r"], a["W_in"], a["W_out"], cf, alpha)
+            return float((f["y"] * a["dy"]).sum() + d_aux * f["aux_loss"]), f
+
+        base, fwd = loss_of()
+        assert fwd["dropped"].sum() > 0
+        bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd,
+                              alpha, d_aux)
+        rng = np.random.default_rng(0)
+        for name in ("x", "W_r", "W_in", "W_out"):
+            grad = bwd["d" + name]
+            flat_idx = rng.choice(inp[name].size, size=min(40, inp[name].size), replace=False)
+            for fi in flat_idx:
+                idx = np.unravel_index(fi, inp[name].shape)
+                plus, minus = inp[name].copy(), inp[name].copy()
+                plus[idx] += eps
+                minus[idx] -= eps
+                lp, fp_ = loss_of(**{name: plus})
+                lm, fm_ = loss_of(**{name: minus})
+                assert np.array_equal(fp_["expert_index"], fwd["expert_index"])
+                assert np.array_equal(fm_["expert_index"], fwd["expert_index"])
+                fd = (lp - lm) / (2 * eps)
+                assert abs(fd - grad[idx]) <= 2e-7 * max(1.0, abs(grad[idx])), (name, idx, fd, grad[idx])
+    finally:
+        oracle.use_f64_inputs(False)
+
+
+def test_backward_closed_forms():
+    # E = 1: gate is constant 1 => dW_r = 0, db_r = 0, textbook dense-FFN gradients
+    s = SwitchShape("t", 30, 12, 20, 1, 1.0, dtype="f32", seed_index=19)
+    inp = _np_inputs(s)
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, 0.01)
+    bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd, 0.01, 1.0)
+    x, Wi, Wo, dy = (inp[k].astype(np.float64) for k in ("x", "W_in", "W_out", "dy"))
+    hpre = x @ Wi[0]
+    a = np.maximum(hpre, 0)
+    dh = (dy @ Wo[0].T) * (hpre > 0)
+    assert np.abs(bwd["dW_r"]).max() < 1e-15 and np.abs(bwd["db_r"]).max() < 1e-15
+    np.testing.assert_allclose(bwd["dW_out"][0], a.T @ dy, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(bwd["dW_in"][0], x.T @ dh, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(bwd["dx"], dh @ Wi[0].T, rtol=1e-12, atol=1e-13)
+
+    # only the aux loss upstream (dy = 0): expert weights get no gradient; and
+    # with d_aux = 0 a dropped token gets no gradient at all
+    s = SwitchShape("t", 64, 12, 20, 4, 0.5, dtype="f32", seed_index=20)
+    inp = _np_inputs(s)
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.5, 0.01)
+    z = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0 * inp["dy"], fwd, 0.01, 1.0)
+    assert np.all(z["dW_in"] == 0) and np.all(z["dW_out"] == 0) and np.abs(z["dW_r"]).max() > 0
+    w = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd, 0.01, 0.0)
+    drop = fwd["dropped"].astype(bool)
+    assert drop.any() and np.all(w["dx"][drop] == 0) and np.all(w["dgate"][drop] == 0)
+
+
+def test_expert_subset_matches_full_run():
+    s = SwitchShape("t", 80, 12, 20, 5, 1.0, dtype="f32", seed_index=21)
+    inp = _np_inputs(s)
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, 0.01)
+    full = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd, 0.01, 1.0)
+    sel = [3, 1]
+    part_f = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, 0.01, expert_sel=sel)
+    in_sel = np.isin(fwd["expert_index"], sel)
+    np.testing.assert_array_equal(part_f["y"][in_sel], fwd["y"][in_sel])
+    assert np.all(np.isnan(part_f["y"][~in_sel]))
+    dy_masked = inp["dy"] * in_sel[:, None]
+    part = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], dy_masked, fwd, 0.01, 1.0,
+                           expert_sel=sel)
+    full_m = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], dy_masked, fwd, 0.01, 1.0)
+    np.testing.assert_array_equal(part["dW_in"][0], full["dW_in"][3])
+    np.testing.assert_array_equal(part["dW_out"][1], full["dW_out"][1])
+    np.testing.assert_array_equal(part["dW_r"], full_m["dW_r"])
+    np.testing.assert_array_equal(part["dx"][in_sel], full_m["dx"][in_sel])
