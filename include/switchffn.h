@@ -1,0 +1,142 @@
+/*
+ * switchffn.h -- C ABI of the MI355X (gfx950) Switch FFN layer library.
+ *
+ * The layer is the sparse feed-forward layer of the Switch Transformer
+ * (arXiv 2101.03961): a top-1 router, capacity-limited dispatch of tokens to
+ * experts, one ReLU FFN per expert, a gate-weighted combine, and the
+ * load-balancing auxiliary loss, forward and backward.  One routing group holds
+ * all T tokens (the appendix listing's num_cores = 1).
+ *
+ * General rules
+ *   - Every tensor pointer is a DEVICE pointer (HBM) unless a comment says
+ *     "host".  The caller owns all memory; the library never allocates, frees
+ *     or keeps a pointer after the call's work has run.
+ *   - Tensors are dense, row-major, with the shapes given below; base pointers
+ *     must be 16-byte aligned.
+ *   - Calls are asynchronous: work is queued on `hip_stream` (a hipStream_t
+ *     passed as void*; NULL = the default stream) and the call returns without
+ *     synchronising.
+ *   - Every function returns SW_OK (0) or a negative sw_status.  Errors are
+ *     detected on the host before anything is launched; nothing is thrown
+ *     across the ABI.  Inputs must be finite (NaN/Inf behaviour unspecified).
+ *   - Gradients are overwritten, not accumulated.
+ *   - act_dtype SW_BF16: x, W_in, W_out, y, dy, dx, dW_in, dW_out are bfloat16
+ *     (d_model and d_ff must be multiples of 8); products are accumulated in
+ *     fp32 and rounded once (nearest-even) at each store.  SW_F32: the same
+ *     tensors are fp32.  The router (W_r, b_r, logits, softmax, gate, aux loss,
+ *     dW_r, db_r) is fp32 in both cases ("selective precision", Sec. 2.4).
+ */
+#ifndef SWITCHFFN_H
+#define SWITCHFFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SW_F32 = 0, SW_BF16 = 1 } sw_dtype;
+
+typedef enum {
+    SW_OK = 0,
+    SW_ERR_NULL = -1,      /* a required pointer is NULL                         */
+    SW_ERR_SHAPE = -2,     /* T, d_model, d_ff, E out of range / not multiple of 8 */
+    SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite */
+    SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16            */
+    SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
+    SW_ERR_ALIGN = -6,     /* a tensor pointer is not 16-byte aligned            */
+    SW_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch (see hipGetLastError) */
+    SW_ERR_STATE = -8      /* profiling calls out of order                       */
+} sw_status;
+
+/* Layer description (host struct, passed by pointer, copied by the callee). */
+typedef struct {
+    int64_t T;               /* tokens in the batch (>= 1, < 2^31)                  */
+    int64_t d_model;         /* token width                                         */
+    int64_t d_ff;            /* expert hidden width                                 */
+    int64_t E;               /* number of experts (1 .. 4096)                       */
+    double capacity_factor;  /* > 0; Eq. 3                                          */
+    float alpha;             /* auxiliary-loss coefficient (Sec. 2.2; paper: 1e-2)  */
+    int32_t act_dtype;       /* sw_dtype of activations and expert weights          */
+} switch_config;
+
+/* Expert capacity, Eq. 3, rounded down:
+ *   capacity = floor((double)T / (double)E * capacity_factor).
+ * Zero is legal (every token is dropped).  Host only. */
+int switch_capacity(const switch_config *cfg, int64_t *capacity_out /* host */);
+
+/* Bytes of device workspace that switch_forward/switch_backward need for this
+ * configuration (saved activations, routing tables, gradient staging).  Host
+ * only.  The workspace must be 256-byte aligned. */
+int switch_workspace_size(const switch_config *cfg, size_t *bytes_out /* host */);
+
+/*
+ * Forward pass (Sec. 2.1, 2.2; Fig. 2; Eqs. 1, 3-6).
+ *   logits h = x W_r (+ b_r), fp32;  p = softmax(h)                    (Eq. 1)
+ *   expert_index[t] = arg max_i h[t,i] (lowest index on ties), gate[t] = p[t, expert_index[t]]
+ *   position_in_expert[t] = number of earlier tokens (s < t) with the same expert
+ *   dropped[t] = position_in_expert[t] >= capacity                     (Eq. 3, Fig. 3)
+ *   y[t,:] = gate[t] * ReLU(x[t,:] W_in[e]) W_out[e]  if kept, +0 if dropped
+ *            (the residual connection is the caller's)
+ *   aux_loss = alpha * E * sum_i f_i P_i, f_i = expert_counts[i] / T over ALL
+ *            tokens (before truncation), P_i = mean_t p[t,i]            (Eqs. 4-6)
+ * The workspace keeps what switch_backward needs; it must stay untouched
+ * between the two calls.
+ */
+int switch_forward(const switch_config *cfg,
+                   const void *x,               /* [T, d_model]        act_dtype            */
+                   const float *W_r,            /* [d_model, E]        fp32                 */
+                   const float *b_r,            /* [E] fp32 or NULL (the paper has no router bias) */
+                   const void *W_in,            /* [E, d_model, d_ff]  act_dtype            */
+                   const void *W_out,           /* [E, d_ff, d_model]  act_dtype            */
+                   void *y,                     /* [T, d_model]        act_dtype  (out)     */
+                   int32_t *expert_index,       /* [T]   (out)                              */
+                   float *gate,                 /* [T]   (out) raw top-1 probability, not masked by dropped */
+                   int32_t *position_in_expert, /* [T]   (out) raw rank, defined for dropped tokens too */
+                   uint8_t *dropped,            /* [T]   (out) 0 / 1                        */
+                   int32_t *expert_counts,      /* [E]   (out) tokens that chose each expert, sums to T */
+                   float *aux_loss,             /* [1]   (out) device scalar                */
+                   float *router_logits,        /* [T, E] (out) fp32 logits, or NULL        */
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward pass of  L = sum_t <dy[t,:], y[t,:]> + d_aux * aux_loss,
+ * derived from the forward definition with f held constant (Sec. 2.2: P is
+ * differentiable, f is not) and ReLU'(0) = 0.  Must follow a switch_forward
+ * with the same cfg, inputs and workspace.  Dropped tokens receive only the
+ * auxiliary-loss part of dx; weight-gradient blocks of experts that kept no
+ * token are written as zeros.
+ */
+int switch_backward(const switch_config *cfg,
+                    const void *dy,      /* [T, d_model] act_dtype                       */
+                    float d_aux,         /* host scalar: dL/d(aux_loss)                  */
+                    const void *x, const float *W_r, const float *b_r /* or NULL */,
+                    const void *W_in, const void *W_out,
+                    void *dx,            /* [T, d_model]       act_dtype (out)           */
+                    float *dW_r,         /* [d_model, E]       fp32      (out)           */
+                    float *db_r,         /* [E] fp32 (out) or NULL                       */
+                    void *dW_in,         /* [E, d_model, d_ff] act_dtype (out)           */
+                    void *dW_out,        /* [E, d_ff, d_model] act_dtype (out)           */
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Human-readable name of a status code.  Host; static storage. */
+const char *switch_status_string(int status);
+
+/*
+ * Per-kernel timing with HIP events, for measurement.  While enabled, every
+ * kernel the library launches is bracketed by two events recorded on the
+ * call's stream.  switch_profile_collect synchronises those events and adds
+ * the elapsed times to per-kernel totals; switch_profile_get reads them.
+ * Host only; not thread safe; events are created on first use and kept.
+ */
+int switch_profile_enable(int on);         /* on != 0: start recording (clears totals) */
+int switch_profile_collect(void);          /* wait for recorded events, accumulate     */
+int switch_profile_count(void);            /* number of distinct kernel names seen     */
+int switch_profile_get(int i, const char **name /* host, static */, double *total_ms,
+                       int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWITCHFFN_H */

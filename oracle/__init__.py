@@ -81,7 +81,7 @@ def _load():
     lib.swo_backward.restype = None
     lib.swo_backward.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f32p,
                                  _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, _c_i64p,
-                                 _c_i32p, _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p,
+                                 _c_i32p, _c_u8p, _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p,
                                  _c_f64p, _c_f64p]
     _libs[key] = lib
     return lib
@@ -183,8 +183,25 @@ def positions(expert_index, E: int, C: int):
     return pos, dropped, kept
 
 
-def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None) -> np.ndarray:
-    """y_t = gate_t * ReLU(x_t W_in[e_t]) W_out[e_t] for kept tokens, 0 for dropped."""
+def _token_mask(expert_index, E, expert_sel, token_sel):
+    """uint8[T] mask of the tokens to evaluate, or None for all of them."""
+    if expert_sel is None and token_sel is None:
+        return None
+    e = np.asarray(expert_index)
+    mask = np.zeros(e.shape[0], dtype=np.uint8)
+    if expert_sel is not None:
+        mask[np.isin(e, np.asarray(list(expert_sel), dtype=e.dtype))] = 1
+    if token_sel is not None:
+        mask[np.asarray(list(token_sel), dtype=np.int64)] = 1
+    return mask
+
+
+def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None,
+               token_sel=None) -> np.ndarray:
+    """y_t = gate_t * ReLU(x_t W_in[e_t]) W_out[e_t] for kept tokens, 0 for dropped.
+
+    With expert_sel / token_sel only tokens of those experts / those tokens are
+    evaluated; all other rows are NaN."""
     x, W_in, W_out = _f32(x), _f32(W_in), _f32(W_out)
     T, d = x.shape
     E, d2, f = W_in.shape
@@ -192,10 +209,7 @@ def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None) -> 
     e = np.ascontiguousarray(expert_index, dtype=np.int32)
     dr = np.ascontiguousarray(dropped, dtype=np.uint8)
     g = np.ascontiguousarray(gate, dtype=np.float64)
-    sel = None
-    if expert_sel is not None:
-        sel = np.zeros(E, dtype=np.uint8)
-        sel[list(expert_sel)] = 1
+    sel = _token_mask(e, E, expert_sel, token_sel)
     y = np.empty((T, d), dtype=np.float64)
     _load().swo_expert_ffn(T, d, f, E, _ptr(x, _c_f32p), _ptr(W_in, _c_f32p), _ptr(W_out, _c_f32p),
                            _ptr(e, _c_i32p), _ptr(dr, _c_u8p), _ptr(g, _c_f64p),
@@ -208,7 +222,8 @@ def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None) -> 
 # --------------------------------------------------------------------------
 def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
             logits_override=None, expert_index_override=None,
-            expert_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False) -> Dict:
+            expert_sel: Optional[Sequence[int]] = None,
+            token_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False) -> Dict:
     """Whole forward pass.
 
     logits_override: use these logits (e.g. another implementation's fp32
@@ -217,7 +232,8 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     expert_index_override: keep this module's probabilities but force the
         routing decision (used when a near-tie arg max legitimately differs,
         so that one flipped token does not shift every later position).
-    expert_sel: evaluate the expert FFN only for these experts.
+    expert_sel / token_sel: evaluate the expert FFN only for the tokens of
+        these experts plus these tokens (other rows of y are NaN).
     """
     x32 = _f32(x)
     T, d = x32.shape
@@ -238,18 +254,19 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
                expert_counts=counts, f=f_vec, P=P_vec, position_in_expert=pos,
                dropped=dropped, kept_counts=kept)
     if not skip_ffn:
-        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel)
+        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel)
     return out
 
 
 def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.0,
-             expert_sel: Optional[Sequence[int]] = None) -> Dict:
+             expert_sel: Optional[Sequence[int]] = None,
+             token_sel: Optional[Sequence[int]] = None) -> Dict:
     """Whole backward pass for L = sum <dy, y> + d_aux * aux_loss.
 
-    With expert_sel, weight gradients are returned only for those experts
-    (stacked in the given order); dx rows of other experts' tokens are NaN and
-    their gate gradient is taken as 0 in dW_r / db_r (exact only if dy is zero
-    on those tokens).
+    With expert_sel (and optionally token_sel, extra single tokens), weight
+    gradients are returned only for the experts of expert_sel (stacked in the
+    given order); dx rows of unselected tokens are NaN and their gate gradient is
+    taken as 0 in dW_r / db_r (exact only if dy is zero on those tokens).
     """
     x32, W_r32, W_in32, W_out32, dy32 = _f32(x), _f32(W_r), _f32(W_in), _f32(W_out), _f32(dy)
     T, d = x32.shape
@@ -259,6 +276,9 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
     g = np.ascontiguousarray(fwd["gate"], dtype=np.float64)
     p = np.ascontiguousarray(fwd["probs"], dtype=np.float64)
     counts = np.ascontiguousarray(fwd["expert_counts"], dtype=np.int64)
+    tmask = _token_mask(e, E, expert_sel, token_sel)
+    if expert_sel is None and token_sel is not None:
+        expert_sel = []
     if expert_sel is None:
         sel_slot = None
         nsel = E
@@ -279,7 +299,7 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
                          _ptr(W_in32, _c_f32p), _ptr(W_out32, _c_f32p), _ptr(dy32, _c_f32p),
                          float(d_aux), float(alpha), _ptr(e, _c_i32p), _ptr(dr, _c_u8p),
                          _ptr(g, _c_f64p), _ptr(p, _c_f64p), _ptr(counts, _c_i64p),
-                         _ptr(sel_slot, _c_i32p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
+                         _ptr(sel_slot, _c_i32p), _ptr(tmask, _c_u8p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
                          _ptr(db_r, _c_f64p), _ptr(dW_in, _c_f64p), _ptr(dW_out, _c_f64p),
                          _ptr(dgate, _c_f64p), _ptr(dlog, _c_f64p))
     return dict(dx=dx, dW_r=dW_r, db_r=db_r, dW_in=dW_in, dW_out=dW_out, dgate=dgate,

@@ -13,8 +13,8 @@
  *   - Row-major:  x[T][d], W_r[d][E], W_in[E][d][f], W_out[E][f][d].
  *   - Loops run in the order the definition is written (k ascending inside a
  *     dot product, tokens in sequence order); there is no blocking or fusion.
- *     OpenMP is used only across independent tokens / experts / output rows,
- *     which does not change any summation order.
+ *     OpenMP is used only across independent tokens / output elements, which
+ *     does not change any summation order.
  *
  * Readings of the paper taken here (each also listed in the design notes):
  *   - capacity = floor(T / E * capacity_factor), evaluated in double (Eq. 3
@@ -33,6 +33,7 @@
  *   - ReLU'(0) = 0.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -128,58 +129,76 @@ void swo_positions(int64_t T, int64_t E, int64_t C, const int32_t *expert_index,
     free(seen);
 }
 
+/* Work sharing.  The expert part is evaluated token by token, in sequence
+ * order; inside one token the independent output elements (columns of h, of o,
+ * rows of the weight gradients) are split over the OpenMP team.  Every element
+ * is still produced by one thread, with its sum taken in ascending index order,
+ * so the arithmetic does not depend on the number of threads. */
+static void my_range(int64_t n, int64_t *lo, int64_t *hi) {
+    int64_t nt = omp_get_num_threads(), id = omp_get_thread_num();
+    *lo = n * id / nt;
+    *hi = n * (id + 1) / nt;
+}
+
 /* One token through one expert: h = x W_in, a = ReLU(h), o = a W_out (Sec. 5,
- * review of the FFN layer). */
+ * review of the FFN layer).  Called by every thread of the team. */
 static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, const in_t *Wo,
                       double *hpre, double *a, double *o) {
-    for (int64_t j = 0; j < f; ++j) hpre[j] = 0.0;
+    int64_t j0, j1, i0, i1;
+    my_range(f, &j0, &j1);
+    my_range(d, &i0, &i1);
+    for (int64_t j = j0; j < j1; ++j) hpre[j] = 0.0;
     for (int64_t k = 0; k < d; ++k) {
         double xk = (double)xt[k];
         const in_t *row = Wi + k * f;
-        for (int64_t j = 0; j < f; ++j) hpre[j] += xk * (double)row[j];
+        for (int64_t j = j0; j < j1; ++j) hpre[j] += xk * (double)row[j];
     }
-    for (int64_t j = 0; j < f; ++j) a[j] = hpre[j] > 0.0 ? hpre[j] : 0.0;
-    for (int64_t i = 0; i < d; ++i) o[i] = 0.0;
+    for (int64_t j = j0; j < j1; ++j) a[j] = hpre[j] > 0.0 ? hpre[j] : 0.0;
+#pragma omp barrier
+    for (int64_t i = i0; i < i1; ++i) o[i] = 0.0;
     for (int64_t j = 0; j < f; ++j) {
         double aj = a[j];
         const in_t *row = Wo + j * d;
-        for (int64_t i = 0; i < d; ++i) o[i] += aj * (double)row[i];
+        for (int64_t i = i0; i < i1; ++i) o[i] += aj * (double)row[i];
     }
+#pragma omp barrier
 }
 
 /* ---- layer output: y_t = gate_t * FFN_{e_t}(x_t) for kept tokens, 0 for
  * dropped ones (Fig. 2 caption; Sec. 2.2 on dropped tokens).
- * expert_sel (may be NULL = all): experts with expert_sel[e] == 0 are skipped
- * and their tokens' rows are filled with NaN ("not computed"). */
+ * token_sel (may be NULL = all): tokens with token_sel[t] == 0 are skipped and
+ * their rows are filled with NaN ("not computed"). */
 void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
                     const in_t *W_in, const in_t *W_out, const int32_t *expert_index,
-                    const uint8_t *dropped, const double *gate, const uint8_t *expert_sel,
+                    const uint8_t *dropped, const double *gate, const uint8_t *token_sel,
                     double *y /* [T][d] */) {
+    double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
+    double *a = (double *)malloc(sizeof(double) * (size_t)f);
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
 #pragma omp parallel
     {
-        double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
-        double *a = (double *)malloc(sizeof(double) * (size_t)f);
-        double *o = (double *)malloc(sizeof(double) * (size_t)d);
-#pragma omp for schedule(dynamic, 16)
+        int64_t i0, i1;
+        my_range(d, &i0, &i1);
         for (int64_t t = 0; t < T; ++t) {
             int32_t e = expert_index[t];
             double *yt = y + t * d;
-            if (expert_sel && !expert_sel[e]) {
-                for (int64_t i = 0; i < d; ++i) yt[i] = NAN;
+            if (token_sel && !token_sel[t]) {
+                for (int64_t i = i0; i < i1; ++i) yt[i] = NAN;
                 continue;
             }
             if (dropped[t]) {
-                for (int64_t i = 0; i < d; ++i) yt[i] = 0.0;
+                for (int64_t i = i0; i < i1; ++i) yt[i] = 0.0;
                 continue;
             }
             ffn_token(d, f, x + t * d, W_in + (int64_t)e * d * f, W_out + (int64_t)e * f * d,
                       hpre, a, o);
-            for (int64_t i = 0; i < d; ++i) yt[i] = gate[t] * o[i];
+            for (int64_t i = i0; i < i1; ++i) yt[i] = gate[t] * o[i];
+#pragma omp barrier
         }
-        free(hpre);
-        free(a);
-        free(o);
     }
+    free(hpre);
+    free(a);
+    free(o);
     (void)E;
 }
 
@@ -196,88 +215,97 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
  *   dl[t,j]  = p[t,j] (dp[t,j] - sum_i p[t,i] dp[t,i])         (softmax)
  *   dW_r = x^T dl,  db_r = sum_t dl_t,  dx_t += dl_t W_r^T
  *
- * sel_slot[e] >= 0 selects expert e; its weight gradients go to slot
- * sel_slot[e] of dW_in_sel / dW_out_sel.  sel_slot == NULL selects all experts
- * with slot e.  Tokens of unselected experts get dgate = 0 in the router part
- * (only meaningful when dy is zero there) and NaN rows in dx_expert.
+ * Partial evaluation (for sampled checks on large layers):
+ *   token_sel[t] == 0 (token_sel may be NULL = all selected): the token's expert
+ *     FFN is not evaluated; its dgate is taken as 0 in the router part (exact
+ *     only if dy is zero on that token) and its dx row is NaN.
+ *   sel_slot[e] >= 0 (sel_slot may be NULL = slot e for every expert): expert
+ *     e's weight gradients are accumulated into slot sel_slot[e] of dW_in_sel /
+ *     dW_out_sel -- complete only if every kept token of e is selected.
  */
 void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, const in_t *W_r,
                   const in_t *W_in, const in_t *W_out, const in_t *dy, double d_aux,
                   double alpha, const int32_t *expert_index, const uint8_t *dropped,
                   const double *gate, const double *p /* [T][E] */, const int64_t *counts,
                   const int32_t *sel_slot /* [E] or NULL */,
-                  double *dx /* [T][d] */, double *dW_r /* [d][E] */, double *db_r /* [E] */,
+                  const uint8_t *token_sel /* [T] or NULL */, double *dx /* [T][d] */,
+                  double *dW_r /* [d][E] */, double *db_r /* [E] */,
                   double *dW_in_sel /* [nsel][d][f] */, double *dW_out_sel /* [nsel][f][d] */,
                   double *dgate /* [T] */, double *dlogits /* [T][E] */) {
-    /* expert part: one thread owns one expert and walks its tokens in order */
+    /* expert part: tokens in sequence order, see "Work sharing" above */
+    double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
+    double *a = (double *)malloc(sizeof(double) * (size_t)f);
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    double *dout = (double *)malloc(sizeof(double) * (size_t)d);
+    double *dh = (double *)malloc(sizeof(double) * (size_t)f);
 #pragma omp parallel
     {
-        double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
-        double *a = (double *)malloc(sizeof(double) * (size_t)f);
-        double *o = (double *)malloc(sizeof(double) * (size_t)d);
-        double *dout = (double *)malloc(sizeof(double) * (size_t)d);
-        double *dh = (double *)malloc(sizeof(double) * (size_t)f);
-#pragma omp for schedule(dynamic, 1)
+        int64_t j0, j1, k0, k1;
+        my_range(f, &j0, &j1);
+        my_range(d, &k0, &k1);
         for (int64_t e = 0; e < E; ++e) {
             int64_t slot = sel_slot ? sel_slot[e] : e;
+            if (slot < 0) continue;
+            double *gWi = dW_in_sel + slot * d * f;
+            double *gWo = dW_out_sel + slot * f * d;
+            for (int64_t k = k0; k < k1; ++k)
+                for (int64_t j = 0; j < f; ++j) gWi[k * f + j] = 0.0;
+            for (int64_t j = j0; j < j1; ++j)
+                for (int64_t i = 0; i < d; ++i) gWo[j * d + i] = 0.0;
+        }
+#pragma omp barrier
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t e = expert_index[t];
+            int64_t slot = sel_slot ? sel_slot[e] : e;
+            double *dxt = dx + t * d;
+            if ((token_sel && !token_sel[t]) || dropped[t]) {
+                double fill = (token_sel && !token_sel[t]) ? NAN : 0.0;
+                for (int64_t k = k0; k < k1; ++k) dxt[k] = fill;
+                if (omp_get_thread_num() == 0) dgate[t] = 0.0;
+                continue;
+            }
             const in_t *Wi = W_in + e * d * f;
             const in_t *Wo = W_out + e * f * d;
             double *gWi = slot >= 0 ? dW_in_sel + slot * d * f : NULL;
             double *gWo = slot >= 0 ? dW_out_sel + slot * f * d : NULL;
-            if (slot >= 0) {
-                for (int64_t q = 0; q < d * f; ++q) gWi[q] = 0.0;
-                for (int64_t q = 0; q < d * f; ++q) gWo[q] = 0.0;
-            }
-            for (int64_t t = 0; t < T; ++t) {
-                if (expert_index[t] != e) continue;
-                double *dxt = dx + t * d;
-                if (slot < 0) {
-                    dgate[t] = 0.0;
-                    for (int64_t k = 0; k < d; ++k) dxt[k] = NAN;
-                    continue;
-                }
-                if (dropped[t]) {
-                    dgate[t] = 0.0;
-                    for (int64_t k = 0; k < d; ++k) dxt[k] = 0.0;
-                    continue;
-                }
-                const in_t *xt = x + t * d;
-                const in_t *dyt = dy + t * d;
-                ffn_token(d, f, xt, Wi, Wo, hpre, a, o);
-                double dg = 0.0;
-                for (int64_t i = 0; i < d; ++i) {
-                    dout[i] = gate[t] * (double)dyt[i];
-                    dg += (double)dyt[i] * o[i];
-                }
-                dgate[t] = dg;
-                for (int64_t j = 0; j < f; ++j) {
-                    const in_t *row = Wo + j * d;
+            const in_t *xt = x + t * d;
+            const in_t *dyt = dy + t * d;
+            ffn_token(d, f, xt, Wi, Wo, hpre, a, o);
+            /* gate gradient: a short dot product, taken whole by every thread */
+            double dg = 0.0;
+            for (int64_t i = 0; i < d; ++i) dg += (double)dyt[i] * o[i];
+            if (omp_get_thread_num() == 0) dgate[t] = dg;
+            for (int64_t i = k0; i < k1; ++i) dout[i] = gate[t] * (double)dyt[i];
+#pragma omp barrier
+            for (int64_t j = j0; j < j1; ++j) {
+                const in_t *row = Wo + j * d;
+                double aj = a[j], s = 0.0;
+                if (gWo) {
                     double *grow = gWo + j * d;
-                    double aj = a[j], s = 0.0;
-                    for (int64_t i = 0; i < d; ++i) {
-                        grow[i] += aj * dout[i];
-                        s += dout[i] * (double)row[i];
-                    }
-                    dh[j] = hpre[j] > 0.0 ? s : 0.0;
+                    for (int64_t i = 0; i < d; ++i) grow[i] += aj * dout[i];
                 }
-                for (int64_t k = 0; k < d; ++k) {
-                    const in_t *row = Wi + k * f;
-                    double *grow = gWi + k * f;
-                    double xk = (double)xt[k], s = 0.0;
-                    for (int64_t j = 0; j < f; ++j) {
-                        grow[j] += xk * dh[j];
-                        s += dh[j] * (double)row[j];
-                    }
-                    dxt[k] = s;
-                }
+                for (int64_t i = 0; i < d; ++i) s += dout[i] * (double)row[i];
+                dh[j] = hpre[j] > 0.0 ? s : 0.0;
             }
+#pragma omp barrier
+            for (int64_t k = k0; k < k1; ++k) {
+                const in_t *row = Wi + k * f;
+                double xk = (double)xt[k], s = 0.0;
+                if (gWi) {
+                    double *grow = gWi + k * f;
+                    for (int64_t j = 0; j < f; ++j) grow[j] += xk * dh[j];
+                }
+                for (int64_t j = 0; j < f; ++j) s += dh[j] * (double)row[j];
+                dxt[k] = s;
+            }
+#pragma omp barrier
         }
-        free(hpre);
-        free(a);
-        free(o);
-        free(dout);
-        free(dh);
     }
+    free(hpre);
+    free(a);
+    free(o);
+    free(dout);
+    free(dh);
 
     /* router part: softmax backward per token */
 #pragma omp parallel

@@ -1,0 +1,264 @@
+// C ABI of the Switch FFN library: argument checks, workspace layout, kernel
+// sequencing, event-based kernel timing.  See include/switchffn.h.
+#include <math.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace sw {
+
+int check_config(const switch_config *cfg) {
+    if (!cfg) return SW_ERR_NULL;
+    if (cfg->act_dtype != SW_F32 && cfg->act_dtype != SW_BF16) return SW_ERR_DTYPE;
+    if (cfg->T < 1 || cfg->T >= (int64_t)1 << 31) return SW_ERR_SHAPE;
+    if (cfg->E < 1 || cfg->E > 4096) return SW_ERR_SHAPE;
+    if (cfg->d_model < 1 || cfg->d_ff < 1) return SW_ERR_SHAPE;
+    if (cfg->d_model >= (int64_t)1 << 24 || cfg->d_ff >= (int64_t)1 << 24) return SW_ERR_SHAPE;
+    const int64_t mult = cfg->act_dtype == SW_BF16 ? 8 : 4;   // rows move as 16-byte chunks
+    if (cfg->d_model % mult || cfg->d_ff % mult) return SW_ERR_SHAPE;
+    if (!(cfg->capacity_factor > 0.0) || !isfinite(cfg->capacity_factor)) return SW_ERR_VALUE;
+    if (!isfinite(cfg->alpha)) return SW_ERR_VALUE;
+    // slot indices (expert * capacity + position) are kept in 32 bits
+    const double c = floor((double)cfg->T / (double)cfg->E * cfg->capacity_factor);
+    if (c * (double)cfg->E >= 2147483647.0) return SW_ERR_SHAPE;
+    return SW_OK;
+}
+
+int64_t capacity_of(const switch_config *cfg) {
+    return (int64_t)floor((double)cfg->T / (double)cfg->E * cfg->capacity_factor);
+}
+
+Workspace layout_workspace(const switch_config *cfg) {
+    Workspace w{};
+    w.T = cfg->T; w.d = cfg->d_model; w.f = cfg->d_ff; w.E = cfg->E;
+    w.C = capacity_of(cfg);
+    w.nb = ceil_div(w.T, kRouteTB);
+    w.elt = cfg->act_dtype == SW_BF16 ? 2 : 4;
+    w.nsplit = w.nb < 64 ? w.nb : 64;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t T = w.T, E = w.E, C = w.C, d = w.d, f = w.f, nb = w.nb;
+    w.probs = take(T * E * 4);
+    w.idx = take(T * 4);
+    w.gate = take(T * 4);
+    w.pos = take(T * 4);
+    w.dropped = take(T);
+    w.local_rank = take(nb * kRouteTB * 4);
+    w.block_counts = take(nb * E * 4);
+    w.block_psum = take(nb * E * 4);
+    w.block_off = take(nb * E * 4);
+    w.counts = take(E * 4);
+    w.kept = take(E * 4);
+    w.slot_token = take(E * C * 4);
+    w.Xd = take(E * C * d * w.elt);
+    w.A = take(E * C * f * w.elt);
+    w.O = take(E * C * d * w.elt);
+    w.dO = take(E * C * d * w.elt);
+    w.dH = take(E * C * f * w.elt);
+    w.dXd = take(E * C * d * w.elt);
+    w.dgate = take(T * 4);
+    w.dlogits = take(T * E * 4);
+    w.dWr_part = take((size_t)w.nsplit * d * E * 4);
+    w.dbr_part = take((size_t)w.nsplit * E * 4);
+    w.total = off;
+    return w;
+}
+
+// ---- event-based kernel timing -------------------------------------------------
+struct ProfEntry {
+    const char *name;
+    double total_ms;
+    int64_t launches;
+};
+struct ProfRecord {
+    int entry;
+    hipEvent_t start, stop;
+};
+static bool g_prof_on = false;
+static std::vector<ProfEntry> g_entries;
+static std::vector<ProfRecord> g_records;     // pending (not yet collected)
+static std::vector<hipEvent_t> g_event_pool;  // free events
+static int g_open = -1;
+
+static hipEvent_t get_event() {
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void prof_begin(const char *name, hipStream_t s) {
+    if (!g_prof_on) return;
+    int entry = -1;
+    for (size_t i = 0; i < g_entries.size(); ++i)
+        if (strcmp(g_entries[i].name, name) == 0) { entry = (int)i; break; }
+    if (entry < 0) {
+        g_entries.push_back({name, 0.0, 0});
+        entry = (int)g_entries.size() - 1;
+    }
+    ProfRecord r{entry, get_event(), get_event()};
+    if (!r.start || !r.stop) return;
+    (void)hipEventRecord(r.start, s);
+    g_records.push_back(r);
+    g_open = (int)g_records.size() - 1;
+}
+
+void prof_end(hipStream_t s) {
+    if (!g_prof_on || g_open < 0) return;
+    (void)hipEventRecord(g_records[g_open].stop, s);
+    g_open = -1;
+}
+
+static int status_of(hipError_t e) { return e == hipSuccess ? SW_OK : SW_ERR_LAUNCH; }
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace sw
+
+using namespace sw;
+
+extern "C" {
+
+int switch_capacity(const switch_config *cfg, int64_t *capacity_out) {
+    if (!cfg || !capacity_out) return SW_ERR_NULL;
+    int st = check_config(cfg);
+    if (st != SW_OK) return st;
+    *capacity_out = capacity_of(cfg);
+    return SW_OK;
+}
+
+int switch_workspace_size(const switch_config *cfg, size_t *bytes_out) {
+    if (!cfg || !bytes_out) return SW_ERR_NULL;
+    int st = check_config(cfg);
+    if (st != SW_OK) return st;
+    *bytes_out = layout_workspace(cfg).total;
+    return SW_OK;
+}
+
+int switch_forward(const switch_config *cfg, const void *x, const float *W_r, const float *b_r,
+                   const void *W_in, const void *W_out, void *y, int32_t *expert_index,
+                   float *gate, int32_t *position_in_expert, uint8_t *dropped,
+                   int32_t *expert_counts, float *aux_loss, float *router_logits, void *workspace,
+                   size_t workspace_bytes, void *hip_stream) {
+    int st = check_config(cfg);
+    if (st != SW_OK) return st;
+    if (!x || !W_r || !W_in || !W_out || !y || !expert_index || !gate || !position_in_expert ||
+        !dropped || !expert_counts || !aux_loss)
+        return SW_ERR_NULL;
+    if (!aligned16(x) || !aligned16(W_r) || !aligned16(W_in) || !aligned16(W_out) ||
+        !aligned16(y) || (router_logits && !aligned16(router_logits)))
+        return SW_ERR_ALIGN;
+    const Workspace w = layout_workspace(cfg);
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < w.total)
+        return SW_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int dt = cfg->act_dtype;
+    auto gemm = dt == SW_BF16 ? launch_gemm_bf16 : launch_gemm_f32;
+
+    if ((st = status_of(launch_router_fwd(w, dt, x, W_r, b_r, ws, expert_index, gate,
+                                          router_logits, s))))
+        return st;
+    if ((st = status_of(launch_route_scan(w, cfg->alpha, ws, expert_counts, aux_loss, s))))
+        return st;
+    if ((st = status_of(launch_dispatch(w, dt, x, ws, position_in_expert, dropped, s)))) return st;
+    if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
+    if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
+    if ((st = status_of(launch_combine(w, dt, ws, y, s)))) return st;
+    return SW_OK;
+}
+
+int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const void *x,
+                    const float *W_r, const float *b_r, const void *W_in, const void *W_out,
+                    void *dx, float *dW_r, float *db_r, void *dW_in, void *dW_out, void *workspace,
+                    size_t workspace_bytes, void *hip_stream) {
+    (void)b_r;   // the bias enters the gradients only through the saved probabilities
+    int st = check_config(cfg);
+    if (st != SW_OK) return st;
+    if (!dy || !x || !W_r || !W_in || !W_out || !dx || !dW_r || !dW_in || !dW_out)
+        return SW_ERR_NULL;
+    if (!isfinite(d_aux)) return SW_ERR_VALUE;
+    if (!aligned16(dy) || !aligned16(x) || !aligned16(W_r) || !aligned16(W_in) ||
+        !aligned16(W_out) || !aligned16(dx) || !aligned16(dW_r) || !aligned16(dW_in) ||
+        !aligned16(dW_out))
+        return SW_ERR_ALIGN;
+    const Workspace w = layout_workspace(cfg);
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < w.total)
+        return SW_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int dt = cfg->act_dtype;
+    auto gemm = dt == SW_BF16 ? launch_gemm_bf16 : launch_gemm_f32;
+
+    if ((st = status_of(launch_combine_bwd(w, dt, dy, ws, s)))) return st;
+    if ((st = status_of(gemm(GEMM_DGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if ((st = status_of(gemm(GEMM_WGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if ((st = status_of(gemm(GEMM_DGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if ((st = status_of(gemm(GEMM_WGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if ((st = status_of(launch_router_bwd(w, dt, cfg->alpha, d_aux, x, W_r, ws, dx, dW_r, db_r, s))))
+        return st;
+    return SW_OK;
+}
+
+const char *switch_status_string(int status) {
+    switch (status) {
+    case SW_OK: return "ok";
+    case SW_ERR_NULL: return "a required pointer is NULL";
+    case SW_ERR_SHAPE: return "shape out of range (T, E, d_model, d_ff; 16-byte row chunks)";
+    case SW_ERR_VALUE: return "capacity_factor must be finite and > 0; alpha, d_aux finite";
+    case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16";
+    case SW_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
+    case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case SW_ERR_LAUNCH: return "HIP launch failed";
+    case SW_ERR_STATE: return "profiling call out of order";
+    default: return "unknown status";
+    }
+}
+
+int switch_profile_enable(int on) {
+    if (on) {
+        for (auto &r : g_records) {
+            g_event_pool.push_back(r.start);
+            g_event_pool.push_back(r.stop);
+        }
+        g_records.clear();
+        g_entries.clear();
+        g_open = -1;
+    }
+    g_prof_on = on != 0;
+    return SW_OK;
+}
+
+int switch_profile_collect(void) {
+    if (g_open >= 0) return SW_ERR_STATE;
+    for (auto &r : g_records) {
+        if (hipEventSynchronize(r.stop) != hipSuccess) return SW_ERR_LAUNCH;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return SW_ERR_LAUNCH;
+        g_entries[r.entry].total_ms += ms;
+        g_entries[r.entry].launches += 1;
+        g_event_pool.push_back(r.start);
+        g_event_pool.push_back(r.stop);
+    }
+    g_records.clear();
+    return SW_OK;
+}
+
+int switch_profile_count(void) { return (int)g_entries.size(); }
+
+int switch_profile_get(int i, const char **name, double *total_ms, int64_t *launches) {
+    if (i < 0 || i >= (int)g_entries.size()) return SW_ERR_SHAPE;
+    if (name) *name = g_entries[i].name;
+    if (total_ms) *total_ms = g_entries[i].total_ms;
+    if (launches) *launches = g_entries[i].launches;
+    return SW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "switchffn.h"
+
+namespace sw {
+
+typedef __bf16 bf16;
+
+// ---- element helpers -------------------------------------------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
+
+constexpr int kWave = 64;
+
+// Token block of the router / position kernels: one block of kRouteTB threads
+// owns kRouteTB consecutive tokens.
+constexpr int kRouteTB = 256;
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- workspace layout (byte offsets into the caller's workspace) ------------
+struct Workspace {
+    int64_t T, d, f, E, C, nb;  // nb = number of token blocks
+    size_t elt;                 // bytes per activation element
+    size_t probs;               // f32 [T][E]   router probabilities (saved for backward)
+    size_t idx;                 // i32 [T]
+    size_t gate;                // f32 [T]
+    size_t pos;                 // i32 [T]
+    size_t dropped;             // u8  [T]
+    size_t local_rank;          // i32 [T]      rank among same-expert tokens of the block
+    size_t block_counts;        // i32 [nb][E]
+    size_t block_psum;          // f32 [nb][E]
+    size_t block_off;           // i32 [nb][E]  exclusive prefix of block_counts over blocks
+    size_t counts;              // i32 [E]
+    size_t kept;                // i32 [E]      min(count, C)
+    size_t slot_token;          // i32 [E][C]   token held by each slot (valid for slot < kept[e])
+    size_t Xd;                  // act [E][C][d]   dispatched tokens
+    size_t A;                   // act [E][C][f]   ReLU(Xd W_in)
+    size_t O;                   // act [E][C][d]   A W_out
+    size_t dO;                  // act [E][C][d]
+    size_t dH;                  // act [E][C][f]
+    size_t dXd;                 // act [E][C][d]
+    size_t dgate;               // f32 [T]
+    size_t dlogits;             // f32 [T][E]
+    size_t dWr_part;            // f32 [nsplit][d][E]  split-T partial sums of dW_r
+    size_t dbr_part;            // f32 [nsplit][E]
+    int64_t nsplit;
+    size_t total;
+};
+
+int check_config(const switch_config *cfg);
+int64_t capacity_of(const switch_config *cfg);
+Workspace layout_workspace(const switch_config *cfg);
+
+// ---- profiling hooks ---------------------------------------------------------
+void prof_begin(const char *name, hipStream_t s);
+void prof_end(hipStream_t s);
+
+struct ProfScope {
+    hipStream_t s;
+    ProfScope(const char *name, hipStream_t st) : s(st) { prof_begin(name, st); }
+    ~ProfScope() { prof_end(s); }
+};
+
+// ---- kernel launchers (each returns hipSuccess or the launch error) ----------
+// Router forward: logits, softmax, arg max, gate, in-block rank, per-block
+// expert histogram and probability sums.
+hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const float *W_r,
+                             const float *b_r, char *ws, int32_t *expert_index, float *gate,
+                             float *router_logits, hipStream_t s);
+// Per-expert scan over token blocks, counts, kept, aux loss.
+hipError_t launch_route_scan(const Workspace &w, float alpha, char *ws, int32_t *expert_counts,
+                             float *aux_loss, hipStream_t s);
+// Positions, dropped mask, gather of kept tokens into expert-major slots.
+hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *ws,
+                           int32_t *position_in_expert, uint8_t *dropped, hipStream_t s);
+hipError_t launch_combine(const Workspace &w, int dtype, char *ws, void *y, hipStream_t s);
+hipError_t launch_combine_bwd(const Workspace &w, int dtype, const void *dy, char *ws,
+                              hipStream_t s);
+hipError_t launch_router_bwd(const Workspace &w, int dtype, float alpha, float d_aux,
+                             const void *x, const float *W_r, char *ws, void *dx, float *dW_r,
+                             float *db_r, hipStream_t s);
+
+// Grouped GEMMs over experts.  Each computes, for every expert e,
+//   C_e[q][p] = sum_k Q_e(q,k) * P_e(p,k)
+// where C_e is row-major with p contiguous.
+enum GemmKind {
+    GEMM_FWD1,   // A  = relu(Xd W_in)            q: slot  p: d_ff     k: d_model
+    GEMM_FWD2,   // O  = A W_out                  q: slot  p: d_model  k: d_ff
+    GEMM_DGRAD2, // dH = (dO W_out^T) * [A > 0]   q: slot  p: d_ff     k: d_model
+    GEMM_DGRAD1, // dXd = dH W_in^T               q: slot  p: d_model  k: d_ff
+    GEMM_WGRAD2, // dW_out = A^T dO               q: d_ff  p: d_model  k: slot (< kept)
+    GEMM_WGRAD1  // dW_in = Xd^T dH               q: d_model p: d_ff   k: slot (< kept)
+};
+hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
+                            const void *W_out, void *dW_in, void *dW_out, hipStream_t s);
+hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
+                           const void *W_out, void *dW_in, void *dW_out, hipStream_t s);
+
+}  // namespace sw

@@ -1,0 +1,237 @@
+// Position assignment, dispatch gather, combine scatter and its backward.
+// All of these stream rows through HBM once; they are laid out so that a wave
+// moves whole 16-byte chunks of a row with every lane busy.
+#include "common.h"
+
+namespace sw {
+
+// 16-byte chunk of a row
+struct __attribute__((aligned(16))) Chunk16 {
+    uint32_t w[4];
+};
+
+template <typename XT> struct Vec;
+template <> struct Vec<bf16> { static constexpr int N = 8; };
+template <> struct Vec<float> { static constexpr int N = 4; };
+
+template <typename XT> __device__ __forceinline__ void unpack(const Chunk16 &c, float *v);
+template <> __device__ __forceinline__ void unpack<float>(const Chunk16 &c, float *v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(c.w[i]);
+}
+template <> __device__ __forceinline__ void unpack<bf16>(const Chunk16 &c, float *v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {   // bf16 -> fp32 is a 16-bit shift
+        v[2 * i] = __uint_as_float(c.w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(c.w[i] & 0xffff0000u);
+    }
+}
+template <typename XT> __device__ __forceinline__ Chunk16 pack(const float *v);
+template <> __device__ __forceinline__ Chunk16 pack<float>(const float *v) {
+    Chunk16 c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c.w[i] = __float_as_uint(v[i]);
+    return c;
+}
+template <> __device__ __forceinline__ Chunk16 pack<bf16>(const float *v) {
+    Chunk16 c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 pr;
+        pr[0] = (bf16)v[2 * i];       // round to nearest even
+        pr[1] = (bf16)v[2 * i + 1];
+        c.w[i] = __builtin_bit_cast(uint32_t, pr);
+    }
+    return c;
+}
+
+// -----------------------------------------------------------------------------
+// position_in_expert[t] = block_off[block(t)][e_t] + local_rank[t]; dropped mask;
+// slot -> token table for kept tokens.
+// -----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void positions_kernel(
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ local_rank,
+    const int32_t *__restrict__ block_off, int32_t *__restrict__ pos_out,
+    uint8_t *__restrict__ dropped_out, int32_t *__restrict__ pos_ws,
+    uint8_t *__restrict__ dropped_ws, int32_t *__restrict__ slot_token, int T, int E, int C) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    const int e = idx[t];
+    const int p = block_off[(size_t)(t / kRouteTB) * E + e] + local_rank[t];
+    const uint8_t dr = p >= C;
+    pos_out[t] = p;
+    pos_ws[t] = p;
+    dropped_out[t] = dr;
+    dropped_ws[t] = dr;
+    if (!dr) slot_token[(size_t)e * C + p] = t;
+}
+
+// -----------------------------------------------------------------------------
+// Dispatch: Xd[e_t * C + pos_t][:] = x[t][:] for kept tokens.  One thread per
+// 16-byte chunk; cpr = chunks per row.
+// -----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dispatch_kernel(const Chunk16 *__restrict__ x,
+                                                       Chunk16 *__restrict__ Xd,
+                                                       const int32_t *__restrict__ idx,
+                                                       const int32_t *__restrict__ pos,
+                                                       const uint8_t *__restrict__ dropped,
+                                                       size_t total_chunks, int cpr, int C) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < total_chunks; c += stride) {
+        const int t = (int)(c / cpr);
+        const int col = (int)(c % cpr);
+        if (dropped[t]) continue;
+        const size_t slot = (size_t)idx[t] * C + pos[t];
+        Xd[slot * cpr + col] = x[c];
+    }
+}
+
+// -----------------------------------------------------------------------------
+// Combine: y[t][:] = gate[t] * O[slot_t][:] for kept tokens, +0 for dropped.
+// -----------------------------------------------------------------------------
+template <typename XT>
+__global__ __launch_bounds__(256) void combine_kernel(const Chunk16 *__restrict__ O,
+                                                      Chunk16 *__restrict__ y,
+                                                      const int32_t *__restrict__ idx,
+                                                      const int32_t *__restrict__ pos,
+                                                      const uint8_t *__restrict__ dropped,
+                                                      const float *__restrict__ gate,
+                                                      size_t total_chunks, int cpr, int C) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < total_chunks; c += stride) {
+        const int t = (int)(c / cpr);
+        const int col = (int)(c % cpr);
+        Chunk16 out = {{0u, 0u, 0u, 0u}};
+        if (!dropped[t]) {
+            const size_t slot = (size_t)idx[t] * C + pos[t];
+            const Chunk16 in = O[slot * cpr + col];
+            float v[Vec<XT>::N];
+            unpack<XT>(in, v);
+            const float g = gate[t];
+#pragma unroll
+            for (int i = 0; i < Vec<XT>::N; ++i) v[i] *= g;
+            out = pack<XT>(v);
+        }
+        y[c] = out;
+    }
+}
+
+// -----------------------------------------------------------------------------
+// Combine backward: for kept tokens dO[slot_t][:] = gate[t] * dy[t][:] and
+// dgate[t] = <dy[t], O[slot_t]>; dropped tokens get dgate = 0.  One wave per token.
+// -----------------------------------------------------------------------------
+template <typename XT>
+__global__ __launch_bounds__(256) void combine_bwd_kernel(
+    const Chunk16 *__restrict__ dy, const Chunk16 *__restrict__ O, Chunk16 *__restrict__ dO,
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ pos,
+    const uint8_t *__restrict__ dropped, const float *__restrict__ gate,
+    float *__restrict__ dgate, int T, int cpr, int C) {
+    const int lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    if (dropped[t]) {
+        if (lane == 0) dgate[t] = 0.f;
+        return;
+    }
+    const size_t slot = (size_t)idx[t] * C + pos[t];
+    const float g = gate[t];
+    float dot = 0.f;
+    for (int col = lane; col < cpr; col += kWave) {
+        const Chunk16 a = dy[(size_t)t * cpr + col];
+        const Chunk16 b = O[slot * cpr + col];
+        float av[Vec<XT>::N], bv[Vec<XT>::N];
+        unpack<XT>(a, av);
+        unpack<XT>(b, bv);
+#pragma unroll
+        for (int i = 0; i < Vec<XT>::N; ++i) {
+            dot = fmaf(av[i], bv[i], dot);
+            av[i] *= g;
+        }
+        dO[slot * cpr + col] = pack<XT>(av);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, kWave);
+    if (lane == 0) dgate[t] = dot;
+}
+
+// -----------------------------------------------------------------------------
+// launchers
+// -----------------------------------------------------------------------------
+static inline unsigned stream_grid(size_t total_chunks) {
+    size_t blocks = (total_chunks + 255) / 256;
+    const size_t cap = 256 * 16;   // 16 blocks per CU; grid-stride beyond that
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (unsigned)blocks;
+}
+
+hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *ws,
+                           int32_t *position_in_expert, uint8_t *dropped, hipStream_t s) {
+    hipError_t err;
+    {
+        ProfScope ps("positions", s);
+        hipLaunchKernelGGL(positions_kernel, dim3((unsigned)ceil_div(w.T, 256)), dim3(256), 0, s,
+                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.local_rank),
+                           (const int32_t *)(ws + w.block_off), position_in_expert, dropped,
+                           (int32_t *)(ws + w.pos), (uint8_t *)(ws + w.dropped),
+                           (int32_t *)(ws + w.slot_token), (int)w.T, (int)w.E, (int)w.C);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    if (w.C == 0) return hipSuccess;
+    {
+        ProfScope ps("dispatch_gather", s);
+        const int vec = dtype == SW_BF16 ? 8 : 4;
+        const int cpr = (int)(w.d / vec);
+        const size_t total = (size_t)w.T * cpr;
+        hipLaunchKernelGGL(dispatch_kernel, dim3(stream_grid(total)), dim3(256), 0, s,
+                           (const Chunk16 *)x, (Chunk16 *)(ws + w.Xd),
+                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
+                           (const uint8_t *)(ws + w.dropped), total, cpr, (int)w.C);
+        err = hipGetLastError();
+    }
+    return err;
+}
+
+hipError_t launch_combine(const Workspace &w, int dtype, char *ws, void *y, hipStream_t s) {
+    ProfScope ps("combine_scatter", s);
+    const int vec = dtype == SW_BF16 ? 8 : 4;
+    const int cpr = (int)(w.d / vec);
+    const size_t total = (size_t)w.T * cpr;
+    if (dtype == SW_BF16)
+        hipLaunchKernelGGL(combine_kernel<bf16>, dim3(stream_grid(total)), dim3(256), 0, s,
+                           (const Chunk16 *)(ws + w.O), (Chunk16 *)y,
+                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
+                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate), total,
+                           cpr, (int)w.C);
+    else
+        hipLaunchKernelGGL(combine_kernel<float>, dim3(stream_grid(total)), dim3(256), 0, s,
+                           (const Chunk16 *)(ws + w.O), (Chunk16 *)y,
+                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
+                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate), total,
+                           cpr, (int)w.C);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_bwd(const Workspace &w, int dtype, const void *dy, char *ws,
+                              hipStream_t s) {
+    ProfScope ps("combine_bwd", s);
+    const int vec = dtype == SW_BF16 ? 8 : 4;
+    const int cpr = (int)(w.d / vec);
+    dim3 grid((unsigned)ceil_div(w.T, 256 / kWave));
+    if (dtype == SW_BF16)
+        hipLaunchKernelGGL(combine_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const Chunk16 *)dy,
+                           (const Chunk16 *)(ws + w.O), (Chunk16 *)(ws + w.dO),
+                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
+                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
+                           (float *)(ws + w.dgate), (int)w.T, cpr, (int)w.C);
+    else
+        hipLaunchKernelGGL(combine_bwd_kernel<float>, grid, dim3(256), 0, s, (const Chunk16 *)dy,
+                           (const Chunk16 *)(ws + w.O), (Chunk16 *)(ws + w.dO),
+                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
+                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
+                           (float *)(ws + w.dgate), (int)w.T, cpr, (int)w.C);
+    return hipGetLastError();
+}
+
+}  // namespace sw

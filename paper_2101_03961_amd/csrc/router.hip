@@ -1,0 +1,590 @@
+// Router kernels: fp32 logits, softmax, top-1, in-block ranks, per-expert scan,
+// load-balancing loss, and the router's backward pass.
+//
+// The router is computed in fp32 whatever the activation dtype is (Sec. 2.4,
+// selective precision): x is widened to fp32 before the contraction.
+#include "common.h"
+
+namespace sw {
+
+// -----------------------------------------------------------------------------
+// Logits tile kernel:  h[t][e] = sum_k x[t][k] W_r[k][e] (+ b_r[e]), fp32 FMA chain
+// over k ascending.  Block = 256 tokens x 64 experts, thread = 8 tokens x 8 experts.
+// -----------------------------------------------------------------------------
+constexpr int kLogTB = 256;  // tokens per block
+constexpr int kLogEB = 64;   // experts per block
+constexpr int kLogKC = 16;   // k chunk
+
+template <typename XT>
+__global__ __launch_bounds__(256) void router_logits_kernel(const XT *__restrict__ x,
+                                                            const float *__restrict__ W_r,
+                                                            const float *__restrict__ b_r,
+                                                            float *__restrict__ logits, int T,
+                                                            int d, int E) {
+    __shared__ float xs[kLogKC][kLogTB + 4];
+    __shared__ float wsm[kLogKC][kLogEB + 4];
+    const int tid = threadIdx.x;
+    const int t0 = blockIdx.x * kLogTB;
+    const int e0 = blockIdx.y * kLogEB;
+    const int tx = tid % 8;   // expert group
+    const int ty = tid / 8;   // token group
+    float acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = 0; k0 < d; k0 += kLogKC) {
+        {   // x tile: thread loads 16 consecutive k of one token, stores transposed
+            const int t = t0 + tid;
+#pragma unroll
+            for (int kk = 0; kk < kLogKC; ++kk) {
+                float v = 0.f;
+                if (t < T && k0 + kk < d) v = to_f32(x[(size_t)t * d + k0 + kk]);
+                xs[kk][tid] = v;
+            }
+        }
+        {   // W tile: 16 x 64, four consecutive experts per thread
+            const int kk = tid / 16;
+            const int ee = (tid % 16) * 4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float v = 0.f;
+                if (k0 + kk < d && e0 + ee + j < E) v = W_r[(size_t)(k0 + kk) * E + e0 + ee + j];
+                wsm[kk][ee + j] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < kLogKC; ++kk) {
+            float xv[8], wv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xv[i] = xs[kk][ty * 8 + i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wv[j] = wsm[kk][tx * 8 + j];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(xv[i], wv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int t = t0 + ty * 8 + i;
+        if (t >= T) continue;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int e = e0 + tx * 8 + j;
+            if (e < E) logits[(size_t)t * E + e] = acc[i][j] + (b_r ? b_r[e] : 0.f);
+        }
+    }
+}
+
+// -----------------------------------------------------------------------------
+// Softmax / top-1 / block statistics.  Block = kRouteTB tokens, 4 waves; a wave
+// walks its 64 tokens one at a time with lanes striding the experts.
+// EPL = experts per lane (E <= 64 * EPL).
+// -----------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+template <int EPL>
+__global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
+    float *__restrict__ probs /* in: logits, out: p */, float *__restrict__ logits_copy,
+    int32_t *__restrict__ idx_out, float *__restrict__ gate_out, int32_t *__restrict__ idx_ws,
+    float *__restrict__ gate_ws, int32_t *__restrict__ local_rank,
+    int32_t *__restrict__ block_counts, float *__restrict__ block_psum, int T, int E) {
+    extern __shared__ char smem_raw[];
+    // layout: idx_s[kRouteTB] | hist[E] | psum_w[4][E]
+    int32_t *idx_s = (int32_t *)smem_raw;
+    int32_t *hist = idx_s + kRouteTB;
+    float *psum_w = (float *)(hist + E);
+
+    const int tid = threadIdx.x;
+    const int lane = tid % kWave;
+    const int wave = tid / kWave;
+    const int b = blockIdx.x;
+    for (int e = tid; e < E; e += kRouteTB) hist[e] = 0;
+
+    float pacc[EPL];
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) pacc[j] = 0.f;
+
+    for (int i = 0; i < kWave; ++i) {
+        const int tl = wave * kWave + i;
+        const int t = b * kRouteTB + tl;
+        if (t >= T) {
+            if (lane == 0) idx_s[tl] = -1;
+            continue;
+        }
+        float *row = probs + (size_t)t * E;
+        float h[EPL];
+        float best = -INFINITY;
+        int besti = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane + j * kWave;
+            h[j] = e < E ? row[e] : -INFINITY;
+            if (logits_copy && e < E) logits_copy[(size_t)t * E + e] = h[j];
+            if (h[j] > best) { best = h[j]; besti = e; }   // ascending e: lowest index kept on ties
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const float ov = __shfl_xor(best, m, kWave);
+            const int oi = __shfl_xor(besti, m, kWave);
+            if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+        }
+        float ex[EPL];
+        float z = 0.f;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane + j * kWave;
+            ex[j] = e < E ? expf(h[j] - best) : 0.f;
+            z += ex[j];
+        }
+        z = wave_sum(z);
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane + j * kWave;
+            const float p = ex[j] / z;
+            if (e < E) row[e] = p;
+            pacc[j] += p;   // padded experts add 0
+        }
+        if (lane == 0) {
+            const float g = 1.0f / z;   // exp(0) / z: probability of the arg max
+            idx_s[tl] = besti;
+            idx_out[t] = besti;
+            idx_ws[t] = besti;
+            gate_out[t] = g;
+            gate_ws[t] = g;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+        const int e = lane + j * kWave;
+        if (e < E) psum_w[wave * E + e] = pacc[j];
+    }
+    __syncthreads();
+    // rank of each token among the block's earlier tokens with the same expert
+    {
+        const int me = idx_s[tid];
+        if (me >= 0) {
+            int r = 0;
+            for (int s = 0; s < tid; ++s) r += (idx_s[s] == me);
+            local_rank[b * kRouteTB + tid] = r;
+            atomicAdd(&hist[me], 1);   // integer: result independent of order
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += kRouteTB) {
+        block_counts[(size_t)b * E + e] = hist[e];
+        // fixed order over the four waves
+        block_psum[(size_t)b * E + e] =
+            ((psum_w[e] + psum_w[E + e]) + psum_w[2 * E + e]) + psum_w[3 * E + e];
+    }
+}
+
+// -----------------------------------------------------------------------------
+// Per-expert scan over token blocks (single block of 1024 threads).
+//   block_off[b][e] = sum_{b' < b} block_counts[b'][e]
+//   counts[e], kept[e] = min(counts[e], C),  P-sum[e] in fixed order
+//   aux = alpha * E * sum_e (counts[e] / T) * (psum[e] / T)             (Eqs. 4-6)
+// -----------------------------------------------------------------------------
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
+    const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
+    int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
+    int32_t *__restrict__ counts_out, float *__restrict__ aux_out, int nb, int E, int C, int T,
+    float alpha) {
+    __shared__ int32_t part_cnt[kScanThreads];
+    __shared__ float part_ps[kScanThreads];
+    __shared__ double red[kScanThreads];
+    const int tid = threadIdx.x;
+    const int Ew = E < kScanThreads ? E : kScanThreads;   // experts handled per pass
+    const int P = kScanThreads / Ew;                      // block-range parts per expert
+    const int el = tid % Ew;
+    const int part = tid / Ew;
+    const int per = (nb + P - 1) / P;
+    const int b_lo = part * per;
+    const int b_hi = (b_lo + per < nb) ? b_lo + per : nb;
+    double loss_acc = 0.0;
+    for (int ebase = 0; ebase < E; ebase += Ew) {
+        const int e = ebase + el;
+        const bool active = part < P && e < E;
+        int csum = 0;
+        float psum = 0.f;
+        if (active)
+            for (int b = b_lo; b < b_hi; ++b) {
+                csum += block_counts[(size_t)b * E + e];
+                psum += block_psum[(size_t)b * E + e];
+            }
+        part_cnt[tid] = csum;
+        part_ps[tid] = psum;
+        __syncthreads();
+        int start = 0;
+        if (active) {
+            for (int q = 0; q < part; ++q) start += part_cnt[q * Ew + el];
+            int run = start;
+            for (int b = b_lo; b < b_hi; ++b) {
+                block_off[(size_t)b * E + e] = run;
+                run += block_counts[(size_t)b * E + e];
+            }
+        }
+        if (part == 0 && e < E) {
+            int total = 0;
+            float ptot = 0.f;
+            for (int q = 0; q < P; ++q) {
+                total += part_cnt[q * Ew + el];
+                ptot += part_ps[q * Ew + el];
+            }
+            counts_ws[e] = total;
+            counts_out[e] = total;
+            kept_ws[e] = total < C ? total : C;
+            loss_acc += ((double)total / (double)T) * ((double)ptot / (double)T);
+        }
+        __syncthreads();
+    }
+    red[tid] = loss_acc;
+    __syncthreads();
+    for (int s = kScanThreads / 2; s >= 1; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) aux_out[0] = (float)((double)alpha * (double)E * red[0]);
+}
+
+// -----------------------------------------------------------------------------
+// Backward, step 1: gradient w.r.t. the logits.
+//   dp[t][i] = dgate[t] [i = e_t] + d_aux * alpha * E * (counts[i] / T) / T
+//   dl[t][j] = p[t][j] (dp[t][j] - sum_i p[t][i] dp[t][i])
+// One wave per token, lanes stride the experts.
+// -----------------------------------------------------------------------------
+template <int EPL>
+__global__ __launch_bounds__(256) void router_dlogits_kernel(
+    const float *__restrict__ probs, const int32_t *__restrict__ idx,
+    const float *__restrict__ dgate, const int32_t *__restrict__ counts,
+    float *__restrict__ dlogits, int T, int E, float aux_scale /* d_aux*alpha*E/T^2 */) {
+    const int lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    const int me = idx[t];
+    const float dg = dgate[t];
+    float p[EPL], dp[EPL];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+        const int e = lane + j * kWave;
+        p[j] = e < E ? probs[(size_t)t * E + e] : 0.f;
+        dp[j] = e < E ? aux_scale * (float)counts[e] : 0.f;
+        if (e == me) dp[j] += dg;
+        s += p[j] * dp[j];
+    }
+    s = wave_sum(s);
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+        const int e = lane + j * kWave;
+        if (e < E) dlogits[(size_t)t * E + e] = p[j] * (dp[j] - s);
+    }
+}
+
+// -----------------------------------------------------------------------------
+// Backward, step 2:  dx[t][k] = sum_j dl[t][j] W_r[k][j] + kept_t * dXd[slot_t][k]
+// Block = 256 tokens x 64 k, thread = 8 tokens x 8 k, reduction over experts.
+// -----------------------------------------------------------------------------
+template <typename XT>
+__global__ __launch_bounds__(256) void router_dx_kernel(
+    const float *__restrict__ dlogits, const float *__restrict__ W_r,
+    const XT *__restrict__ dXd, const int32_t *__restrict__ idx, const int32_t *__restrict__ pos,
+    const uint8_t *__restrict__ dropped, XT *__restrict__ dx, int T, int d, int E, int C) {
+    __shared__ float ds[kLogKC][kLogTB + 4];
+    __shared__ float wsm[kLogKC][kLogEB + 4];
+    const int tid = threadIdx.x;
+    const int t0 = blockIdx.x * kLogTB;
+    const int k0 = blockIdx.y * kLogEB;
+    const int tx = tid % 8, ty = tid / 8;
+    float acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+    for (int j0 = 0; j0 < E; j0 += kLogKC) {
+        {
+            const int t = t0 + tid;
+#pragma unroll
+            for (int jj = 0; jj < kLogKC; ++jj) {
+                float v = 0.f;
+                if (t < T && j0 + jj < E) v = dlogits[(size_t)t * E + j0 + jj];
+                ds[jj][tid] = v;
+            }
+        }
+        {   // W_r[k][j] -> wsm[jj][kk]; thread reads 4 consecutive j of one k
+            const int kk = tid / 4;            // 0..63
+            const int jq = (tid % 4) * 4;      // 0,4,8,12
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float v = 0.f;
+                if (k0 + kk < d && j0 + jq + u < E) v = W_r[(size_t)(k0 + kk) * E + j0 + jq + u];
+                wsm[jq + u][kk] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int jj = 0; jj < kLogKC; ++jj) {
+            float dv[8], wv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dv[i] = ds[jj][ty * 8 + i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wv[j] = wsm[jj][tx * 8 + j];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(dv[i], wv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int t = t0 + ty * 8 + i;
+        if (t >= T) continue;
+        const bool kept = !dropped[t];
+        const size_t slot = kept ? (size_t)idx[t] * C + pos[t] : 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = k0 + tx * 8 + j;
+            if (k >= d) continue;
+            float v = acc[i][j];
+            if (kept) v += to_f32(dXd[slot * d + k]);
+            dx[(size_t)t * d + k] = from_f32<XT>(v);
+        }
+    }
+}
+
+// -----------------------------------------------------------------------------
+// Backward, step 3:  dW_r[k][j] = sum_t x[t][k] dl[t][j], split over token ranges.
+// Block = 64 k x 64 j output tile over one token range; thread = 4 k x 4 j.
+// Partial sums are combined in split order by reduce_partials_kernel, so the
+// result does not depend on scheduling.
+// -----------------------------------------------------------------------------
+constexpr int kWrTile = 64;
+constexpr int kWrTC = 16;
+
+template <typename XT>
+__global__ __launch_bounds__(256) void router_dWr_kernel(const XT *__restrict__ x,
+                                                         const float *__restrict__ dlogits,
+                                                         float *__restrict__ part, int T, int d,
+                                                         int E, int tokens_per_split) {
+    __shared__ float xs[kWrTC][kWrTile + 4];
+    __shared__ float ls[kWrTC][kWrTile + 4];
+    const int tid = threadIdx.x;
+    const int k0 = blockIdx.x * kWrTile;
+    const int j0 = blockIdx.y * kWrTile;
+    const int split = blockIdx.z;
+    const int t_lo = split * tokens_per_split;
+    const int t_hi = (t_lo + tokens_per_split < T) ? t_lo + tokens_per_split : T;
+    const int tx = tid % 16, ty = tid / 16;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (int tb = t_lo; tb < t_hi; tb += kWrTC) {
+        {
+            const int tt = tid / 16;          // 0..15 token within chunk
+            const int cc = (tid % 16) * 4;    // 4 consecutive columns
+            const int t = tb + tt;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float xv = 0.f, lv = 0.f;
+                if (t < t_hi) {
+                    if (k0 + cc + u < d) xv = to_f32(x[(size_t)t * d + k0 + cc + u]);
+                    if (j0 + cc + u < E) lv = dlogits[(size_t)t * E + j0 + cc + u];
+                }
+                xs[tt][cc + u] = xv;
+                ls[tt][cc + u] = lv;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int tt = 0; tt < kWrTC; ++tt) {
+            float xv[4], lv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xv[i] = xs[tt][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lv[j] = ls[tt][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(xv[i], lv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    float *out = part + (size_t)split * d * E;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = k0 + ty * 4 + i;
+        if (k >= d) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = j0 + tx * 4 + j;
+            if (e < E) out[(size_t)k * E + e] = acc[i][j];
+        }
+    }
+}
+
+// db_r partials: part[split][j] = sum over the split's tokens of dl[t][j]
+__global__ __launch_bounds__(256) void router_dbr_kernel(const float *__restrict__ dlogits,
+                                                         float *__restrict__ part, int T, int E,
+                                                         int tokens_per_split) {
+    const int split = blockIdx.x;
+    const int t_lo = split * tokens_per_split;
+    const int t_hi = (t_lo + tokens_per_split < T) ? t_lo + tokens_per_split : T;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        float s = 0.f;
+        for (int t = t_lo; t < t_hi; ++t) s += dlogits[(size_t)t * E + e];
+        part[(size_t)split * E + e] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part,
+                                                              float *__restrict__ out, size_t n,
+                                                              int nsplit) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int q = 0; q < nsplit; ++q) s += part[(size_t)q * n + i];
+    out[i] = s;
+}
+
+// -----------------------------------------------------------------------------
+// launchers
+// -----------------------------------------------------------------------------
+template <int EPL>
+static hipError_t softmax_launch(const Workspace &w, char *ws, int32_t *expert_index, float *gate,
+                                 float *router_logits, hipStream_t s) {
+    const size_t smem = sizeof(int32_t) * kRouteTB + sizeof(int32_t) * w.E + sizeof(float) * 4 * w.E;
+    hipLaunchKernelGGL(router_softmax_kernel<EPL>, dim3((unsigned)w.nb), dim3(kRouteTB), smem, s,
+                       (float *)(ws + w.probs), router_logits, expert_index, gate,
+                       (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
+                       (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
+                       (float *)(ws + w.block_psum), (int)w.T, (int)w.E);
+    return hipGetLastError();
+}
+
+#define SW_DISPATCH_EPL(E, CALL)                  \
+    do {                                          \
+        if ((E) <= 64) { CALL(1); }               \
+        else if ((E) <= 128) { CALL(2); }         \
+        else if ((E) <= 256) { CALL(4); }         \
+        else if ((E) <= 512) { CALL(8); }         \
+        else if ((E) <= 1024) { CALL(16); }       \
+        else if ((E) <= 2048) { CALL(32); }       \
+        else { CALL(64); }                        \
+    } while (0)
+
+hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const float *W_r,
+                             const float *b_r, char *ws, int32_t *expert_index, float *gate,
+                             float *router_logits, hipStream_t s) {
+    hipError_t err;
+    {
+        ProfScope ps("router_logits", s);
+        dim3 grid((unsigned)ceil_div(w.T, kLogTB), (unsigned)ceil_div(w.E, kLogEB));
+        if (dtype == SW_BF16)
+            hipLaunchKernelGGL(router_logits_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)x,
+                               W_r, b_r, (float *)(ws + w.probs), (int)w.T, (int)w.d, (int)w.E);
+        else
+            hipLaunchKernelGGL(router_logits_kernel<float>, grid, dim3(256), 0, s,
+                               (const float *)x, W_r, b_r, (float *)(ws + w.probs), (int)w.T,
+                               (int)w.d, (int)w.E);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    {
+        ProfScope ps("router_softmax_top1", s);
+#define CALL(N) err = softmax_launch<N>(w, ws, expert_index, gate, router_logits, s)
+        SW_DISPATCH_EPL(w.E, CALL);
+#undef CALL
+    }
+    return err;
+}
+
+hipError_t launch_route_scan(const Workspace &w, float alpha, char *ws, int32_t *expert_counts,
+                             float *aux_loss, hipStream_t s) {
+    ProfScope ps("route_scan_aux", s);
+    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(kScanThreads), 0, s,
+                       (const int32_t *)(ws + w.block_counts), (const float *)(ws + w.block_psum),
+                       (int32_t *)(ws + w.block_off), (int32_t *)(ws + w.counts),
+                       (int32_t *)(ws + w.kept), expert_counts, aux_loss, (int)w.nb, (int)w.E,
+                       (int)w.C, (int)w.T, alpha);
+    return hipGetLastError();
+}
+
+template <typename XT>
+static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux, const XT *x,
+                                   const float *W_r, char *ws, XT *dx, float *dW_r, float *db_r,
+                                   hipStream_t s) {
+    hipError_t err = hipSuccess;
+    float *dlogits = (float *)(ws + w.dlogits);
+    {
+        ProfScope ps("router_dlogits", s);
+        const float aux_scale =
+            (float)((double)d_aux * (double)alpha * (double)w.E / ((double)w.T * (double)w.T));
+#define CALL(N)                                                                                  \
+    hipLaunchKernelGGL(router_dlogits_kernel<N>, dim3((unsigned)ceil_div(w.T, 4)), dim3(256), 0, \
+                       s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),          \
+                       (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts), dlogits, \
+                       (int)w.T, (int)w.E, aux_scale)
+        SW_DISPATCH_EPL(w.E, CALL);
+#undef CALL
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    {
+        ProfScope ps("router_dx", s);
+        dim3 grid((unsigned)ceil_div(w.T, kLogTB), (unsigned)ceil_div(w.d, kLogEB));
+        hipLaunchKernelGGL(router_dx_kernel<XT>, grid, dim3(256), 0, s, dlogits, W_r,
+                           (const XT *)(ws + w.dXd), (const int32_t *)(ws + w.idx),
+                           (const int32_t *)(ws + w.pos), (const uint8_t *)(ws + w.dropped), dx,
+                           (int)w.T, (int)w.d, (int)w.E, (int)w.C);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    const int tokens_per_split = (int)ceil_div(w.T, w.nsplit);
+    {
+        ProfScope ps("router_dWr", s);
+        dim3 grid((unsigned)ceil_div(w.d, kWrTile), (unsigned)ceil_div(w.E, kWrTile),
+                  (unsigned)w.nsplit);
+        hipLaunchKernelGGL(router_dWr_kernel<XT>, grid, dim3(256), 0, s, x, dlogits,
+                           (float *)(ws + w.dWr_part), (int)w.T, (int)w.d, (int)w.E,
+                           tokens_per_split);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+        const size_t n = (size_t)w.d * w.E;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0,
+                           s, (const float *)(ws + w.dWr_part), dW_r, n, (int)w.nsplit);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    if (db_r) {
+        ProfScope ps("router_dbr", s);
+        hipLaunchKernelGGL(router_dbr_kernel, dim3((unsigned)w.nsplit), dim3(256), 0, s, dlogits,
+                           (float *)(ws + w.dbr_part), (int)w.T, (int)w.E, tokens_per_split);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(w.E, 256)), dim3(256),
+                           0, s, (const float *)(ws + w.dbr_part), db_r, (size_t)w.E,
+                           (int)w.nsplit);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    return err;
+}
+
+hipError_t launch_router_bwd(const Workspace &w, int dtype, float alpha, float d_aux,
+                             const void *x, const float *W_r, char *ws, void *dx, float *dW_r,
+                             float *db_r, hipStream_t s) {
+    if (dtype == SW_BF16)
+        return router_bwd_typed<bf16>(w, alpha, d_aux, (const bf16 *)x, W_r, ws, (bf16 *)dx, dW_r,
+                                      db_r, s);
+    return router_bwd_typed<float>(w, alpha, d_aux, (const float *)x, W_r, ws, (float *)dx, dW_r,
+                                   db_r, s);
+}
+
+}  // namespace sw

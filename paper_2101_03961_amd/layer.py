@@ -1,0 +1,70 @@
+"""Buffer-owning convenience wrapper around the C ABI.
+
+`SwitchLayer` allocates the output tensors and the workspace with torch (device
+memory and streams are all torch is used for) and forwards every call to
+`switch_forward` / `switch_backward`.  It performs no arithmetic.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import torch
+
+from . import binding as B
+
+
+class SwitchLayer:
+    def __init__(self, T: int, d_model: int, d_ff: int, E: int, capacity_factor: float,
+                 alpha: float = 0.01, dtype: str = "bf16", device: str = "cuda:0",
+                 want_logits: bool = False):
+        if not torch.cuda.is_available():
+            raise RuntimeError("SwitchLayer needs a GPU: the layer runs only in the HIP library")
+        self.cfg = B.SwitchConfig(T, d_model, d_ff, E, float(capacity_factor), float(alpha),
+                                  B.SW_BF16 if dtype == "bf16" else B.SW_F32)
+        self.device = torch.device(device)
+        self.act = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.capacity = B.switch_capacity(self.cfg)
+        self.workspace_bytes = B.switch_workspace_size(self.cfg)
+        dev = self.device
+        # torch's caching allocator hands out 512-byte aligned blocks
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        self.y = torch.empty((T, d_model), dtype=self.act, device=dev)
+        self.expert_index = torch.empty(T, dtype=torch.int32, device=dev)
+        self.gate = torch.empty(T, dtype=torch.float32, device=dev)
+        self.position_in_expert = torch.empty(T, dtype=torch.int32, device=dev)
+        self.dropped = torch.empty(T, dtype=torch.uint8, device=dev)
+        self.expert_counts = torch.empty(E, dtype=torch.int32, device=dev)
+        self.aux_loss = torch.empty(1, dtype=torch.float32, device=dev)
+        self.router_logits = (torch.empty((T, E), dtype=torch.float32, device=dev)
+                              if want_logits else None)
+        self.dx = self.dW_r = self.db_r = self.dW_in = self.dW_out = None
+
+    def _stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def forward(self, x, W_r, W_in, W_out, b_r=None) -> Dict[str, torch.Tensor]:
+        B.switch_forward(self.cfg, x, W_r, b_r, W_in, W_out, self.y, self.expert_index, self.gate,
+                         self.position_in_expert, self.dropped, self.expert_counts, self.aux_loss,
+                         self.router_logits, self.workspace, self.workspace_bytes, self._stream())
+        return dict(y=self.y, expert_index=self.expert_index, gate=self.gate,
+                    position_in_expert=self.position_in_expert, dropped=self.dropped,
+                    expert_counts=self.expert_counts, aux_loss=self.aux_loss,
+                    router_logits=self.router_logits)
+
+    def alloc_grads(self, with_bias: bool = True) -> None:
+        c, dev = self.cfg, self.device
+        self.dx = torch.empty((c.T, c.d_model), dtype=self.act, device=dev)
+        self.dW_r = torch.empty((c.d_model, c.E), dtype=torch.float32, device=dev)
+        self.db_r = torch.empty(c.E, dtype=torch.float32, device=dev) if with_bias else None
+        self.dW_in = torch.empty((c.E, c.d_model, c.d_ff), dtype=self.act, device=dev)
+        self.dW_out = torch.empty((c.E, c.d_ff, c.d_model), dtype=self.act, device=dev)
+
+    def backward(self, dy, x, W_r, W_in, W_out, b_r=None, d_aux: float = 1.0
+                 ) -> Dict[str, Optional[torch.Tensor]]:
+        if self.dx is None:
+            self.alloc_grads()
+        B.switch_backward(self.cfg, dy, d_aux, x, W_r, b_r, W_in, W_out, self.dx, self.dW_r,
+                          self.db_r, self.dW_in, self.dW_out, self.workspace, self.workspace_bytes,
+                          self._stream())
+        return dict(dx=self.dx, dW_r=self.dW_r, db_r=self.db_r, dW_in=self.dW_in,
+                    dW_out=self.dW_out)

@@ -1,0 +1,223 @@
+"""Helpers for the GPU parity tests (not collected by pytest).
+
+Comparison protocol
+  routing stage   The oracle is fed the GPU's own fp32 logits: expert_index,
+                  position_in_expert, dropped and expert_counts must then be
+                  bit-identical (the arg max is decided on fp32 logits on both
+                  sides), gate and aux loss agree to fp32 accuracy.
+  end to end      The oracle computes its own fp64 logits.  Logits must agree to
+                  fp32 accumulation accuracy, and every token whose arg max
+                  differs must have an fp64 top-2 logit gap below 1e-5.
+  dense tensors   y and all gradients are compared with the oracle run on its own
+                  fp64 logits but with the routing decision pinned to the GPU's
+                  expert_index, so that one legitimately flipped near-tie does not
+                  shift every later position.
+Error metric for dense tensors.  Every tensor is cut into blocks whose elements
+share one error scale: a token's output vector (rows of y and dx), one expert's
+weight-gradient matrix (dW_in[e], dW_out[e]: a sum over that expert's tokens),
+the whole of dW_r and db_r (sums over all tokens):
+    block error = ||gpu_blk - ref_blk||_2 / ||ref_blk||_2         (acceptance)
+    elem error  = |gpu - ref| / max(|ref|, RMS of its row, RMS of its column in the block)
+                                                                  (sanity bound)
+Acceptance: max block error <= 1e-5 on the all-fp32 path, <= 2e-2 on the bf16 path
+(bf16 storage of A, O and of every output, fp32 accumulation).  This is the
+"error normalised by the output RMS" read per output block.  It has to be read
+that way: one bf16 rounding alone is up to 2^-8 = 0.4 % of an element, so an
+element of 5 RMS is off by 2e-2 RMS even when correctly rounded, and three
+roundings in sequence (A, O, y) put the largest of millions of elements at about
+2 % of its row's RMS by statistics alone; the block-wise L2 error of correct
+arithmetic stays near 0.4 %, while any wrong or missing term (one bad element in
+a 768-wide row is 3.6 %) exceeds the bound.  The element-wise sanity bound is
+1e-5 (fp32) / 5e-2 (bf16) and is what catches a single bad element in a large
+block.  A reference block that is exactly zero must be matched exactly.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2101_03961_amd.layer import SwitchLayer
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}          # max block-wise relative L2 error
+ELEM_TOL = {"f32": 1e-5, "bf16": 5e-2}     # max element error, floor = row / column RMS
+LOGIT_ATOL = 2e-5      # fp32 accumulation of d_model products against fp64
+GAP_RULE = 1e-5        # arg max may differ only below this fp64 top-2 logit gap
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    if t.dtype in (torch.bfloat16, torch.float16):
+        t = t.float()
+    return t.detach().cpu().numpy()
+
+
+def np_inputs(inp):
+    return {k: (None if v is None else to_np(v)) for k, v in inp.items()}
+
+
+# trailing dimensions that form one error block, per tensor
+BLOCK_DIMS = {"y": 1, "dx": 1, "dW_in": 2, "dW_out": 2, "dW_r": 2, "db_r": 1}
+
+
+def row_errors(a: np.ndarray, ref: np.ndarray, block_dims: int = 1):
+    """(max block-wise relative L2 error, max element error) -- see module docstring."""
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert a.shape == ref.shape, (a.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0, 0.0
+    cols = ref.shape[-1] if ref.ndim else 1
+    rows = ref.shape[-2] if (block_dims == 2 and ref.ndim >= 2) else 1
+    a3, r3 = a.reshape(-1, rows, cols), ref.reshape(-1, rows, cols)
+    diff = a3 - r3
+    blk_rms = np.sqrt(np.mean(r3 * r3, axis=(1, 2)))
+    zero = blk_rms == 0.0
+    if zero.any():
+        if np.any(diff[zero] != 0.0):
+            return float("inf"), float("inf")
+        if zero.all():
+            return 0.0, 0.0
+        diff, r3, blk_rms = diff[~zero], r3[~zero], blk_rms[~zero]
+    blk = np.sqrt(np.mean(diff * diff, axis=(1, 2))) / blk_rms
+    # element floor: the element itself, or the RMS of its row / its column inside
+    # the block (a weight-gradient element's error scales with the norms of the
+    # activation column and the gradient column that meet in it)
+    floor = np.maximum(np.abs(r3), np.sqrt(np.mean(r3 * r3, axis=2, keepdims=True)))
+    if rows > 1:
+        floor = np.maximum(floor, np.sqrt(np.mean(r3 * r3, axis=1, keepdims=True)))
+    floor = np.where(floor == 0.0, blk_rms[:, None, None], floor)
+    elem = np.abs(diff) / floor
+    return float(blk.max()), float(elem.max())
+
+
+def assert_close(name, a, ref, dtype):
+    assert np.all(np.isfinite(np.asarray(a, dtype=np.float64))), name + " has non-finite values"
+    row, elem = row_errors(a, ref, BLOCK_DIMS[name.split("[")[0]])
+    assert row <= TOL[dtype], "%s: max block error %.3e > %.1e" % (name, row, TOL[dtype])
+    assert elem <= ELEM_TOL[dtype], "%s: max element error %.3e > %.1e" % (name, elem, ELEM_TOL[dtype])
+    return row
+
+
+def run_gpu(shape, inp, d_aux=1.0, backward=True, dy=None):
+    """One forward (+ backward) through the C ABI; returns (layer, numpy dict)."""
+    layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
+                        shape.alpha, shape.dtype, device=str(inp["x"].device), want_logits=True)
+    out = layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"])
+    res = {k: to_np(v) for k, v in out.items() if v is not None}
+    if backward:
+        g = layer.backward(inp["dy"] if dy is None else dy, inp["x"], inp["W_r"], inp["W_in"],
+                           inp["W_out"], inp["b_r"], d_aux)
+        res.update({k: to_np(v) for k, v in g.items() if v is not None})
+    torch.cuda.synchronize()
+    return layer, res
+
+
+def check_routing(shape, npi, gpu):
+    """Routing-stage and end-to-end checks; returns the oracle forward (no FFN)
+    on fp64 logits with routing pinned to the GPU's expert_index."""
+    T, E = shape.T, shape.E
+    # (i) routing stage on identical logits: bit exact
+    same = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], shape.capacity_factor,
+                          shape.alpha, b_r=npi["b_r"], logits_override=gpu["router_logits"],
+                          skip_ffn=True)
+    assert np.array_equal(gpu["expert_index"], same["expert_index"]), "expert_index"
+    assert np.array_equal(gpu["position_in_expert"], same["position_in_expert"]), "position"
+    assert np.array_equal(gpu["dropped"], same["dropped"]), "dropped"
+    assert np.array_equal(gpu["expert_counts"].astype(np.int64), same["expert_counts"]), "counts"
+    assert int(gpu["expert_counts"].sum()) == T
+    np.testing.assert_allclose(gpu["gate"], same["gate"], rtol=1e-5, atol=0)
+    assert abs(float(gpu["aux_loss"][0]) - same["aux_loss"]) <= 1e-5 * abs(same["aux_loss"])
+    # (ii) end to end against fp64 logits
+    h64 = oracle.logits(npi["x"], npi["W_r"], npi["b_r"])
+    assert np.max(np.abs(gpu["router_logits"] - h64)) <= LOGIT_ATOL * max(1.0, np.abs(h64).max())
+    e64 = h64.argmax(axis=1)
+    flipped = np.nonzero(e64 != gpu["expert_index"])[0]
+    if flipped.size:
+        srt = np.sort(h64[flipped], axis=1)
+        gap = srt[:, -1] - srt[:, -2]
+        assert np.all(gap < GAP_RULE), "arg max differs at a gap of %.3e" % gap.max()
+    pinned = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"],
+                            shape.capacity_factor, shape.alpha, b_r=npi["b_r"],
+                            logits_override=h64, expert_index_override=gpu["expert_index"],
+                            skip_ffn=True)
+    assert np.array_equal(gpu["dropped"], pinned["dropped"])
+    np.testing.assert_allclose(gpu["gate"], pinned["gate"], rtol=3e-5, atol=0)
+    assert abs(float(gpu["aux_loss"][0]) - pinned["aux_loss"]) <= 1e-5 * abs(pinned["aux_loss"])
+    return pinned, int(flipped.size)
+
+
+def check_dropped_rows_are_zero(gpu, dtype):
+    drop = gpu["dropped"].astype(bool)
+    rows = gpu["y"][drop]
+    assert np.all(rows == 0.0) and not np.any(np.signbit(rows)), "dropped rows must be +0"
+
+
+def compare_full(shape, inp, d_aux=1.0):
+    """Whole-tensor parity of forward and backward; returns a dict of errors."""
+    tol = shape.dtype
+    npi = np_inputs(inp)
+    _, gpu = run_gpu(shape, inp, d_aux)
+    fwd, flips = check_routing(shape, npi, gpu)
+    fwd["y"] = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
+                                 fwd["dropped"], fwd["gate"])
+    errs = {"flips": flips}
+    errs["y"] = assert_close("y", gpu["y"], fwd["y"], tol)
+    check_dropped_rows_are_zero(gpu, shape.dtype)
+    bwd = oracle.backward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], npi["dy"], fwd,
+                          shape.alpha, d_aux)
+    for k in ("dx", "dW_r", "db_r", "dW_in", "dW_out"):
+        errs[k] = assert_close(k, gpu[k], bwd[k], tol)
+    return errs, gpu, fwd, bwd
+
+
+def compare_sampled(shape, inp, n_experts=3, n_tokens=32, d_aux=1.0, seed=0):
+    """Parity at sizes where the full fp64 oracle is too slow: routing on all
+    tokens, the expert FFN forward/backward on a few whole experts (always the
+    fullest and the emptiest non-empty one) plus a few single tokens; router
+    weight gradients with dy zeroed outside those tokens."""
+    tol = shape.dtype
+    npi = np_inputs(inp)
+    layer, gpu = run_gpu(shape, inp, d_aux)
+    fwd, flips = check_routing(shape, npi, gpu)
+    counts = fwd["expert_counts"]
+    rng = np.random.default_rng(seed)
+    nonempty = np.nonzero(counts > 0)[0]
+    order = nonempty[np.argsort(counts[nonempty], kind="stable")]
+    sel = {int(order[-1]), int(order[0])}
+    while len(sel) < min(n_experts, len(nonempty)):
+        sel.add(int(rng.choice(nonempty)))
+    sel = sorted(sel)
+    toks = rng.choice(shape.T, size=min(n_tokens, shape.T), replace=False)
+    drop_idx = np.nonzero(fwd["dropped"])[0]
+    if drop_idx.size:
+        toks = np.concatenate([toks, drop_idx[:4]])
+    tmask = np.isin(fwd["expert_index"], sel)
+    tmask[toks] = True
+
+    y_ref = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
+                              fwd["dropped"], fwd["gate"], expert_sel=sel, token_sel=toks)
+    errs = {"flips": flips, "experts": sel, "tokens_checked": int(tmask.sum())}
+    errs["y"] = assert_close("y[sampled]", gpu["y"][tmask], y_ref[tmask], tol)
+    check_dropped_rows_are_zero(gpu, shape.dtype)
+
+    bwd = oracle.backward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], npi["dy"], fwd,
+                          shape.alpha, d_aux, expert_sel=sel, token_sel=toks)
+    errs["dx"] = assert_close("dx[sampled]", gpu["dx"][tmask], bwd["dx"][tmask], tol)
+    errs["dW_in"] = assert_close("dW_in[sel]", gpu["dW_in"][sel], bwd["dW_in"], tol)
+    errs["dW_out"] = assert_close("dW_out[sel]", gpu["dW_out"][sel], bwd["dW_out"], tol)
+    empty = np.nonzero(counts == 0)[0]
+    if empty.size:
+        assert np.all(gpu["dW_in"][empty] == 0) and np.all(gpu["dW_out"][empty] == 0)
+
+    # router weight gradients: zero dy outside the evaluated tokens, so that the
+    # oracle's partial evaluation is exact, and run the GPU backward again
+    dy_masked = inp["dy"] * torch.from_numpy(tmask).to(inp["dy"].device)[:, None].to(inp["dy"].dtype)
+    g2 = layer.backward(dy_masked, inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"], d_aux)
+    torch.cuda.synchronize()
+    bwd2 = oracle.backward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], to_np(dy_masked), fwd,
+                           shape.alpha, d_aux, expert_sel=sel, token_sel=toks)
+    errs["dW_r"] = assert_close("dW_r", to_np(g2["dW_r"]), bwd2["dW_r"], tol)
+    errs["db_r"] = assert_close("db_r", to_np(g2["db_r"]), bwd2["db_r"], tol)
+    # tokens outside the mask now get only the router/aux part of dx, which the
+    # oracle does evaluate for every token once their expert part is zero
+    return errs

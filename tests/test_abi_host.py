@@ -1,0 +1,98 @@
+"""Host-side checks of the C ABI: the library loads, exports every declared
+symbol, and refuses bad arguments before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2101_03961_amd as sw
+from paper_2101_03961_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "switchffn.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(switch_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(sw.library_path())
+    names = _declared_functions()
+    assert {"switch_forward", "switch_backward", "switch_capacity", "switch_workspace_size",
+            "switch_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_capacity_and_workspace_host_functions():
+    cases = {(256, 4, 1.25): 80, (65536, 128, 1.0): 512, (65536, 128, 1.25): 640,
+             (16384, 64, 1.25): 320, (32768, 64, 1.0): 512, (10, 3, 1.0): 3, (5, 8, 1.0): 0}
+    for (T, E, cf), C in cases.items():
+        cfg = sw.SwitchConfig(T, 64, 256, E, cf, 0.01, sw.SW_F32)
+        assert sw.switch_capacity(cfg) == C
+        assert sw.switch_workspace_size(cfg) > 0
+    a = sw.switch_workspace_size(sw.SwitchConfig(4096, 64, 256, 8, 1.0, 0.01, sw.SW_BF16))
+    b = sw.switch_workspace_size(sw.SwitchConfig(4096, 64, 256, 8, 2.0, 0.01, sw.SW_BF16))
+    assert b > a
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(T=0), -2), (dict(E=0), -2), (dict(E=5000), -2), (dict(d_model=0), -2),
+    (dict(d_model=12), -2),            # bf16 rows must be whole 16-byte chunks
+    (dict(d_ff=100), -2),
+    (dict(capacity_factor=0.0), -3), (dict(capacity_factor=-1.0), -3),
+    (dict(capacity_factor=float("nan")), -3), (dict(capacity_factor=float("inf")), -3),
+    (dict(alpha=float("nan")), -3), (dict(act_dtype=7), -4),
+])
+def test_bad_config_is_refused(kw, status):
+    base = dict(T=256, d_model=64, d_ff=256, E=4, capacity_factor=1.25, alpha=0.01,
+                act_dtype=sw.SW_BF16)
+    base.update(kw)
+    cfg = sw.SwitchConfig(*[base[k] for k in ("T", "d_model", "d_ff", "E", "capacity_factor",
+                                              "alpha", "act_dtype")])
+    with pytest.raises(sw.SwitchError) as ei:
+        sw.switch_capacity(cfg)
+    assert ei.value.status == status
+    with pytest.raises(sw.SwitchError):
+        sw.switch_workspace_size(cfg)
+    # forward / backward refuse the same configuration before looking at pointers
+    assert sw.switch_forward(cfg, *([None] * 13), None, 0, check=False) == status
+    assert sw.switch_backward(cfg, None, 1.0, *([None] * 10), None, 0, check=False) == status
+
+
+def test_null_misaligned_and_small_workspace_are_refused():
+    cfg = sw.SwitchConfig(256, 64, 256, 4, 1.25, 0.01, sw.SW_F32)
+    need = sw.switch_workspace_size(cfg)
+    ok = 0x1000  # fake, aligned, never dereferenced: checks run before any launch
+    args = [ok] * 13
+    assert sw.switch_forward(cfg, *([None] + args[1:]), ok, need, check=False) == -1   # x NULL
+    assert sw.switch_forward(cfg, *([ok + 4] + args[1:]), ok, need, check=False) == -6  # misaligned
+    args_nl = list(args)
+    args_nl[12] = None                                                                  # logits optional
+    assert sw.switch_forward(cfg, *args_nl, None, need, check=False) == -5              # no workspace
+    assert sw.switch_forward(cfg, *args_nl, ok, need - 1, check=False) == -5            # too small
+    assert sw.switch_forward(cfg, *args_nl, ok + 16, need, check=False) == -5           # misaligned ws
+    bargs = [ok] * 10
+    assert sw.switch_backward(cfg, None, 1.0, *bargs, ok, need, check=False) == -1
+    assert sw.switch_backward(cfg, ok, float("nan"), *bargs, ok, need, check=False) == -3
+    assert sw.switch_backward(cfg, ok, 1.0, *bargs, ok, 16, check=False) == -5
+
+
+def test_status_strings():
+    assert sw.switch_status_string(0) == "ok"
+    seen = {sw.switch_status_string(s) for s in range(-8, 1)}
+    assert len(seen) == 9
+    assert "unknown" in sw.switch_status_string(-99)
+
+
+def test_binding_has_no_fallback_path():
+    """The Python side only marshals arguments: it must not import the oracle
+    or implement the layer itself."""
+    for mod in ("binding.py", "layer.py", "__init__.py"):
+        src = open(os.path.join(os.path.dirname(binding.__file__), mod)).read()
+        assert "import oracle" not in src and "from oracle" not in src
+        assert "softmax" not in src and "matmul" not in src and "einsum" not in src

@@ -1,0 +1,121 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Protocol and tolerances: tests/parity.py."""
+import numpy as np
+import pytest
+import torch
+
+from synth_inputs import CONFIGS, SwitchShape, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return "cuda:0"
+
+
+def _report(name, errs):
+    print("\n[parity] %s: %s" % (name, {k: (("%.2e" % v) if isinstance(v, float) else v)
+                                        for k, v in errs.items()}), flush=True)
+
+
+# ----------------------------------------------------------------- fp32 path
+def test_tiny_fp32_full_parity():
+    from parity import compare_full
+    s = CONFIGS["tiny"]
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=1.0)
+    _report("tiny", errs)
+    assert fwd["capacity"] == 80
+
+
+@pytest.mark.parametrize("T,d,f,E,cf,bias", [
+    (300, 20, 36, 3, 0.7, True),      # ragged everything, drops, router bias
+    (1000, 64, 128, 8, 1.0, False),   # several token blocks
+    (64, 32, 64, 1, 1.0, False),      # single expert: dense FFN, gate 1
+    (257, 16, 32, 5, 4.0, False),     # no drops
+])
+def test_fp32_shapes_full_parity(T, d, f, E, cf, bias):
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype="f32", zipf_bias=bias, seed_index=31)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.7)
+    _report("fp32 %s" % ((T, d, f, E, cf, bias),), errs)
+    if E == 1:
+        assert np.all(gpu["gate"] == 1.0)
+        assert np.abs(gpu["dW_r"]).max() == 0.0
+
+
+# ----------------------------------------------------------------- bf16 path
+@pytest.mark.parametrize("T,d,f,E,cf,bias", [
+    (2000, 264, 520, 5, 1.5, False),   # 3 ragged token tiles, K tail (264 = 4*64 + 8), ragged p tiles
+    (4096, 128, 256, 16, 1.0, True),   # Zipf bias: overflow and empty experts
+    (1024, 64, 64, 1, 1.0, False),     # single expert, 4 full token tiles
+    (777, 72, 136, 7, 0.5, False),     # heavy dropping, odd sizes
+    (3000, 512, 768, 4, 1.25, False),  # several k steps and 3 x 2 p tiles
+])
+def test_bf16_shapes_full_parity(T, d, f, E, cf, bias):
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype="bf16", zipf_bias=bias, seed_index=41)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=1.0)
+    _report("bf16 %s" % ((T, d, f, E, cf, bias),), errs)
+    if bias:
+        assert fwd["dropped"].sum() > 0 and (fwd["expert_counts"] == 0).any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_capacity_zero_everything_dropped(dtype):
+    from parity import compare_full
+    s = SwitchShape("t", 5, 64, 64, 8, 1.0, dtype=dtype, seed_index=51)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, bwd = compare_full(s, inp)
+    assert fwd["capacity"] == 0 and gpu["dropped"].all()
+    assert np.all(gpu["y"] == 0) and np.all(gpu["dW_in"] == 0) and np.all(gpu["dW_out"] == 0)
+    assert np.abs(gpu["dx"]).max() > 0          # the auxiliary loss still reaches x
+
+
+def test_exact_ties_go_to_expert_zero():
+    from parity import run_gpu
+    s = SwitchShape("t", 300, 64, 64, 6, 1.0, dtype="bf16", seed_index=52)
+    inp = make_inputs(s, _dev())
+    inp["W_r"].zero_()
+    _, gpu = run_gpu(s, inp, backward=False)
+    assert np.all(gpu["expert_index"] == 0)
+    assert np.all(gpu["gate"] == np.float32(1.0) / np.float32(6.0))
+    assert gpu["expert_counts"].tolist() == [300, 0, 0, 0, 0, 0]
+    assert np.array_equal(gpu["position_in_expert"], np.arange(300))
+    assert np.array_equal(gpu["dropped"], (np.arange(300) >= 50).astype(np.uint8))
+    assert abs(float(gpu["aux_loss"][0]) - 0.01) < 1e-7      # P uniform => loss = alpha
+
+
+def test_run_to_run_determinism():
+    from parity import run_gpu
+    s = SwitchShape("t", 5000, 256, 512, 12, 1.0, dtype="bf16", seed_index=53)
+    inp = make_inputs(s, _dev())
+    _, a = run_gpu(s, inp)
+    _, b = run_gpu(s, inp)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+# ------------------------------------------- full sizes, sampled against oracle
+@pytest.mark.parametrize("name,n_experts", [
+    ("base_cf1.0", 3), ("base_cf1.25", 2), ("base_zipf", 3), ("large", 2), ("c_share", 2),
+])
+def test_full_size_sampled_parity(name, n_experts):
+    from parity import compare_sampled
+    s = CONFIGS[name]
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=n_experts, n_tokens=24)
+    _report(name, errs)
+
+
+def test_xxl_sampled_parity():
+    """Largest shape: one whole (emptiest) expert for the weight gradients plus
+    single tokens; the fp64 oracle needs about 0.5 GFLOP per token here."""
+    from parity import compare_sampled
+    s = CONFIGS["xxl"]
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=2, n_tokens=16)
+    _report("xxl", errs)
