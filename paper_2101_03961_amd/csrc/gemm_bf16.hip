@@ -1,23 +1,43 @@
 // Grouped expert GEMMs on bf16 MFMA (gfx950), fp32 accumulation.
 //
-// For every expert e the kernel computes a tile of
+// For every expert e the kernel computes tiles of
 //     C_e[q][p] = sum_k Q_e(q,k) * P_e(p,k)          (C row-major, p contiguous)
-// with a 256 (p) x 256 (q) x 64 (k) block tile, four wavefronts in a 2 x 2
-// arrangement, each owning a 128 x 128 sub-tile as 4 x 4 MFMA 32x32x16 tiles
-// (256 fp32 accumulators per lane).  Both operand tiles are staged in LDS as
-// [row][64 k] with k contiguous, which is what the MFMA operand registers want
-// (8 consecutive k per lane); an operand whose memory layout is k-major
-// ([k][row], row contiguous -- the weights in the forward pass, both operands
-// of the weight-gradient GEMMs) is transposed in registers, 8x8 elements per
-// lane, between the global load and the LDS store.  P feeds the MFMA "A" side,
-// so each lane ends up with four consecutive p of one q and stores 8 bytes.
+// with a 256 (p) x 256 (q) block tile, four wavefronts in a 2 x 2 arrangement,
+// each owning a 128 x 128 sub-tile as 4 x 4 MFMA 32x32x16 tiles (256 fp32
+// accumulators per lane).  P feeds the MFMA "A" side, Q the "B" side.
 //
-// LDS is double buffered (2 x 64 KB): one barrier per k step, global loads for
-// step i+1 are in flight while step i is multiplied.
+// Data path.  Operand tiles go from HBM/L2 straight into LDS with
+// buffer_load_dwordx4 ... lds (no registers, no ds_write: LDS stores issued by
+// the waves cost ~30 cycles of issue each and were the bottleneck of an earlier
+// register-staged version).  k advances 32 at a time through a ring of four LDS
+// stages (4 x 32 KB); the loads of step kt+4 are issued while step kt is being
+// multiplied, i.e. three steps (~1.5 us) ahead of their use.
+//   - An operand stored [row][k] (k contiguous) is kept in LDS as [row][32 k];
+//     a lane's MFMA fragment (8 consecutive k of one row) is one ds_read_b128.
+//   - An operand stored [k][row] (row contiguous: the weights in the forward
+//     pass, both operands of the weight-gradient GEMMs) is kept in LDS exactly
+//     as in memory, [32 k][256 rows], and fragments are fetched with the
+//     transposing LDS read ds_read_b64_tr_b16 (two per fragment), which hands
+//     each lane four consecutive k of its own row.
+//   In both layouts the 16-byte chunks of an LDS row are XOR-permuted (the
+//   permutation is applied to the global address each lane fetches, since the
+//   LDS side of a direct load is fixed to lane * 16) so that fragment reads
+//   spread over all banks.
 //
-// Work assignment: one block per (expert, p tile, q tile); q tiles beyond the
-// expert's kept-token count exit at once.  Block ids are spread so that the
-// tiles of one expert land on the same XCD (and its L2) next to each other.
+// Schedule per k step and wave: 32 MFMAs in two sub-steps of 16.  Fragments are
+// double buffered in registers and read one sub-step ahead; the single barrier
+// of the step sits between the two sub-steps, so the MFMA pipe always has the
+// other sub-step's work queued while waves meet.
+//
+// Ragged edges cost no branches: loads are bounded by the buffer descriptor
+// (rows past the expert's kept tokens, k past the reduction length read as
+// zero), and lanes whose chunk is invalid in the other dimension use an offset
+// beyond every descriptor.
+//
+// Work assignment: persistent blocks, one per CU, each walking a strided list of
+// (expert, p tile, q tile) tiles of its XCD; q tiles beyond the expert's
+// kept-token count are skipped.  The epilogue turns each wave's sub-tile around
+// through LDS so that C is written in whole 256-byte row segments.
 #include "common.h"
 
 namespace sw {
@@ -25,15 +45,29 @@ namespace sw {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kBP = 256;        // block tile, p rows
-constexpr int kBQ = 256;        // block tile, q rows
-constexpr int kBK = 64;         // k per step
+constexpr int kBP = 256;                          // block tile, p rows
+constexpr int kBQ = 256;                          // block tile, q rows
+constexpr int kBK = 32;                           // k per pipeline step
+constexpr int kStages = 4;                        // LDS ring depth
 constexpr int kGemmThreads = 256;
-constexpr int kTileBytes = kBP * kBK * 2;          // 32 KB per operand tile
-constexpr int kStageBytes = 2 * kTileBytes;        // P + Q
-constexpr int kGemmLds = 2 * kStageBytes;          // double buffered: 128 KB
+constexpr int kOpBytes = kBP * kBK * 2;           // 16 KB per operand per stage
+constexpr int kStageBytes = 2 * kOpBytes;         // P then Q
+constexpr int kGemmLds = kStages * kStageBytes;   // 128 KB
 constexpr int kXcds = 8;
+// Tiles that share an operand tile (the q tiles of one weight tile, the p tiles of
+// one activation tile) run at the same time on the same XCD.  If they also walked
+// k in the same order, up to a dozen CUs would ask their L2 for the same lines at
+// the same moment, and those hits-under-miss queue up behind each other.  Each
+// tile therefore starts its k loop kRotate steps further along than its
+// neighbour (and wraps around): the first block to reach a line fetches it, the
+// others find it in L2 a few steps later.  fp32 sums are taken in a different but
+// fixed order per tile, so results stay deterministic.
+constexpr int kRotate = 3;
 
 struct GemmArgs {
     const bf16 *Q;      // per expert: q_batch elements
@@ -47,184 +81,362 @@ struct GemmArgs {
     int tiles_q, tiles_p, total_tiles;
 };
 
-// 16-byte chunk position inside a [row][64 k] LDS tile, XOR-swizzled so that
-// both the MFMA operand reads (32 consecutive rows, one chunk column) and the
-// transposing stores (rows 8 apart) spread over all banks.
-__device__ __forceinline__ int lds_off(int row, int kc) {
-    return row * (kBK * 2) + (((kc ^ (row + (row >> 3))) & 7) << 4);
+// Offset used by lanes that must read zeros: beyond every descriptor (all
+// descriptors are kept below 2 GB by the host-side shape check).
+constexpr uint32_t kOobOffset = 0x80000000u;
+
+// Raw buffer descriptor: base, stride 0, size in bytes, 32-bit data format.
+__device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes) {
+    const uint64_t a = (uint64_t)base;
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
 }
 
-struct Stage {
-    uint4 v[8];
+// One direct global -> LDS load of 16 bytes per lane: lane l's bytes land at
+// LDS offset lds_base + 16 l.  lds_base and soff are wave-uniform.
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\t"
+                 "s_nop 0\n\t"
+                 "buffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+// ---- operand stored [row][k], k contiguous ---------------------------------------
+// LDS stage layout: [256 rows][32 k] = 64 bytes per row, four 16-byte chunks,
+// chunk c of row r kept at position c ^ dswz(r).  dswz uses row bits 1..3, so
+// that 8 (or 16) consecutive rows reading the same logical chunk touch every
+// bank once whether the LDS cycles 128 or 256 bytes.
+__device__ __forceinline__ int dswz(int row) {
+    return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
+}
+
+struct DirectOperand {
+    i32x4 rsrc;
+    uint32_t voff;       // byte offset of the lane's chunk in the wave's first 16 rows
+    uint32_t row_step;   // bytes of 64 rows
+    int c8;              // first k (within the step) of the lane's chunk
+    int klim;
+    uint32_t frag0;      // LDS byte offset (within an operand stage) of the lane's fragment, sub-step 0
+
+    // wave_rows: first row (0 or 128) of the wave's 128-row half of the tile
+    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim_,
+                                         int lane, int wave, int wave_rows) {
+        rsrc = make_rsrc(base, (uint32_t)rowlim * (uint32_t)ld * 2u);
+        const int r = wave * 16 + (lane >> 2);          // + 64 per load
+        const int c = (lane & 3) ^ dswz(r);
+        c8 = c << 3;
+        voff = ((uint32_t)(row0 + r) * (uint32_t)ld + (uint32_t)c8) * 2u;
+        row_step = 64u * (uint32_t)ld * 2u;
+        klim = klim_;
+        const int fr = wave_rows + (lane & 31);
+        frag0 = (uint32_t)(fr * 64 + (((lane >> 5) ^ dswz(fr)) << 4));
+    }
+    static constexpr int kPieces = 4;   // LDS reads per k sub-step: one per fragment
+    // load i of four: rows 64 i + [16 wave, 16 wave + 16)
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
+        const uint32_t vo = (k0 + c8 < klim) ? voff : kOobOffset;
+        dma16(rsrc, vo, (uint32_t)i * row_step + (uint32_t)k0 * 2u,
+              lds_op + (uint32_t)((i * 64 + wave * 16) * 64));
+    }
+    // piece x = fragment x (rows 32 x ..), k sub-step ks (0/1): chunk 2 ks + lane/32
+    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
+                                               s16x4 (&h)[4][2]) const {
+        const s16x8 v =
+            *(const s16x8 *)(lds_op + ((frag0 ^ (uint32_t)(ks << 5)) + (uint32_t)(x * 32 * 64)));
+        h[x][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+        h[x][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+    }
 };
 
-// Operand stored [row][k], k contiguous: thread loads 8 chunks (row = id/8, kc = id%8).
-__device__ __forceinline__ void load_direct(Stage &st, const bf16 *base, int ld, int row0,
-                                            int rowlim, int k0, int klim, int tid) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int id = i * kGemmThreads + tid;
-        const int row = row0 + (id >> 3);
-        const int k = k0 + ((id & 7) << 3);
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row < rowlim && k < klim) v = *(const uint4 *)(base + (size_t)row * ld + k);
-        st.v[i] = v;
-    }
-}
-__device__ __forceinline__ void store_direct(const Stage &st, char *tile, int tid) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int id = i * kGemmThreads + tid;
-        *(uint4 *)(tile + lds_off(id >> 3, id & 7)) = st.v[i];
-    }
-}
+// ---- operand stored [k][row], row contiguous ---------------------------------------
+// LDS stage layout: [32 k][256 rows] = 512 bytes per k, 32 chunks of 8 rows,
+// chunk c of k-row k kept at position c ^ 2 (k mod 4): the four k-rows one
+// transposing read touches then sit 32 bytes apart.
+struct TransOperand {
+    i32x4 rsrc;
+    uint32_t voff[2];       // lane's byte offset for loads with even / odd index
+    uint32_t k_step;        // bytes of one k row
+    uint32_t frag_base[4];  // LDS byte offset of the lane's share of fragment i (ks = 0, first half)
 
-// Operand stored [k][row], row contiguous: thread loads an 8 (k) x 8 (row) block.
-__device__ __forceinline__ void load_trans(Stage &st, const bf16 *base, int ld, int row0,
-                                           int rowlim, int k0, int klim, int tid) {
-    const int kg = tid >> 5;          // 0..7
-    const int rc = tid & 31;          // 0..31
-    const int row = row0 + (rc << 3);
+    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim,
+                                         int lane, int wave, int wave_rows) {
+        rsrc = make_rsrc(base, (uint32_t)klim * (uint32_t)ld * 2u);
+        k_step = (uint32_t)ld * 2u;
+        const int kk = lane >> 5, pc = lane & 31;       // k-row within the load's pair, LDS chunk
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int k = k0 + (kg << 3) + j;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row < rowlim && k < klim) v = *(const uint4 *)(base + (size_t)k * ld + row);
-        st.v[j] = v;
-    }
-}
-__device__ __forceinline__ void store_trans(const Stage &st, char *tile, int tid) {
-    const int kg = tid >> 5;
-    const int rc = tid & 31;
-    const uint32_t *w = (const uint32_t *)st.v;   // w[j*4 + c2]: row j, elements 2c2, 2c2+1
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        const int c2 = c >> 1;
-        uint32_t o[4];
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const uint32_t lo = w[(2 * m) * 4 + c2];
-            const uint32_t hi = w[(2 * m + 1) * 4 + c2];
-            o[m] = (c & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+        for (int par = 0; par < 2; ++par) {
+            const int kr = wave * 8 + 2 * par + kk;     // k-rows of loads par, par + 2: same k mod 4
+            const int c = pc ^ ((kr & 3) << 1);
+            const int row = row0 + (c << 3);
+            voff[par] = row < rowlim
+                            ? ((uint32_t)(wave * 8 + kk) * (uint32_t)ld + (uint32_t)row) * 2u
+                            : kOobOffset;
         }
-        *(uint4 *)(tile + lds_off((rc << 3) + c, kg)) = make_uint4(o[0], o[1], o[2], o[3]);
+        // transposing read: lanes form groups of 16; group g covers rows 16 (g&1) .. +16 of
+        // the fragment and k 8 (g>>1) .. +8; inside a group lane j supplies the 8 bytes
+        // at k-row j/4, rows 4 (j%4) .. +4, and receives k-rows 0..3 of row j.
+        const int g = lane >> 4, j = lane & 15;
+        const int kq = j >> 2;                          // k mod 4 of the supplied k-row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = wave_rows + i * 32 + (g & 1) * 16 + (j & 3) * 4;
+            const int chunk = (n >> 3) ^ (kq << 1);
+            frag_base[i] = (uint32_t)((((g >> 1) * 8 + kq) * 512) + (chunk << 4) + ((n & 4) << 1));
+        }
     }
-}
+    static constexpr int kPieces = 8;   // LDS reads per k sub-step: two per fragment
+    // load i of four: k-rows 8 wave + 2 i + {0, 1}
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
+        dma16(rsrc, voff[i & 1], (uint32_t)(k0 + 2 * i) * k_step,
+              lds_op + (uint32_t)((wave * 8 + 2 * i) * 512));
+    }
+    // piece x = half (x & 1: k 0..3 / 4..7 of the lane's eight) of fragment x >> 1
+    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
+                                               s16x4 (&h)[4][2]) const {
+        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+        const char *p0 = lds_op + frag_base[x >> 1] + ks * (16 * 512) + (x & 1) * (4 * 512);
+        h[x >> 1][x & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
+    }
+};
+
+template <bool TRANS> struct OperandOf { typedef DirectOperand type; };
+template <> struct OperandOf<true> { typedef TransOperand type; };
 
 enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
+
+// One output tile of one expert.
+struct Tile {
+    int e, p0, q0, qlim, klim;
+    int rot_seed;   // pt + qt: where in k this tile starts (see kRotate)
+};
+
+// Tiles are numbered expert-major, then p tile, then q tile (fastest), and the
+// number line is cut into kXcds equal ranges, one per XCD.  Block b runs on XCD
+// b % kXcds (workgroups are dealt to XCDs round-robin) and walks that XCD's range
+// with the stride of the blocks sharing the XCD, so at any moment the CUs of an
+// XCD work on neighbouring tiles -- the q tiles that share a weight tile, the p
+// tiles that share an activation tile -- and find each other's data in their L2.
+template <bool Q_LIMITED, bool K_LIMITED>
+__device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, int stride,
+                                          Tile &t) {
+    const int tiles_pe = a.tiles_q * a.tiles_p;
+    for (; L < L_end; L += stride) {
+        const int e = L / tiles_pe;
+        const int rem = L - e * tiles_pe;
+        const int pt = rem / a.tiles_q;
+        const int qt = rem - pt * a.tiles_q;
+        const int kept = a.kept[e];
+        t.e = e;
+        t.p0 = pt * kBP;
+        t.q0 = qt * kBQ;
+        t.rot_seed = pt + qt;
+        t.qlim = Q_LIMITED ? (kept < a.Qdim ? kept : a.Qdim) : a.Qdim;
+        t.klim = K_LIMITED ? (kept < a.Kdim ? kept : a.Kdim) : a.Kdim;
+        if (t.q0 < t.qlim) {   // q tiles past the expert's kept tokens have no work
+            L += stride;
+            return true;
+        }
+    }
+    return false;
+}
+
+// wait until at most N of this wave's direct loads are still in flight
+#define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave & 1;
     const int wq = wave >> 1;
+    // LDS address of the ring (the dynamic segment starts the block's allocation)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
 
-    // block id -> tile, keeping one expert's tiles on one XCD
-    const int per_xcd = gridDim.x / kXcds;
-    const int L = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (L >= a.total_tiles) return;
-    const int tiles_pe = a.tiles_q * a.tiles_p;
-    const int e = L / tiles_pe;
-    const int rem = L - e * tiles_pe;
-    const int pt = rem / a.tiles_q;
-    const int qt = rem - pt * a.tiles_q;
-    const int p0 = pt * kBP;
-    const int q0 = qt * kBQ;
+    // persistent block: one per CU, a strided walk over its XCD's tile range
+    const int per_xcd = (a.total_tiles + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds;
+    const int stride = gridDim.x / kXcds;
+    int L = xcd * per_xcd + blockIdx.x / kXcds;
+    const int L_end = min((xcd + 1) * per_xcd, a.total_tiles);
 
-    const int kept = a.kept[e];
-    const int qlim = Q_LIMITED ? (kept < a.Qdim ? kept : a.Qdim) : a.Qdim;
-    const int klim = K_LIMITED ? (kept < a.Kdim ? kept : a.Kdim) : a.Kdim;
-    if (q0 >= qlim) return;
+    Tile t;
+    while (next_tile<Q_LIMITED, K_LIMITED>(a, L, L_end, stride, t)) {
+        typename OperandOf<P_TRANS>::type op;
+        typename OperandOf<Q_TRANS>::type oq;
+        op.init(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave, wp * 128);
+        oq.init(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave, wq * 128);
+        const int nk = (t.klim + kBK - 1) / kBK;
+        const int rot = nk > 0 ? (kRotate * t.rot_seed) % nk : 0;
+        // k offset of pipeline step j: rotated inside the range, past the end beyond it
+        auto k_of = [&](int j) -> int {
+            int r = j + rot;
+            if (r >= nk) r -= nk;
+            return j < nk ? r * kBK : nk * kBK;
+        };
 
-    const bf16 *Q = a.Q + (size_t)e * a.q_batch;
-    const bf16 *P = a.P + (size_t)e * a.p_batch;
-
-    f32x16 acc[4][4];
+        f32x16 acc[4][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const int nk = (klim + kBK - 1) / kBK;
-    Stage sp, sq;
-    if (nk > 0) {
-        if (P_TRANS) load_trans(sp, P, a.ldp, p0, a.Pdim, 0, klim, tid);
-        else load_direct(sp, P, a.ldp, p0, a.Pdim, 0, klim, tid);
-        if (Q_TRANS) load_trans(sq, Q, a.ldq, q0, qlim, 0, klim, tid);
-        else load_direct(sq, Q, a.ldq, q0, qlim, 0, klim, tid);
-    }
-    for (int kt = 0; kt < nk; ++kt) {
-        char *tp = lds + (kt & 1) * kStageBytes;
-        char *tq = tp + kTileBytes;
-        if (P_TRANS) store_trans(sp, tp, tid); else store_direct(sp, tp, tid);
-        if (Q_TRANS) store_trans(sq, tq, tid); else store_direct(sq, tq, tid);
-        __syncthreads();
-        if (kt + 1 < nk) {
-            const int k0 = (kt + 1) * kBK;
-            if (P_TRANS) load_trans(sp, P, a.ldp, p0, a.Pdim, k0, klim, tid);
-            else load_direct(sp, P, a.ldp, p0, a.Pdim, k0, klim, tid);
-            if (Q_TRANS) load_trans(sq, Q, a.ldq, q0, qlim, k0, klim, tid);
-            else load_direct(sq, Q, a.ldq, q0, qlim, k0, klim, tid);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int kc = ks * 2 + (lane >> 5);
-            bf16x8 fa[4], fb[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                fa[i] = *(const bf16x8 *)(tp + lds_off(wp * 128 + i * 32 + (lane & 31), kc));
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                fb[j] = *(const bf16x8 *)(tq + lds_off(wq * 128 + j * 32 + (lane & 31), kc));
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        // fragments: two register sets, each fragment as two 8-byte halves
+        s16x4 fa[2][4][2], fb[2][4][2];
+        constexpr int kNP = OperandOf<P_TRANS>::type::kPieces;
+        constexpr int kNR = kNP + OperandOf<Q_TRANS>::type::kPieces;   // LDS reads per sub-step
+
+// direct loads of k step KT, load G of eight (P: 0..3, Q: 4..7)
+#define SW_ISSUE_ONE(KT, G)                                                           \
+    do {                                                                              \
+        const uint32_t st_ = lds0 + (uint32_t)(((KT) & (kStages - 1)) * kStageBytes); \
+        if ((G) < 4) op.issue_one(st_, k0_, wave, (G));                               \
+        else oq.issue_one(st_ + kOpBytes, k0_, wave, (G)-4);                          \
+    } while (0)
+// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of step KT, sub-step KS into SET
+#define SW_READ_GROUP(SET, KT, KS, G)                                                 \
+    do {                                                                              \
+        const char *st_ = lds + ((KT) & (kStages - 1)) * kStageBytes;                 \
+        _Pragma("unroll") for (int x_ = (G)*kNR / 8; x_ < ((G) + 1) * kNR / 8; ++x_) { \
+            if (x_ < kNP) op.read_piece(st_, x_, KS, fa[SET]);                        \
+            else oq.read_piece(st_ + kOpBytes, x_ - kNP, KS, fb[SET]);                \
+        }                                                                             \
+    } while (0)
+// MFMAs 2 G and 2 G + 1 of the sixteen of a sub-step (fragment pairs in row-major order)
+#define SW_MFMA_PAIR(SET, G)                                                          \
+    _Pragma("unroll") for (int m_ = 2 * (G); m_ < 2 * (G) + 2; ++m_) {                \
+        const int i_ = m_ >> 2, j_ = m_ & 3;                                          \
+        const s16x8 a8_ = __builtin_shufflevector(fa[SET][i_][0], fa[SET][i_][1], 0, 1, 2, 3, 4, 5, 6, 7); \
+        const s16x8 b8_ = __builtin_shufflevector(fb[SET][j_][0], fb[SET][j_][1], 0, 1, 2, 3, 4, 5, 6, 7); \
+        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
+            __builtin_bit_cast(bf16x8, a8_), __builtin_bit_cast(bf16x8, b8_), acc[i_][j_], 0, 0, 0); \
     }
 
-    // epilogue: lane holds, for q = lane%32 of each 32x32 tile, p = 8*(r/4) + 4*(lane/32) + r%4
-    bf16 *Cout = a.Cout + (size_t)e * a.c_batch;
-    const bf16 *mask = EPI == EPI_MASK ? a.mask + (size_t)e * a.c_batch : nullptr;
+        // Prologue: the whole ring is filled (steps past the k range read zeros),
+        // then step 0 is awaited and its first fragments fetched.
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int q = q0 + wq * 128 + j * 32 + (lane & 31);
-        if (q >= qlim) continue;
+        for (int kt = 0; kt < kStages; ++kt) {
+            const int k0_ = k_of(kt);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+            for (int g = 0; g < 8; ++g) SW_ISSUE_ONE(kt, g);
+        }
+        SW_WAIT_VMCNT(24);
+        __syncthreads();
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int p = p0 + wp * 128 + i * 32 + g * 8 + ((lane >> 5) << 2);
-                if (p >= a.Pdim) continue;
-                float v[4];
+        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, 0, 0, g);
+
+        for (int kt = 0; kt < nk; ++kt) {
+            // sub-step 0 of step kt; the fragments of sub-step 1 are fetched between its MFMAs
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = acc[i][j][g * 4 + r];
-                if (EPI == EPI_RELU) {
+            for (int g = 0; g < 8; ++g) {
+                SW_READ_GROUP(1, kt, 1, g);
+                SW_MFMA_PAIR(0, g)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // step kt+1 must have landed (two younger steps may still fly); after
+            // the barrier nobody reads stage kt any more, so step kt+4 goes there
+            SW_WAIT_VMCNT(16);
+            __syncthreads();
+            const int k0_ = k_of(kt + kStages);
+            // sub-step 1 of step kt; between its MFMAs: the loads of step kt+4 and the
+            // first fragments of step kt+1
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
-                }
-                if (EPI == EPI_MASK) {
-                    const bf16x4 m = *(const bf16x4 *)(mask + (size_t)q * a.ldc + p);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = (float)m[r] > 0.f ? v[r] : 0.f;
-                }
-                bf16x4 o;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (bf16)v[r];
-                *(bf16x4 *)(Cout + (size_t)q * a.ldc + p) = o;
+            for (int g = 0; g < 8; ++g) {
+                SW_ISSUE_ONE(kt + kStages, g);
+                SW_READ_GROUP(0, kt + 1, 0, g);
+                SW_MFMA_PAIR(1, g)
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+#undef SW_ISSUE_ONE
+#undef SW_READ_GROUP
+#undef SW_MFMA_PAIR
+
+        // Epilogue.  A lane holds, for q = lane%32 of each 32x32 MFMA tile, the four
+        // consecutive p = 8*(r/4) + 4*(lane/32) + r%4: 8-byte pieces scattered over 32
+        // rows.  Each wave therefore turns its 128 x 128 sub-tile around through its
+        // own 32 KB of LDS ([q][p] bf16, 16-byte chunks XOR-swizzled by row) and
+        // writes whole 256-byte row segments, 16 bytes per lane.
+        SW_WAIT_VMCNT(0);   // the ring's trailing (zero) loads have landed
+        __syncthreads();    // and every wave is done reading the ring
+        char *ep = lds + wave * (128 * 256);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = j * 32 + (lane & 31);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = acc[i][j][g * 4 + r];
+                    if (EPI == EPI_RELU) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+                    }
+                    bf16x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (bf16)v[r];
+                    const int c = i * 4 + g;
+                    *(bf16x4 *)(ep + row * 256 + ((c ^ (row & 15)) << 4) + ((lane >> 5) << 3)) = o;
+                }
+            }
+        }
+        bf16 *Cout = a.Cout + (size_t)t.e * a.c_batch;
+        const bf16 *mask = EPI == EPI_MASK ? a.mask + (size_t)t.e * a.c_batch : nullptr;
+        const int c = lane & 15;
+        const int p = t.p0 + wp * 128 + c * 8;
+#pragma unroll 4
+        for (int it = 0; it < 32; ++it) {
+            const int row = it * 4 + (lane >> 4);
+            const int q = t.q0 + wq * 128 + row;
+            u32x4 val = *(const u32x4 *)(ep + row * 256 + ((c ^ (row & 15)) << 4));
+            if (q < t.qlim && p < a.Pdim) {
+                const size_t off = (size_t)q * a.ldc + p;
+                if (EPI == EPI_MASK) {
+                    // keep an element where the saved activation is > 0 (bf16: sign clear, not zero)
+                    const u32x4 m = *(const u32x4 *)(mask + off);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const uint32_t lo = m[w] & 0xffffu, hi = m[w] >> 16;
+                        const uint32_t keep = ((lo - 1u) < 0x7fffu ? 0xffffu : 0u) |
+                                              ((hi - 1u) < 0x7fffu ? 0xffff0000u : 0u);
+                        val[w] &= keep;
+                    }
+                }
+                *(u32x4 *)(Cout + off) = val;
+            }
+        }
+        __syncthreads();   // the epilogue's LDS reads are done before the ring is refilled
     }
+}
+#undef SW_WAIT_VMCNT
+
+// Number of CUs of the current device, rounded down to a multiple of kXcds.
+static int persistent_blocks() {
+    static int blocks = 0;
+    if (blocks == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus < kXcds)
+            cus = 256;
+        blocks = cus / kXcds * kXcds;
+    }
+    return blocks;
 }
 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED>
-static hipError_t gemm_launch(const GemmArgs &a, int E, hipStream_t s) {
+static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
     auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -233,9 +445,11 @@ static hipError_t gemm_launch(const GemmArgs &a, int E, hipStream_t s) {
         if (err != hipSuccess) return err;
         attr_set = true;
     }
-    const int64_t blocks = ceil_div(a.total_tiles, kXcds) * kXcds;
+    // one block per CU (the 128 KB of LDS and 512 registers per lane allow no more)
+    int blocks = persistent_blocks();
+    const int needed = (int)(ceil_div(a.total_tiles, kXcds) * kXcds);
+    if (needed < blocks) blocks = needed;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kGemmThreads), kGemmLds, s, a);
-    (void)E;
     return hipGetLastError();
 }
 
@@ -264,7 +478,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm1_fwd_relu", s);
-        return gemm_launch<false, true, EPI_RELU, true, false>(a, E, s);
+        return gemm_launch<false, true, EPI_RELU, true, false>(a, s);
     }
     case GEMM_FWD2: {
         a.Q = A; a.q_batch = (size_t)C * f; a.ldq = f;
@@ -273,7 +487,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(C, d, f);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm2_fwd", s);
-        return gemm_launch<false, true, EPI_NONE, true, false>(a, E, s);
+        return gemm_launch<false, true, EPI_NONE, true, false>(a, s);
     }
     case GEMM_DGRAD2: {
         a.Q = dO; a.q_batch = (size_t)C * d; a.ldq = d;
@@ -282,7 +496,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm2_dgrad_relumask", s);
-        return gemm_launch<false, false, EPI_MASK, true, false>(a, E, s);
+        return gemm_launch<false, false, EPI_MASK, true, false>(a, s);
     }
     case GEMM_DGRAD1: {
         a.Q = dH; a.q_batch = (size_t)C * f; a.ldq = f;
@@ -291,7 +505,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(C, d, f);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm1_dgrad", s);
-        return gemm_launch<false, false, EPI_NONE, true, false>(a, E, s);
+        return gemm_launch<false, false, EPI_NONE, true, false>(a, s);
     }
     case GEMM_WGRAD2: {
         a.Q = A; a.q_batch = (size_t)C * f; a.ldq = f;      // [k = slot][q = f]
@@ -299,7 +513,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         a.Cout = (bf16 *)dW_out; a.c_batch = (size_t)f * d; a.ldc = d;
         finish(f, d, C);
         ProfScope ps("gemm2_wgrad", s);
-        return gemm_launch<true, true, EPI_NONE, false, true>(a, E, s);
+        return gemm_launch<true, true, EPI_NONE, false, true>(a, s);
     }
     case GEMM_WGRAD1: {
         a.Q = Xd; a.q_batch = (size_t)C * d; a.ldq = d;     // [k = slot][q = d]
@@ -307,7 +521,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         a.Cout = (bf16 *)dW_in; a.c_batch = (size_t)d * f; a.ldc = f;
         finish(d, f, C);
         ProfScope ps("gemm1_wgrad", s);
-        return gemm_launch<true, true, EPI_NONE, false, true>(a, E, s);
+        return gemm_launch<true, true, EPI_NONE, false, true>(a, s);
     }
     }
     return hipErrorInvalidValue;
