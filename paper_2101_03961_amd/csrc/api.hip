@@ -63,6 +63,8 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.dlogits = take(T * E * 4);
     w.dWr_part = take((size_t)w.nsplit * d * E * 4);
     w.dbr_part = take((size_t)w.nsplit * E * 4);
+    w.dpad = ceil_div(w.d, 32) * 32;
+    w.wsplit = take((size_t)3 * 128 * w.dpad * 2);
     w.total = off;
     return w;
 }
@@ -163,9 +165,13 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
     const int dt = cfg->act_dtype;
     auto gemm = dt == SW_BF16 ? launch_gemm_bf16 : launch_gemm_f32;
 
-    if ((st = status_of(launch_router_fwd(w, dt, x, W_r, b_r, ws, expert_index, gate,
-                                          router_logits, s))))
-        return st;
+    if (router_fwd_mfma_supported(w, dt))
+        st = status_of(launch_router_fwd_mfma(w, x, W_r, b_r, ws, expert_index, gate,
+                                              router_logits, s));
+    else
+        st = status_of(launch_router_fwd(w, dt, x, W_r, b_r, ws, expert_index, gate,
+                                         router_logits, s));
+    if (st) return st;
     if ((st = status_of(launch_route_scan(w, cfg->alpha, ws, expert_counts, aux_loss, s))))
         return st;
     if ((st = status_of(launch_dispatch(w, dt, x, ws, position_in_expert, dropped, s)))) return st;

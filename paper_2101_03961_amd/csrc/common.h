@@ -53,6 +53,8 @@ struct Workspace {
     size_t dlogits;             // f32 [T][E]
     size_t dWr_part;            // f32 [nsplit][d][E]  split-T partial sums of dW_r
     size_t dbr_part;            // f32 [nsplit][E]
+    size_t wsplit;              // bf16 [3][128][dpad]  W_r^T as three bf16 terms (MFMA router)
+    int64_t dpad;               // d rounded up to a multiple of 32
     int64_t nsplit;
     size_t total;
 };
@@ -77,6 +79,11 @@ struct ProfScope {
 hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const float *W_r,
                              const float *b_r, char *ws, int32_t *expert_index, float *gate,
                              float *router_logits, hipStream_t s);
+// The same on bf16 MFMA (bf16 x, E <= 128, E % 4 == 0): see router_mfma.hip.
+bool router_fwd_mfma_supported(const Workspace &w, int dtype);
+hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float *W_r,
+                                  const float *b_r, char *ws, int32_t *expert_index, float *gate,
+                                  float *router_logits, hipStream_t s);
 // Per-expert scan over token blocks, counts, kept, aux loss.
 hipError_t launch_route_scan(const Workspace &w, float alpha, char *ws, int32_t *expert_counts,
                              float *aux_loss, hipStream_t s);

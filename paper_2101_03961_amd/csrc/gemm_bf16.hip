@@ -39,23 +39,16 @@
 // kept-token count are skipped.  The epilogue turns each wave's sub-tile around
 // through LDS so that C is written in whole 256-byte row segments.
 #include "common.h"
+#include "lds_operands.h"
 
 namespace sw {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kBP = 256;                          // block tile, p rows
 constexpr int kBQ = 256;                          // block tile, q rows
 constexpr int kBK = 32;                           // k per pipeline step
 constexpr int kStages = 4;                        // LDS ring depth
 constexpr int kGemmThreads = 256;
-constexpr int kOpBytes = kBP * kBK * 2;           // 16 KB per operand per stage
+static_assert(kOpBytes == kBP * kBK * 2, "operand stage size");
 constexpr int kStageBytes = 2 * kOpBytes;         // P then Q
 constexpr int kGemmLds = kStages * kStageBytes;   // 128 KB
 constexpr int kXcds = 8;
@@ -79,130 +72,6 @@ struct GemmArgs {
     int Qdim, Pdim, Kdim;
     const int32_t *kept;
     int tiles_q, tiles_p, total_tiles;
-};
-
-// Offset used by lanes that must read zeros: beyond every descriptor (all
-// descriptors are kept below 2 GB by the host-side shape check).
-constexpr uint32_t kOobOffset = 0x80000000u;
-
-// Raw buffer descriptor: base, stride 0, size in bytes, 32-bit data format.
-__device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes) {
-    const uint64_t a = (uint64_t)base;
-    i32x4 r;
-    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
-    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(a >> 32) & 0xffffu));
-    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-    r[3] = 0x00020000;
-    return r;
-}
-
-// One direct global -> LDS load of 16 bytes per lane: lane l's bytes land at
-// LDS offset lds_base + 16 l.  lds_base and soff are wave-uniform.
-__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\t"
-                 "s_nop 0\n\t"
-                 "buffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
-}
-
-// ---- operand stored [row][k], k contiguous ---------------------------------------
-// LDS stage layout: [256 rows][32 k] = 64 bytes per row, four 16-byte chunks,
-// chunk c of row r kept at position c ^ dswz(r).  dswz uses row bits 1..3, so
-// that 8 (or 16) consecutive rows reading the same logical chunk touch every
-// bank once whether the LDS cycles 128 or 256 bytes.
-__device__ __forceinline__ int dswz(int row) {
-    return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
-}
-
-struct DirectOperand {
-    i32x4 rsrc;
-    uint32_t voff;       // byte offset of the lane's chunk in the wave's first 16 rows
-    uint32_t row_step;   // bytes of 64 rows
-    int c8;              // first k (within the step) of the lane's chunk
-    int klim;
-    uint32_t frag0;      // LDS byte offset (within an operand stage) of the lane's fragment, sub-step 0
-
-    // wave_rows: first row (0 or 128) of the wave's 128-row half of the tile
-    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim_,
-                                         int lane, int wave, int wave_rows) {
-        rsrc = make_rsrc(base, (uint32_t)rowlim * (uint32_t)ld * 2u);
-        const int r = wave * 16 + (lane >> 2);          // + 64 per load
-        const int c = (lane & 3) ^ dswz(r);
-        c8 = c << 3;
-        voff = ((uint32_t)(row0 + r) * (uint32_t)ld + (uint32_t)c8) * 2u;
-        row_step = 64u * (uint32_t)ld * 2u;
-        klim = klim_;
-        const int fr = wave_rows + (lane & 31);
-        frag0 = (uint32_t)(fr * 64 + (((lane >> 5) ^ dswz(fr)) << 4));
-    }
-    static constexpr int kPieces = 4;   // LDS reads per k sub-step: one per fragment
-    // load i of four: rows 64 i + [16 wave, 16 wave + 16)
-    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
-        const uint32_t vo = (k0 + c8 < klim) ? voff : kOobOffset;
-        dma16(rsrc, vo, (uint32_t)i * row_step + (uint32_t)k0 * 2u,
-              lds_op + (uint32_t)((i * 64 + wave * 16) * 64));
-    }
-    // piece x = fragment x (rows 32 x ..), k sub-step ks (0/1): chunk 2 ks + lane/32
-    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
-                                               s16x4 (&h)[4][2]) const {
-        const s16x8 v =
-            *(const s16x8 *)(lds_op + ((frag0 ^ (uint32_t)(ks << 5)) + (uint32_t)(x * 32 * 64)));
-        h[x][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
-        h[x][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
-    }
-};
-
-// ---- operand stored [k][row], row contiguous ---------------------------------------
-// LDS stage layout: [32 k][256 rows] = 512 bytes per k, 32 chunks of 8 rows,
-// chunk c of k-row k kept at position c ^ 2 (k mod 4): the four k-rows one
-// transposing read touches then sit 32 bytes apart.
-struct TransOperand {
-    i32x4 rsrc;
-    uint32_t voff[2];       // lane's byte offset for loads with even / odd index
-    uint32_t k_step;        // bytes of one k row
-    uint32_t frag_base[4];  // LDS byte offset of the lane's share of fragment i (ks = 0, first half)
-
-    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim,
-                                         int lane, int wave, int wave_rows) {
-        rsrc = make_rsrc(base, (uint32_t)klim * (uint32_t)ld * 2u);
-        k_step = (uint32_t)ld * 2u;
-        const int kk = lane >> 5, pc = lane & 31;       // k-row within the load's pair, LDS chunk
-#pragma unroll
-        for (int par = 0; par < 2; ++par) {
-            const int kr = wave * 8 + 2 * par + kk;     // k-rows of loads par, par + 2: same k mod 4
-            const int c = pc ^ ((kr & 3) << 1);
-            const int row = row0 + (c << 3);
-            voff[par] = row < rowlim
-                            ? ((uint32_t)(wave * 8 + kk) * (uint32_t)ld + (uint32_t)row) * 2u
-                            : kOobOffset;
-        }
-        // transposing read: lanes form groups of 16; group g covers rows 16 (g&1) .. +16 of
-        // the fragment and k 8 (g>>1) .. +8; inside a group lane j supplies the 8 bytes
-        // at k-row j/4, rows 4 (j%4) .. +4, and receives k-rows 0..3 of row j.
-        const int g = lane >> 4, j = lane & 15;
-        const int kq = j >> 2;                          // k mod 4 of the supplied k-row
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int n = wave_rows + i * 32 + (g & 1) * 16 + (j & 3) * 4;
-            const int chunk = (n >> 3) ^ (kq << 1);
-            frag_base[i] = (uint32_t)((((g >> 1) * 8 + kq) * 512) + (chunk << 4) + ((n & 4) << 1));
-        }
-    }
-    static constexpr int kPieces = 8;   // LDS reads per k sub-step: two per fragment
-    // load i of four: k-rows 8 wave + 2 i + {0, 1}
-    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
-        dma16(rsrc, voff[i & 1], (uint32_t)(k0 + 2 * i) * k_step,
-              lds_op + (uint32_t)((wave * 8 + 2 * i) * 512));
-    }
-    // piece x = half (x & 1: k 0..3 / 4..7 of the lane's eight) of fragment x >> 1
-    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
-                                               s16x4 (&h)[4][2]) const {
-        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
-        const char *p0 = lds_op + frag_base[x >> 1] + ks * (16 * 512) + (x & 1) * (4 * 512);
-        h[x >> 1][x & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
-    }
 };
 
 template <bool TRANS> struct OperandOf { typedef DirectOperand type; };

@@ -1,0 +1,255 @@
+// Router forward on the matrix cores, for bf16 tokens and up to 128 experts.
+//
+// The router stays an fp32 computation (Sec. 2.4, selective precision): x is
+// bf16 already, and the fp32 router weights are split into three bf16 terms
+// W_r = hi + mid + lo (8 + 8 + 8 mantissa bits, the split is exact), so every
+// product x * term is exact in fp32 and the bf16 MFMA, which accumulates in
+// fp32, produces the same logits as an fp32 FMA chain up to summation order.
+// That moves the 2 T d E multiply-adds from the fp32 vector ALU (where they
+// cost several times the HBM time of reading x) to the matrix cores.
+//
+// One block owns 256 consecutive tokens and all experts.  A wave owns 64 tokens:
+// MFMA "A" = weights (rows = experts), "B" = tokens, so a lane ends up with 64 of
+// its token's logits in registers and the other 64 in lane ^ 32; softmax, arg
+// max and gate need one cross-lane exchange.  The probabilities then go through
+// LDS to be written as whole rows, and the block's per-expert probability sums,
+// expert histogram and in-block ranks are taken from that tile in a fixed order.
+#include "common.h"
+#include "lds_operands.h"
+
+namespace sw {
+
+constexpr int kRmTokens = 256;
+constexpr int kRmExperts = 128;                        // padded expert count
+constexpr int kRmStages = 3;
+constexpr int kRmXBytes = kOpBytes;                    // 256 tokens x 32 k
+constexpr int kRmWBytes = 3 * kRmExperts * 32 * 2;     // three terms x 128 experts x 32 k
+constexpr int kRmStageBytes = kRmXBytes + kRmWBytes;   // 40 KB
+constexpr int kRmPitch = kRmExperts + 4;               // floats per row of the probability tile
+constexpr int kRmTileBytes = kRmTokens * kRmPitch * 4; // 132 KB
+constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + kRmExperts * 4;
+
+// W_r [d][E] fp32 -> wsplit [3][128][dpad] bf16: term s of expert e, k contiguous;
+// rows of absent experts and columns past d are zero.
+__global__ __launch_bounds__(256) void router_split_kernel(const float *__restrict__ W_r,
+                                                           bf16 *__restrict__ wsplit, int d,
+                                                           int dpad, int E) {
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    const int e = blockIdx.y;
+    if (k >= dpad) return;
+    float w = (k < d && e < E) ? W_r[(size_t)k * E + e] : 0.f;
+    const bf16 hi = (bf16)w;
+    const float r1 = w - (float)hi;
+    const bf16 mid = (bf16)r1;
+    const float r2 = r1 - (float)mid;
+    const bf16 lo = (bf16)r2;
+    const size_t plane = (size_t)kRmExperts * dpad;
+    wsplit[(size_t)e * dpad + k] = hi;
+    wsplit[plane + (size_t)e * dpad + k] = mid;
+    wsplit[2 * plane + (size_t)e * dpad + k] = lo;
+}
+
+#define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
+
+__global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
+    const bf16 *__restrict__ x, const bf16 *__restrict__ wsplit, const float *__restrict__ b_r,
+    float *__restrict__ probs, float *__restrict__ logits_out, int32_t *__restrict__ idx_out,
+    float *__restrict__ gate_out, int32_t *__restrict__ idx_ws, float *__restrict__ gate_ws,
+    int32_t *__restrict__ local_rank, int32_t *__restrict__ block_counts,
+    float *__restrict__ block_psum, int T, int d, int dpad, int E) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    const int b = blockIdx.x;
+    const int t0 = b * kRmTokens;
+
+    DirectOperand ox, ow;
+    ox.init(x, d, t0, T, d, lane, wave, wave * 64);
+    ow.init(wsplit, dpad, 0, 3 * kRmExperts, dpad, lane, wave, 0);
+    const int nk = dpad / 32;
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int et = 0; et < 4; ++et)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tt][et][r] = 0.f;
+
+    auto issue = [&](int kt) {
+        const uint32_t st = lds0 + (uint32_t)((kt % kRmStages) * kRmStageBytes);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ox.issue_one(st, kt * 32, wave, i);
+#pragma unroll
+        for (int i = 0; i < 6; ++i) ow.issue_one(st + kRmXBytes, kt * 32, wave, i);
+    };
+    issue(0);
+    issue(1);
+    issue(2);
+    SW_WAIT_VMCNT(20);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const char *st = lds + (kt % kRmStages) * kRmStageBytes;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 fx[2];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) fx[tt] = ox.read_frag(st, tt, ks);
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+#pragma unroll
+                for (int et = 0; et < 4; ++et) {
+                    const bf16x8 fw = ow.read_frag(st + kRmXBytes, s * 4 + et, ks);
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+                        acc[tt][et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx[tt], acc[tt][et], 0, 0, 0);
+                }
+        }
+        // step kt+1 has landed (step kt+2 may still fly); after the barrier stage kt is free
+        SW_WAIT_VMCNT(10);
+        __syncthreads();
+        issue(kt + kRmStages);
+    }
+    SW_WAIT_VMCNT(0);
+    __syncthreads();
+
+    // ---- softmax, arg max, gate: lane and lane ^ 32 share a token -----------------
+    float *ptile = (float *)lds;                                   // [256][kRmPitch]
+    int32_t *idx_s = (int32_t *)(lds + kRmTileBytes);              // [256]
+    int32_t *hist = idx_s + kRmTokens;                             // [128]
+    if (tid < kRmExperts) hist[tid] = 0;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        const int tl = wave * 64 + tt * 32 + (lane & 31);
+        const int t = t0 + tl;
+        float best = -INFINITY;
+        int besti = 0x7fffffff;
+#pragma unroll
+        for (int et = 0; et < 4; ++et)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int e = et * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);   // ascending
+                float h = -INFINITY;
+                if (e < E) h = acc[tt][et][r] + (b_r ? b_r[e] : 0.f);
+                acc[tt][et][r] = h;
+                if (h > best) { best = h; besti = e; }   // lowest index kept on ties
+            }
+        {
+            const float ov = __shfl_xor(best, 32, kWave);
+            const int oi = __shfl_xor(besti, 32, kWave);
+            if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+        }
+        if (logits_out && t < T) {
+#pragma unroll
+            for (int et = 0; et < 4; ++et)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int e = et * 32 + 8 * g + 4 * (lane >> 5);
+                    if (e < E)   // E is a multiple of 4: whole groups of four are in or out
+                        *(float4 *)(logits_out + (size_t)t * E + e) =
+                            make_float4(acc[tt][et][4 * g], acc[tt][et][4 * g + 1],
+                                        acc[tt][et][4 * g + 2], acc[tt][et][4 * g + 3]);
+                }
+        }
+        float z = 0.f;
+#pragma unroll
+        for (int et = 0; et < 4; ++et)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float ex = expf(acc[tt][et][r] - best);   // exp(-inf) = 0 for absent experts
+                acc[tt][et][r] = ex;
+                z += ex;
+            }
+        z += __shfl_xor(z, 32, kWave);
+#pragma unroll
+        for (int et = 0; et < 4; ++et)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int e = et * 32 + 8 * g + 4 * (lane >> 5);
+                *(float4 *)(ptile + tl * kRmPitch + e) =
+                    make_float4(acc[tt][et][4 * g] / z, acc[tt][et][4 * g + 1] / z,
+                                acc[tt][et][4 * g + 2] / z, acc[tt][et][4 * g + 3] / z);
+            }
+        if (lane < 32) {
+            if (t < T) {
+                const float gt = 1.0f / z;   // exp(0) / z: probability of the arg max
+                idx_s[tl] = besti;
+                idx_out[t] = besti;
+                idx_ws[t] = besti;
+                gate_out[t] = gt;
+                gate_ws[t] = gt;
+            } else {
+                idx_s[tl] = -1;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- probabilities out as whole rows; block statistics -------------------------
+    const int nvalid = (T - t0) < kRmTokens ? (T - t0) : kRmTokens;
+    {
+        const int c4 = (tid & 31) * 4;
+        for (int row = tid >> 5; row < nvalid; row += 8)
+            if (c4 < E)
+                *(float4 *)(probs + (size_t)(t0 + row) * E + c4) =
+                    *(const float4 *)(ptile + row * kRmPitch + c4);
+    }
+    {
+        const int me = idx_s[tid];
+        if (me >= 0) {
+            int r = 0;
+            for (int s = 0; s < tid; ++s) r += (idx_s[s] == me);
+            local_rank[t0 + tid] = r;
+            atomicAdd(&hist[me], 1);   // integer: result independent of order
+        }
+    }
+    __syncthreads();
+    if (tid < E) {
+        float s = 0.f;
+        for (int row = 0; row < nvalid; ++row) s += ptile[row * kRmPitch + tid];
+        block_psum[(size_t)b * E + tid] = s;
+        block_counts[(size_t)b * E + tid] = hist[tid];
+    }
+}
+#undef SW_WAIT_VMCNT
+
+bool router_fwd_mfma_supported(const Workspace &w, int dtype) {
+    // x is addressed through one buffer descriptor with 32-bit byte offsets
+    return dtype == SW_BF16 && w.E <= kRmExperts && (w.E % 4) == 0 &&
+           (uint64_t)w.T * (uint64_t)w.d * 2u < 0x7fffffffu;
+}
+
+hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float *W_r,
+                                  const float *b_r, char *ws, int32_t *expert_index, float *gate,
+                                  float *router_logits, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    hipError_t err;
+    {
+        ProfScope ps("router_split_weights", s);
+        dim3 grid((unsigned)ceil_div(w.dpad, 256), kRmExperts);
+        hipLaunchKernelGGL(router_split_kernel, grid, dim3(256), 0, s, W_r, (bf16 *)(ws + w.wsplit),
+                           (int)w.d, (int)w.dpad, (int)w.E);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    {
+        ProfScope ps("router_fwd_mfma", s);
+        hipLaunchKernelGGL(router_fwd_mfma_kernel, dim3((unsigned)w.nb), dim3(256), kRmLds, s,
+                           (const bf16 *)x, (const bf16 *)(ws + w.wsplit), b_r,
+                           (float *)(ws + w.probs), router_logits, expert_index, gate,
+                           (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
+                           (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
+                           (float *)(ws + w.block_psum), (int)w.T, (int)w.d, (int)w.dpad, (int)w.E);
+        err = hipGetLastError();
+    }
+    return err;
+}
+
+}  // namespace sw
