@@ -65,6 +65,11 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.dbr_part = take((size_t)w.nsplit * E * 4);
     w.dpad = ceil_div(w.d, 32) * 32;
     w.wsplit = take((size_t)3 * 128 * w.dpad * 2);
+    w.wsplit_b = take(d * 256 * 2);
+    w.dl_split = take(T * 256 * 2);
+    w.tps_m = ceil_div(ceil_div(w.T, 85), 32) * 32;
+    w.nsplit_m = ceil_div(w.T, w.tps_m);
+    w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
     w.total = off;
     return w;
 }

@@ -55,6 +55,10 @@ struct Workspace {
     size_t dbr_part;            // f32 [nsplit][E]
     size_t wsplit;              // bf16 [3][128][dpad]  W_r^T as three bf16 terms (MFMA router)
     int64_t dpad;               // d rounded up to a multiple of 32
+    size_t wsplit_b;            // bf16 [d][256]   W_r rows as hi | lo halves (MFMA router backward)
+    size_t dl_split;            // bf16 [T][256]   dlogits rows as hi | lo halves
+    size_t dWr_part_m;          // f32 [nsplit_m][d][256]  partial sums of x^T [dl_hi | dl_lo]
+    int64_t tps_m, nsplit_m;    // tokens per split (multiple of 32), number of splits
     int64_t nsplit;
     size_t total;
 };
@@ -96,6 +100,9 @@ hipError_t launch_combine_bwd(const Workspace &w, int dtype, const void *dy, cha
 hipError_t launch_router_bwd(const Workspace &w, int dtype, float alpha, float d_aux,
                              const void *x, const float *W_r, char *ws, void *dx, float *dW_r,
                              float *db_r, hipStream_t s);
+// MFMA pieces of the router backward (bf16, E <= 128), in gemm_bf16.hip
+hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStream_t s);
+hipError_t launch_router_dWr_mfma(const Workspace &w, const void *x, char *ws, hipStream_t s);
 
 // Grouped GEMMs over experts.  Each computes, for every expert e,
 //   C_e[q][p] = sum_k Q_e(q,k) * P_e(p,k)

@@ -50,7 +50,8 @@ constexpr int kStages = 4;                        // LDS ring depth
 constexpr int kGemmThreads = 256;
 static_assert(kOpBytes == kBP * kBK * 2, "operand stage size");
 constexpr int kStageBytes = 2 * kOpBytes;         // P then Q
-constexpr int kGemmLds = kStages * kStageBytes;   // 128 KB
+constexpr int kRingBytes = kStages * kStageBytes;  // 128 KB
+constexpr int kGemmLds = kRingBytes + kBQ * 4;    // + one int per q row (ROUTER_DX: slot of the addend)
 constexpr int kXcds = 8;
 // Tiles that share an operand tile (the q tiles of one weight tile, the p tiles of
 // one activation tile) run at the same time on the same XCD.  If they also walked
@@ -72,7 +73,22 @@ struct GemmArgs {
     int Qdim, Pdim, Kdim;
     const int32_t *kept;
     int tiles_q, tiles_p, total_tiles;
+    // router backward uses of the kernel (see GemmMode)
+    const int32_t *tok_idx, *tok_pos;   // ROUTER_DX: slot of each token's row of the addend
+    const uint8_t *tok_dropped;
+    int cap;
+    float *Cf;                          // ROUTER_DWR: fp32 partial sums [split][q][p]
+    int T_total, tps;                   // ROUTER_DWR: tokens, tokens per split
 };
+
+// What the "experts" and the k dimension of a launch are.
+//   EXPERTS     the grouped expert GEMMs: batch = experts, limits from kept[].
+//   ROUTER_DX   dx = dl W_r^T + gathered dXd: one batch; k runs over three blocks of
+//               128 experts pairing the bf16 halves of dl (hi|lo per row, 256 wide)
+//               with those of W_r^T (hi|lo per row): hi*hi, hi*lo, lo*hi.
+//   ROUTER_DWR  partial sums of x^T [dl_hi | dl_lo] over token ranges: batch = token
+//               range, k = tokens of the range, fp32 output.
+enum GemmMode { MODE_EXPERTS = 0, MODE_ROUTER_DX = 1, MODE_ROUTER_DWR = 2 };
 
 template <bool TRANS> struct OperandOf { typedef DirectOperand type; };
 template <> struct OperandOf<true> { typedef TransOperand type; };
@@ -91,7 +107,7 @@ struct Tile {
 // with the stride of the blocks sharing the XCD, so at any moment the CUs of an
 // XCD work on neighbouring tiles -- the q tiles that share a weight tile, the p
 // tiles that share an activation tile -- and find each other's data in their L2.
-template <bool Q_LIMITED, bool K_LIMITED>
+template <bool Q_LIMITED, bool K_LIMITED, int MODE>
 __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, int stride,
                                           Tile &t) {
     const int tiles_pe = a.tiles_q * a.tiles_p;
@@ -100,7 +116,9 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
         const int rem = L - e * tiles_pe;
         const int pt = rem / a.tiles_q;
         const int qt = rem - pt * a.tiles_q;
-        const int kept = a.kept[e];
+        int kept = 0;
+        if (MODE == MODE_EXPERTS) kept = a.kept[e];
+        if (MODE == MODE_ROUTER_DWR) kept = min(a.tps, a.T_total - e * a.tps);
         t.e = e;
         t.p0 = pt * kBP;
         t.q0 = qt * kBQ;
@@ -118,7 +136,7 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
 // wait until at most N of this wave's direct loads are still in flight
 #define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
 
-template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED>
+template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
@@ -137,18 +155,38 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     const int L_end = min((xcd + 1) * per_xcd, a.total_tiles);
 
     Tile t;
-    while (next_tile<Q_LIMITED, K_LIMITED>(a, L, L_end, stride, t)) {
+    while (next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, t)) {
         typename OperandOf<P_TRANS>::type op;
         typename OperandOf<Q_TRANS>::type oq;
-        op.init(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave, wp * 128);
-        oq.init(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave, wq * 128);
+        // width of the operand rows in k: the reduction length, except for ROUTER_DX
+        // whose 384 k values are read from 256-wide (hi | lo) rows
+        const int kwidth = MODE == MODE_ROUTER_DX ? 256 : t.klim;
+        op.init(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, kwidth, lane, wave, wp * 128);
+        oq.init(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, kwidth, lane, wave, wq * 128);
+        if (MODE == MODE_ROUTER_DX) {
+            // slot of each token row's addend (-1: dropped token, nothing to add); read in
+            // the epilogue, after several barriers
+            int32_t *slot_s = (int32_t *)(lds + kRingBytes);
+            const int q = t.q0 + tid;
+            int slot = -1;
+            if (q < t.qlim && !a.tok_dropped[q]) slot = a.tok_idx[q] * a.cap + a.tok_pos[q];
+            slot_s[tid] = slot;
+        }
         const int nk = (t.klim + kBK - 1) / kBK;
         const int rot = nk > 0 ? (kRotate * t.rot_seed) % nk : 0;
-        // k offset of pipeline step j: rotated inside the range, past the end beyond it
-        auto k_of = [&](int j) -> int {
+        // k offsets (P, Q) of pipeline step j: rotated inside the range, past the end beyond it
+        int k0p_ = 0, k0q_ = 0;
+        auto k_of = [&](int j) {
             int r = j + rot;
             if (r >= nk) r -= nk;
-            return j < nk ? r * kBK : nk * kBK;
+            if (j >= nk) r = nk;
+            if (MODE == MODE_ROUTER_DX) {
+                // steps 0..3: dl_hi x W_hi, 4..7: dl_hi x W_lo, 8..11: dl_lo x W_hi; 12: past the end
+                k0q_ = r < 8 ? 32 * (r & 3) : (r < 12 ? 128 + 32 * (r - 8) : 256);
+                k0p_ = r < 4 ? 32 * r : (r < 8 ? 128 + 32 * (r - 4) : (r < 12 ? 32 * (r - 8) : 256));
+            } else {
+                k0p_ = k0q_ = r * kBK;
+            }
         };
 
         f32x16 acc[4][4];
@@ -168,8 +206,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #define SW_ISSUE_ONE(KT, G)                                                           \
     do {                                                                              \
         const uint32_t st_ = lds0 + (uint32_t)(((KT) & (kStages - 1)) * kStageBytes); \
-        if ((G) < 4) op.issue_one(st_, k0_, wave, (G));                               \
-        else oq.issue_one(st_ + kOpBytes, k0_, wave, (G)-4);                          \
+        if ((G) < 4) op.issue_one(st_, k0p_, wave, (G));                              \
+        else oq.issue_one(st_ + kOpBytes, k0q_, wave, (G)-4);                         \
     } while (0)
 // LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of step KT, sub-step KS into SET
 #define SW_READ_GROUP(SET, KT, KS, G)                                                 \
@@ -194,7 +232,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         // then step 0 is awaited and its first fragments fetched.
 #pragma unroll
         for (int kt = 0; kt < kStages; ++kt) {
-            const int k0_ = k_of(kt);
+            k_of(kt);
 #pragma unroll
             for (int g = 0; g < 8; ++g) SW_ISSUE_ONE(kt, g);
         }
@@ -215,7 +253,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             // the barrier nobody reads stage kt any more, so step kt+4 goes there
             SW_WAIT_VMCNT(16);
             __syncthreads();
-            const int k0_ = k_of(kt + kStages);
+            k_of(kt + kStages);
             // sub-step 1 of step kt; between its MFMAs: the loads of step kt+4 and the
             // first fragments of step kt+1
 #pragma unroll
@@ -237,6 +275,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         // writes whole 256-byte row segments, 16 bytes per lane.
         SW_WAIT_VMCNT(0);   // the ring's trailing (zero) loads have landed
         __syncthreads();    // and every wave is done reading the ring
+        if (MODE == MODE_ROUTER_DWR) {
+            // fp32 partial sums straight from the accumulators: four consecutive p per lane
+            float *Cf = a.Cf + (size_t)t.e * a.c_batch;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int q = t.q0 + wq * 128 + j * 32 + (lane & 31);
+                if (q >= t.qlim) continue;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int p = t.p0 + wp * 128 + i * 32 + g * 8 + ((lane >> 5) << 2);
+                        if (p < a.Pdim)
+                            *(float4 *)(Cf + (size_t)q * a.ldc + p) =
+                                make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1],
+                                            acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                    }
+            }
+            continue;
+        }
         char *ep = lds + wave * (128 * 256);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -264,7 +322,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         const bf16 *mask = EPI == EPI_MASK ? a.mask + (size_t)t.e * a.c_batch : nullptr;
         const int c = lane & 15;
         const int p = t.p0 + wp * 128 + c * 8;
-#pragma unroll 4
+#pragma unroll 8
         for (int it = 0; it < 32; ++it) {
             const int row = it * 4 + (lane >> 4);
             const int q = t.q0 + wq * 128 + row;
@@ -281,6 +339,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                                               ((hi - 1u) < 0x7fffu ? 0xffff0000u : 0u);
                         val[w] &= keep;
                     }
+                }
+                const int slot = MODE == MODE_ROUTER_DX
+                                     ? ((const int32_t *)(lds + kRingBytes))[wq * 128 + row] : -1;
+                if (MODE == MODE_ROUTER_DX && slot >= 0) {
+                    // add the token's row of the expert-side gradient (fp32 add, one rounding)
+                    const u32x4 gsrc = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
+                    const bf16x8 va = __builtin_bit_cast(bf16x8, val);
+                    const bf16x8 vb = __builtin_bit_cast(bf16x8, gsrc);
+                    bf16x8 vo;
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
+                    val = __builtin_bit_cast(u32x4, vo);
                 }
                 *(u32x4 *)(Cout + off) = val;
             }
@@ -304,9 +374,10 @@ static int persistent_blocks() {
     return blocks;
 }
 
-template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED>
+template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED,
+          int MODE = MODE_EXPERTS>
 static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
-    auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED>;
+    auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED, MODE>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute((const void *)kern,
@@ -394,6 +465,41 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     }
     }
     return hipErrorInvalidValue;
+}
+
+// dx = dl W_r^T + (kept) dXd[slot]: dl as bf16 hi|lo rows [T][256], W_r^T as bf16 hi|lo rows
+// [d][256]; see GemmMode.
+hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStream_t s) {
+    GemmArgs a{};
+    a.Q = (const bf16 *)(ws + w.dl_split); a.q_batch = 0; a.ldq = 256;
+    a.P = (const bf16 *)(ws + w.wsplit_b); a.p_batch = 0; a.ldp = 256;
+    a.Cout = (bf16 *)dx; a.c_batch = 0; a.ldc = (int)w.d;
+    a.mask = (const bf16 *)(ws + w.dXd);
+    a.tok_idx = (const int32_t *)(ws + w.idx);
+    a.tok_pos = (const int32_t *)(ws + w.pos);
+    a.tok_dropped = (const uint8_t *)(ws + w.dropped);
+    a.cap = (int)w.C;
+    a.Qdim = (int)w.T; a.Pdim = (int)w.d; a.Kdim = 384;
+    a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
+    a.tiles_p = (int)ceil_div(a.Pdim, kBP);
+    a.total_tiles = a.tiles_q * a.tiles_p;
+    ProfScope ps("router_dx_mfma", s);
+    return gemm_launch<false, false, EPI_NONE, false, false, MODE_ROUTER_DX>(a, s);
+}
+
+// Partial sums over token ranges of x^T [dl_hi | dl_lo]  ->  part[split][d][256] (fp32).
+hipError_t launch_router_dWr_mfma(const Workspace &w, const void *x, char *ws, hipStream_t s) {
+    GemmArgs a{};
+    a.Q = (const bf16 *)x; a.q_batch = (size_t)w.tps_m * w.d; a.ldq = (int)w.d;          // [k = token][q = d]
+    a.P = (const bf16 *)(ws + w.dl_split); a.p_batch = (size_t)w.tps_m * 256; a.ldp = 256;  // [k = token][p]
+    a.Cf = (float *)(ws + w.dWr_part_m); a.c_batch = (size_t)w.d * 256; a.ldc = 256;
+    a.T_total = (int)w.T; a.tps = (int)w.tps_m;
+    a.Qdim = (int)w.d; a.Pdim = 256; a.Kdim = (int)w.tps_m;
+    a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
+    a.tiles_p = 1;
+    a.total_tiles = a.tiles_q * a.tiles_p * (int)w.nsplit_m;
+    ProfScope ps("router_dWr_mfma", s);
+    return gemm_launch<true, true, EPI_NONE, false, true, MODE_ROUTER_DWR>(a, s);
 }
 
 }  // namespace sw

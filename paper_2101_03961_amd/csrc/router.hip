@@ -268,7 +268,8 @@ template <int EPL>
 __global__ __launch_bounds__(256) void router_dlogits_kernel(
     const float *__restrict__ probs, const int32_t *__restrict__ idx,
     const float *__restrict__ dgate, const int32_t *__restrict__ counts,
-    float *__restrict__ dlogits, int T, int E, float aux_scale /* d_aux*alpha*E/T^2 */) {
+    float *__restrict__ dlogits, bf16 *__restrict__ dl_split /* [T][256] hi | lo, or nullptr */,
+    int T, int E, float aux_scale /* d_aux*alpha*E/T^2 */) {
     const int lane = threadIdx.x % kWave;
     const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
     if (t >= T) return;
@@ -288,8 +289,34 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
 #pragma unroll
     for (int j = 0; j < EPL; ++j) {
         const int e = lane + j * kWave;
-        if (e < E) dlogits[(size_t)t * E + e] = p[j] * (dp[j] - s);
+        const float dl = e < E ? p[j] * (dp[j] - s) : 0.f;
+        if (e < E) dlogits[(size_t)t * E + e] = dl;
+        if (dl_split && e < 128) {   // two bf16 terms (16 mantissa bits) for the MFMA contractions
+            const bf16 hi = (bf16)dl;
+            dl_split[(size_t)t * 256 + e] = hi;
+            dl_split[(size_t)t * 256 + 128 + e] = (bf16)(dl - (float)hi);
+        }
     }
+    if (dl_split)   // columns of the 128-wide halves that no lane visited above
+        for (int e = lane + EPL * kWave; e < 128; e += kWave) {
+            dl_split[(size_t)t * 256 + e] = (bf16)0.f;
+            dl_split[(size_t)t * 256 + 128 + e] = (bf16)0.f;
+        }
+}
+
+// dW_r[k][j] = sum over splits of (part[s][k][j] + part[s][k][128 + j]), fixed order
+__global__ __launch_bounds__(256) void reduce_dWr_split_kernel(const float *__restrict__ part,
+                                                               float *__restrict__ dW_r, int d,
+                                                               int E, int nsplit) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= d * E) return;
+    const int k = i / E, j = i - k * E;
+    float s = 0.f;
+    for (int q = 0; q < nsplit; ++q) {
+        const float *row = part + ((size_t)q * d + k) * 256;
+        s += row[j] + row[128 + j];
+    }
+    dW_r[i] = s;
 }
 
 // -----------------------------------------------------------------------------
@@ -528,6 +555,12 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
                                    hipStream_t s) {
     hipError_t err = hipSuccess;
     float *dlogits = (float *)(ws + w.dlogits);
+    // bf16 tokens and up to 128 experts: the two contractions run on the matrix cores
+    // (dl and W_r as two bf16 terms each; x is bf16 already)
+    // (the forward pass took the same path and left W_r's bf16 terms in the workspace)
+    const bool mfma = router_fwd_mfma_supported(w, sizeof(XT) == 2 ? SW_BF16 : SW_F32) &&
+                      (uint64_t)w.T * 512u < 0x7fffffffu;
+    bf16 *dl_split = mfma ? (bf16 *)(ws + w.dl_split) : nullptr;
     {
         ProfScope ps("router_dlogits", s);
         const float aux_scale =
@@ -536,12 +569,20 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
     hipLaunchKernelGGL(router_dlogits_kernel<N>, dim3((unsigned)ceil_div(w.T, 4)), dim3(256), 0, \
                        s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),          \
                        (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts), dlogits, \
-                       (int)w.T, (int)w.E, aux_scale)
+                       dl_split, (int)w.T, (int)w.E, aux_scale)
         SW_DISPATCH_EPL(w.E, CALL);
 #undef CALL
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
-    {
+    if (mfma) {
+        if ((err = launch_router_dx_mfma(w, ws, dx, s)) != hipSuccess) return err;
+        if ((err = launch_router_dWr_mfma(w, x, ws, s)) != hipSuccess) return err;
+        ProfScope ps("router_dWr_reduce", s);
+        hipLaunchKernelGGL(reduce_dWr_split_kernel, dim3((unsigned)ceil_div(w.d * w.E, 256)),
+                           dim3(256), 0, s, (const float *)(ws + w.dWr_part_m), dW_r, (int)w.d,
+                           (int)w.E, (int)w.nsplit_m);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    } else {
         ProfScope ps("router_dx", s);
         dim3 grid((unsigned)ceil_div(w.T, kLogTB), (unsigned)ceil_div(w.d, kLogEB));
         hipLaunchKernelGGL(router_dx_kernel<XT>, grid, dim3(256), 0, s, dlogits, W_r,
@@ -551,7 +592,7 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     const int tokens_per_split = (int)ceil_div(w.T, w.nsplit);
-    {
+    if (!mfma) {
         ProfScope ps("router_dWr", s);
         dim3 grid((unsigned)ceil_div(w.d, kWrTile), (unsigned)ceil_div(w.E, kWrTile),
                   (unsigned)w.nsplit);

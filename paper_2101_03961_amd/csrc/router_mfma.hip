@@ -30,9 +30,12 @@ constexpr int kRmTileBytes = kRmTokens * kRmPitch * 4; // 132 KB
 constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + kRmExperts * 4;
 
 // W_r [d][E] fp32 -> wsplit [3][128][dpad] bf16: term s of expert e, k contiguous;
-// rows of absent experts and columns past d are zero.
+// rows of absent experts and columns past d are zero.  Also, for the backward
+// pass, wsplit_b [d][256] bf16: row k holds hi(W_r[k][0..127]) | lo(...), where
+// hi + lo carries 16 mantissa bits.
 __global__ __launch_bounds__(256) void router_split_kernel(const float *__restrict__ W_r,
-                                                           bf16 *__restrict__ wsplit, int d,
+                                                           bf16 *__restrict__ wsplit,
+                                                           bf16 *__restrict__ wsplit_b, int d,
                                                            int dpad, int E) {
     const int k = blockIdx.x * 256 + threadIdx.x;
     const int e = blockIdx.y;
@@ -47,6 +50,10 @@ __global__ __launch_bounds__(256) void router_split_kernel(const float *__restri
     wsplit[(size_t)e * dpad + k] = hi;
     wsplit[plane + (size_t)e * dpad + k] = mid;
     wsplit[2 * plane + (size_t)e * dpad + k] = lo;
+    if (k < d) {
+        wsplit_b[(size_t)k * 256 + e] = hi;
+        wsplit_b[(size_t)k * 256 + 128 + e] = mid;
+    }
 }
 
 #define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
@@ -236,7 +243,7 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
         ProfScope ps("router_split_weights", s);
         dim3 grid((unsigned)ceil_div(w.dpad, 256), kRmExperts);
         hipLaunchKernelGGL(router_split_kernel, grid, dim3(256), 0, s, W_r, (bf16 *)(ws + w.wsplit),
-                           (int)w.d, (int)w.dpad, (int)w.E);
+                           (bf16 *)(ws + w.wsplit_b), (int)w.d, (int)w.dpad, (int)w.E);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     {
