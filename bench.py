@@ -41,6 +41,8 @@ def kernel_work(shape, kept, elt):
     gemm = 2.0 * kept * d * f
     w_bytes = float(E) * d * f * elt
     return {
+        "router_split_weights": (0.0, d * E * 4 + 3 * 128 * d * 2 + d * 512, "hbm"),
+        "router_fwd_mfma": (6.0 * T * d * E, T * d * elt + T * E * 4 + T * 12, "hbm"),
         "router_logits": (2.0 * T * d * E, T * d * elt + T * E * 4 + d * E * 4, "hbm"),
         "router_softmax_top1": (0.0, 2.0 * T * E * 4 + T * 8, "hbm"),
         "route_scan_aux": (0.0, 3.0 * (T / 256.0) * E * 4, "hbm"),
@@ -54,7 +56,10 @@ def kernel_work(shape, kept, elt):
         "gemm2_wgrad": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "gemm1_dgrad": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "gemm1_wgrad": (gemm, w_bytes + kept * (d + f) * elt, "mfma"),
-        "router_dlogits": (0.0, 2.0 * T * E * 4 + T * 8, "hbm"),
+        "router_dlogits": (0.0, 2.0 * T * E * 4 + T * 512 + T * 8, "hbm"),
+        "router_dx_mfma": (6.0 * T * d * E, T * 512 + kept * d * elt + T * d * elt, "hbm"),
+        "router_dWr_mfma": (4.0 * T * d * E, T * d * elt + T * 512, "hbm"),
+        "router_dWr_reduce": (0.0, d * E * 4.0, "hbm"),
         "router_dx": (2.0 * T * d * E, T * E * 4 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr": (2.0 * T * d * E, T * d * elt + T * E * 4, "hbm"),
         "router_dbr": (0.0, T * E * 4.0, "hbm"),
@@ -158,10 +163,15 @@ def main() -> int:
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"],
                 "peak": dk["peak"], "unit": dk["unit"], "frac": dk["frac"], "traffic": None,
                 "avg_us": dk["avg_us"]}
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    # HBM bytes per launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE (see profiles/):
+    # lines "<config> <kernel> <bytes>"
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(traffic_file):
         with open(traffic_file) as fh:
-            roofline["traffic"] = json.load(fh).get(args.config, {}).get(dominant)
+            for ln in fh:
+                parts = ln.split("#")[0].split()
+                if len(parts) == 3 and parts[0] == args.config and parts[1] == dominant:
+                    roofline["traffic"] = float(parts[2])
     gemm_names = [k for k in kernels if kernels[k]["bound"] == "mfma"]
     gemm_s = sum(kernels[k]["avg_us"] * kernels[k]["launches_per_step"] for k in gemm_names) * 1e-6
     gemm_flops = sum(work[k][0] for k in gemm_names)

@@ -67,7 +67,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.wsplit = take((size_t)3 * 128 * w.dpad * 2);
     w.wsplit_b = take(d * 256 * 2);
     w.dl_split = take(T * 256 * 2);
-    w.tps_m = ceil_div(ceil_div(w.T, 85), 32) * 32;
+    w.tps_m = ceil_div(ceil_div(w.T, 85), 64) * 64;
     w.nsplit_m = ceil_div(w.T, w.tps_m);
     w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
     w.total = off;

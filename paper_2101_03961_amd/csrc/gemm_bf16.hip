@@ -45,11 +45,11 @@ namespace sw {
 
 constexpr int kBP = 256;                          // block tile, p rows
 constexpr int kBQ = 256;                          // block tile, q rows
-constexpr int kBK = 32;                           // k per pipeline step
-constexpr int kStages = 4;                        // LDS ring depth
+constexpr int kBK = 64;                           // k per pipeline step
+constexpr int kStages = 2;                        // LDS stages
 constexpr int kGemmThreads = 256;
-static_assert(kOpBytes == kBP * kBK * 2, "operand stage size");
-constexpr int kStageBytes = 2 * kOpBytes;         // P then Q
+static_assert(kOpBytes64 == kBP * kBK * 2, "operand stage size");
+constexpr int kStageBytes = 2 * kOpBytes64;       // P then Q
 constexpr int kRingBytes = kStages * kStageBytes;  // 128 KB
 constexpr int kGemmLds = kRingBytes + kBQ * 4;    // + one int per q row (ROUTER_DX: slot of the addend)
 constexpr int kXcds = 8;
@@ -90,8 +90,8 @@ struct GemmArgs {
 //               range, k = tokens of the range, fp32 output.
 enum GemmMode { MODE_EXPERTS = 0, MODE_ROUTER_DX = 1, MODE_ROUTER_DWR = 2 };
 
-template <bool TRANS> struct OperandOf { typedef DirectOperand type; };
-template <> struct OperandOf<true> { typedef TransOperand type; };
+template <bool TRANS> struct OperandOf { typedef DirectOperand64 type; };
+template <> struct OperandOf<true> { typedef TransOperand64 type; };
 
 enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
 
@@ -181,9 +181,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             if (r >= nk) r -= nk;
             if (j >= nk) r = nk;
             if (MODE == MODE_ROUTER_DX) {
-                // steps 0..3: dl_hi x W_hi, 4..7: dl_hi x W_lo, 8..11: dl_lo x W_hi; 12: past the end
-                k0q_ = r < 8 ? 32 * (r & 3) : (r < 12 ? 128 + 32 * (r - 8) : 256);
-                k0p_ = r < 4 ? 32 * r : (r < 8 ? 128 + 32 * (r - 4) : (r < 12 ? 32 * (r - 8) : 256));
+                // steps 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi; 6: past the end
+                k0q_ = r < 4 ? 64 * (r & 1) : (r < 6 ? 128 + 64 * (r - 4) : 256);
+                k0p_ = r < 2 ? 64 * r : (r < 4 ? 128 + 64 * (r - 2) : (r < 6 ? 64 * (r - 4) : 256));
             } else {
                 k0p_ = k0q_ = r * kBK;
             }
@@ -202,12 +202,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         constexpr int kNP = OperandOf<P_TRANS>::type::kPieces;
         constexpr int kNR = kNP + OperandOf<Q_TRANS>::type::kPieces;   // LDS reads per sub-step
 
-// direct loads of k step KT, load G of eight (P: 0..3, Q: 4..7)
+// direct loads of k step KT, load G of sixteen (P: 0..7, Q: 8..15)
 #define SW_ISSUE_ONE(KT, G)                                                           \
     do {                                                                              \
         const uint32_t st_ = lds0 + (uint32_t)(((KT) & (kStages - 1)) * kStageBytes); \
-        if ((G) < 4) op.issue_one(st_, k0p_, wave, (G));                              \
-        else oq.issue_one(st_ + kOpBytes, k0q_, wave, (G)-4);                         \
+        if ((G) < 8) op.issue_one(st_, k0p_, wave, (G));                              \
+        else oq.issue_one(st_ + kOpBytes64, k0q_, wave, (G)-8);                       \
     } while (0)
 // LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of step KT, sub-step KS into SET
 #define SW_READ_GROUP(SET, KT, KS, G)                                                 \
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         const char *st_ = lds + ((KT) & (kStages - 1)) * kStageBytes;                 \
         _Pragma("unroll") for (int x_ = (G)*kNR / 8; x_ < ((G) + 1) * kNR / 8; ++x_) { \
             if (x_ < kNP) op.read_piece(st_, x_, KS, fa[SET]);                        \
-            else oq.read_piece(st_ + kOpBytes, x_ - kNP, KS, fb[SET]);                \
+            else oq.read_piece(st_ + kOpBytes64, x_ - kNP, KS, fb[SET]);              \
         }                                                                             \
     } while (0)
 // MFMAs 2 G and 2 G + 1 of the sixteen of a sub-step (fragment pairs in row-major order)
@@ -228,37 +228,51 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             __builtin_bit_cast(bf16x8, a8_), __builtin_bit_cast(bf16x8, b8_), acc[i_][j_], 0, 0, 0); \
     }
 
-        // Prologue: the whole ring is filled (steps past the k range read zeros),
-        // then step 0 is awaited and its first fragments fetched.
+        // Prologue: both stages are filled (steps past the k range read zeros), then
+        // step 0 is awaited and its first fragments fetched.
 #pragma unroll
         for (int kt = 0; kt < kStages; ++kt) {
             k_of(kt);
 #pragma unroll
-            for (int g = 0; g < 8; ++g) SW_ISSUE_ONE(kt, g);
+            for (int g = 0; g < 16; ++g) SW_ISSUE_ONE(kt, g);
         }
-        SW_WAIT_VMCNT(24);
+        SW_WAIT_VMCNT(16);
         __syncthreads();
 #pragma unroll
         for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, 0, 0, g);
 
+        // One k step = four sub-steps of 16 MFMAs.  Fragments of a sub-step are read
+        // (into the other of two register sets) between the MFMAs of the sub-step
+        // before it.  After the third sub-step's MFMAs nobody reads this stage any
+        // more: the step's one barrier sits there, and the fourth sub-step runs with
+        // the loads of step kt+2 (into the stage just freed) and the first fragments
+        // of step kt+1 between its MFMAs.
         for (int kt = 0; kt < nk; ++kt) {
-            // sub-step 0 of step kt; the fragments of sub-step 1 are fetched between its MFMAs
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
                 SW_READ_GROUP(1, kt, 1, g);
                 SW_MFMA_PAIR(0, g)
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // step kt+1 must have landed (two younger steps may still fly); after
-            // the barrier nobody reads stage kt any more, so step kt+4 goes there
-            SW_WAIT_VMCNT(16);
-            __syncthreads();
-            k_of(kt + kStages);
-            // sub-step 1 of step kt; between its MFMAs: the loads of step kt+4 and the
-            // first fragments of step kt+1
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
-                SW_ISSUE_ONE(kt + kStages, g);
+                SW_READ_GROUP(0, kt, 2, g);
+                SW_MFMA_PAIR(1, g)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                SW_READ_GROUP(1, kt, 3, g);
+                SW_MFMA_PAIR(0, g)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            SW_WAIT_VMCNT(0);   // step kt+1 has landed
+            __syncthreads();
+            k_of(kt + kStages);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                SW_ISSUE_ONE(kt + kStages, 2 * g);
+                SW_ISSUE_ONE(kt + kStages, 2 * g + 1);
                 SW_READ_GROUP(0, kt + 1, 0, g);
                 SW_MFMA_PAIR(1, g)
                 __builtin_amdgcn_sched_barrier(0);
@@ -273,8 +287,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         // rows.  Each wave therefore turns its 128 x 128 sub-tile around through its
         // own 32 KB of LDS ([q][p] bf16, 16-byte chunks XOR-swizzled by row) and
         // writes whole 256-byte row segments, 16 bytes per lane.
-        SW_WAIT_VMCNT(0);   // the ring's trailing (zero) loads have landed
-        __syncthreads();    // and every wave is done reading the ring
+        SW_WAIT_VMCNT(0);   // the trailing (zero) loads have landed
+        __syncthreads();    // and every wave is done reading the stages
         if (MODE == MODE_ROUTER_DWR) {
             // fp32 partial sums straight from the accumulators: four consecutive p per lane
             float *Cf = a.Cf + (size_t)t.e * a.c_batch;

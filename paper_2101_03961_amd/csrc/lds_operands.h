@@ -144,4 +144,94 @@ struct TransOperand {
     }
 };
 
+// =============================================================================
+// 64-k variants (one pipeline step = 64 k): an operand row of a [row][k] tile is a
+// whole 128-byte line, so every request the loads make is a full cache line.
+// =============================================================================
+constexpr int kOpBytes64 = 256 * 64 * 2;   // 32 KB per operand stage
+
+// [row][k] operand: LDS [256 rows][64 k] = 128 bytes per row, eight 16-byte chunks,
+// chunk c of row r at position c ^ ((r >> 1) & 7): 16 consecutive rows reading the
+// same logical chunk cover all 64 banks.
+struct DirectOperand64 {
+    i32x4 rsrc;
+    uint32_t voff;       // byte offset of the lane's chunk in the wave's first 8 rows
+    uint32_t row_step;   // bytes of 32 rows
+    int c8;              // first k (within the step) of the lane's chunk
+    int klim;
+    uint32_t frag0;      // LDS byte offset of the lane's fragment, sub-step 0
+
+    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim_,
+                                         int lane, int wave, int wave_rows) {
+        rsrc = make_rsrc(base, (uint32_t)rowlim * (uint32_t)ld * 2u);
+        const int r = wave * 8 + (lane >> 3);           // + 32 per load
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        c8 = c << 3;
+        voff = ((uint32_t)(row0 + r) * (uint32_t)ld + (uint32_t)c8) * 2u;
+        row_step = 32u * (uint32_t)ld * 2u;
+        klim = klim_;
+        const int fr = wave_rows + (lane & 31);
+        frag0 = (uint32_t)(fr * 128 + (((lane >> 5) ^ ((fr >> 1) & 7)) << 4));
+    }
+    static constexpr int kPieces = 4;   // LDS reads per k sub-step: one per fragment
+    // load i of eight: rows 32 i + [8 wave, 8 wave + 8)
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
+        const uint32_t vo = (k0 + c8 < klim) ? voff : kOobOffset;
+        dma16(rsrc, vo, (uint32_t)i * row_step + (uint32_t)k0 * 2u,
+              lds_op + (uint32_t)((i * 32 + wave * 8) * 128));
+    }
+    // piece x = fragment x (rows 32 x ..), k sub-step ks (0..3): chunk 2 ks + lane/32
+    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
+                                               s16x4 (&h)[4][2]) const {
+        const s16x8 v =
+            *(const s16x8 *)(lds_op + ((frag0 ^ (uint32_t)(ks << 5)) + (uint32_t)(x * 32 * 128)));
+        h[x][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+        h[x][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+    }
+};
+
+// [k][row] operand: LDS [64 k][256 rows], laid out and read like TransOperand.
+struct TransOperand64 {
+    i32x4 rsrc;
+    uint32_t voff[2];       // lane's byte offset for loads with even / odd index
+    uint32_t k_step;        // bytes of one k row
+    uint32_t frag_base[4];  // LDS byte offset of the lane's share of fragment i (ks = 0, first half)
+
+    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim,
+                                         int lane, int wave, int wave_rows) {
+        rsrc = make_rsrc(base, (uint32_t)klim * (uint32_t)ld * 2u);
+        k_step = (uint32_t)ld * 2u;
+        const int kk = lane >> 5, pc = lane & 31;
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+            const int kr = wave * 16 + 2 * par + kk;    // loads par, par + 2, ...: same k mod 4
+            const int c = pc ^ ((kr & 3) << 1);
+            const int row = row0 + (c << 3);
+            voff[par] = row < rowlim
+                            ? ((uint32_t)(wave * 16 + kk) * (uint32_t)ld + (uint32_t)row) * 2u
+                            : kOobOffset;
+        }
+        const int g = lane >> 4, j = lane & 15;
+        const int kq = j >> 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = wave_rows + i * 32 + (g & 1) * 16 + (j & 3) * 4;
+            const int chunk = (n >> 3) ^ (kq << 1);
+            frag_base[i] = (uint32_t)((((g >> 1) * 8 + kq) * 512) + (chunk << 4) + ((n & 4) << 1));
+        }
+    }
+    static constexpr int kPieces = 8;   // LDS reads per k sub-step: two per fragment
+    // load i of eight: k-rows 16 wave + 2 i + {0, 1}
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
+        dma16(rsrc, voff[i & 1], (uint32_t)(k0 + 2 * i) * k_step,
+              lds_op + (uint32_t)((wave * 16 + 2 * i) * 512));
+    }
+    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
+                                               s16x4 (&h)[4][2]) const {
+        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+        const char *p0 = lds_op + frag_base[x >> 1] + ks * (16 * 512) + (x & 1) * (4 * 512);
+        h[x >> 1][x & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
+    }
+};
+
 }  // namespace sw
