@@ -48,11 +48,11 @@ def kernel_work(shape, kept, elt):
         "route_scan_aux": (0.0, 3.0 * (T / 256.0) * E * 4, "hbm"),
         "positions": (0.0, T * (4 + 4 + 4 + 4 + 1 + 4 + 1), "hbm"),
         "dispatch_gather": (0.0, 2.0 * kept * d * elt, "hbm"),
-        "gemm1_fwd_relu": (gemm, w_bytes + kept * (d + f) * elt, "mfma"),
+        "gemm1_fwd_relu": (gemm, w_bytes + kept * (d + f) * elt + kept * f / 8.0, "mfma"),
         "gemm2_fwd": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "combine_scatter": (0.0, kept * d * elt + T * d * elt + T * 4, "hbm"),
         "combine_bwd": (0.0, 3.0 * kept * d * elt + T * 8, "hbm"),
-        "gemm2_dgrad_relumask": (gemm, w_bytes + kept * (d + 2 * f) * elt, "mfma"),
+        "gemm2_dgrad_relumask": (gemm, w_bytes + kept * (d + f) * elt + kept * f / 8.0, "mfma"),
         "gemm2_wgrad": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "gemm1_dgrad": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "gemm1_wgrad": (gemm, w_bytes + kept * (d + f) * elt, "mfma"),

@@ -70,6 +70,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.tps_m = ceil_div(ceil_div(w.T, 85), 64) * 64;
     w.nsplit_m = ceil_div(w.T, w.tps_m);
     w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
+    w.relu_bits = take(E * ceil_div(f, kGemmTile) * ceil_div(C, kGemmTile) * kReluBitsPerTile);
     w.total = off;
     return w;
 }

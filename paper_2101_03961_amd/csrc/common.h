@@ -24,6 +24,10 @@ constexpr int kWave = 64;
 // owns kRouteTB consecutive tokens.
 constexpr int kRouteTB = 256;
 
+// Output tile of the bf16 grouped GEMM (square), and the bytes of ReLU-mask bits per tile.
+constexpr int kGemmTile = 256;
+constexpr int kReluBitsPerTile = kGemmTile * kGemmTile / 8;
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -59,6 +63,8 @@ struct Workspace {
     size_t dl_split;            // bf16 [T][256]   dlogits rows as hi | lo halves
     size_t dWr_part_m;          // f32 [nsplit_m][d][256]  partial sums of x^T [dl_hi | dl_lo]
     int64_t tps_m, nsplit_m;    // tokens per split (multiple of 32), number of splits
+    size_t relu_bits;           // u8  [E][f tiles][slot tiles][kReluBitsPerTile]  one bit per element of A:
+                                //     A > 0, in the order the bf16 GEMM epilogue visits a tile
     int64_t nsplit;
     size_t total;
 };

@@ -9,14 +9,15 @@
 // Data path.  Operand tiles go from HBM/L2 straight into LDS with
 // buffer_load_dwordx4 ... lds (no registers, no ds_write: LDS stores issued by
 // the waves cost ~30 cycles of issue each and were the bottleneck of an earlier
-// register-staged version).  k advances 32 at a time through a ring of four LDS
-// stages (4 x 32 KB); the loads of step kt+4 are issued while step kt is being
-// multiplied, i.e. three steps (~1.5 us) ahead of their use.
-//   - An operand stored [row][k] (k contiguous) is kept in LDS as [row][32 k];
+// register-staged version).  k advances 64 at a time through two LDS stages
+// (2 x 64 KB): every row of an operand tile is then one full 128-byte line per
+// step.  The sixteen loads a wave issues for step kt+2 go out between the MFMAs
+// of the last quarter of step kt, right after the barrier that frees the stage.
+//   - An operand stored [row][k] (k contiguous) is kept in LDS as [row][64 k];
 //     a lane's MFMA fragment (8 consecutive k of one row) is one ds_read_b128.
 //   - An operand stored [k][row] (row contiguous: the weights in the forward
 //     pass, both operands of the weight-gradient GEMMs) is kept in LDS exactly
-//     as in memory, [32 k][256 rows], and fragments are fetched with the
+//     as in memory, [64 k][256 rows], and fragments are fetched with the
 //     transposing LDS read ds_read_b64_tr_b16 (two per fragment), which hands
 //     each lane four consecutive k of its own row.
 //   In both layouts the 16-byte chunks of an LDS row are XOR-permuted (the
@@ -24,10 +25,10 @@
 //   LDS side of a direct load is fixed to lane * 16) so that fragment reads
 //   spread over all banks.
 //
-// Schedule per k step and wave: 32 MFMAs in two sub-steps of 16.  Fragments are
+// Schedule per k step and wave: 64 MFMAs in four sub-steps of 16.  Fragments are
 // double buffered in registers and read one sub-step ahead; the single barrier
-// of the step sits between the two sub-steps, so the MFMA pipe always has the
-// other sub-step's work queued while waves meet.
+// of the step sits before the last sub-step, so the MFMA pipe always has that
+// sub-step's work queued while waves meet.
 //
 // Ragged edges cost no branches: loads are bounded by the buffer descriptor
 // (rows past the expert's kept tokens, k past the reduction length read as
@@ -36,15 +37,20 @@
 //
 // Work assignment: persistent blocks, one per CU, each walking a strided list of
 // (expert, p tile, q tile) tiles of its XCD; q tiles beyond the expert's
-// kept-token count are skipped.  The epilogue turns each wave's sub-tile around
-// through LDS so that C is written in whole 256-byte row segments.
+// kept-token count are skipped.  Tiles that share an operand tile run at the same
+// time on one XCD and walk k in the same order, so that each line is fetched from
+// HBM once per XCD (measured: starting neighbours a few k steps apart, to turn
+// hits under a miss into plain hits, raised HBM traffic by a third -- the leading
+// block's lines were evicted before the followers arrived -- and saved no time).
+// The epilogue turns each wave's sub-tile around through LDS so that C is written
+// in whole 256-byte row segments.
 #include "common.h"
 #include "lds_operands.h"
 
 namespace sw {
 
-constexpr int kBP = 256;                          // block tile, p rows
-constexpr int kBQ = 256;                          // block tile, q rows
+constexpr int kBP = kGemmTile;                    // block tile, p rows
+constexpr int kBQ = kGemmTile;                    // block tile, q rows
 constexpr int kBK = 64;                           // k per pipeline step
 constexpr int kStages = 2;                        // LDS stages
 constexpr int kGemmThreads = 256;
@@ -53,21 +59,13 @@ constexpr int kStageBytes = 2 * kOpBytes64;       // P then Q
 constexpr int kRingBytes = kStages * kStageBytes;  // 128 KB
 constexpr int kGemmLds = kRingBytes + kBQ * 4;    // + one int per q row (ROUTER_DX: slot of the addend)
 constexpr int kXcds = 8;
-// Tiles that share an operand tile (the q tiles of one weight tile, the p tiles of
-// one activation tile) run at the same time on the same XCD.  If they also walked
-// k in the same order, up to a dozen CUs would ask their L2 for the same lines at
-// the same moment, and those hits-under-miss queue up behind each other.  Each
-// tile therefore starts its k loop kRotate steps further along than its
-// neighbour (and wraps around): the first block to reach a line fetches it, the
-// others find it in L2 a few steps later.  fp32 sums are taken in a different but
-// fixed order per tile, so results stay deterministic.
-constexpr int kRotate = 3;
 
 struct GemmArgs {
     const bf16 *Q;      // per expert: q_batch elements
     const bf16 *P;
     bf16 *Cout;
-    const bf16 *mask;   // same layout as Cout (ReLU mask source) or nullptr
+    const bf16 *mask;   // ROUTER_DX: rows added to the product in the epilogue
+    uint8_t *relu_bits; // EPI_RELU writes, EPI_MASK reads: one bit per output element, tile-private order
     size_t q_batch, p_batch, c_batch;
     int ldq, ldp, ldc;  // leading dimensions in elements
     int Qdim, Pdim, Kdim;
@@ -98,7 +96,7 @@ enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
 // One output tile of one expert.
 struct Tile {
     int e, p0, q0, qlim, klim;
-    int rot_seed;   // pt + qt: where in k this tile starts (see kRotate)
+    int index;      // (e * tiles_p + p tile) * tiles_q + q tile
 };
 
 // Tiles are numbered expert-major, then p tile, then q tile (fastest), and the
@@ -122,7 +120,7 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
         t.e = e;
         t.p0 = pt * kBP;
         t.q0 = qt * kBQ;
-        t.rot_seed = pt + qt;
+        t.index = L;
         t.qlim = Q_LIMITED ? (kept < a.Qdim ? kept : a.Qdim) : a.Qdim;
         t.klim = K_LIMITED ? (kept < a.Kdim ? kept : a.Kdim) : a.Kdim;
         if (t.q0 < t.qlim) {   // q tiles past the expert's kept tokens have no work
@@ -173,13 +171,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             slot_s[tid] = slot;
         }
         const int nk = (t.klim + kBK - 1) / kBK;
-        const int rot = nk > 0 ? (kRotate * t.rot_seed) % nk : 0;
-        // k offsets (P, Q) of pipeline step j: rotated inside the range, past the end beyond it
+        // k offsets (P, Q) of pipeline step j; steps past the range read zeros
         int k0p_ = 0, k0q_ = 0;
         auto k_of = [&](int j) {
-            int r = j + rot;
-            if (r >= nk) r -= nk;
-            if (j >= nk) r = nk;
+            const int r = j < nk ? j : nk;
             if (MODE == MODE_ROUTER_DX) {
                 // steps 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi; 6: past the end
                 k0q_ = r < 4 ? 64 * (r & 1) : (r < 6 ? 128 + 64 * (r - 4) : 256);
@@ -333,41 +328,72 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             }
         }
         bf16 *Cout = a.Cout + (size_t)t.e * a.c_batch;
-        const bf16 *mask = EPI == EPI_MASK ? a.mask + (size_t)t.e * a.c_batch : nullptr;
         const int c = lane & 15;
         const int p = t.p0 + wp * 128 + c * 8;
-#pragma unroll 8
-        for (int it = 0; it < 32; ++it) {
-            const int row = it * 4 + (lane >> 4);
-            const int q = t.q0 + wq * 128 + row;
-            u32x4 val = *(const u32x4 *)(ep + row * 256 + ((c ^ (row & 15)) << 4));
-            if (q < t.qlim && p < a.Pdim) {
-                const size_t off = (size_t)q * a.ldc + p;
-                if (EPI == EPI_MASK) {
-                    // keep an element where the saved activation is > 0 (bf16: sign clear, not zero)
-                    const u32x4 m = *(const u32x4 *)(mask + off);
+        // ReLU mask: byte `it` of a lane's 32 bytes says which of the eight elements of the
+        // 16-byte piece the lane handles in iteration `it` are > 0.  EPI_RELU (the first
+        // forward GEMM) writes the bits, EPI_MASK (the gradient w.r.t. the hidden
+        // activations, same tiling and same lane-to-element map) applies them: 32 bytes per
+        // lane instead of a second read of the activations.
+        uint32_t *bits = EPI == EPI_NONE ? nullptr
+                         : (uint32_t *)(a.relu_bits + (size_t)t.index * kReluBitsPerTile +
+                                        (size_t)(wave * 64 + lane) * 32);
+        uint32_t mb[8];
+        if (EPI == EPI_MASK) {
+            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        const uint32_t lo = m[w] & 0xffffu, hi = m[w] >> 16;
-                        const uint32_t keep = ((lo - 1u) < 0x7fffu ? 0xffffu : 0u) |
-                                              ((hi - 1u) < 0x7fffu ? 0xffff0000u : 0u);
-                        val[w] &= keep;
-                    }
-                }
-                const int slot = MODE == MODE_ROUTER_DX
-                                     ? ((const int32_t *)(lds + kRingBytes))[wq * 128 + row] : -1;
-                if (MODE == MODE_ROUTER_DX && slot >= 0) {
-                    // add the token's row of the expert-side gradient (fp32 add, one rounding)
-                    const u32x4 gsrc = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
-                    const bf16x8 va = __builtin_bit_cast(bf16x8, val);
-                    const bf16x8 vb = __builtin_bit_cast(bf16x8, gsrc);
-                    bf16x8 vo;
-#pragma unroll
-                    for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
-                    val = __builtin_bit_cast(u32x4, vo);
-                }
-                *(u32x4 *)(Cout + off) = val;
+            for (int w = 0; w < 4; ++w) { mb[w] = b0[w]; mb[4 + w] = b1[w]; }
+        }
+#pragma nounroll
+        for (int it8 = 0; it8 < 4; ++it8) {
+            // the eight mask bytes of this round of eight iterations
+            uint32_t m_lo = 0u, m_hi = 0u;
+            if (EPI == EPI_MASK) {
+                m_lo = it8 == 0 ? mb[0] : (it8 == 1 ? mb[2] : (it8 == 2 ? mb[4] : mb[6]));
+                m_hi = it8 == 0 ? mb[1] : (it8 == 1 ? mb[3] : (it8 == 2 ? mb[5] : mb[7]));
             }
+#pragma unroll
+            for (int i8 = 0; i8 < 8; ++i8) {
+                const int row = (it8 * 8 + i8) * 4 + (lane >> 4);
+                const int q = t.q0 + wq * 128 + row;
+                u32x4 val = *(const u32x4 *)(ep + row * 256 + ((c ^ (row & 15)) << 4));
+                if (EPI == EPI_RELU) {
+                    // After ReLU every half word is a non-negative bf16, so adding 0x7fff
+                    // carries into its top bit exactly when it is > 0.  Bits 0..3 of the
+                    // byte: low halves of the four words, bits 4..7: high halves.
+                    uint32_t u = 0;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        u |= ((val[w] + 0x7fff7fffu) & 0x80008000u) >> (15 - w);
+                    const uint32_t byte = (u | (u >> 12)) & 0xffu;
+                    if (i8 < 4) m_lo |= byte << (8 * i8);
+                    else m_hi |= byte << (8 * (i8 - 4));
+                }
+                if (EPI == EPI_MASK) {
+                    uint32_t byte = (i8 < 4 ? m_lo >> (8 * i8) : m_hi >> (8 * (i8 - 4))) & 0xffu;
+                    byte |= byte << 12;   // bit w -> bit w, bit 4+w -> bit 16+w
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        val[w] &= ((byte >> w) & 0x10001u) * 0xffffu;
+                }
+                if (q < t.qlim && p < a.Pdim) {
+                    const size_t off = (size_t)q * a.ldc + p;
+                    const int slot = MODE == MODE_ROUTER_DX
+                                         ? ((const int32_t *)(lds + kRingBytes))[wq * 128 + row] : -1;
+                    if (MODE == MODE_ROUTER_DX && slot >= 0) {
+                        // add the token's row of the expert-side gradient (fp32 add, one rounding)
+                        const u32x4 gsrc = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
+                        const bf16x8 va = __builtin_bit_cast(bf16x8, val);
+                        const bf16x8 vb = __builtin_bit_cast(bf16x8, gsrc);
+                        bf16x8 vo;
+#pragma unroll
+                        for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
+                        val = __builtin_bit_cast(u32x4, vo);
+                    }
+                    *(u32x4 *)(Cout + off) = val;
+                }
+            }
+            if (EPI == EPI_RELU) *(uint2 *)(bits + 2 * it8) = make_uint2(m_lo, m_hi);
         }
         __syncthreads();   // the epilogue's LDS reads are done before the ring is refilled
     }
@@ -429,6 +455,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         a.Q = Xd; a.q_batch = (size_t)C * d; a.ldq = d;
         a.P = (const bf16 *)W_in; a.p_batch = (size_t)d * f; a.ldp = f;
         a.Cout = A; a.c_batch = (size_t)C * f; a.ldc = f;
+        a.relu_bits = (uint8_t *)(ws + w.relu_bits);
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm1_fwd_relu", s);
@@ -446,7 +473,8 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     case GEMM_DGRAD2: {
         a.Q = dO; a.q_batch = (size_t)C * d; a.ldq = d;
         a.P = (const bf16 *)W_out; a.p_batch = (size_t)f * d; a.ldp = d;   // [p = f][k = d]
-        a.Cout = dH; a.c_batch = (size_t)C * f; a.ldc = f; a.mask = A;
+        a.Cout = dH; a.c_batch = (size_t)C * f; a.ldc = f;
+        a.relu_bits = (uint8_t *)(ws + w.relu_bits);
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm2_dgrad_relumask", s);
