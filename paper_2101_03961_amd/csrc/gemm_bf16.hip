@@ -57,7 +57,8 @@ constexpr int kGemmThreads = 256;
 static_assert(kOpBytes64 == kBP * kBK * 2, "operand stage size");
 constexpr int kStageBytes = 2 * kOpBytes64;       // P then Q
 constexpr int kRingBytes = kStages * kStageBytes;  // 128 KB
-constexpr int kGemmLds = kRingBytes + kBQ * 4;    // + one int per q row (ROUTER_DX: slot of the addend)
+constexpr int kTurnBytes = 32 * 256;              // per wave: 32 rows x 128 bf16 of the epilogue's turn-around
+constexpr int kGemmLds = kRingBytes + 4 * kTurnBytes;   // 160 KB: all of a CU's LDS
 constexpr int kXcds = 8;
 
 struct GemmArgs {
@@ -152,62 +153,56 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     int L = xcd * per_xcd + blockIdx.x / kXcds;
     const int L_end = min((xcd + 1) * per_xcd, a.total_tiles);
 
-    Tile t;
-    while (next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, t)) {
-        typename OperandOf<P_TRANS>::type op;
-        typename OperandOf<Q_TRANS>::type oq;
+    Tile cur, nxt;
+    if (!next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, cur)) return;
+
+    // The k steps of all tiles of this block form one pipeline: while a tile's last two
+    // steps are multiplied, the loads of the next tile's first two steps are already
+    // under way, and they stay in flight during the epilogue (which has its own LDS).
+    // A tile takes at least two steps (steps past its k range read zeros).
+    auto steps_of = [&](const Tile &t) { return (t.klim + kBK - 1) / kBK; };
+    typename OperandOf<P_TRANS>::type op;
+    typename OperandOf<Q_TRANS>::type oq;
+    op.init_frag(lane, wp * 128);
+    oq.init_frag(lane, wq * 128);
+    int ld_nk = 0;      // k steps (with data) of the tile the loads are in
+    auto begin_loads = [&](const Tile &t) {
         // width of the operand rows in k: the reduction length, except for ROUTER_DX
         // whose 384 k values are read from 256-wide (hi | lo) rows
         const int kwidth = MODE == MODE_ROUTER_DX ? 256 : t.klim;
-        op.init(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, kwidth, lane, wave, wp * 128);
-        oq.init(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, kwidth, lane, wave, wq * 128);
+        op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, kwidth, lane, wave);
+        oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, kwidth, lane, wave);
+        ld_nk = steps_of(t);
+    };
+    // k offsets (P, Q) of step j of the tile the loads are in; steps past its range read zeros
+    int k0p_ = 0, k0q_ = 0;
+    auto k_of = [&](int j) {
+        const int r = j < ld_nk ? j : ld_nk;
         if (MODE == MODE_ROUTER_DX) {
-            // slot of each token row's addend (-1: dropped token, nothing to add); read in
-            // the epilogue, after several barriers
-            int32_t *slot_s = (int32_t *)(lds + kRingBytes);
-            const int q = t.q0 + tid;
-            int slot = -1;
-            if (q < t.qlim && !a.tok_dropped[q]) slot = a.tok_idx[q] * a.cap + a.tok_pos[q];
-            slot_s[tid] = slot;
+            // steps 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi; 6: past the end
+            k0q_ = r < 4 ? 64 * (r & 1) : (r < 6 ? 128 + 64 * (r - 4) : 256);
+            k0p_ = r < 2 ? 64 * r : (r < 4 ? 128 + 64 * (r - 2) : (r < 6 ? 64 * (r - 4) : 256));
+        } else {
+            k0p_ = k0q_ = r * kBK;
         }
-        const int nk = (t.klim + kBK - 1) / kBK;
-        // k offsets (P, Q) of pipeline step j; steps past the range read zeros
-        int k0p_ = 0, k0q_ = 0;
-        auto k_of = [&](int j) {
-            const int r = j < nk ? j : nk;
-            if (MODE == MODE_ROUTER_DX) {
-                // steps 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi; 6: past the end
-                k0q_ = r < 4 ? 64 * (r & 1) : (r < 6 ? 128 + 64 * (r - 4) : 256);
-                k0p_ = r < 2 ? 64 * r : (r < 4 ? 128 + 64 * (r - 2) : (r < 6 ? 64 * (r - 4) : 256));
-            } else {
-                k0p_ = k0q_ = r * kBK;
-            }
-        };
+    };
 
-        f32x16 acc[4][4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // fragments: two register sets, each fragment as two 8-byte halves
+    s16x4 fa[2][4][2], fb[2][4][2];
+    constexpr int kNP = OperandOf<P_TRANS>::type::kPieces;
+    constexpr int kNR = kNP + OperandOf<Q_TRANS>::type::kPieces;   // LDS reads per sub-step
 
-        // fragments: two register sets, each fragment as two 8-byte halves
-        s16x4 fa[2][4][2], fb[2][4][2];
-        constexpr int kNP = OperandOf<P_TRANS>::type::kPieces;
-        constexpr int kNR = kNP + OperandOf<Q_TRANS>::type::kPieces;   // LDS reads per sub-step
-
-// direct loads of k step KT, load G of sixteen (P: 0..7, Q: 8..15)
-#define SW_ISSUE_ONE(KT, G)                                                           \
+// direct loads into the stage of pipeline step GS, load G of sixteen (P: 0..7, Q: 8..15)
+#define SW_ISSUE_ONE(GS, G)                                                           \
     do {                                                                              \
-        const uint32_t st_ = lds0 + (uint32_t)(((KT) & (kStages - 1)) * kStageBytes); \
+        const uint32_t st_ = lds0 + (uint32_t)(((GS) & (kStages - 1)) * kStageBytes); \
         if ((G) < 8) op.issue_one(st_, k0p_, wave, (G));                              \
         else oq.issue_one(st_ + kOpBytes64, k0q_, wave, (G)-8);                       \
     } while (0)
-// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of step KT, sub-step KS into SET
-#define SW_READ_GROUP(SET, KT, KS, G)                                                 \
+// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of pipeline step GS, sub-step KS into SET
+#define SW_READ_GROUP(SET, GS, KS, G)                                                 \
     do {                                                                              \
-        const char *st_ = lds + ((KT) & (kStages - 1)) * kStageBytes;                 \
+        const char *st_ = lds + ((GS) & (kStages - 1)) * kStageBytes;                 \
         _Pragma("unroll") for (int x_ = (G)*kNR / 8; x_ < ((G) + 1) * kNR / 8; ++x_) { \
             if (x_ < kNP) op.read_piece(st_, x_, KS, fa[SET]);                        \
             else oq.read_piece(st_ + kOpBytes64, x_ - kNP, KS, fb[SET]);              \
@@ -223,180 +218,223 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             __builtin_bit_cast(bf16x8, a8_), __builtin_bit_cast(bf16x8, b8_), acc[i_][j_], 0, 0, 0); \
     }
 
-        // Prologue: both stages are filled (steps past the k range read zeros), then
-        // step 0 is awaited and its first fragments fetched.
-#pragma unroll
-        for (int kt = 0; kt < kStages; ++kt) {
-            k_of(kt);
-#pragma unroll
-            for (int g = 0; g < 16; ++g) SW_ISSUE_ONE(kt, g);
-        }
-        SW_WAIT_VMCNT(16);
-        __syncthreads();
-#pragma unroll
-        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, 0, 0, g);
+// One k step (pipeline step GS) = four sub-steps of 16 MFMAs.  Fragments of a sub-step
+// are read (into the other of two register sets) between the MFMAs of the sub-step before
+// it.  After the third sub-step's MFMAs nobody reads this stage any more: the step's one
+// barrier sits there, and the fourth sub-step runs with the loads of the step after next
+// (into the stage just freed; k offsets from the preceding k_of) and the first fragments
+// of the next step between its MFMAs.
+#define SW_K_STEP(GS)                                                                 \
+    do {                                                                              \
+        _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
+            SW_READ_GROUP(1, GS, 1, g);                                               \
+            SW_MFMA_PAIR(0, g)                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                        \
+        }                                                                             \
+        _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
+            SW_READ_GROUP(0, GS, 2, g);                                               \
+            SW_MFMA_PAIR(1, g)                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                        \
+        }                                                                             \
+        _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
+            SW_READ_GROUP(1, GS, 3, g);                                               \
+            SW_MFMA_PAIR(0, g)                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                        \
+        }                                                                             \
+        SW_WAIT_VMCNT(0); /* the next step has landed */                              \
+        __syncthreads();                                                              \
+        _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
+            SW_ISSUE_ONE(GS, 2 * g);                                                  \
+            SW_ISSUE_ONE(GS, 2 * g + 1);                                              \
+            SW_READ_GROUP(0, (GS) + 1, 0, g);                                         \
+            SW_MFMA_PAIR(1, g)                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                        \
+        }                                                                             \
+    } while (0)
 
-        // One k step = four sub-steps of 16 MFMAs.  Fragments of a sub-step are read
-        // (into the other of two register sets) between the MFMAs of the sub-step
-        // before it.  After the third sub-step's MFMAs nobody reads this stage any
-        // more: the step's one barrier sits there, and the fourth sub-step runs with
-        // the loads of step kt+2 (into the stage just freed) and the first fragments
-        // of step kt+1 between its MFMAs.
-        for (int kt = 0; kt < nk; ++kt) {
+    // Start of the pipeline: both stages are filled with the first tile's steps 0 and 1,
+    // then step 0 is awaited.
+    begin_loads(cur);
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                SW_READ_GROUP(1, kt, 1, g);
-                SW_MFMA_PAIR(0, g)
-                __builtin_amdgcn_sched_barrier(0);
-            }
+    for (int st = 0; st < kStages; ++st) {
+        k_of(st);
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                SW_READ_GROUP(0, kt, 2, g);
-                SW_MFMA_PAIR(1, g)
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                SW_READ_GROUP(1, kt, 3, g);
-                SW_MFMA_PAIR(0, g)
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            SW_WAIT_VMCNT(0);   // step kt+1 has landed
-            __syncthreads();
-            k_of(kt + kStages);
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                SW_ISSUE_ONE(kt + kStages, 2 * g);
-                SW_ISSUE_ONE(kt + kStages, 2 * g + 1);
-                SW_READ_GROUP(0, kt + 1, 0, g);
-                SW_MFMA_PAIR(1, g)
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int g = 0; g < 16; ++g) SW_ISSUE_ONE(st, g);
+    }
+    SW_WAIT_VMCNT(16);
+    __syncthreads();
+
+    int gs = 0;   // pipeline step of the current tile's first k step
+    while (true) {
+        const int nsteps = steps_of(cur) > 2 ? steps_of(cur) : 2;
+        const bool have_next = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, nxt);
+
+        // ROUTER_DX: slot of the addend of rows lane and lane + 64 of the wave's 128 rows
+        // (-1: dropped token or past the end: nothing to add)
+        int slot_lo = -1, slot_hi = -1;
+        if (MODE == MODE_ROUTER_DX) {
+            const int q = cur.q0 + wq * 128 + lane;
+            if (q < cur.qlim && !a.tok_dropped[q]) slot_lo = a.tok_idx[q] * a.cap + a.tok_pos[q];
+            if (q + 64 < cur.qlim && !a.tok_dropped[q + 64])
+                slot_hi = a.tok_idx[q + 64] * a.cap + a.tok_pos[q + 64];
         }
-#undef SW_ISSUE_ONE
-#undef SW_READ_GROUP
-#undef SW_MFMA_PAIR
+        uint32_t mb[8];   // EPI_MASK: the lane's 32 bytes of ReLU bits of this tile
+        auto bits_of = [&](int ln) {
+            return (uint32_t *)(a.relu_bits + (size_t)cur.index * kReluBitsPerTile +
+                                (size_t)(wave * 64 + ln) * 32);
+        };
+
+        f32x16 acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        // first fragments of the tile's first step (it has landed: awaited in the step before)
+#pragma unroll
+        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, gs, 0, g);
+
+        // all but the last two steps load two steps ahead inside the tile
+        for (int kt = 0; kt < nsteps - 2; ++kt) {
+            k_of(kt + 2);
+            SW_K_STEP(gs + kt);
+        }
+        // the last two steps load the next tile's first two (after the last tile: zeros)
+        if (EPI == EPI_MASK) {
+            // asked for here so that they are not queued behind the next tile's loads
+            const uint32_t *bits = bits_of(lane);
+            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mb[w] = b0[w]; mb[4 + w] = b1[w]; }
+        }
+        if (have_next) {
+            begin_loads(nxt);
+        } else {
+            op.disable_load();
+            oq.disable_load();
+        }
+        for (int kt = 0; kt < 2; ++kt) {
+            k_of(kt);
+            SW_K_STEP(gs + nsteps - 2 + kt);
+        }
+        gs += nsteps;
 
         // Epilogue.  A lane holds, for q = lane%32 of each 32x32 MFMA tile, the four
         // consecutive p = 8*(r/4) + 4*(lane/32) + r%4: 8-byte pieces scattered over 32
-        // rows.  Each wave therefore turns its 128 x 128 sub-tile around through its
-        // own 32 KB of LDS ([q][p] bf16, 16-byte chunks XOR-swizzled by row) and
-        // writes whole 256-byte row segments, 16 bytes per lane.
-        SW_WAIT_VMCNT(0);   // the trailing (zero) loads have landed
-        __syncthreads();    // and every wave is done reading the stages
+        // rows.  Each wave therefore turns its 128 x 128 sub-tile around, 32 rows at a
+        // time, through 8 KB of LDS of its own ([q][p] bf16, 16-byte chunks XOR-swizzled
+        // by row) and writes whole 256-byte row segments, 16 bytes per lane.  No barrier:
+        // the LDS traffic is private to the wave and in order.
+        // The lane number is laundered so that the epilogue's per-lane addresses are computed
+        // here, per tile, instead of being kept in registers across the k loop.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
         if (MODE == MODE_ROUTER_DWR) {
             // fp32 partial sums straight from the accumulators: four consecutive p per lane
-            float *Cf = a.Cf + (size_t)t.e * a.c_batch;
+            float *Cf = a.Cf + (size_t)cur.e * a.c_batch;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int q = t.q0 + wq * 128 + j * 32 + (lane & 31);
-                if (q >= t.qlim) continue;
+                const int q = cur.q0 + wq * 128 + j * 32 + (ln & 31);
+                if (q >= cur.qlim) continue;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int p = t.p0 + wp * 128 + i * 32 + g * 8 + ((lane >> 5) << 2);
+                        const int p = cur.p0 + wp * 128 + i * 32 + g * 8 + ((ln >> 5) << 2);
                         if (p < a.Pdim)
                             *(float4 *)(Cf + (size_t)q * a.ldc + p) =
                                 make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1],
                                             acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
                     }
             }
-            continue;
-        }
-        char *ep = lds + wave * (128 * 256);
+        } else {
+            char *ep = lds + kRingBytes + wave * kTurnBytes;
+            bf16 *Cout = a.Cout + (size_t)cur.e * a.c_batch;
+            const int c = ln & 15;
+            uint32_t *bits = EPI == EPI_NONE ? nullptr : bits_of(ln);
+            const int p = cur.p0 + wp * 128 + c * 8;
+            // ReLU mask: byte j * 8 + i8 of a lane's 32 bytes says which of the eight
+            // elements of the 16-byte piece the lane handles in round j, iteration i8 are
+            // > 0.  EPI_RELU (the first forward GEMM) writes the bits, EPI_MASK (the gradient
+            // w.r.t. the hidden activations, same tiling and same lane-to-element map)
+            // applies them: 32 bytes per lane instead of a second read of the activations.
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = j * 32 + (lane & 31);
+            for (int j = 0; j < 4; ++j) {
+                const int wrow = ln & 31;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < 4; ++i) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    float v[4];
+                    for (int g = 0; g < 4; ++g) {
+                        float v[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = acc[i][j][g * 4 + r];
+                        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][g * 4 + r];
+                        if (EPI == EPI_RELU) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+                        }
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (bf16)v[r];
+                        const int ch = i * 4 + g;
+                        *(bf16x4 *)(ep + wrow * 256 + ((ch ^ (wrow & 15)) << 4) + ((ln >> 5) << 3)) = o;
+                    }
+                }
+                uint32_t m_lo = 0u, m_hi = 0u;
+                if (EPI == EPI_MASK) { m_lo = mb[2 * j]; m_hi = mb[2 * j + 1]; }
+#pragma unroll
+                for (int i8 = 0; i8 < 8; ++i8) {
+                    const int rrow = i8 * 4 + (ln >> 4);       // row within the round
+                    const int row = j * 32 + rrow;               // row within the wave's sub-tile
+                    const int q = cur.q0 + wq * 128 + row;
+                    u32x4 val = *(const u32x4 *)(ep + rrow * 256 + ((c ^ (rrow & 15)) << 4));
                     if (EPI == EPI_RELU) {
+                        // After ReLU every half word is a non-negative bf16, so adding 0x7fff
+                        // carries into its top bit exactly when it is > 0.  Bits 0..3 of the
+                        // byte: low halves of the four words, bits 4..7: high halves.
+                        uint32_t u = 0;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+                        for (int w = 0; w < 4; ++w)
+                            u |= ((val[w] + 0x7fff7fffu) & 0x80008000u) >> (15 - w);
+                        const uint32_t byte = (u | (u >> 12)) & 0xffu;
+                        if (i8 < 4) m_lo |= byte << (8 * i8);
+                        else m_hi |= byte << (8 * (i8 - 4));
                     }
-                    bf16x4 o;
+                    if (EPI == EPI_MASK) {
+                        uint32_t byte = (i8 < 4 ? m_lo >> (8 * i8) : m_hi >> (8 * (i8 - 4))) & 0xffu;
+                        byte |= byte << 12;   // bit w -> bit w, bit 4+w -> bit 16+w
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (bf16)v[r];
-                    const int c = i * 4 + g;
-                    *(bf16x4 *)(ep + row * 256 + ((c ^ (row & 15)) << 4) + ((lane >> 5) << 3)) = o;
-                }
-            }
-        }
-        bf16 *Cout = a.Cout + (size_t)t.e * a.c_batch;
-        const int c = lane & 15;
-        const int p = t.p0 + wp * 128 + c * 8;
-        // ReLU mask: byte `it` of a lane's 32 bytes says which of the eight elements of the
-        // 16-byte piece the lane handles in iteration `it` are > 0.  EPI_RELU (the first
-        // forward GEMM) writes the bits, EPI_MASK (the gradient w.r.t. the hidden
-        // activations, same tiling and same lane-to-element map) applies them: 32 bytes per
-        // lane instead of a second read of the activations.
-        uint32_t *bits = EPI == EPI_NONE ? nullptr
-                         : (uint32_t *)(a.relu_bits + (size_t)t.index * kReluBitsPerTile +
-                                        (size_t)(wave * 64 + lane) * 32);
-        uint32_t mb[8];
-        if (EPI == EPI_MASK) {
-            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) { mb[w] = b0[w]; mb[4 + w] = b1[w]; }
-        }
-#pragma nounroll
-        for (int it8 = 0; it8 < 4; ++it8) {
-            // the eight mask bytes of this round of eight iterations
-            uint32_t m_lo = 0u, m_hi = 0u;
-            if (EPI == EPI_MASK) {
-                m_lo = it8 == 0 ? mb[0] : (it8 == 1 ? mb[2] : (it8 == 2 ? mb[4] : mb[6]));
-                m_hi = it8 == 0 ? mb[1] : (it8 == 1 ? mb[3] : (it8 == 2 ? mb[5] : mb[7]));
-            }
-#pragma unroll
-            for (int i8 = 0; i8 < 8; ++i8) {
-                const int row = (it8 * 8 + i8) * 4 + (lane >> 4);
-                const int q = t.q0 + wq * 128 + row;
-                u32x4 val = *(const u32x4 *)(ep + row * 256 + ((c ^ (row & 15)) << 4));
-                if (EPI == EPI_RELU) {
-                    // After ReLU every half word is a non-negative bf16, so adding 0x7fff
-                    // carries into its top bit exactly when it is > 0.  Bits 0..3 of the
-                    // byte: low halves of the four words, bits 4..7: high halves.
-                    uint32_t u = 0;
-#pragma unroll
-                    for (int w = 0; w < 4; ++w)
-                        u |= ((val[w] + 0x7fff7fffu) & 0x80008000u) >> (15 - w);
-                    const uint32_t byte = (u | (u >> 12)) & 0xffu;
-                    if (i8 < 4) m_lo |= byte << (8 * i8);
-                    else m_hi |= byte << (8 * (i8 - 4));
-                }
-                if (EPI == EPI_MASK) {
-                    uint32_t byte = (i8 < 4 ? m_lo >> (8 * i8) : m_hi >> (8 * (i8 - 4))) & 0xffu;
-                    byte |= byte << 12;   // bit w -> bit w, bit 4+w -> bit 16+w
-#pragma unroll
-                    for (int w = 0; w < 4; ++w)
-                        val[w] &= ((byte >> w) & 0x10001u) * 0xffffu;
-                }
-                if (q < t.qlim && p < a.Pdim) {
-                    const size_t off = (size_t)q * a.ldc + p;
-                    const int slot = MODE == MODE_ROUTER_DX
-                                         ? ((const int32_t *)(lds + kRingBytes))[wq * 128 + row] : -1;
-                    if (MODE == MODE_ROUTER_DX && slot >= 0) {
-                        // add the token's row of the expert-side gradient (fp32 add, one rounding)
-                        const u32x4 gsrc = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
-                        const bf16x8 va = __builtin_bit_cast(bf16x8, val);
-                        const bf16x8 vb = __builtin_bit_cast(bf16x8, gsrc);
-                        bf16x8 vo;
-#pragma unroll
-                        for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
-                        val = __builtin_bit_cast(u32x4, vo);
+                        for (int w = 0; w < 4; ++w) val[w] &= ((byte >> w) & 0x10001u) * 0xffffu;
                     }
-                    *(u32x4 *)(Cout + off) = val;
+                    int slot = -1;
+                    if (MODE == MODE_ROUTER_DX) slot = __shfl(j < 2 ? slot_lo : slot_hi, row & 63);
+                    if (q < cur.qlim && p < a.Pdim) {
+                        const size_t off = (size_t)q * a.ldc + p;
+                        if (MODE == MODE_ROUTER_DX && slot >= 0) {
+                            // add the token's row of the expert-side gradient (fp32 add, one rounding)
+                            const u32x4 gsrc = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
+                            const bf16x8 va = __builtin_bit_cast(bf16x8, val);
+                            const bf16x8 vb = __builtin_bit_cast(bf16x8, gsrc);
+                            bf16x8 vo;
+#pragma unroll
+                            for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
+                            val = __builtin_bit_cast(u32x4, vo);
+                        }
+                        *(u32x4 *)(Cout + off) = val;
+                    }
                 }
+                if (EPI == EPI_RELU) *(uint2 *)(bits + 2 * j) = make_uint2(m_lo, m_hi);
             }
-            if (EPI == EPI_RELU) *(uint2 *)(bits + 2 * it8) = make_uint2(m_lo, m_hi);
         }
-        __syncthreads();   // the epilogue's LDS reads are done before the ring is refilled
+        if (!have_next) break;
+        cur = nxt;
     }
+    SW_WAIT_VMCNT(0);   // the trailing (zero) loads have landed
+#undef SW_K_STEP
+#undef SW_ISSUE_ONE
+#undef SW_READ_GROUP
+#undef SW_MFMA_PAIR
 }
 #undef SW_WAIT_VMCNT
 

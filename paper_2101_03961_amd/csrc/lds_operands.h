@@ -161,8 +161,9 @@ struct DirectOperand64 {
     int klim;
     uint32_t frag0;      // LDS byte offset of the lane's fragment, sub-step 0
 
-    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim_,
-                                         int lane, int wave, int wave_rows) {
+    // load side: point at rows [row0, ...) of a [rowlim][ld] matrix, k < klim_
+    __device__ __forceinline__ void init_load(const bf16 *base, int ld, int row0, int rowlim,
+                                              int klim_, int lane, int wave) {
         rsrc = make_rsrc(base, (uint32_t)rowlim * (uint32_t)ld * 2u);
         const int r = wave * 8 + (lane >> 3);           // + 32 per load
         const int c = (lane & 7) ^ ((r >> 1) & 7);
@@ -170,6 +171,11 @@ struct DirectOperand64 {
         voff = ((uint32_t)(row0 + r) * (uint32_t)ld + (uint32_t)c8) * 2u;
         row_step = 32u * (uint32_t)ld * 2u;
         klim = klim_;
+    }
+    // every load reads zeros from now on
+    __device__ __forceinline__ void disable_load() { klim = 0; }
+    // read side: wave_rows = first row (0 or 128) of the wave's half of the tile
+    __device__ __forceinline__ void init_frag(int lane, int wave_rows) {
         const int fr = wave_rows + (lane & 31);
         frag0 = (uint32_t)(fr * 128 + (((lane >> 5) ^ ((fr >> 1) & 7)) << 4));
     }
@@ -197,8 +203,8 @@ struct TransOperand64 {
     uint32_t k_step;        // bytes of one k row
     uint32_t frag_base[4];  // LDS byte offset of the lane's share of fragment i (ks = 0, first half)
 
-    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim,
-                                         int lane, int wave, int wave_rows) {
+    __device__ __forceinline__ void init_load(const bf16 *base, int ld, int row0, int rowlim,
+                                              int klim, int lane, int wave) {
         rsrc = make_rsrc(base, (uint32_t)klim * (uint32_t)ld * 2u);
         k_step = (uint32_t)ld * 2u;
         const int kk = lane >> 5, pc = lane & 31;
@@ -211,6 +217,9 @@ struct TransOperand64 {
                             ? ((uint32_t)(wave * 16 + kk) * (uint32_t)ld + (uint32_t)row) * 2u
                             : kOobOffset;
         }
+    }
+    __device__ __forceinline__ void disable_load() { voff[0] = voff[1] = kOobOffset; }
+    __device__ __forceinline__ void init_frag(int lane, int wave_rows) {
         const int g = lane >> 4, j = lane & 15;
         const int kq = j >> 2;
 #pragma unroll
