@@ -59,7 +59,7 @@ def kernel_work(shape, kept, elt):
         "router_dlogits": (0.0, 2.0 * T * E * 4 + T * 512 + T * 8, "hbm"),
         "router_dx_mfma": (6.0 * T * d * E, T * 512 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr_mfma": (4.0 * T * d * E, T * d * elt + T * 512, "hbm"),
-        "router_dWr_reduce": (0.0, d * E * 4.0, "hbm"),
+        "router_dWr_reduce": (0.0, -(-T // (-(-(-(-T // 85)) // 64) * 64)) * d * 256 * 4.0 + d * E * 4.0, "hbm"),
         "router_dx": (2.0 * T * d * E, T * E * 4 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr": (2.0 * T * d * E, T * d * elt + T * E * 4, "hbm"),
         "router_dbr": (0.0, T * E * 4.0, "hbm"),

@@ -97,10 +97,11 @@ enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
 // One output tile of one expert.
 struct Tile {
     int e, p0, q0, qlim, klim;
-    int index;      // (e * tiles_p + p tile) * tiles_q + q tile
+    int index;      // number of the tile among all tiles of the launch
 };
 
-// Tiles are numbered expert-major, then p tile, then q tile (fastest), and the
+// Tiles are numbered expert-major; inside an expert the dimension with fewer tiles runs
+// fastest, so that the tiles sharing a tile of the larger operand are neighbours.  The
 // number line is cut into kXcds equal ranges, one per XCD.  Block b runs on XCD
 // b % kXcds (workgroups are dealt to XCDs round-robin) and walks that XCD's range
 // with the stride of the blocks sharing the XCD, so at any moment the CUs of an
@@ -113,8 +114,14 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
     for (; L < L_end; L += stride) {
         const int e = L / tiles_pe;
         const int rem = L - e * tiles_pe;
-        const int pt = rem / a.tiles_q;
-        const int qt = rem - pt * a.tiles_q;
+        int pt, qt;
+        if (a.tiles_q <= a.tiles_p) {
+            pt = rem / a.tiles_q;
+            qt = rem - pt * a.tiles_q;
+        } else {
+            qt = rem / a.tiles_p;
+            pt = rem - qt * a.tiles_p;
+        }
         int kept = 0;
         if (MODE == MODE_EXPERTS) kept = a.kept[e];
         if (MODE == MODE_ROUTER_DWR) kept = min(a.tps, a.T_total - e * a.tps);
