@@ -68,27 +68,26 @@ __global__ __launch_bounds__(256) void positions_kernel(
 }
 
 // -----------------------------------------------------------------------------
-// Dispatch: Xd[e_t * C + pos_t][:] = x[t][:] for kept tokens.  One thread per
-// 16-byte chunk; cpr = chunks per row.
+// Dispatch: Xd[e_t * C + pos_t][:] = x[t][:] for kept tokens.  One wave per token
+// (its index loads are wave-uniform), one 16-byte chunk per lane and pass;
+// cpr = chunks per row.
 // -----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dispatch_kernel(const Chunk16 *__restrict__ x,
                                                        Chunk16 *__restrict__ Xd,
                                                        const int32_t *__restrict__ idx,
                                                        const int32_t *__restrict__ pos,
                                                        const uint8_t *__restrict__ dropped,
-                                                       size_t total_chunks, int cpr, int C) {
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < total_chunks; c += stride) {
-        const int t = (int)(c / cpr);
-        const int col = (int)(c % cpr);
-        if (dropped[t]) continue;
-        const size_t slot = (size_t)idx[t] * C + pos[t];
-        Xd[slot * cpr + col] = x[c];
-    }
+                                                       int T, int cpr, int C) {
+    const int lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T || dropped[t]) return;
+    const size_t slot = (size_t)idx[t] * C + pos[t];
+    for (int col = lane; col < cpr; col += kWave) Xd[slot * cpr + col] = x[(size_t)t * cpr + col];
 }
 
 // -----------------------------------------------------------------------------
 // Combine: y[t][:] = gate[t] * O[slot_t][:] for kept tokens, +0 for dropped.
+// One wave per token.
 // -----------------------------------------------------------------------------
 template <typename XT>
 __global__ __launch_bounds__(256) void combine_kernel(const Chunk16 *__restrict__ O,
@@ -97,23 +96,24 @@ __global__ __launch_bounds__(256) void combine_kernel(const Chunk16 *__restrict_
                                                       const int32_t *__restrict__ pos,
                                                       const uint8_t *__restrict__ dropped,
                                                       const float *__restrict__ gate,
-                                                      size_t total_chunks, int cpr, int C) {
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < total_chunks; c += stride) {
-        const int t = (int)(c / cpr);
-        const int col = (int)(c % cpr);
-        Chunk16 out = {{0u, 0u, 0u, 0u}};
-        if (!dropped[t]) {
-            const size_t slot = (size_t)idx[t] * C + pos[t];
-            const Chunk16 in = O[slot * cpr + col];
-            float v[Vec<XT>::N];
-            unpack<XT>(in, v);
-            const float g = gate[t];
+                                                      int T, int cpr, int C) {
+    const int lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    if (dropped[t]) {
+        const Chunk16 zero = {{0u, 0u, 0u, 0u}};
+        for (int col = lane; col < cpr; col += kWave) y[(size_t)t * cpr + col] = zero;
+        return;
+    }
+    const size_t slot = (size_t)idx[t] * C + pos[t];
+    const float g = gate[t];
+    for (int col = lane; col < cpr; col += kWave) {
+        const Chunk16 in = O[slot * cpr + col];
+        float v[Vec<XT>::N];
+        unpack<XT>(in, v);
 #pragma unroll
-            for (int i = 0; i < Vec<XT>::N; ++i) v[i] *= g;
-            out = pack<XT>(v);
-        }
-        y[c] = out;
+        for (int i = 0; i < Vec<XT>::N; ++i) v[i] *= g;
+        y[(size_t)t * cpr + col] = pack<XT>(v);
     }
 }
 
@@ -158,14 +158,6 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
 // -----------------------------------------------------------------------------
 // launchers
 // -----------------------------------------------------------------------------
-static inline unsigned stream_grid(size_t total_chunks) {
-    size_t blocks = (total_chunks + 255) / 256;
-    const size_t cap = 256 * 16;   // 16 blocks per CU; grid-stride beyond that
-    if (blocks > cap) blocks = cap;
-    if (blocks < 1) blocks = 1;
-    return (unsigned)blocks;
-}
-
 hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, hipStream_t s) {
     hipError_t err;
@@ -183,11 +175,10 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *w
         ProfScope ps("dispatch_gather", s);
         const int vec = dtype == SW_BF16 ? 8 : 4;
         const int cpr = (int)(w.d / vec);
-        const size_t total = (size_t)w.T * cpr;
-        hipLaunchKernelGGL(dispatch_kernel, dim3(stream_grid(total)), dim3(256), 0, s,
-                           (const Chunk16 *)x, (Chunk16 *)(ws + w.Xd),
+        hipLaunchKernelGGL(dispatch_kernel, dim3((unsigned)ceil_div(w.T, 256 / kWave)), dim3(256),
+                           0, s, (const Chunk16 *)x, (Chunk16 *)(ws + w.Xd),
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), total, cpr, (int)w.C);
+                           (const uint8_t *)(ws + w.dropped), (int)w.T, cpr, (int)w.C);
         err = hipGetLastError();
     }
     return err;
@@ -197,19 +188,19 @@ hipError_t launch_combine(const Workspace &w, int dtype, char *ws, void *y, hipS
     ProfScope ps("combine_scatter", s);
     const int vec = dtype == SW_BF16 ? 8 : 4;
     const int cpr = (int)(w.d / vec);
-    const size_t total = (size_t)w.T * cpr;
+    const dim3 grid((unsigned)ceil_div(w.T, 256 / kWave));
     if (dtype == SW_BF16)
-        hipLaunchKernelGGL(combine_kernel<bf16>, dim3(stream_grid(total)), dim3(256), 0, s,
+        hipLaunchKernelGGL(combine_kernel<bf16>, grid, dim3(256), 0, s,
                            (const Chunk16 *)(ws + w.O), (Chunk16 *)y,
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate), total,
-                           cpr, (int)w.C);
+                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
+                           (int)w.T, cpr, (int)w.C);
     else
-        hipLaunchKernelGGL(combine_kernel<float>, dim3(stream_grid(total)), dim3(256), 0, s,
+        hipLaunchKernelGGL(combine_kernel<float>, grid, dim3(256), 0, s,
                            (const Chunk16 *)(ws + w.O), (Chunk16 *)y,
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate), total,
-                           cpr, (int)w.C);
+                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
+                           (int)w.T, cpr, (int)w.C);
     return hipGetLastError();
 }
 
