@@ -20,6 +20,10 @@
  *     detected on the host before anything is launched; nothing is thrown
  *     across the ABI.  Inputs must be finite (NaN/Inf behaviour unspecified).
  *   - Gradients are overwritten, not accumulated.
+ *   - An empty batch (T = 0) is legal: forward writes expert_counts = 0 and
+ *     aux_loss = 0 (both fractions of Eq. 4 are empty sums), backward writes
+ *     zeros to dW_r, db_r, dW_in, dW_out; the per-token arguments and the
+ *     workspace are not touched and may be NULL.
  *   - act_dtype SW_BF16: x, W_in, W_out, y, dy, dx, dW_in, dW_out are bfloat16
  *     (d_model and d_ff must be multiples of 8); products are accumulated in
  *     fp32 and rounded once (nearest-even) at each store.  SW_F32: the same
@@ -52,7 +56,7 @@ typedef enum {
 
 /* Layer description (host struct, passed by pointer, copied by the callee). */
 typedef struct {
-    int64_t T;               /* tokens in the batch (>= 1, < 2^31)                  */
+    int64_t T;               /* tokens in the batch (0 .. 2^31 - 1)                 */
     int64_t d_model;         /* token width                                         */
     int64_t d_ff;            /* expert hidden width                                 */
     int64_t E;               /* number of experts (1 .. 4096)                       */

@@ -102,6 +102,13 @@ double swo_aux_loss(int64_t T, int64_t E, const int32_t *expert_index, const dou
     double loss = 0.0;
     for (int64_t i = 0; i < E; ++i) counts[i] = 0;
     for (int64_t t = 0; t < T; ++t) counts[expert_index[t]] += 1;
+    if (T == 0) { /* empty batch: both fractions are empty sums; the loss is taken as 0 */
+        for (int64_t i = 0; i < E; ++i) {
+            if (f_out) f_out[i] = 0.0;
+            if (P_out) P_out[i] = 0.0;
+        }
+        return 0.0;
+    }
     for (int64_t i = 0; i < E; ++i) {
         double f_i = (double)counts[i] / (double)T;
         double P_i = 0.0;

@@ -13,7 +13,7 @@ namespace sw {
 int check_config(const switch_config *cfg) {
     if (!cfg) return SW_ERR_NULL;
     if (cfg->act_dtype != SW_F32 && cfg->act_dtype != SW_BF16) return SW_ERR_DTYPE;
-    if (cfg->T < 1 || cfg->T >= (int64_t)1 << 31) return SW_ERR_SHAPE;
+    if (cfg->T < 0 || cfg->T >= (int64_t)1 << 31) return SW_ERR_SHAPE;
     if (cfg->E < 1 || cfg->E > 4096) return SW_ERR_SHAPE;
     if (cfg->d_model < 1 || cfg->d_ff < 1) return SW_ERR_SHAPE;
     if (cfg->d_model >= (int64_t)1 << 24 || cfg->d_ff >= (int64_t)1 << 24) return SW_ERR_SHAPE;
@@ -68,6 +68,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.wsplit_b = take(d * 256 * 2);
     w.dl_split = take(T * 256 * 2);
     w.tps_m = ceil_div(ceil_div(w.T, 85), 64) * 64;
+    if (w.tps_m < 64) w.tps_m = 64;   // empty batch
     w.nsplit_m = ceil_div(w.T, w.tps_m);
     w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
     w.relu_bits = take(E * ceil_div(f, kGemmTile) * ceil_div(C, kGemmTile) * kReluBitsPerTile);
@@ -150,6 +151,21 @@ int switch_workspace_size(const switch_config *cfg, size_t *bytes_out) {
     return SW_OK;
 }
 
+// 4-byte words set to zero (stays valid under stream capture, unlike a memset node)
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *__restrict__ p, size_t words) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += stride) p[i] = 0u;
+}
+
+static int fill_zero(void *p, size_t bytes, hipStream_t s) {
+    const size_t words = bytes / 4;
+    if (words == 0) return SW_OK;
+    size_t blocks = (words + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint32_t *)p, words);
+    return status_of(hipGetLastError());
+}
+
 int switch_forward(const switch_config *cfg, const void *x, const float *W_r, const float *b_r,
                    const void *W_in, const void *W_out, void *y, int32_t *expert_index,
                    float *gate, int32_t *position_in_expert, uint8_t *dropped,
@@ -157,6 +173,11 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
                    size_t workspace_bytes, void *hip_stream) {
     int st = check_config(cfg);
     if (st != SW_OK) return st;
+    if (cfg->T == 0) {   // empty batch: no token, no routing; counts and loss are zero
+        if (!expert_counts || !aux_loss) return SW_ERR_NULL;
+        if ((st = fill_zero(expert_counts, (size_t)cfg->E * 4, (hipStream_t)hip_stream))) return st;
+        return fill_zero(aux_loss, 4, (hipStream_t)hip_stream);
+    }
     if (!x || !W_r || !W_in || !W_out || !y || !expert_index || !gate || !position_in_expert ||
         !dropped || !expert_counts || !aux_loss)
         return SW_ERR_NULL;
@@ -194,9 +215,20 @@ int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const
     (void)b_r;   // the bias enters the gradients only through the saved probabilities
     int st = check_config(cfg);
     if (st != SW_OK) return st;
+    if (!isfinite(d_aux)) return SW_ERR_VALUE;
+    if (cfg->T == 0) {   // empty batch: every weight gradient is an empty sum
+        if (!dW_r || !dW_in || !dW_out) return SW_ERR_NULL;
+        if (!aligned16(dW_r) || !aligned16(dW_in) || !aligned16(dW_out)) return SW_ERR_ALIGN;
+        hipStream_t s0 = (hipStream_t)hip_stream;
+        const size_t elt = cfg->act_dtype == SW_BF16 ? 2 : 4;
+        const size_t wbytes = (size_t)cfg->E * cfg->d_model * cfg->d_ff * elt;
+        if ((st = fill_zero(dW_r, (size_t)cfg->d_model * cfg->E * 4, s0))) return st;
+        if (db_r && (st = fill_zero(db_r, (size_t)cfg->E * 4, s0))) return st;
+        if ((st = fill_zero(dW_in, wbytes, s0))) return st;
+        return fill_zero(dW_out, wbytes, s0);
+    }
     if (!dy || !x || !W_r || !W_in || !W_out || !dx || !dW_r || !dW_in || !dW_out)
         return SW_ERR_NULL;
-    if (!isfinite(d_aux)) return SW_ERR_VALUE;
     if (!aligned16(dy) || !aligned16(x) || !aligned16(W_r) || !aligned16(W_in) ||
         !aligned16(W_out) || !aligned16(dx) || !aligned16(dW_r) || !aligned16(dW_in) ||
         !aligned16(dW_out))

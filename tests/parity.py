@@ -90,11 +90,14 @@ def row_errors(a: np.ndarray, ref: np.ndarray, block_dims: int = 1):
     return float(blk.max()), float(elem.max())
 
 
-def assert_close(name, a, ref, dtype):
+def assert_close(name, a, ref, dtype, widen=1.0):
+    """`widen` > 1 multiplies both bounds; only for blocks whose every element hangs on a
+    few ill-conditioned scalars (see test_few_tokens)."""
     assert np.all(np.isfinite(np.asarray(a, dtype=np.float64))), name + " has non-finite values"
     row, elem = row_errors(a, ref, BLOCK_DIMS[name.split("[")[0]])
-    assert row <= TOL[dtype], "%s: max block error %.3e > %.1e" % (name, row, TOL[dtype])
-    assert elem <= ELEM_TOL[dtype], "%s: max element error %.3e > %.1e" % (name, elem, ELEM_TOL[dtype])
+    tol, etol = TOL[dtype] * widen, ELEM_TOL[dtype] * widen
+    assert row <= tol, "%s: max block error %.3e > %.1e" % (name, row, tol)
+    assert elem <= etol, "%s: max element error %.3e > %.1e" % (name, elem, etol)
     return row
 
 
@@ -152,8 +155,10 @@ def check_dropped_rows_are_zero(gpu, dtype):
     assert np.all(rows == 0.0) and not np.any(np.signbit(rows)), "dropped rows must be +0"
 
 
-def compare_full(shape, inp, d_aux=1.0):
-    """Whole-tensor parity of forward and backward; returns a dict of errors."""
+def compare_full(shape, inp, d_aux=1.0, widen=None):
+    """Whole-tensor parity of forward and backward; returns a dict of errors.
+    widen: optional {tensor name: factor on its tolerance}."""
+    widen = widen or {}
     tol = shape.dtype
     npi = np_inputs(inp)
     _, gpu = run_gpu(shape, inp, d_aux)
@@ -166,7 +171,7 @@ def compare_full(shape, inp, d_aux=1.0):
     bwd = oracle.backward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], npi["dy"], fwd,
                           shape.alpha, d_aux)
     for k in ("dx", "dW_r", "db_r", "dW_in", "dW_out"):
-        errs[k] = assert_close(k, gpu[k], bwd[k], tol)
+        errs[k] = assert_close(k, gpu[k], bwd[k], tol, widen.get(k, 1.0))
     return errs, gpu, fwd, bwd
 
 

@@ -41,7 +41,7 @@ def test_capacity_and_workspace_host_functions():
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(T=0), -2), (dict(E=0), -2), (dict(E=5000), -2), (dict(d_model=0), -2),
+    (dict(T=-1), -2), (dict(T=2**31), -2), (dict(E=0), -2), (dict(E=5000), -2), (dict(d_model=0), -2),
     (dict(d_model=12), -2),            # bf16 rows must be whole 16-byte chunks
     (dict(d_ff=100), -2),
     (dict(capacity_factor=0.0), -3), (dict(capacity_factor=-1.0), -3),

@@ -75,6 +75,70 @@ def test_capacity_zero_everything_dropped(dtype):
     assert np.abs(gpu["dx"]).max() > 0          # the auxiliary loss still reaches x
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,E,cf", [
+    (1, 4, 4.0),     # a single token, capacity 1
+    (7, 16, 4.0),    # more experts than tokens, capacity 1
+    (7, 16, 1.0),    # ... and capacity floor(7/16) = 0
+    (255, 3, 1.0),   # one short token block
+    (257, 3, 1.0),   # one token into the second block
+])
+def test_few_tokens(dtype, T, E, cf):
+    from parity import compare_full
+    s = SwitchShape("t", T, 64, 72, E, cf, dtype=dtype, seed_index=54)
+    inp = make_inputs(s, _dev())
+    # With a handful of kept tokens all of dW_r and db_r is a few gate gradients
+    # <dy_t, o_t> times fixed vectors.  Each is one 64-term dot product of mixed signs whose
+    # bf16 operand rounding (2^-9 per term) is not averaged down by anything, so the relative
+    # error of the whole block is that of the worst-conditioned dot product.
+    widen = {"dW_r": 5.0, "db_r": 5.0} if (dtype == "bf16" and T < 16) else None
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.3, widen=widen)
+    _report("few tokens %s %s" % (dtype, (T, E, cf)), errs)
+    assert fwd["capacity"] == int(np.floor(T / E * cf))
+
+
+@pytest.mark.parametrize("T,d,f,E,cf", [
+    (1500, 96, 64, 128, 2.0),    # the widest router the matrix-core kernel takes
+    (1500, 96, 64, 124, 2.0),    # four experts short of it
+    (3000, 64, 64, 132, 1.0),    # one step wider: vector-ALU router, bf16 tokens
+    (3000, 64, 64, 256, 1.0),    # two experts per lane in the softmax kernels
+    (2048, 72, 64, 126, 1.0),    # E not a multiple of 4: vector-ALU router
+])
+def test_bf16_router_widths(T, d, f, E, cf):
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype="bf16", seed_index=55)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=1.0)
+    _report("bf16 router E=%d" % E, errs)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_empty_batch(dtype):
+    """T = 0: counts and loss zero, weight gradients zero, nothing else touched."""
+    import torch
+    import oracle
+    from paper_2101_03961_amd.layer import SwitchLayer
+    s = SwitchShape("t", 0, 64, 72, 4, 1.0, dtype=dtype, seed_index=56)
+    inp = make_inputs(s, _dev())
+    layer = SwitchLayer(0, 64, 72, 4, 1.0, s.alpha, dtype, device=_dev())
+    layer.expert_counts.fill_(7)
+    layer.aux_loss.fill_(7.0)
+    layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], None)
+    layer.alloc_grads(with_bias=True)
+    for g in (layer.dW_r, layer.db_r, layer.dW_in, layer.dW_out):
+        g.fill_(1.0)
+    layer.backward(inp["dy"], inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], None, 1.0)
+    torch.cuda.synchronize()
+    to_np = lambda t: t.float().cpu().numpy()
+    ref = oracle.forward(to_np(inp["x"]), to_np(inp["W_r"]), to_np(inp["W_in"]),
+                         to_np(inp["W_out"]), 1.0, s.alpha)
+    assert ref["aux_loss"] == 0.0 and ref["capacity"] == 0 and ref["y"].shape == (0, 64)
+    assert float(layer.aux_loss[0]) == ref["aux_loss"]
+    assert layer.expert_counts.tolist() == ref["expert_counts"].tolist() == [0, 0, 0, 0]
+    for g in (layer.dW_r, layer.db_r, layer.dW_in, layer.dW_out):
+        assert float(g.float().abs().max()) == 0.0
+
+
 def test_exact_ties_go_to_expert_zero():
     from parity import run_gpu
     s = SwitchShape("t", 300, 64, 64, 6, 1.0, dtype="bf16", seed_index=52)

@@ -413,3 +413,45 @@ def test_expert_subset_matches_full_run():
     np.testing.assert_array_equal(part["dW_out"][1], full["dW_out"][1])
     np.testing.assert_array_equal(part["dW_r"], full_m["dW_r"])
     np.testing.assert_array_equal(part["dx"][in_sel], full_m["dx"][in_sel])
+
+
+def test_token_subset_matches_full_run():
+    """Single-token evaluation (used by the full-size GPU checks) is the full run restricted
+    to those tokens, bit for bit, when dy is zero elsewhere."""
+    s = SwitchShape("t", 90, 12, 20, 4, 0.8, dtype="f32", seed_index=22)
+    inp = _np_inputs(s)
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.8, 0.01)
+    kept = np.flatnonzero(fwd["dropped"] == 0)
+    drop = np.flatnonzero(fwd["dropped"] == 1)
+    assert len(drop) > 0
+    toks = [int(kept[0]), int(kept[7]), int(drop[0]), int(kept[-1])]
+    part_f = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.8, 0.01,
+                            token_sel=toks)
+    np.testing.assert_array_equal(part_f["y"][toks], fwd["y"][toks])
+    others = np.setdiff1d(np.arange(s.T), toks)
+    assert np.all(np.isnan(part_f["y"][others]))
+    sel = np.zeros(s.T, dtype=bool)
+    sel[toks] = True
+    dy_masked = inp["dy"] * sel[:, None]
+    part = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], dy_masked, fwd, 0.01,
+                           1.0, token_sel=toks)
+    full_m = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], dy_masked, fwd,
+                             0.01, 1.0)
+    np.testing.assert_array_equal(part["dx"][toks], full_m["dx"][toks])
+    np.testing.assert_array_equal(part["dW_r"], full_m["dW_r"])
+    np.testing.assert_array_equal(part["db_r"], full_m["db_r"])
+    assert part["dW_in"].shape[0] == 0
+
+
+def test_empty_batch():
+    """No tokens: empty sums everywhere; the loss (0/0 in Eq. 4) is taken as 0."""
+    x = np.zeros((0, 8), np.float32)
+    W_r = np.ones((8, 3), np.float32)
+    W_in = np.ones((3, 8, 4), np.float32)
+    W_out = np.ones((3, 4, 8), np.float32)
+    fwd = oracle.forward(x, W_r, W_in, W_out, 1.25, 0.01)
+    assert fwd["capacity"] == 0 and fwd["aux_loss"] == 0.0
+    assert fwd["expert_counts"].tolist() == [0, 0, 0] and fwd["y"].shape == (0, 8)
+    bwd = oracle.backward(x, W_r, W_in, W_out, x.copy(), fwd, 0.01, 1.0)
+    for k in ("dW_r", "db_r", "dW_in", "dW_out"):
+        assert not bwd[k].any()
