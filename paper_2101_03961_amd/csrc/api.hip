@@ -53,6 +53,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.counts = take(E * 4);
     w.kept = take(E * 4);
     w.slot_token = take(E * C * 4);
+    w.tok_slot = take(T * 4);
     w.Xd = take(E * C * d * w.elt);
     w.A = take(E * C * f * w.elt);
     w.O = take(E * C * d * w.elt);

@@ -47,6 +47,7 @@ struct Workspace {
     size_t counts;              // i32 [E]
     size_t kept;                // i32 [E]      min(count, C)
     size_t slot_token;          // i32 [E][C]   token held by each slot (valid for slot < kept[e])
+    size_t tok_slot;            // i32 [T]      slot (e * C + pos) of each kept token, -1 for dropped ones
     size_t Xd;                  // act [E][C][d]   dispatched tokens
     size_t A;                   // act [E][C][f]   ReLU(Xd W_in)
     size_t O;                   // act [E][C][d]   A W_out

@@ -54,7 +54,8 @@ __global__ __launch_bounds__(256) void positions_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ local_rank,
     const int32_t *__restrict__ block_off, int32_t *__restrict__ pos_out,
     uint8_t *__restrict__ dropped_out, int32_t *__restrict__ pos_ws,
-    uint8_t *__restrict__ dropped_ws, int32_t *__restrict__ slot_token, int T, int E, int C) {
+    uint8_t *__restrict__ dropped_ws, int32_t *__restrict__ slot_token,
+    int32_t *__restrict__ tok_slot, int T, int E, int C) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= T) return;
     const int e = idx[t];
@@ -65,6 +66,7 @@ __global__ __launch_bounds__(256) void positions_kernel(
     dropped_out[t] = dr;
     dropped_ws[t] = dr;
     if (!dr) slot_token[(size_t)e * C + p] = t;
+    tok_slot[t] = dr ? -1 : e * C + p;
 }
 
 // -----------------------------------------------------------------------------
@@ -167,7 +169,8 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *w
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.local_rank),
                            (const int32_t *)(ws + w.block_off), position_in_expert, dropped,
                            (int32_t *)(ws + w.pos), (uint8_t *)(ws + w.dropped),
-                           (int32_t *)(ws + w.slot_token), (int)w.T, (int)w.E, (int)w.C);
+                           (int32_t *)(ws + w.slot_token), (int32_t *)(ws + w.tok_slot), (int)w.T,
+                           (int)w.E, (int)w.C);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (w.C == 0) return hipSuccess;

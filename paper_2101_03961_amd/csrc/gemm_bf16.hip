@@ -73,9 +73,7 @@ struct GemmArgs {
     const int32_t *kept;
     int tiles_q, tiles_p, total_tiles;
     // router backward uses of the kernel (see GemmMode)
-    const int32_t *tok_idx, *tok_pos;   // ROUTER_DX: slot of each token's row of the addend
-    const uint8_t *tok_dropped;
-    int cap;
+    const int32_t *tok_slot;            // ROUTER_DX: row of the addend for each token, -1: none
     float *Cf;                          // ROUTER_DWR: fp32 partial sums [split][q][p]
     int T_total, tps;                   // ROUTER_DWR: tokens, tokens per split
 };
@@ -280,10 +278,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         // (-1: dropped token or past the end: nothing to add)
         int slot_lo = -1, slot_hi = -1;
         if (MODE == MODE_ROUTER_DX) {
+            // (asked for here, used only in the epilogue: nothing waits for them before)
             const int q = cur.q0 + wq * 128 + lane;
-            if (q < cur.qlim && !a.tok_dropped[q]) slot_lo = a.tok_idx[q] * a.cap + a.tok_pos[q];
-            if (q + 64 < cur.qlim && !a.tok_dropped[q + 64])
-                slot_hi = a.tok_idx[q + 64] * a.cap + a.tok_pos[q + 64];
+            if (q < cur.qlim) slot_lo = a.tok_slot[q];
+            if (q + 64 < cur.qlim) slot_hi = a.tok_slot[q + 64];
         }
         uint32_t mb[8];   // EPI_MASK: the lane's 32 bytes of ReLU bits of this tile
         auto bits_of = [&](int ln) {
@@ -367,6 +365,23 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             // > 0.  EPI_RELU (the first forward GEMM) writes the bits, EPI_MASK (the gradient
             // w.r.t. the hidden activations, same tiling and same lane-to-element map)
             // applies them: 32 bytes per lane instead of a second read of the activations.
+            // ROUTER_DX: all 32 addend pieces of the lane are asked for first, at once, so that
+            // their latency overlaps the turn-around instead of adding up round by round
+            u32x4 addend[4][8];
+            bool has_addend[4][8];
+            if (MODE == MODE_ROUTER_DX) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i8 = 0; i8 < 8; ++i8) {
+                        const int row = j * 32 + i8 * 4 + (ln >> 4);
+                        const int slot = __shfl(j < 2 ? slot_lo : slot_hi, row & 63);
+                        has_addend[j][i8] = slot >= 0 && p < a.Pdim;
+                        addend[j][i8] = u32x4{0u, 0u, 0u, 0u};
+                        if (has_addend[j][i8])
+                            addend[j][i8] = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
+                    }
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int wrow = ln & 31;
@@ -414,15 +429,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
                         for (int w = 0; w < 4; ++w) val[w] &= ((byte >> w) & 0x10001u) * 0xffffu;
                     }
-                    int slot = -1;
-                    if (MODE == MODE_ROUTER_DX) slot = __shfl(j < 2 ? slot_lo : slot_hi, row & 63);
                     if (q < cur.qlim && p < a.Pdim) {
                         const size_t off = (size_t)q * a.ldc + p;
-                        if (MODE == MODE_ROUTER_DX && slot >= 0) {
+                        if (MODE == MODE_ROUTER_DX && has_addend[j][i8]) {
                             // add the token's row of the expert-side gradient (fp32 add, one rounding)
-                            const u32x4 gsrc = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
                             const bf16x8 va = __builtin_bit_cast(bf16x8, val);
-                            const bf16x8 vb = __builtin_bit_cast(bf16x8, gsrc);
+                            const bf16x8 vb = __builtin_bit_cast(bf16x8, addend[j][i8]);
                             bf16x8 vo;
 #pragma unroll
                             for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
@@ -562,10 +574,7 @@ hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStre
     a.P = (const bf16 *)(ws + w.wsplit_b); a.p_batch = 0; a.ldp = 256;
     a.Cout = (bf16 *)dx; a.c_batch = 0; a.ldc = (int)w.d;
     a.mask = (const bf16 *)(ws + w.dXd);
-    a.tok_idx = (const int32_t *)(ws + w.idx);
-    a.tok_pos = (const int32_t *)(ws + w.pos);
-    a.tok_dropped = (const uint8_t *)(ws + w.dropped);
-    a.cap = (int)w.C;
+    a.tok_slot = (const int32_t *)(ws + w.tok_slot);
     a.Qdim = (int)w.T; a.Pdim = (int)w.d; a.Kdim = 384;
     a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
     a.tiles_p = (int)ceil_div(a.Pdim, kBP);
