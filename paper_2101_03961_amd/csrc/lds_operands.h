@@ -93,57 +93,6 @@ struct DirectOperand {
     }
 };
 
-// ---- operand stored [k][row], row contiguous ---------------------------------------
-// LDS stage layout: [32 k][256 rows] = 512 bytes per k, 32 chunks of 8 rows,
-// chunk c of k-row k kept at position c ^ 2 (k mod 4): the four k-rows one
-// transposing read touches then sit 32 bytes apart.
-struct TransOperand {
-    i32x4 rsrc;
-    uint32_t voff[2];       // lane's byte offset for loads with even / odd index
-    uint32_t k_step;        // bytes of one k row
-    uint32_t frag_base[4];  // LDS byte offset of the lane's share of fragment i (ks = 0, first half)
-
-    __device__ __forceinline__ void init(const bf16 *base, int ld, int row0, int rowlim, int klim,
-                                         int lane, int wave, int wave_rows) {
-        rsrc = make_rsrc(base, (uint32_t)klim * (uint32_t)ld * 2u);
-        k_step = (uint32_t)ld * 2u;
-        const int kk = lane >> 5, pc = lane & 31;       // k-row within the load's pair, LDS chunk
-#pragma unroll
-        for (int par = 0; par < 2; ++par) {
-            const int kr = wave * 8 + 2 * par + kk;     // k-rows of loads par, par + 2: same k mod 4
-            const int c = pc ^ ((kr & 3) << 1);
-            const int row = row0 + (c << 3);
-            voff[par] = row < rowlim
-                            ? ((uint32_t)(wave * 8 + kk) * (uint32_t)ld + (uint32_t)row) * 2u
-                            : kOobOffset;
-        }
-        // transposing read: lanes form groups of 16; group g covers rows 16 (g&1) .. +16 of
-        // the fragment and k 8 (g>>1) .. +8; inside a group lane j supplies the 8 bytes
-        // at k-row j/4, rows 4 (j%4) .. +4, and receives k-rows 0..3 of row j.
-        const int g = lane >> 4, j = lane & 15;
-        const int kq = j >> 2;                          // k mod 4 of the supplied k-row
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int n = wave_rows + i * 32 + (g & 1) * 16 + (j & 3) * 4;
-            const int chunk = (n >> 3) ^ (kq << 1);
-            frag_base[i] = (uint32_t)((((g >> 1) * 8 + kq) * 512) + (chunk << 4) + ((n & 4) << 1));
-        }
-    }
-    static constexpr int kPieces = 8;   // LDS reads per k sub-step: two per fragment
-    // load i of four: k-rows 8 wave + 2 i + {0, 1}
-    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
-        dma16(rsrc, voff[i & 1], (uint32_t)(k0 + 2 * i) * k_step,
-              lds_op + (uint32_t)((wave * 8 + 2 * i) * 512));
-    }
-    // piece x = half (x & 1: k 0..3 / 4..7 of the lane's eight) of fragment x >> 1
-    __device__ __forceinline__ void read_piece(const char *lds_op, int x, int ks,
-                                               s16x4 (&h)[4][2]) const {
-        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
-        const char *p0 = lds_op + frag_base[x >> 1] + ks * (16 * 512) + (x & 1) * (4 * 512);
-        h[x >> 1][x & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
-    }
-};
-
 // =============================================================================
 // 64-k variants (one pipeline step = 64 k): an operand row of a [row][k] tile is a
 // whole 128-byte line, so every request the loads make is a full cache line.
@@ -196,7 +145,14 @@ struct DirectOperand64 {
     }
 };
 
-// [k][row] operand: LDS [64 k][256 rows], laid out and read like TransOperand.
+// [k][row] operand (row contiguous): LDS [64 k][256 rows] = 512 bytes per k-row, 32 chunks
+// of 8 rows; chunk c of k-row k is kept at position c ^ 4 (k mod 4).  One transposing read
+// (ds_read_b64_tr_b16) has lanes 0..31 fetch 64 bytes (rows 0..31 of the fragment) from each
+// of four consecutive k-rows; 512 bytes apart they would all fall on the same banks, the
+// permutation puts them into the four different quarters of the 256-byte bank window.
+// Lanes form groups of 16; group g covers rows 16 (g&1) .. +16 of the fragment and
+// k 8 (g>>1) .. +8; inside a group lane j supplies the 8 bytes at k-row j/4, rows
+// 4 (j%4) .. +4, and receives k-rows 0..3 of row j.
 struct TransOperand64 {
     i32x4 rsrc;
     uint32_t voff[2];       // lane's byte offset for loads with even / odd index
@@ -211,7 +167,7 @@ struct TransOperand64 {
 #pragma unroll
         for (int par = 0; par < 2; ++par) {
             const int kr = wave * 16 + 2 * par + kk;    // loads par, par + 2, ...: same k mod 4
-            const int c = pc ^ ((kr & 3) << 1);
+            const int c = pc ^ ((kr & 3) << 2);
             const int row = row0 + (c << 3);
             voff[par] = row < rowlim
                             ? ((uint32_t)(wave * 16 + kk) * (uint32_t)ld + (uint32_t)row) * 2u
@@ -225,7 +181,7 @@ struct TransOperand64 {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int n = wave_rows + i * 32 + (g & 1) * 16 + (j & 3) * 4;
-            const int chunk = (n >> 3) ^ (kq << 1);
+            const int chunk = (n >> 3) ^ (kq << 2);
             frag_base[i] = (uint32_t)((((g >> 1) * 8 + kq) * 512) + (chunk << 4) + ((n & 4) << 1));
         }
     }
