@@ -72,15 +72,16 @@ def _load():
     lib.swo_top1.restype = None
     lib.swo_top1.argtypes = [i64, i64, _c_f64p, _c_f64p, _c_i32p, _c_f64p]
     lib.swo_aux_loss.restype = f64
-    lib.swo_aux_loss.argtypes = [i64, i64, _c_i32p, _c_f64p, f64, _c_i64p, _c_f64p, _c_f64p]
+    lib.swo_aux_loss.argtypes = [i64, i64, i64, _c_i32p, _c_f64p, f64, _c_i64p, _c_i64p, _c_f64p,
+                                 _c_f64p]
     lib.swo_positions.restype = None
-    lib.swo_positions.argtypes = [i64, i64, i64, _c_i32p, _c_i32p, _c_u8p, _c_i64p]
+    lib.swo_positions.argtypes = [i64, i64, i64, i64, _c_i32p, _c_i32p, _c_u8p, _c_i64p]
     lib.swo_expert_ffn.restype = None
     lib.swo_expert_ffn.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_i32p,
                                    _c_u8p, _c_f64p, _c_u8p, _c_f64p]
     lib.swo_backward.restype = None
     lib.swo_backward.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f32p,
-                                 _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, _c_i64p,
+                                 _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, i64, _c_i64p,
                                  _c_i32p, _c_u8p, _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p,
                                  _c_f64p, _c_f64p]
     _libs[key] = lib
@@ -121,9 +122,10 @@ def max_threads() -> int:
 # --------------------------------------------------------------------------
 # step-level wrappers (one per oracle step)
 # --------------------------------------------------------------------------
-def capacity(T: int, E: int, capacity_factor: float) -> int:
-    """Eq. 3 with floor rounding."""
-    return int(_load().swo_capacity(T, E, float(capacity_factor)))
+def capacity(T: int, E: int, capacity_factor: float, n_groups: int = 1) -> int:
+    """Eq. 3 with floor rounding, for the tokens of one routing group."""
+    assert n_groups >= 1 and T % n_groups == 0
+    return int(_load().swo_capacity(T // n_groups, E, float(capacity_factor)))
 
 
 def logits(x, W_r, b_r=None) -> np.ndarray:
@@ -158,29 +160,39 @@ def top1(h, p):
     return e, g
 
 
-def aux_loss(expert_index, p, alpha: float):
-    """Eqs. 4-6.  Returns (loss, counts[E], f[E], P[E])."""
+def aux_loss(expert_index, p, alpha: float, n_groups: int = 1, with_group_counts: bool = False):
+    """Eqs. 4-6, averaged over the routing groups.  Returns (loss, counts[E], f, P) with f and
+    P of shape [E] for one group and [n_groups][E] otherwise (+ counts per group if asked)."""
     e = np.ascontiguousarray(expert_index, dtype=np.int32)
     p = np.ascontiguousarray(p, dtype=np.float64)
     T, E = p.shape
+    assert n_groups >= 1 and T % n_groups == 0
     counts = np.empty(E, dtype=np.int64)
-    f = np.empty(E, dtype=np.float64)
-    P = np.empty(E, dtype=np.float64)
-    loss = _load().swo_aux_loss(T, E, _ptr(e, _c_i32p), _ptr(p, _c_f64p), float(alpha),
-                                _ptr(counts, _c_i64p), _ptr(f, _c_f64p), _ptr(P, _c_f64p))
+    counts_g = np.empty((n_groups, E), dtype=np.int64)
+    f = np.empty((n_groups, E), dtype=np.float64)
+    P = np.empty((n_groups, E), dtype=np.float64)
+    loss = _load().swo_aux_loss(T, E, n_groups, _ptr(e, _c_i32p), _ptr(p, _c_f64p), float(alpha),
+                                _ptr(counts, _c_i64p), _ptr(counts_g, _c_i64p),
+                                _ptr(f, _c_f64p), _ptr(P, _c_f64p))
+    if n_groups == 1:
+        f, P = f[0], P[0]
+    if with_group_counts:
+        return float(loss), counts, f, P, counts_g
     return float(loss), counts, f, P
 
 
-def positions(expert_index, E: int, C: int):
-    """Sequence-order rank within the chosen expert, dropped mask, kept counts."""
+def positions(expert_index, E: int, C: int, n_groups: int = 1):
+    """Sequence-order rank within the chosen expert (inside the token's group), dropped mask,
+    kept counts ([E], or [n_groups][E] for several groups).  C: per-group capacity."""
     e = np.ascontiguousarray(expert_index, dtype=np.int32)
     T = e.shape[0]
+    assert n_groups >= 1 and T % n_groups == 0
     pos = np.empty(T, dtype=np.int32)
     dropped = np.empty(T, dtype=np.uint8)
-    kept = np.empty(E, dtype=np.int64)
-    _load().swo_positions(T, E, C, _ptr(e, _c_i32p), _ptr(pos, _c_i32p), _ptr(dropped, _c_u8p),
-                          _ptr(kept, _c_i64p))
-    return pos, dropped, kept
+    kept = np.empty((n_groups, E), dtype=np.int64)
+    _load().swo_positions(T, E, C, n_groups, _ptr(e, _c_i32p), _ptr(pos, _c_i32p),
+                          _ptr(dropped, _c_u8p), _ptr(kept, _c_i64p))
+    return pos, dropped, (kept[0] if n_groups == 1 else kept)
 
 
 def _token_mask(expert_index, E, expert_sel, token_sel):
@@ -223,9 +235,12 @@ def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None,
 def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
             logits_override=None, expert_index_override=None,
             expert_sel: Optional[Sequence[int]] = None,
-            token_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False) -> Dict:
+            token_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False,
+            n_groups: int = 1) -> Dict:
     """Whole forward pass.
 
+    n_groups: routing groups of T / n_groups consecutive tokens (capacity, positions and the
+        auxiliary loss per group; 1 = the whole batch is one group).
     logits_override: use these logits (e.g. another implementation's fp32
         logits, widened) instead of computing them -- for the routing-stage
         comparison, which is defined on identical logits.
@@ -238,7 +253,7 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     x32 = _f32(x)
     T, d = x32.shape
     E = np.asarray(W_r).shape[1]
-    C = capacity(T, E, capacity_factor)
+    C = capacity(T, E, capacity_factor, n_groups)
     if logits_override is None:
         h = logits(x32, W_r, b_r)
     else:
@@ -248,11 +263,11 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     if expert_index_override is not None:
         e = np.ascontiguousarray(expert_index_override, dtype=np.int32)
         g = p[np.arange(T), e].copy()
-    loss, counts, f_vec, P_vec = aux_loss(e, p, alpha)
-    pos, dropped, kept = positions(e, E, C)
+    loss, counts, f_vec, P_vec, counts_g = aux_loss(e, p, alpha, n_groups, with_group_counts=True)
+    pos, dropped, kept = positions(e, E, C, n_groups)
     out = dict(capacity=C, logits=h, probs=p, expert_index=e, gate=g, aux_loss=loss,
                expert_counts=counts, f=f_vec, P=P_vec, position_in_expert=pos,
-               dropped=dropped, kept_counts=kept)
+               dropped=dropped, kept_counts=kept, n_groups=n_groups, group_counts=counts_g)
     if not skip_ffn:
         out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel)
     return out
@@ -275,7 +290,12 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
     dr = np.ascontiguousarray(fwd["dropped"], dtype=np.uint8)
     g = np.ascontiguousarray(fwd["gate"], dtype=np.float64)
     p = np.ascontiguousarray(fwd["probs"], dtype=np.float64)
-    counts = np.ascontiguousarray(fwd["expert_counts"], dtype=np.int64)
+    n_groups = int(fwd.get("n_groups", 1))
+    if "group_counts" in fwd:
+        counts_g = np.ascontiguousarray(fwd["group_counts"], dtype=np.int64)
+    else:
+        counts_g = np.ascontiguousarray(fwd["expert_counts"], dtype=np.int64).reshape(1, -1)
+    assert counts_g.shape == (n_groups, E)
     tmask = _token_mask(e, E, expert_sel, token_sel)
     if expert_sel is None and token_sel is not None:
         expert_sel = []
@@ -298,7 +318,7 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
     _load().swo_backward(T, d, f, E, _ptr(x32, _c_f32p), _ptr(W_r32, _c_f32p),
                          _ptr(W_in32, _c_f32p), _ptr(W_out32, _c_f32p), _ptr(dy32, _c_f32p),
                          float(d_aux), float(alpha), _ptr(e, _c_i32p), _ptr(dr, _c_u8p),
-                         _ptr(g, _c_f64p), _ptr(p, _c_f64p), _ptr(counts, _c_i64p),
+                         _ptr(g, _c_f64p), _ptr(p, _c_f64p), n_groups, _ptr(counts_g, _c_i64p),
                          _ptr(sel_slot, _c_i32p), _ptr(tmask, _c_u8p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
                          _ptr(db_r, _c_f64p), _ptr(dW_in, _c_f64p), _ptr(dW_out, _c_f64p),
                          _ptr(dgate, _c_f64p), _ptr(dlog, _c_f64p))

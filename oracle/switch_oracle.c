@@ -2,7 +2,10 @@
  * Switch FFN layer -- CPU oracle (TEST INFRASTRUCTURE, not a product path).
  *
  * A plain, slow, fp64 evaluation of the layer's definition, written from the
- * paper (arXiv 2101.03961): one routing group holding all T tokens.  It is the
+ * paper (arXiv 2101.03961).  The T tokens form n_groups routing groups of
+ * T / n_groups consecutive tokens each (the appendix listing's num_cores;
+ * capacity, position and the auxiliary loss are taken per group, the experts
+ * are shared); n_groups = 1 is one group holding all tokens.  It is the
  * thing the GPU library is compared against; it shares no code, header or
  * table with that library and must never be called from it.
  *
@@ -28,6 +31,9 @@
  *   - f_i in the auxiliary loss counts arg max decisions over ALL tokens,
  *     before any capacity truncation (Eq. 5), and is a constant under
  *     differentiation; P_i is differentiable (Sec. 2.2).
+ *   - with several groups the loss is the mean over groups of the one-group
+ *     loss (the listing's mean over [num_cores, num_experts] times N^2), and
+ *     the capacity is floor(T_group / E * capacity_factor).
  *   - the residual connection is outside the layer: a dropped token's output
  *     row is zero.
  *   - ReLU'(0) = 0.
@@ -95,43 +101,57 @@ void swo_top1(int64_t T, int64_t E, const double *h, const double *p,
     }
 }
 
-/* ---- Eqs. 4-6: loss = alpha * N * sum_i f_i P_i -------------------------- */
-double swo_aux_loss(int64_t T, int64_t E, const int32_t *expert_index, const double *p,
-                    double alpha, int64_t *counts /* [E] */, double *f_out /* [E] or NULL */,
-                    double *P_out /* [E] or NULL */) {
-    double loss = 0.0;
+/* ---- Eqs. 4-6: loss = alpha * N * sum_i f_i P_i, averaged over the groups ---
+ * counts [E]: arg max decisions per expert over all tokens.  counts_g, f_out,
+ * P_out: [n_groups][E] (each may be NULL): per-group counts, f and P. */
+double swo_aux_loss(int64_t T, int64_t E, int64_t n_groups, const int32_t *expert_index,
+                    const double *p, double alpha, int64_t *counts, int64_t *counts_g,
+                    double *f_out, double *P_out) {
     for (int64_t i = 0; i < E; ++i) counts[i] = 0;
     for (int64_t t = 0; t < T; ++t) counts[expert_index[t]] += 1;
-    if (T == 0) { /* empty batch: both fractions are empty sums; the loss is taken as 0 */
+    const int64_t Tg = T / n_groups;
+    double total = 0.0;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        double loss = 0.0;
         for (int64_t i = 0; i < E; ++i) {
-            if (f_out) f_out[i] = 0.0;
-            if (P_out) P_out[i] = 0.0;
+            int64_t cnt = 0;
+            double P_i = 0.0;
+            for (int64_t t = g * Tg; t < (g + 1) * Tg; ++t) {
+                cnt += (expert_index[t] == i);
+                P_i += p[t * E + i];
+            }
+            /* empty batch: both fractions are empty sums; the loss is taken as 0 */
+            double f_i = Tg > 0 ? (double)cnt / (double)Tg : 0.0;
+            P_i = Tg > 0 ? P_i / (double)Tg : 0.0;
+            if (counts_g) counts_g[g * E + i] = cnt;
+            if (f_out) f_out[g * E + i] = f_i;
+            if (P_out) P_out[g * E + i] = P_i;
+            loss += f_i * P_i;
         }
-        return 0.0;
+        total += alpha * (double)E * loss;
     }
-    for (int64_t i = 0; i < E; ++i) {
-        double f_i = (double)counts[i] / (double)T;
-        double P_i = 0.0;
-        for (int64_t t = 0; t < T; ++t) P_i += p[t * E + i];
-        P_i /= (double)T;
-        if (f_out) f_out[i] = f_i;
-        if (P_out) P_out[i] = P_i;
-        loss += f_i * P_i;
-    }
-    return alpha * (double)E * loss;
+    return total / (double)n_groups;
 }
 
-/* ---- position in expert, sequence order; overflow is dropped ------------- */
-void swo_positions(int64_t T, int64_t E, int64_t C, const int32_t *expert_index,
-                   int32_t *position_in_expert, uint8_t *dropped, int64_t *kept /* [E] */) {
+/* ---- position in expert, sequence order inside the token's group; overflow is
+ * dropped.  C is the per-group capacity; kept: [n_groups][E]. ---------------- */
+void swo_positions(int64_t T, int64_t E, int64_t C, int64_t n_groups,
+                   const int32_t *expert_index, int32_t *position_in_expert, uint8_t *dropped,
+                   int64_t *kept) {
     int64_t *seen = (int64_t *)calloc((size_t)E, sizeof(int64_t));
-    for (int64_t i = 0; i < E; ++i) kept[i] = 0;
-    for (int64_t t = 0; t < T; ++t) {
-        int32_t e = expert_index[t];
-        int64_t pos = seen[e]++;
-        position_in_expert[t] = (int32_t)pos;
-        dropped[t] = (uint8_t)(pos >= C);
-        if (pos < C) kept[e] += 1;
+    const int64_t Tg = T / n_groups;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        for (int64_t i = 0; i < E; ++i) {
+            seen[i] = 0;
+            kept[g * E + i] = 0;
+        }
+        for (int64_t t = g * Tg; t < (g + 1) * Tg; ++t) {
+            int32_t e = expert_index[t];
+            int64_t pos = seen[e]++;
+            position_in_expert[t] = (int32_t)pos;
+            dropped[t] = (uint8_t)(pos >= C);
+            if (pos < C) kept[g * E + e] += 1;
+        }
     }
     free(seen);
 }
@@ -212,13 +232,13 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
 /* ---- backward ------------------------------------------------------------
  * Scalar objective  L = sum_t <dy_t, y_t> + d_aux * aux_loss.
  * Chain rule through y_t = k_t g_t o_t, o = a W_out, a = ReLU(h), h = x W_in,
- * g_t = p[t, e_t], p = softmax(x W_r + b_r), aux = alpha E sum_i f_i P_i with f
- * held constant:
+ * g_t = p[t, e_t], p = softmax(x W_r + b_r), aux = mean over groups g of
+ * alpha E sum_i f_gi P_gi with f held constant (T_g tokens per group, n groups):
  *   do_t  = k_t g_t dy_t                 dg_t = k_t <dy_t, o_t>
  *   dW_out[e] += a_t^T do_t              da_t = do_t W_out[e]^T
  *   dh_t  = da_t * 1[h_t > 0]            dW_in[e] += x_t^T dh_t
  *   dx_t  = dh_t W_in[e]^T  (expert part)
- *   dp[t,i]  = dg_t 1[i = e_t] + d_aux alpha E f_i / T
+ *   dp[t,i]  = dg_t 1[i = e_t] + d_aux alpha E f_gi / (n T_g)      (t in group g)
  *   dl[t,j]  = p[t,j] (dp[t,j] - sum_i p[t,i] dp[t,i])         (softmax)
  *   dW_r = x^T dl,  db_r = sum_t dl_t,  dx_t += dl_t W_r^T
  *
@@ -233,7 +253,8 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
 void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, const in_t *W_r,
                   const in_t *W_in, const in_t *W_out, const in_t *dy, double d_aux,
                   double alpha, const int32_t *expert_index, const uint8_t *dropped,
-                  const double *gate, const double *p /* [T][E] */, const int64_t *counts,
+                  const double *gate, const double *p /* [T][E] */, int64_t n_groups,
+                  const int64_t *counts_g /* [n_groups][E] */,
                   const int32_t *sel_slot /* [E] or NULL */,
                   const uint8_t *token_sel /* [T] or NULL */, double *dx /* [T][d] */,
                   double *dW_r /* [d][E] */, double *db_r /* [E] */,
@@ -323,8 +344,10 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
             const double *pt = p + t * E;
             double s = 0.0;
             for (int64_t i = 0; i < E; ++i) {
-                double f_i = (double)counts[i] / (double)T;
-                dp[i] = d_aux * alpha * (double)E * f_i / (double)T;
+                const int64_t Tg = T / n_groups;
+                const int64_t g = t / Tg;
+                double f_i = (double)counts_g[g * E + i] / (double)Tg;
+                dp[i] = d_aux * alpha * (double)E * f_i / ((double)n_groups * (double)Tg);
                 if (i == expert_index[t]) dp[i] += dgate[t];
                 s += pt[i] * dp[i];
             }

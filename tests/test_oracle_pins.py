@@ -455,3 +455,83 @@ def test_empty_batch():
     bwd = oracle.backward(x, W_r, W_in, W_out, x.copy(), fwd, 0.01, 1.0)
     for k in ("dW_r", "db_r", "dW_in", "dW_out"):
         assert not bwd[k].any()
+
+
+# ------------------------------------------------------------ routing groups
+# (appendix listing: tokens arrive as [num_cores, tokens_per_core, d]; capacity, cumulative
+# position and the loss's two fractions are per core, the experts are shared)
+
+@pytest.mark.parametrize("n", [2, 3, 5])
+def test_groups_equal_independent_layers(n):
+    """n routing groups == n separate one-group layers over the same weights: outputs
+    concatenated, loss averaged, weight gradients summed (each layer seeing d_aux / n)."""
+    Tg = 30
+    s = SwitchShape("t", n * Tg, 12, 20, 4, 0.9, dtype="f32", seed_index=23)
+    inp = _np_inputs(s)
+    alpha, d_aux = 0.02, 0.7
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.9, alpha, n_groups=n)
+    bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd, alpha,
+                          d_aux)
+    assert fwd["capacity"] == int(np.floor(Tg / 4 * 0.9))
+    assert fwd["dropped"].any()
+    loss = 0.0
+    acc = {k: 0.0 for k in ("dW_r", "db_r", "dW_in", "dW_out")}
+    counts = np.zeros(4, dtype=np.int64)
+    for g in range(n):
+        sl = slice(g * Tg, (g + 1) * Tg)
+        f1 = oracle.forward(inp["x"][sl], inp["W_r"], inp["W_in"], inp["W_out"], 0.9, alpha)
+        b1 = oracle.backward(inp["x"][sl], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"][sl],
+                             f1, alpha, d_aux / n)
+        for k in ("expert_index", "position_in_expert", "dropped"):
+            np.testing.assert_array_equal(fwd[k][sl], f1[k])
+        np.testing.assert_array_equal(fwd["gate"][sl], f1["gate"])
+        np.testing.assert_array_equal(fwd["y"][sl], f1["y"])
+        np.testing.assert_array_equal(fwd["kept_counts"][g], f1["kept_counts"])
+        np.testing.assert_array_equal(fwd["group_counts"][g], f1["expert_counts"])
+        np.testing.assert_allclose(bwd["dx"][sl], b1["dx"], rtol=1e-13, atol=1e-15)
+        loss += f1["aux_loss"] / n
+        counts += f1["expert_counts"]
+        for k in acc:
+            acc[k] = acc[k] + b1[k]
+    assert abs(fwd["aux_loss"] - loss) < 1e-15
+    np.testing.assert_array_equal(fwd["expert_counts"], counts)
+    for k in acc:
+        np.testing.assert_allclose(bwd[k], acc[k], rtol=1e-12, atol=1e-15)
+
+
+def test_group_loss_matches_appendix_mean_form():
+    """mean over [cores, experts] of (mean_tokens mask) * (mean_tokens p), times N^2 alpha."""
+    rng = np.random.default_rng(5)
+    n, Tg, E, alpha = 4, 25, 6, 0.03
+    h = rng.normal(size=(n * Tg, E))
+    p = oracle.softmax(h)
+    e, _ = oracle.top1(h, p)
+    loss, counts, f, P = oracle.aux_loss(e, p, alpha, n_groups=n)
+    mask = np.eye(E)[e].reshape(n, Tg, E)
+    density_1 = mask.mean(axis=1)
+    density_1_proxy = p.reshape(n, Tg, E).mean(axis=1)
+    ref = np.mean(density_1_proxy * density_1) * E ** 2 * alpha
+    assert abs(loss - ref) < 1e-15
+    np.testing.assert_allclose(f, density_1, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(P, density_1_proxy, rtol=1e-14, atol=1e-16)
+    np.testing.assert_array_equal(counts, mask.sum(axis=(0, 1)).astype(np.int64))
+
+
+def test_group_positions_by_definition():
+    rng = np.random.default_rng(6)
+    n, Tg, E, C = 3, 17, 4, 3
+    e = rng.integers(0, E, size=n * Tg).astype(np.int32)
+    pos, dropped, kept = oracle.positions(e, E, C, n_groups=n)
+    for t in range(n * Tg):
+        g0 = (t // Tg) * Tg
+        rank = sum(1 for s in range(g0, t) if e[s] == e[t])
+        assert pos[t] == rank and dropped[t] == (rank >= C)
+    for g in range(n):
+        cnt = np.bincount(e[g * Tg:(g + 1) * Tg], minlength=E)
+        np.testing.assert_array_equal(kept[g], np.minimum(cnt, C))
+
+
+def test_group_capacity_uses_group_size():
+    assert oracle.capacity(65536, 128, 1.0, n_groups=8) == 64
+    assert oracle.capacity(65536, 128, 1.25, n_groups=8) == 80
+    assert oracle.capacity(90, 4, 0.9, n_groups=3) == 6
