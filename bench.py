@@ -72,12 +72,14 @@ def cpu_baseline(shape, inp, sample_tokens):
     import numpy as np
     import oracle
     n = min(sample_tokens, shape.T)
+    n -= n % shape.n_groups
     to_np = lambda t: None if t is None else t.float().cpu().numpy()
     x, dy = to_np(inp["x"][:n]), to_np(inp["dy"][:n])
     W_r, b_r, W_in, W_out = (to_np(inp[k]) for k in ("W_r", "b_r", "W_in", "W_out"))
     threads = oracle.max_threads()
     t0 = time.perf_counter()
-    fwd = oracle.forward(x, W_r, W_in, W_out, shape.capacity_factor, shape.alpha, b_r=b_r)
+    fwd = oracle.forward(x, W_r, W_in, W_out, shape.capacity_factor, shape.alpha, b_r=b_r,
+                         n_groups=shape.n_groups)
     oracle.backward(x, W_r, W_in, W_out, dy, fwd, shape.alpha, 1.0)
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
@@ -93,6 +95,8 @@ def main() -> int:
     ap.add_argument("--config", default="base_cf1.0")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--n-groups", type=int, default=1,
+                    help="routing groups (1 = the benchmark's workload; >1 for experiments)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
@@ -108,10 +112,12 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     shape = CONFIGS[args.config]
+    if args.n_groups != 1:
+        shape = shape.with_(name="%s_x%dgroups" % (shape.name, args.n_groups), n_groups=args.n_groups)
     dev = "cuda:0"
     inp = make_inputs(shape, dev)
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
-                        shape.alpha, shape.dtype, device=dev)
+                        shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups)
     layer.alloc_grads(with_bias=inp["b_r"] is not None)
 
     def step():
@@ -187,6 +193,7 @@ def main() -> int:
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": shape.name, "T": shape.T, "d_model": shape.d_model,
                    "d_ff": shape.d_ff, "E": shape.E, "capacity_factor": shape.capacity_factor,
+                   "n_groups": shape.n_groups,
                    "capacity": layer.capacity, "kept_tokens": kept,
                    "dropped_frac": 1.0 - kept / shape.T,
                    "count_min_mean_max": [int(counts.min()), float(counts.mean()), int(counts.max())]},

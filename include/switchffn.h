@@ -4,8 +4,9 @@
  * The layer is the sparse feed-forward layer of the Switch Transformer
  * (arXiv 2101.03961): a top-1 router, capacity-limited dispatch of tokens to
  * experts, one ReLU FFN per expert, a gate-weighted combine, and the
- * load-balancing auxiliary loss, forward and backward.  One routing group holds
- * all T tokens (the appendix listing's num_cores = 1).
+ * load-balancing auxiliary loss, forward and backward.  The T tokens form
+ * n_groups routing groups of consecutive tokens (the appendix listing's
+ * num_cores); by default one group holds them all.
  *
  * General rules
  *   - Every tensor pointer is a DEVICE pointer (HBM) unless a comment says
@@ -63,10 +64,17 @@ typedef struct {
     double capacity_factor;  /* > 0; Eq. 3                                          */
     float alpha;             /* auxiliary-loss coefficient (Sec. 2.2; paper: 1e-2)  */
     int32_t act_dtype;       /* sw_dtype of activations and expert weights          */
+    int32_t reserved;        /* set to 0                                            */
+    int64_t n_groups;        /* routing groups of T / n_groups consecutive tokens:
+                                capacity (Eq. 3 with the group's token count),
+                                position_in_expert and the two fractions of the loss
+                                are taken per group, the loss is the mean over groups,
+                                the experts are shared.  Must divide T; 0 is read as 1 */
 } switch_config;
 
 /* Expert capacity, Eq. 3, rounded down:
- *   capacity = floor((double)T / (double)E * capacity_factor).
+ *   capacity = floor((double)(T / n_groups) / (double)E * capacity_factor)
+ * -- slots per expert and routing group.
  * Zero is legal (every token is dropped).  Host only. */
 int switch_capacity(const switch_config *cfg, int64_t *capacity_out /* host */);
 

@@ -27,6 +27,8 @@ class SwitchConfig(ctypes.Structure):
         ("capacity_factor", ctypes.c_double),
         ("alpha", ctypes.c_float),
         ("act_dtype", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("n_groups", ctypes.c_int64),
     ]
 
 

@@ -14,6 +14,8 @@ int check_config(const switch_config *cfg) {
     if (!cfg) return SW_ERR_NULL;
     if (cfg->act_dtype != SW_F32 && cfg->act_dtype != SW_BF16) return SW_ERR_DTYPE;
     if (cfg->T < 0 || cfg->T >= (int64_t)1 << 31) return SW_ERR_SHAPE;
+    if (cfg->n_groups < 0 || cfg->n_groups > 65536) return SW_ERR_SHAPE;
+    if (cfg->n_groups > 1 && (cfg->T % cfg->n_groups) != 0) return SW_ERR_SHAPE;
     if (cfg->E < 1 || cfg->E > 4096) return SW_ERR_SHAPE;
     if (cfg->d_model < 1 || cfg->d_ff < 1) return SW_ERR_SHAPE;
     if (cfg->d_model >= (int64_t)1 << 24 || cfg->d_ff >= (int64_t)1 << 24) return SW_ERR_SHAPE;
@@ -21,21 +23,27 @@ int check_config(const switch_config *cfg) {
     if (cfg->d_model % mult || cfg->d_ff % mult) return SW_ERR_SHAPE;
     if (!(cfg->capacity_factor > 0.0) || !isfinite(cfg->capacity_factor)) return SW_ERR_VALUE;
     if (!isfinite(cfg->alpha)) return SW_ERR_VALUE;
-    // slot indices (expert * capacity + position) are kept in 32 bits
-    const double c = floor((double)cfg->T / (double)cfg->E * cfg->capacity_factor);
-    if (c * (double)cfg->E >= 2147483647.0) return SW_ERR_SHAPE;
+    // slot indices (expert * slots per expert + position) are kept in 32 bits
+    const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
+    const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
+    if (c * n * (double)cfg->E >= 2147483647.0) return SW_ERR_SHAPE;
     return SW_OK;
 }
 
 int64_t capacity_of(const switch_config *cfg) {
-    return (int64_t)floor((double)cfg->T / (double)cfg->E * cfg->capacity_factor);
+    const int64_t n = cfg->n_groups > 1 ? cfg->n_groups : 1;
+    return (int64_t)floor((double)(cfg->T / n) / (double)cfg->E * cfg->capacity_factor);
 }
 
 Workspace layout_workspace(const switch_config *cfg) {
     Workspace w{};
     w.T = cfg->T; w.d = cfg->d_model; w.f = cfg->d_ff; w.E = cfg->E;
-    w.C = capacity_of(cfg);
-    w.nb = ceil_div(w.T, kRouteTB);
+    w.n = cfg->n_groups > 1 ? cfg->n_groups : 1;
+    w.Tg = w.T / w.n;
+    w.Cg = capacity_of(cfg);
+    w.C = w.n * w.Cg;
+    w.nbg = ceil_div(w.Tg, kRouteTB);
+    w.nb = w.n * w.nbg;
     w.elt = cfg->act_dtype == SW_BF16 ? 2 : 4;
     w.nsplit = w.nb < 64 ? w.nb : 64;
     size_t off = 0;
@@ -51,6 +59,9 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.block_psum = take(nb * E * 4);
     w.block_off = take(nb * E * 4);
     w.counts = take(E * 4);
+    w.counts_g = take((size_t)w.n * E * 4);
+    w.psum_g = take((size_t)w.n * E * 4);
+    w.grp_off = take((size_t)w.n * E * 4);
     w.kept = take(E * 4);
     w.slot_token = take(E * C * 4);
     w.tok_slot = take(T * 4);

@@ -29,11 +29,29 @@ constexpr int kGemmTile = 256;
 constexpr int kReluBitsPerTile = kGemmTile * kGemmTile / 8;
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Token blocks of the router kernels: group g's Tg tokens are cut into nbg blocks of kRouteTB
+// (the last one short), so that a block never holds tokens of two routing groups.
+__device__ __forceinline__ void block_token_range(int b, int nbg, int Tg, int &t0, int &tend) {
+    const int g = b / nbg;
+    t0 = g * Tg + (b - g * nbg) * kRouteTB;
+    const int gend = (g + 1) * Tg;
+    tend = t0 + kRouteTB < gend ? t0 + kRouteTB : gend;
+}
+__device__ __forceinline__ int block_of_token(int t, int nbg, int Tg) {
+    const int g = t / Tg;
+    return g * nbg + (t - g * Tg) / kRouteTB;
+}
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- workspace layout (byte offsets into the caller's workspace) ------------
 struct Workspace {
-    int64_t T, d, f, E, C, nb;  // nb = number of token blocks
+    int64_t T, d, f, E;
+    int64_t n;                  // routing groups
+    int64_t Tg;                 // tokens per group (T / n)
+    int64_t Cg;                 // capacity: slots per expert and group (Eq. 3 on Tg tokens)
+    int64_t C;                  // slots per expert in the expert-major buffers: n * Cg
+    int64_t nbg, nb;            // token blocks per group (blocks never straddle groups), in all
     size_t elt;                 // bytes per activation element
     size_t probs;               // f32 [T][E]   router probabilities (saved for backward)
     size_t idx;                 // i32 [T]
@@ -44,10 +62,15 @@ struct Workspace {
     size_t block_counts;        // i32 [nb][E]
     size_t block_psum;          // f32 [nb][E]
     size_t block_off;           // i32 [nb][E]  exclusive prefix of block_counts over blocks
-    size_t counts;              // i32 [E]
-    size_t kept;                // i32 [E]      min(count, C)
+    size_t counts;              // i32 [E]      arg max decisions per expert, all groups
+    size_t counts_g;            // i32 [n][E]   ... per group
+    size_t psum_g;              // f32 [n][E]   sum of router probabilities per group and expert
+    size_t grp_off;             // i32 [n][E]   first slot of group g inside expert e's slots:
+                                //              sum of min(counts_g, Cg) over earlier groups
+    size_t kept;                // i32 [E]      kept tokens per expert: sum over groups of min(count, Cg)
     size_t slot_token;          // i32 [E][C]   token held by each slot (valid for slot < kept[e])
-    size_t tok_slot;            // i32 [T]      slot (e * C + pos) of each kept token, -1 for dropped ones
+    size_t tok_slot;            // i32 [T]      slot (e * C + grp_off[g][e] + pos) of each kept token,
+                                //              -1 for dropped ones
     size_t Xd;                  // act [E][C][d]   dispatched tokens
     size_t A;                   // act [E][C][f]   ReLU(Xd W_in)
     size_t O;                   // act [E][C][d]   A W_out

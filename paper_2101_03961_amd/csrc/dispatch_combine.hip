@@ -47,43 +47,45 @@ template <> __device__ __forceinline__ Chunk16 pack<bf16>(const float *v) {
 }
 
 // -----------------------------------------------------------------------------
-// position_in_expert[t] = block_off[block(t)][e_t] + local_rank[t]; dropped mask;
-// slot -> token table for kept tokens.
+// position_in_expert[t] = block_off[block(t)][e_t] + local_rank[t] (rank inside the token's
+// routing group); dropped mask (position >= Cg); slot of each kept token,
+// e * C + grp_off[g][e] + position, and the slot -> token table.
 // -----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void positions_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ local_rank,
-    const int32_t *__restrict__ block_off, int32_t *__restrict__ pos_out,
-    uint8_t *__restrict__ dropped_out, int32_t *__restrict__ pos_ws,
+    const int32_t *__restrict__ block_off, const int32_t *__restrict__ grp_off,
+    int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out, int32_t *__restrict__ pos_ws,
     uint8_t *__restrict__ dropped_ws, int32_t *__restrict__ slot_token,
-    int32_t *__restrict__ tok_slot, int T, int E, int C) {
+    int32_t *__restrict__ tok_slot, int T, int Tg, int nbg, int E, int C, int Cg) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= T) return;
     const int e = idx[t];
-    const int p = block_off[(size_t)(t / kRouteTB) * E + e] + local_rank[t];
-    const uint8_t dr = p >= C;
+    const int p = block_off[(size_t)block_of_token(t, nbg, Tg) * E + e] + local_rank[t];
+    const uint8_t dr = p >= Cg;
     pos_out[t] = p;
     pos_ws[t] = p;
     dropped_out[t] = dr;
     dropped_ws[t] = dr;
-    if (!dr) slot_token[(size_t)e * C + p] = t;
-    tok_slot[t] = dr ? -1 : e * C + p;
+    const int slot = e * C + grp_off[(size_t)(t / Tg) * E + e] + p;
+    if (!dr) slot_token[slot] = t;
+    tok_slot[t] = dr ? -1 : slot;
 }
 
 // -----------------------------------------------------------------------------
-// Dispatch: Xd[e_t * C + pos_t][:] = x[t][:] for kept tokens.  One wave per token
+// Dispatch: Xd[slot_t][:] = x[t][:] for kept tokens.  One wave per token
 // (its index loads are wave-uniform), one 16-byte chunk per lane and pass;
 // cpr = chunks per row.
 // -----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dispatch_kernel(const Chunk16 *__restrict__ x,
                                                        Chunk16 *__restrict__ Xd,
-                                                       const int32_t *__restrict__ idx,
-                                                       const int32_t *__restrict__ pos,
-                                                       const uint8_t *__restrict__ dropped,
-                                                       int T, int cpr, int C) {
+                                                       const int32_t *__restrict__ tok_slot,
+                                                       int T, int cpr) {
     const int lane = threadIdx.x % kWave;
     const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
-    if (t >= T || dropped[t]) return;
-    const size_t slot = (size_t)idx[t] * C + pos[t];
+    if (t >= T) return;
+    const int slot_or_none = tok_slot[t];
+    if (slot_or_none < 0) return;
+    const size_t slot = (size_t)slot_or_none;
     for (int col = lane; col < cpr; col += kWave) Xd[slot * cpr + col] = x[(size_t)t * cpr + col];
 }
 
@@ -94,20 +96,19 @@ __global__ __launch_bounds__(256) void dispatch_kernel(const Chunk16 *__restrict
 template <typename XT>
 __global__ __launch_bounds__(256) void combine_kernel(const Chunk16 *__restrict__ O,
                                                       Chunk16 *__restrict__ y,
-                                                      const int32_t *__restrict__ idx,
-                                                      const int32_t *__restrict__ pos,
-                                                      const uint8_t *__restrict__ dropped,
+                                                      const int32_t *__restrict__ tok_slot,
                                                       const float *__restrict__ gate,
-                                                      int T, int cpr, int C) {
+                                                      int T, int cpr) {
     const int lane = threadIdx.x % kWave;
     const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
     if (t >= T) return;
-    if (dropped[t]) {
+    const int slot_or_none = tok_slot[t];
+    if (slot_or_none < 0) {
         const Chunk16 zero = {{0u, 0u, 0u, 0u}};
         for (int col = lane; col < cpr; col += kWave) y[(size_t)t * cpr + col] = zero;
         return;
     }
-    const size_t slot = (size_t)idx[t] * C + pos[t];
+    const size_t slot = (size_t)slot_or_none;
     const float g = gate[t];
     for (int col = lane; col < cpr; col += kWave) {
         const Chunk16 in = O[slot * cpr + col];
@@ -126,17 +127,17 @@ __global__ __launch_bounds__(256) void combine_kernel(const Chunk16 *__restrict_
 template <typename XT>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(
     const Chunk16 *__restrict__ dy, const Chunk16 *__restrict__ O, Chunk16 *__restrict__ dO,
-    const int32_t *__restrict__ idx, const int32_t *__restrict__ pos,
-    const uint8_t *__restrict__ dropped, const float *__restrict__ gate,
-    float *__restrict__ dgate, int T, int cpr, int C) {
+    const int32_t *__restrict__ tok_slot, const float *__restrict__ gate,
+    float *__restrict__ dgate, int T, int cpr) {
     const int lane = threadIdx.x % kWave;
     const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
     if (t >= T) return;
-    if (dropped[t]) {
+    const int slot_or_none = tok_slot[t];
+    if (slot_or_none < 0) {
         if (lane == 0) dgate[t] = 0.f;
         return;
     }
-    const size_t slot = (size_t)idx[t] * C + pos[t];
+    const size_t slot = (size_t)slot_or_none;
     const float g = gate[t];
     float dot = 0.f;
     for (int col = lane; col < cpr; col += kWave) {
@@ -167,10 +168,11 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *w
         ProfScope ps("positions", s);
         hipLaunchKernelGGL(positions_kernel, dim3((unsigned)ceil_div(w.T, 256)), dim3(256), 0, s,
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.local_rank),
-                           (const int32_t *)(ws + w.block_off), position_in_expert, dropped,
-                           (int32_t *)(ws + w.pos), (uint8_t *)(ws + w.dropped),
-                           (int32_t *)(ws + w.slot_token), (int32_t *)(ws + w.tok_slot), (int)w.T,
-                           (int)w.E, (int)w.C);
+                           (const int32_t *)(ws + w.block_off), (const int32_t *)(ws + w.grp_off),
+                           position_in_expert, dropped, (int32_t *)(ws + w.pos),
+                           (uint8_t *)(ws + w.dropped), (int32_t *)(ws + w.slot_token),
+                           (int32_t *)(ws + w.tok_slot), (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E,
+                           (int)w.C, (int)w.Cg);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (w.C == 0) return hipSuccess;
@@ -180,8 +182,7 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *w
         const int cpr = (int)(w.d / vec);
         hipLaunchKernelGGL(dispatch_kernel, dim3((unsigned)ceil_div(w.T, 256 / kWave)), dim3(256),
                            0, s, (const Chunk16 *)x, (Chunk16 *)(ws + w.Xd),
-                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (int)w.T, cpr, (int)w.C);
+                           (const int32_t *)(ws + w.tok_slot), (int)w.T, cpr);
         err = hipGetLastError();
     }
     return err;
@@ -195,15 +196,13 @@ hipError_t launch_combine(const Workspace &w, int dtype, char *ws, void *y, hipS
     if (dtype == SW_BF16)
         hipLaunchKernelGGL(combine_kernel<bf16>, grid, dim3(256), 0, s,
                            (const Chunk16 *)(ws + w.O), (Chunk16 *)y,
-                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
-                           (int)w.T, cpr, (int)w.C);
+                           (const int32_t *)(ws + w.tok_slot), (const float *)(ws + w.gate),
+                           (int)w.T, cpr);
     else
         hipLaunchKernelGGL(combine_kernel<float>, grid, dim3(256), 0, s,
                            (const Chunk16 *)(ws + w.O), (Chunk16 *)y,
-                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
-                           (int)w.T, cpr, (int)w.C);
+                           (const int32_t *)(ws + w.tok_slot), (const float *)(ws + w.gate),
+                           (int)w.T, cpr);
     return hipGetLastError();
 }
 
@@ -216,15 +215,13 @@ hipError_t launch_combine_bwd(const Workspace &w, int dtype, const void *dy, cha
     if (dtype == SW_BF16)
         hipLaunchKernelGGL(combine_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const Chunk16 *)dy,
                            (const Chunk16 *)(ws + w.O), (Chunk16 *)(ws + w.dO),
-                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
-                           (float *)(ws + w.dgate), (int)w.T, cpr, (int)w.C);
+                           (const int32_t *)(ws + w.tok_slot), (const float *)(ws + w.gate),
+                           (float *)(ws + w.dgate), (int)w.T, cpr);
     else
         hipLaunchKernelGGL(combine_bwd_kernel<float>, grid, dim3(256), 0, s, (const Chunk16 *)dy,
                            (const Chunk16 *)(ws + w.O), (Chunk16 *)(ws + w.dO),
-                           (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.pos),
-                           (const uint8_t *)(ws + w.dropped), (const float *)(ws + w.gate),
-                           (float *)(ws + w.dgate), (int)w.T, cpr, (int)w.C);
+                           (const int32_t *)(ws + w.tok_slot), (const float *)(ws + w.gate),
+                           (float *)(ws + w.dgate), (int)w.T, cpr);
     return hipGetLastError();
 }
 

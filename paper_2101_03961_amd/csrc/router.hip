@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
     float *__restrict__ probs /* in: logits, out: p */, float *__restrict__ logits_copy,
     int32_t *__restrict__ idx_out, float *__restrict__ gate_out, int32_t *__restrict__ idx_ws,
     float *__restrict__ gate_ws, int32_t *__restrict__ local_rank,
-    int32_t *__restrict__ block_counts, float *__restrict__ block_psum, int T, int E) {
+    int32_t *__restrict__ block_counts, float *__restrict__ block_psum, int nbg, int Tg, int E) {
     extern __shared__ char smem_raw[];
     // layout: idx_s[kRouteTB] | hist[E] | psum_w[4][E]
     int32_t *idx_s = (int32_t *)smem_raw;
@@ -108,6 +108,8 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
     const int lane = tid % kWave;
     const int wave = tid / kWave;
     const int b = blockIdx.x;
+    int t0, tend;
+    block_token_range(b, nbg, Tg, t0, tend);
     for (int e = tid; e < E; e += kRouteTB) hist[e] = 0;
 
     float pacc[EPL];
@@ -116,8 +118,8 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
 
     for (int i = 0; i < kWave; ++i) {
         const int tl = wave * kWave + i;
-        const int t = b * kRouteTB + tl;
-        if (t >= T) {
+        const int t = t0 + tl;
+        if (t >= tend) {
             if (lane == 0) idx_s[tl] = -1;
             continue;
         }
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
         if (me >= 0) {
             int r = 0;
             for (int s = 0; s < tid; ++s) r += (idx_s[s] == me);
-            local_rank[b * kRouteTB + tid] = r;
+            local_rank[t0 + tid] = r;
             atomicAdd(&hist[me], 1);   // integer: result independent of order
         }
     }
@@ -199,8 +201,8 @@ constexpr int kScanThreads = 1024;
 __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
     const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
     int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
-    int32_t *__restrict__ counts_out, float *__restrict__ aux_out, int nb, int E, int C, int T,
-    float alpha) {
+    int32_t *__restrict__ counts_g, int32_t *__restrict__ grp_off, int32_t *__restrict__ counts_out,
+    float *__restrict__ aux_out, int nb, int E, int C, int T, float alpha) {
     __shared__ int32_t part_cnt[kScanThreads];
     __shared__ float part_ps[kScanThreads];
     __shared__ double red[kScanThreads];
@@ -243,6 +245,8 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
                 ptot += part_ps[q * Ew + el];
             }
             counts_ws[e] = total;
+            counts_g[e] = total;   // one group
+            grp_off[e] = 0;
             counts_out[e] = total;
             kept_ws[e] = total < C ? total : C;
             loss_acc += ((double)total / (double)T) * ((double)ptot / (double)T);
@@ -259,22 +263,73 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
 }
 
 // -----------------------------------------------------------------------------
+// The same for several routing groups (single block).  Phase 1, one thread per (group,
+// expert) pair: exclusive scan of the group's blocks, counts_g and P-sums.  Phase 2, one
+// thread per expert: slots of the groups inside the expert's buffer (grp_off), totals, and the
+// expert's share of   aux = (1/n) sum_g alpha E sum_e (counts_g / Tg) (psum_g / Tg).
+// -----------------------------------------------------------------------------
+__global__ __launch_bounds__(kScanThreads) void route_scan_groups_kernel(
+    const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
+    int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
+    int32_t *__restrict__ counts_g, float *__restrict__ psum_g, int32_t *__restrict__ grp_off,
+    int32_t *__restrict__ counts_out, float *__restrict__ aux_out, int n, int nbg, int E, int Cg,
+    int Tg, float alpha) {
+    __shared__ double red[kScanThreads];
+    const int tid = threadIdx.x;
+    for (int pair = tid; pair < n * E; pair += kScanThreads) {
+        const int g = pair / E, e = pair - g * E;
+        int run = 0;
+        float ps = 0.f;
+        for (int b = g * nbg; b < (g + 1) * nbg; ++b) {
+            block_off[(size_t)b * E + e] = run;
+            run += block_counts[(size_t)b * E + e];
+            ps += block_psum[(size_t)b * E + e];
+        }
+        counts_g[pair] = run;
+        psum_g[pair] = ps;
+    }
+    __syncthreads();   // the block's own global writes are visible to it after the barrier
+    double loss_acc = 0.0;
+    for (int e = tid; e < E; e += kScanThreads) {
+        int total = 0, kept = 0;
+        for (int g = 0; g < n; ++g) {
+            const int c = counts_g[g * E + e];
+            grp_off[g * E + e] = kept;
+            kept += c < Cg ? c : Cg;
+            total += c;
+            loss_acc += ((double)c / (double)Tg) * ((double)psum_g[g * E + e] / (double)Tg);
+        }
+        counts_ws[e] = total;
+        counts_out[e] = total;
+        kept_ws[e] = kept;
+    }
+    red[tid] = loss_acc;
+    __syncthreads();
+    for (int s = kScanThreads / 2; s >= 1; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) aux_out[0] = (float)((double)alpha * (double)E * red[0] / (double)n);
+}
+
+// -----------------------------------------------------------------------------
 // Backward, step 1: gradient w.r.t. the logits.
-//   dp[t][i] = dgate[t] [i = e_t] + d_aux * alpha * E * (counts[i] / T) / T
+//   dp[t][i] = dgate[t] [i = e_t] + d_aux * alpha * E * (counts_g[g][i] / Tg) / (n Tg),  t in group g
 //   dl[t][j] = p[t][j] (dp[t][j] - sum_i p[t][i] dp[t][i])
 // One wave per token, lanes stride the experts.
 // -----------------------------------------------------------------------------
 template <int EPL>
 __global__ __launch_bounds__(256) void router_dlogits_kernel(
     const float *__restrict__ probs, const int32_t *__restrict__ idx,
-    const float *__restrict__ dgate, const int32_t *__restrict__ counts,
+    const float *__restrict__ dgate, const int32_t *__restrict__ counts_g /* [n][E] */,
     float *__restrict__ dlogits, bf16 *__restrict__ dl_split /* [T][256] hi | lo, or nullptr */,
-    int T, int E, float aux_scale /* d_aux*alpha*E/T^2 */) {
+    int T, int Tg, int E, float aux_scale /* d_aux*alpha*E/(n Tg^2) */) {
     const int lane = threadIdx.x % kWave;
     const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
     if (t >= T) return;
     const int me = idx[t];
     const float dg = dgate[t];
+    const int32_t *counts = counts_g + (size_t)(t / Tg) * E;
     float p[EPL], dp[EPL];
     float s = 0.f;
 #pragma unroll
@@ -326,8 +381,8 @@ __global__ __launch_bounds__(256) void reduce_dWr_split_kernel(const float *__re
 template <typename XT>
 __global__ __launch_bounds__(256) void router_dx_kernel(
     const float *__restrict__ dlogits, const float *__restrict__ W_r,
-    const XT *__restrict__ dXd, const int32_t *__restrict__ idx, const int32_t *__restrict__ pos,
-    const uint8_t *__restrict__ dropped, XT *__restrict__ dx, int T, int d, int E, int C) {
+    const XT *__restrict__ dXd, const int32_t *__restrict__ tok_slot, XT *__restrict__ dx, int T,
+    int d, int E) {
     __shared__ float ds[kLogKC][kLogTB + 4];
     __shared__ float wsm[kLogKC][kLogEB + 4];
     const int tid = threadIdx.x;
@@ -378,8 +433,9 @@ __global__ __launch_bounds__(256) void router_dx_kernel(
     for (int i = 0; i < 8; ++i) {
         const int t = t0 + ty * 8 + i;
         if (t >= T) continue;
-        const bool kept = !dropped[t];
-        const size_t slot = kept ? (size_t)idx[t] * C + pos[t] : 0;
+        const int slot_or_none = tok_slot[t];
+        const bool kept = slot_or_none >= 0;
+        const size_t slot = kept ? (size_t)slot_or_none : 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int k = k0 + tx * 8 + j;
@@ -498,7 +554,7 @@ static hipError_t softmax_launch(const Workspace &w, char *ws, int32_t *expert_i
                        (float *)(ws + w.probs), router_logits, expert_index, gate,
                        (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
                        (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
-                       (float *)(ws + w.block_psum), (int)w.T, (int)w.E);
+                       (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, (int)w.E);
     return hipGetLastError();
 }
 
@@ -541,11 +597,21 @@ hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const
 hipError_t launch_route_scan(const Workspace &w, float alpha, char *ws, int32_t *expert_counts,
                              float *aux_loss, hipStream_t s) {
     ProfScope ps("route_scan_aux", s);
-    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(kScanThreads), 0, s,
-                       (const int32_t *)(ws + w.block_counts), (const float *)(ws + w.block_psum),
-                       (int32_t *)(ws + w.block_off), (int32_t *)(ws + w.counts),
-                       (int32_t *)(ws + w.kept), expert_counts, aux_loss, (int)w.nb, (int)w.E,
-                       (int)w.C, (int)w.T, alpha);
+    if (w.n == 1)
+        hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(kScanThreads), 0, s,
+                           (const int32_t *)(ws + w.block_counts),
+                           (const float *)(ws + w.block_psum), (int32_t *)(ws + w.block_off),
+                           (int32_t *)(ws + w.counts), (int32_t *)(ws + w.kept),
+                           (int32_t *)(ws + w.counts_g), (int32_t *)(ws + w.grp_off),
+                           expert_counts, aux_loss, (int)w.nb, (int)w.E, (int)w.C, (int)w.T, alpha);
+    else
+        hipLaunchKernelGGL(route_scan_groups_kernel, dim3(1), dim3(kScanThreads), 0, s,
+                           (const int32_t *)(ws + w.block_counts),
+                           (const float *)(ws + w.block_psum), (int32_t *)(ws + w.block_off),
+                           (int32_t *)(ws + w.counts), (int32_t *)(ws + w.kept),
+                           (int32_t *)(ws + w.counts_g), (float *)(ws + w.psum_g),
+                           (int32_t *)(ws + w.grp_off), expert_counts, aux_loss, (int)w.n,
+                           (int)w.nbg, (int)w.E, (int)w.Cg, (int)w.Tg, alpha);
     return hipGetLastError();
 }
 
@@ -563,13 +629,13 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
     bf16 *dl_split = mfma ? (bf16 *)(ws + w.dl_split) : nullptr;
     {
         ProfScope ps("router_dlogits", s);
-        const float aux_scale =
-            (float)((double)d_aux * (double)alpha * (double)w.E / ((double)w.T * (double)w.T));
+        const float aux_scale = (float)((double)d_aux * (double)alpha * (double)w.E /
+                                        ((double)w.n * (double)w.Tg * (double)w.Tg));
 #define CALL(N)                                                                                  \
     hipLaunchKernelGGL(router_dlogits_kernel<N>, dim3((unsigned)ceil_div(w.T, 4)), dim3(256), 0, \
                        s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),          \
-                       (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts), dlogits, \
-                       dl_split, (int)w.T, (int)w.E, aux_scale)
+                       (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts_g),        \
+                       dlogits, dl_split, (int)w.T, (int)w.Tg, (int)w.E, aux_scale)
         SW_DISPATCH_EPL(w.E, CALL);
 #undef CALL
         if ((err = hipGetLastError()) != hipSuccess) return err;
@@ -586,9 +652,8 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
         ProfScope ps("router_dx", s);
         dim3 grid((unsigned)ceil_div(w.T, kLogTB), (unsigned)ceil_div(w.d, kLogEB));
         hipLaunchKernelGGL(router_dx_kernel<XT>, grid, dim3(256), 0, s, dlogits, W_r,
-                           (const XT *)(ws + w.dXd), (const int32_t *)(ws + w.idx),
-                           (const int32_t *)(ws + w.pos), (const uint8_t *)(ws + w.dropped), dx,
-                           (int)w.T, (int)w.d, (int)w.E, (int)w.C);
+                           (const XT *)(ws + w.dXd), (const int32_t *)(ws + w.tok_slot), dx,
+                           (int)w.T, (int)w.d, (int)w.E);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     const int tokens_per_split = (int)ceil_div(w.T, w.nsplit);

@@ -63,17 +63,18 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     float *__restrict__ probs, float *__restrict__ logits_out, int32_t *__restrict__ idx_out,
     float *__restrict__ gate_out, int32_t *__restrict__ idx_ws, float *__restrict__ gate_ws,
     int32_t *__restrict__ local_rank, int32_t *__restrict__ block_counts,
-    float *__restrict__ block_psum, int T, int d, int dpad, int E) {
+    float *__restrict__ block_psum, int nbg, int Tg, int d, int dpad, int E) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
     const int b = blockIdx.x;
-    const int t0 = b * kRmTokens;
+    int t0, tend;   // the block's tokens: [t0, tend), inside one routing group
+    block_token_range(b, nbg, Tg, t0, tend);
 
     DirectOperand ox, ow;
-    ox.init(x, d, t0, T, d, lane, wave, wave * 64);
+    ox.init(x, d, t0, tend, d, lane, wave, wave * 64);
     ow.init(wsplit, dpad, 0, 3 * kRmExperts, dpad, lane, wave, 0);
     const int nk = dpad / 32;
 
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
             const int oi = __shfl_xor(besti, 32, kWave);
             if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
         }
-        if (logits_out && t < T) {
+        if (logits_out && t < tend) {
 #pragma unroll
             for (int et = 0; et < 4; ++et)
 #pragma unroll
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
                                 acc[tt][et][4 * g + 2] / z, acc[tt][et][4 * g + 3] / z);
             }
         if (lane < 32) {
-            if (t < T) {
+            if (t < tend) {
                 const float gt = 1.0f / z;   // exp(0) / z: probability of the arg max
                 idx_s[tl] = besti;
                 idx_out[t] = besti;
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     __syncthreads();
 
     // ---- probabilities out as whole rows; block statistics -------------------------
-    const int nvalid = (T - t0) < kRmTokens ? (T - t0) : kRmTokens;
+    const int nvalid = tend - t0;
     {
         const int c4 = (tid & 31) * 4;
         for (int row = tid >> 5; row < nvalid; row += 8)
@@ -253,7 +254,8 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
                            (float *)(ws + w.probs), router_logits, expert_index, gate,
                            (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
                            (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
-                           (float *)(ws + w.block_psum), (int)w.T, (int)w.d, (int)w.dpad, (int)w.E);
+                           (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, (int)w.d, (int)w.dpad,
+                           (int)w.E);
         err = hipGetLastError();
     }
     return err;

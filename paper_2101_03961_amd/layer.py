@@ -16,11 +16,11 @@ from . import binding as B
 class SwitchLayer:
     def __init__(self, T: int, d_model: int, d_ff: int, E: int, capacity_factor: float,
                  alpha: float = 0.01, dtype: str = "bf16", device: str = "cuda:0",
-                 want_logits: bool = False):
+                 want_logits: bool = False, n_groups: int = 1):
         if not torch.cuda.is_available():
             raise RuntimeError("SwitchLayer needs a GPU: the layer runs only in the HIP library")
         self.cfg = B.SwitchConfig(T, d_model, d_ff, E, float(capacity_factor), float(alpha),
-                                  B.SW_BF16 if dtype == "bf16" else B.SW_F32)
+                                  B.SW_BF16 if dtype == "bf16" else B.SW_F32, 0, int(n_groups))
         self.device = torch.device(device)
         self.act = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.capacity = B.switch_capacity(self.cfg)

@@ -45,6 +45,7 @@ class SwitchShape:
     dtype: str = "bf16"          # storage dtype of x, W_in, W_out, dy: "bf16" or "f32"
     zipf_bias: bool = False      # router bias b_r = 2 ln Zipf(1.1) weights
     seed_index: int = 0
+    n_groups: int = 1            # routing groups of T / n_groups consecutive tokens
 
     def with_(self, **kw) -> "SwitchShape":
         return replace(self, **kw)

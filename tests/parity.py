@@ -104,7 +104,8 @@ def assert_close(name, a, ref, dtype, widen=1.0):
 def run_gpu(shape, inp, d_aux=1.0, backward=True, dy=None):
     """One forward (+ backward) through the C ABI; returns (layer, numpy dict)."""
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
-                        shape.alpha, shape.dtype, device=str(inp["x"].device), want_logits=True)
+                        shape.alpha, shape.dtype, device=str(inp["x"].device), want_logits=True,
+                        n_groups=shape.n_groups)
     out = layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"])
     res = {k: to_np(v) for k, v in out.items() if v is not None}
     if backward:
@@ -122,7 +123,7 @@ def check_routing(shape, npi, gpu):
     # (i) routing stage on identical logits: bit exact
     same = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], shape.capacity_factor,
                           shape.alpha, b_r=npi["b_r"], logits_override=gpu["router_logits"],
-                          skip_ffn=True)
+                          skip_ffn=True, n_groups=shape.n_groups)
     assert np.array_equal(gpu["expert_index"], same["expert_index"]), "expert_index"
     assert np.array_equal(gpu["position_in_expert"], same["position_in_expert"]), "position"
     assert np.array_equal(gpu["dropped"], same["dropped"]), "dropped"
@@ -142,7 +143,7 @@ def check_routing(shape, npi, gpu):
     pinned = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"],
                             shape.capacity_factor, shape.alpha, b_r=npi["b_r"],
                             logits_override=h64, expert_index_override=gpu["expert_index"],
-                            skip_ffn=True)
+                            skip_ffn=True, n_groups=shape.n_groups)
     assert np.array_equal(gpu["dropped"], pinned["dropped"])
     np.testing.assert_allclose(gpu["gate"], pinned["gate"], rtol=3e-5, atol=0)
     assert abs(float(gpu["aux_loss"][0]) - pinned["aux_loss"]) <= 1e-5 * abs(pinned["aux_loss"])

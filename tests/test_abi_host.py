@@ -35,6 +35,11 @@ def test_capacity_and_workspace_host_functions():
         cfg = sw.SwitchConfig(T, 64, 256, E, cf, 0.01, sw.SW_F32)
         assert sw.switch_capacity(cfg) == C
         assert sw.switch_workspace_size(cfg) > 0
+    # routing groups: Eq. 3 on the group's tokens; one group when the field is 0 or 1
+    for n, C in {0: 512, 1: 512, 8: 64, 128: 4, 512: 1, 1024: 0}.items():
+        cfg = sw.SwitchConfig(65536, 64, 256, 128, 1.0, 0.01, sw.SW_BF16, 0, n)
+        assert sw.switch_capacity(cfg) == C
+        assert sw.switch_workspace_size(cfg) > 0
     a = sw.switch_workspace_size(sw.SwitchConfig(4096, 64, 256, 8, 1.0, 0.01, sw.SW_BF16))
     b = sw.switch_workspace_size(sw.SwitchConfig(4096, 64, 256, 8, 2.0, 0.01, sw.SW_BF16))
     assert b > a
@@ -47,13 +52,15 @@ def test_capacity_and_workspace_host_functions():
     (dict(capacity_factor=0.0), -3), (dict(capacity_factor=-1.0), -3),
     (dict(capacity_factor=float("nan")), -3), (dict(capacity_factor=float("inf")), -3),
     (dict(alpha=float("nan")), -3), (dict(act_dtype=7), -4),
+    (dict(n_groups=3), -2),            # 256 tokens do not split into 3 groups
+    (dict(n_groups=-1), -2),
 ])
 def test_bad_config_is_refused(kw, status):
     base = dict(T=256, d_model=64, d_ff=256, E=4, capacity_factor=1.25, alpha=0.01,
-                act_dtype=sw.SW_BF16)
+                act_dtype=sw.SW_BF16, reserved=0, n_groups=1)
     base.update(kw)
     cfg = sw.SwitchConfig(*[base[k] for k in ("T", "d_model", "d_ff", "E", "capacity_factor",
-                                              "alpha", "act_dtype")])
+                                              "alpha", "act_dtype", "reserved", "n_groups")])
     with pytest.raises(sw.SwitchError) as ei:
         sw.switch_capacity(cfg)
     assert ei.value.status == status

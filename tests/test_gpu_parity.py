@@ -112,6 +112,37 @@ def test_bf16_router_widths(T, d, f, E, cf):
     _report("bf16 router E=%d" % E, errs)
 
 
+@pytest.mark.parametrize("dtype,T,d,f,E,cf,n", [
+    ("f32", 600, 32, 48, 4, 1.0, 2),       # 300 tokens per group: blocks of 256 + 44
+    ("f32", 90, 16, 24, 3, 0.9, 5),        # groups smaller than a token block
+    ("bf16", 4096, 128, 256, 16, 1.0, 8),  # groups of two full blocks
+    ("bf16", 3000, 96, 136, 12, 1.25, 3),  # 1000 tokens per group
+    ("bf16", 2100, 64, 72, 7, 0.5, 7),     # heavy dropping in every group, vector-ALU router
+])
+def test_routing_groups(dtype, T, d, f, E, cf, n):
+    """Capacity, positions and the loss fractions per routing group; shared experts."""
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=57, n_groups=n)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.8)
+    _report("groups %s" % ((dtype, T, E, cf, n),), errs)
+    assert fwd["capacity"] == int(np.floor(T / n / E * cf))
+    # positions restart in every group
+    Tg = T // n
+    first = np.array([np.flatnonzero(gpu["expert_index"][g * Tg:(g + 1) * Tg] ==
+                                     gpu["expert_index"][g * Tg])[0] for g in range(n)])
+    assert np.all(first == 0) and np.all(gpu["position_in_expert"][::Tg] == 0)
+
+
+def test_routing_groups_full_size():
+    """Switch-Base shape as eight routing groups (capacity 64 per expert and group)."""
+    from parity import compare_sampled
+    s = CONFIGS["base_cf1.0"].with_(n_groups=8)
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=2, n_tokens=24)
+    _report("base_cf1.0 x 8 groups", errs)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_empty_batch(dtype):
     """T = 0: counts and loss zero, weight gradients zero, nothing else touched."""
