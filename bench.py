@@ -148,7 +148,7 @@ def main() -> int:
     sw.switch_profile_enable(False)
 
     counts = layer.expert_counts.cpu().numpy().astype("int64")
-    kept = int(counts.clip(max=layer.capacity).sum())
+    kept = shape.T - int(layer.dropped.sum().item())
     elt = 2 if shape.dtype == "bf16" else 4
     work = kernel_work(shape, kept, elt)
     kernels = {}
