@@ -255,9 +255,11 @@ int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const
 
     if ((st = status_of(launch_combine_bwd(w, dt, dy, ws, s)))) return st;
     if ((st = status_of(gemm(GEMM_DGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
-    if ((st = status_of(gemm(GEMM_WGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    // dH is consumed right after it is produced (the first-layer data gradient walks the
+    // experts backwards, see launch_gemm_bf16), then the two weight gradients
     if ((st = status_of(gemm(GEMM_DGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
     if ((st = status_of(gemm(GEMM_WGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if ((st = status_of(gemm(GEMM_WGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
     if ((st = status_of(launch_router_bwd(w, dt, cfg->alpha, d_aux, x, W_r, ws, dx, dW_r, db_r, s))))
         return st;
     return SW_OK;
