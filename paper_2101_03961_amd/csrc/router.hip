@@ -367,7 +367,8 @@ __global__ __launch_bounds__(256) void reduce_dWr_split_kernel(const float *__re
     if (i >= d * E) return;
     const int k = i / E, j = i - k * E;
     float s = 0.f;
-    for (int q = 0; q < nsplit; ++q) {
+#pragma unroll 8
+    for (int q = 0; q < nsplit; ++q) {   // unrolled: eight splits' loads in flight, same order of sums
         const float *row = part + ((size_t)q * d + k) * 256;
         s += row[j] + row[128 + j];
     }

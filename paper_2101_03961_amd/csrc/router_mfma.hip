@@ -27,7 +27,7 @@ constexpr int kRmWBytes = 3 * kRmExperts * 32 * 2;     // three terms x 128 expe
 constexpr int kRmStageBytes = kRmXBytes + kRmWBytes;   // 40 KB
 constexpr int kRmPitch = kRmExperts + 4;               // floats per row of the probability tile
 constexpr int kRmTileBytes = kRmTokens * kRmPitch * 4; // 132 KB
-constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + kRmExperts * 4;
+constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + 4 * kRmExperts * 4;
 
 // W_r [d][E] fp32 -> wsplit [3][128][dpad] bf16: term s of expert e, k contiguous;
 // rows of absent experts and columns past d are zero.  Also, for the backward
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     // ---- softmax, arg max, gate: lane and lane ^ 32 share a token -----------------
     float *ptile = (float *)lds;                                   // [256][kRmPitch]
     int32_t *idx_s = (int32_t *)(lds + kRmTileBytes);              // [256]
-    int32_t *hist = idx_s + kRmTokens;                             // [128]
-    if (tid < kRmExperts) hist[tid] = 0;
+    int32_t *hist = idx_s + kRmTokens;                             // [4][128]
+    for (int i = tid; i < 4 * kRmExperts; i += 256) hist[i] = 0;   // one histogram per wave
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
         const int tl = wave * 64 + tt * 32 + (lane & 31);
@@ -166,23 +166,26 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
         for (int et = 0; et < 4; ++et)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float ex = expf(acc[tt][et][r] - best);   // exp(-inf) = 0 for absent experts
+                // exp(-inf) = 0 for absent experts; the hardware exp2 is accurate to about one
+                // ulp, the scaled argument adds |h - best| * 2^-24: far inside the 1e-5 budget
+                const float ex = __expf(acc[tt][et][r] - best);
                 acc[tt][et][r] = ex;
                 z += ex;
             }
         z += __shfl_xor(z, 32, kWave);
+        const float rz = 1.0f / z;   // exp(0) / z: also the probability of the arg max
 #pragma unroll
         for (int et = 0; et < 4; ++et)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int e = et * 32 + 8 * g + 4 * (lane >> 5);
                 *(float4 *)(ptile + tl * kRmPitch + e) =
-                    make_float4(acc[tt][et][4 * g] / z, acc[tt][et][4 * g + 1] / z,
-                                acc[tt][et][4 * g + 2] / z, acc[tt][et][4 * g + 3] / z);
+                    make_float4(acc[tt][et][4 * g] * rz, acc[tt][et][4 * g + 1] * rz,
+                                acc[tt][et][4 * g + 2] * rz, acc[tt][et][4 * g + 3] * rz);
             }
         if (lane < 32) {
             if (t < tend) {
-                const float gt = 1.0f / z;   // exp(0) / z: probability of the arg max
+                const float gt = rz;
                 idx_s[tl] = besti;
                 idx_out[t] = besti;
                 idx_ws[t] = besti;
@@ -205,20 +208,40 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
                     *(const float4 *)(ptile + row * kRmPitch + c4);
     }
     {
+        // rank of each token among the block's earlier tokens of the same expert: lanes below
+        // it in its own wave (64 compares against broadcast lanes) plus the earlier waves'
+        // counts of that expert (per-wave histograms)
+        int32_t *hist_w = hist;   // [4 waves][128]
         const int me = idx_s[tid];
+        int r = 0;
+#pragma unroll
+        for (int sl = 0; sl < 64; ++sl) {
+            const int other = __builtin_amdgcn_readlane(me, sl);
+            r += (sl < lane && other == me) ? 1 : 0;
+        }
+        if (me >= 0) atomicAdd(&hist_w[wave * kRmExperts + me], 1);   // integer: order-free
+        __syncthreads();
         if (me >= 0) {
-            int r = 0;
-            for (int s = 0; s < tid; ++s) r += (idx_s[s] == me);
+            for (int w = 0; w < wave; ++w) r += hist_w[w * kRmExperts + me];
             local_rank[t0 + tid] = r;
-            atomicAdd(&hist[me], 1);   // integer: result independent of order
         }
     }
-    __syncthreads();
     if (tid < E) {
-        float s = 0.f;
-        for (int row = 0; row < nvalid; ++row) s += ptile[row * kRmPitch + tid];
-        block_psum[(size_t)b * E + tid] = s;
-        block_counts[(size_t)b * E + tid] = hist[tid];
+        // column sums in a fixed order: four interleaved chains, then ((s0 + s1) + (s2 + s3))
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int row = 0;
+        for (; row + 3 < nvalid; row += 4) {
+            s0 += ptile[row * kRmPitch + tid];
+            s1 += ptile[(row + 1) * kRmPitch + tid];
+            s2 += ptile[(row + 2) * kRmPitch + tid];
+            s3 += ptile[(row + 3) * kRmPitch + tid];
+        }
+        for (; row < nvalid; ++row) s0 += ptile[row * kRmPitch + tid];
+        block_psum[(size_t)b * E + tid] = (s0 + s1) + (s2 + s3);
+        const int32_t *hist_w = hist;
+        block_counts[(size_t)b * E + tid] =
+            hist_w[tid] + hist_w[kRmExperts + tid] + hist_w[2 * kRmExperts + tid] +
+            hist_w[3 * kRmExperts + tid];
     }
 }
 #undef SW_WAIT_VMCNT
