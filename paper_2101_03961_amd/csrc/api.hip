@@ -74,7 +74,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.dgate = take(T * 4);
     w.dlogits = take(T * E * 4);
     w.dWr_part = take((size_t)w.nsplit * d * E * 4);
-    w.dbr_part = take((size_t)w.nsplit * E * 4);
+    w.dbr_part = take((size_t)ceil_div(w.T, kRouteTB) * E * 4);
     w.dpad = ceil_div(w.d, 32) * 32;
     w.wsplit = take((size_t)3 * 128 * w.dpad * 2);
     w.wsplit_b = take(d * 256 * 2);

@@ -80,7 +80,7 @@ struct Workspace {
     size_t dgate;               // f32 [T]
     size_t dlogits;             // f32 [T][E]
     size_t dWr_part;            // f32 [nsplit][d][E]  split-T partial sums of dW_r
-    size_t dbr_part;            // f32 [nsplit][E]
+    size_t dbr_part;            // f32 [ceil(T / 256)][E]  per-256-token sums of dlogits
     size_t wsplit;              // bf16 [3][128][dpad]  W_r^T as three bf16 terms (MFMA router)
     int64_t dpad;               // d rounded up to a multiple of 32
     size_t wsplit_b;            // bf16 [d][256]   W_r rows as hi | lo halves (MFMA router backward)

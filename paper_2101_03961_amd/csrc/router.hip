@@ -522,15 +522,21 @@ __global__ __launch_bounds__(256) void router_dWr_kernel(const XT *__restrict__ 
 
 // db_r partials: part[split][j] = sum over the split's tokens of dl[t][j]
 __global__ __launch_bounds__(256) void router_dbr_kernel(const float *__restrict__ dlogits,
-                                                         float *__restrict__ part, int T, int E,
-                                                         int tokens_per_split) {
-    const int split = blockIdx.x;
-    const int t_lo = split * tokens_per_split;
-    const int t_hi = (t_lo + tokens_per_split < T) ? t_lo + tokens_per_split : T;
+                                                         float *__restrict__ part, int T, int E) {
+    // one block per 256 tokens; a thread sums a column in four interleaved chains (fixed order)
+    const int t_lo = blockIdx.x * 256;
+    const int t_hi = (t_lo + 256 < T) ? t_lo + 256 : T;
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        float s = 0.f;
-        for (int t = t_lo; t < t_hi; ++t) s += dlogits[(size_t)t * E + e];
-        part[(size_t)split * E + e] = s;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int t = t_lo;
+        for (; t + 3 < t_hi; t += 4) {
+            s0 += dlogits[(size_t)t * E + e];
+            s1 += dlogits[(size_t)(t + 1) * E + e];
+            s2 += dlogits[(size_t)(t + 2) * E + e];
+            s3 += dlogits[(size_t)(t + 3) * E + e];
+        }
+        for (; t < t_hi; ++t) s0 += dlogits[(size_t)t * E + e];
+        part[(size_t)blockIdx.x * E + e] = (s0 + s1) + (s2 + s3);
     }
 }
 
@@ -540,6 +546,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     float s = 0.f;
+#pragma unroll 8
     for (int q = 0; q < nsplit; ++q) s += part[(size_t)q * n + i];
     out[i] = s;
 }
@@ -673,12 +680,12 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
     }
     if (db_r) {
         ProfScope ps("router_dbr", s);
-        hipLaunchKernelGGL(router_dbr_kernel, dim3((unsigned)w.nsplit), dim3(256), 0, s, dlogits,
-                           (float *)(ws + w.dbr_part), (int)w.T, (int)w.E, tokens_per_split);
+        const int nblk = (int)ceil_div(w.T, 256);
+        hipLaunchKernelGGL(router_dbr_kernel, dim3((unsigned)nblk), dim3(256), 0, s, dlogits,
+                           (float *)(ws + w.dbr_part), (int)w.T, (int)w.E);
         if ((err = hipGetLastError()) != hipSuccess) return err;
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(w.E, 256)), dim3(256),
-                           0, s, (const float *)(ws + w.dbr_part), db_r, (size_t)w.E,
-                           (int)w.nsplit);
+                           0, s, (const float *)(ws + w.dbr_part), db_r, (size_t)w.E, nblk);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     return err;
