@@ -52,8 +52,6 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.probs = take(T * E * 4);
     w.idx = take(T * 4);
     w.gate = take(T * 4);
-    w.pos = take(T * 4);
-    w.dropped = take(T);
     w.local_rank = take(nb * kRouteTB * 4);
     w.block_counts = take(nb * E * 4);
     w.block_psum = take(nb * E * 4);

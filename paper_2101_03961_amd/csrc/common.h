@@ -56,8 +56,6 @@ struct Workspace {
     size_t probs;               // f32 [T][E]   router probabilities (saved for backward)
     size_t idx;                 // i32 [T]
     size_t gate;                // f32 [T]
-    size_t pos;                 // i32 [T]
-    size_t dropped;             // u8  [T]
     size_t local_rank;          // i32 [T]      rank among same-expert tokens of the block
     size_t block_counts;        // i32 [nb][E]
     size_t block_psum;          // f32 [nb][E]

@@ -54,8 +54,8 @@ template <> __device__ __forceinline__ Chunk16 pack<bf16>(const float *v) {
 __global__ __launch_bounds__(256) void positions_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ local_rank,
     const int32_t *__restrict__ block_off, const int32_t *__restrict__ grp_off,
-    int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out, int32_t *__restrict__ pos_ws,
-    uint8_t *__restrict__ dropped_ws, int32_t *__restrict__ slot_token,
+    int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out,
+    int32_t *__restrict__ slot_token,
     int32_t *__restrict__ tok_slot, int T, int Tg, int nbg, int E, int C, int Cg) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= T) return;
@@ -63,9 +63,7 @@ __global__ __launch_bounds__(256) void positions_kernel(
     const int p = block_off[(size_t)block_of_token(t, nbg, Tg) * E + e] + local_rank[t];
     const uint8_t dr = p >= Cg;
     pos_out[t] = p;
-    pos_ws[t] = p;
     dropped_out[t] = dr;
-    dropped_ws[t] = dr;
     const int slot = e * C + grp_off[(size_t)(t / Tg) * E + e] + p;
     if (!dr) slot_token[slot] = t;
     tok_slot[t] = dr ? -1 : slot;
@@ -169,8 +167,7 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *w
         hipLaunchKernelGGL(positions_kernel, dim3((unsigned)ceil_div(w.T, 256)), dim3(256), 0, s,
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.local_rank),
                            (const int32_t *)(ws + w.block_off), (const int32_t *)(ws + w.grp_off),
-                           position_in_expert, dropped, (int32_t *)(ws + w.pos),
-                           (uint8_t *)(ws + w.dropped), (int32_t *)(ws + w.slot_token),
+                           position_in_expert, dropped, (int32_t *)(ws + w.slot_token),
                            (int32_t *)(ws + w.tok_slot), (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E,
                            (int)w.C, (int)w.Cg);
         if ((err = hipGetLastError()) != hipSuccess) return err;

@@ -42,8 +42,13 @@
 // HBM once per XCD (measured: starting neighbours a few k steps apart, to turn
 // hits under a miss into plain hits, raised HBM traffic by a third -- the leading
 // block's lines were evicted before the followers arrived -- and saved no time).
-// The epilogue turns each wave's sub-tile around through LDS so that C is written
-// in whole 256-byte row segments.
+// The k steps of all tiles of a block form one load pipeline: a tile's last two steps
+// issue the next tile's first two loads, which stay in flight during the epilogue.
+// The epilogue turns each wave's sub-tile around, 32 rows at a time, through 8 KB of
+// LDS of its own (ring 128 KB + 4 x 8 KB = all 160 KB of a CU) so that C is written
+// in whole 256-byte row segments; fused into it: ReLU and one mask bit per element
+// (first forward GEMM), that mask (gradient w.r.t. the hidden activations), the
+// gathered addend of the router's dx.
 #include "common.h"
 #include "lds_operands.h"
 
