@@ -46,7 +46,9 @@ typedef enum { SW_F32 = 0, SW_BF16 = 1 } sw_dtype;
 typedef enum {
     SW_OK = 0,
     SW_ERR_NULL = -1,      /* a required pointer is NULL                         */
-    SW_ERR_SHAPE = -2,     /* T, d_model, d_ff, E out of range / not multiple of 8 */
+    SW_ERR_SHAPE = -2,     /* T, d_model, d_ff, E, n_groups out of range; rows not whole
+                              16-byte chunks; bf16: an expert's weight matrix or its
+                              slots x max(d_model, d_ff) activations reach 2 GB       */
     SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite */
     SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16            */
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */

@@ -27,6 +27,12 @@ int check_config(const switch_config *cfg) {
     const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
     const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
     if (c * n * (double)cfg->E >= 2147483647.0) return SW_ERR_SHAPE;
+    if (cfg->act_dtype == SW_BF16) {
+        // the bf16 GEMMs address one expert's matrices through 32-bit buffer descriptors
+        const double wide = (double)(cfg->d_model > cfg->d_ff ? cfg->d_model : cfg->d_ff);
+        if ((double)cfg->d_model * (double)cfg->d_ff * 2.0 >= 2147483647.0) return SW_ERR_SHAPE;
+        if (c * n * wide * 2.0 >= 2147483647.0) return SW_ERR_SHAPE;
+    }
     return SW_OK;
 }
 

@@ -53,6 +53,7 @@ def test_capacity_and_workspace_host_functions():
     (dict(capacity_factor=float("nan")), -3), (dict(capacity_factor=float("inf")), -3),
     (dict(alpha=float("nan")), -3), (dict(act_dtype=7), -4),
     (dict(n_groups=3), -2),            # 256 tokens do not split into 3 groups
+    (dict(d_model=65536, d_ff=32768), -2),   # one expert's bf16 matrix would reach 4 GB
     (dict(n_groups=-1), -2),
 ])
 def test_bad_config_is_refused(kw, status):
