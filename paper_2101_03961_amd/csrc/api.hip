@@ -66,6 +66,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.counts_g = take((size_t)w.n * E * 4);
     w.psum_g = take((size_t)w.n * E * 4);
     w.grp_off = take((size_t)w.n * E * 4);
+    w.loss_part = take(8 * 8);
     w.kept = take(E * 4);
     w.slot_token = take(E * C * 4);
     w.tok_slot = take(T * 4);
@@ -215,9 +216,10 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
         st = status_of(launch_router_fwd(w, dt, x, W_r, b_r, ws, expert_index, gate,
                                          router_logits, s));
     if (st) return st;
-    if ((st = status_of(launch_route_scan(w, cfg->alpha, ws, expert_counts, aux_loss, s))))
+    if ((st = status_of(launch_route_scan(w, ws, expert_counts, s)))) return st;
+    if ((st = status_of(launch_dispatch(w, dt, cfg->alpha, x, ws, position_in_expert, dropped,
+                                        aux_loss, s))))
         return st;
-    if ((st = status_of(launch_dispatch(w, dt, x, ws, position_in_expert, dropped, s)))) return st;
     if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
     if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
     if ((st = status_of(launch_combine(w, dt, ws, y, s)))) return st;

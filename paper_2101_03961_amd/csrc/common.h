@@ -63,6 +63,7 @@ struct Workspace {
     size_t counts;              // i32 [E]      arg max decisions per expert, all groups
     size_t counts_g;            // i32 [n][E]   ... per group
     size_t psum_g;              // f32 [n][E]   sum of router probabilities per group and expert
+    size_t loss_part;           // f64 [8]      parts of sum (counts / Tg) (psum / Tg), one per scan block
     size_t grp_off;             // i32 [n][E]   first slot of group g inside expert e's slots:
                                 //              sum of min(counts_g, Cg) over earlier groups
     size_t kept;                // i32 [E]      kept tokens per expert: sum over groups of min(count, Cg)
@@ -117,11 +118,13 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
                                   const float *b_r, char *ws, int32_t *expert_index, float *gate,
                                   float *router_logits, hipStream_t s);
 // Per-expert scan over token blocks, counts, kept, aux loss.
-hipError_t launch_route_scan(const Workspace &w, float alpha, char *ws, int32_t *expert_counts,
-                             float *aux_loss, hipStream_t s);
-// Positions, dropped mask, gather of kept tokens into expert-major slots.
-hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *ws,
-                           int32_t *position_in_expert, uint8_t *dropped, hipStream_t s);
+hipError_t launch_route_scan(const Workspace &w, char *ws, int32_t *expert_counts, hipStream_t s);
+// number of blocks of that launch = parts of the loss that positions_kernel adds up
+int route_scan_blocks(const Workspace &w);
+// Positions, dropped mask, the loss from its parts, gather of kept tokens into expert-major slots.
+hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
+                           int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
+                           hipStream_t s);
 hipError_t launch_combine(const Workspace &w, int dtype, char *ws, void *y, hipStream_t s);
 hipError_t launch_combine_bwd(const Workspace &w, int dtype, const void *dy, char *ws,
                               hipStream_t s);

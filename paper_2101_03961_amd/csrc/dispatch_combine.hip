@@ -49,15 +49,23 @@ template <> __device__ __forceinline__ Chunk16 pack<bf16>(const float *v) {
 // -----------------------------------------------------------------------------
 // position_in_expert[t] = block_off[block(t)][e_t] + local_rank[t] (rank inside the token's
 // routing group); dropped mask (position >= Cg); slot of each kept token,
-// e * C + grp_off[g][e] + position, and the slot -> token table.
+// e * C + grp_off[g][e] + position, and the slot -> token table.  Thread 0 also finishes
+// the auxiliary loss.
 // -----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void positions_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ local_rank,
     const int32_t *__restrict__ block_off, const int32_t *__restrict__ grp_off,
     int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out,
     int32_t *__restrict__ slot_token,
-    int32_t *__restrict__ tok_slot, int T, int Tg, int nbg, int E, int C, int Cg) {
+    int32_t *__restrict__ tok_slot, const double *__restrict__ loss_part, int loss_parts,
+    double loss_scale /* alpha E / n */, float *__restrict__ aux_out, int T, int Tg, int nbg, int E,
+    int C, int Cg) {
     const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t == 0) {   // Eqs. 4-6 from the scan kernel's parts, in block order
+        double sum = 0.0;
+        for (int i = 0; i < loss_parts; ++i) sum += loss_part[i];
+        aux_out[0] = (float)(loss_scale * sum);
+    }
     if (t >= T) return;
     const int e = idx[t];
     const int p = block_off[(size_t)block_of_token(t, nbg, Tg) * E + e] + local_rank[t];
@@ -159,8 +167,9 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
 // -----------------------------------------------------------------------------
 // launchers
 // -----------------------------------------------------------------------------
-hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *ws,
-                           int32_t *position_in_expert, uint8_t *dropped, hipStream_t s) {
+hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
+                           int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
+                           hipStream_t s) {
     hipError_t err;
     {
         ProfScope ps("positions", s);
@@ -168,8 +177,10 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, const void *x, char *w
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.local_rank),
                            (const int32_t *)(ws + w.block_off), (const int32_t *)(ws + w.grp_off),
                            position_in_expert, dropped, (int32_t *)(ws + w.slot_token),
-                           (int32_t *)(ws + w.tok_slot), (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E,
-                           (int)w.C, (int)w.Cg);
+                           (int32_t *)(ws + w.tok_slot), (const double *)(ws + w.loss_part),
+                           route_scan_blocks(w), (double)alpha * (double)w.E / (double)w.n,
+                           aux_loss, (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E, (int)w.C,
+                           (int)w.Cg);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (w.C == 0) return hipSuccess;

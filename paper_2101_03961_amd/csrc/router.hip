@@ -191,7 +191,9 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
 }
 
 // -----------------------------------------------------------------------------
-// Per-expert scan over token blocks (single block of 1024 threads).
+// Per-expert scan over token blocks: each block of 1024 threads takes a slice of the experts
+// and leaves its part of sum_e (counts / T) (psum / T) in loss_part; positions_kernel adds
+// the parts up in block order.
 //   block_off[b][e] = sum_{b' < b} block_counts[b'][e]
 //   counts[e], kept[e] = min(counts[e], C),  P-sum[e] in fixed order
 //   aux = alpha * E * sum_e (counts[e] / T) * (psum[e] / T)             (Eqs. 4-6)
@@ -202,22 +204,26 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
     const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
     int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
     int32_t *__restrict__ counts_g, int32_t *__restrict__ grp_off, int32_t *__restrict__ counts_out,
-    float *__restrict__ aux_out, int nb, int E, int C, int T, float alpha) {
+    double *__restrict__ loss_part, int nb, int E, int C, int T) {
     __shared__ int32_t part_cnt[kScanThreads];
     __shared__ float part_ps[kScanThreads];
     __shared__ double red[kScanThreads];
     const int tid = threadIdx.x;
-    const int Ew = E < kScanThreads ? E : kScanThreads;   // experts handled per pass
-    const int P = kScanThreads / Ew;                      // block-range parts per expert
+    // this block's experts: [e_lo, e_hi)
+    const int slice = (E + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int e_lo = blockIdx.x * slice;
+    const int e_hi = e_lo + slice < E ? e_lo + slice : E;
+    const int Ew = slice < kScanThreads ? slice : kScanThreads;   // experts handled per pass
+    const int P = kScanThreads / Ew;                              // block-range parts per expert
     const int el = tid % Ew;
     const int part = tid / Ew;
     const int per = (nb + P - 1) / P;
     const int b_lo = part * per;
     const int b_hi = (b_lo + per < nb) ? b_lo + per : nb;
     double loss_acc = 0.0;
-    for (int ebase = 0; ebase < E; ebase += Ew) {
+    for (int ebase = e_lo; ebase < e_hi; ebase += Ew) {
         const int e = ebase + el;
-        const bool active = part < P && e < E;
+        const bool active = part < P && e < e_hi;
         int csum = 0;
         float psum = 0.f;
         if (active)
@@ -237,7 +243,7 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
                 run += block_counts[(size_t)b * E + e];
             }
         }
-        if (part == 0 && e < E) {
+        if (part == 0 && e < e_hi) {
             int total = 0;
             float ptot = 0.f;
             for (int q = 0; q < P; ++q) {
@@ -259,7 +265,7 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) aux_out[0] = (float)((double)alpha * (double)E * red[0]);
+    if (tid == 0) loss_part[blockIdx.x] = red[0];
 }
 
 // -----------------------------------------------------------------------------
@@ -272,8 +278,8 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_groups_kernel(
     const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
     int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
     int32_t *__restrict__ counts_g, float *__restrict__ psum_g, int32_t *__restrict__ grp_off,
-    int32_t *__restrict__ counts_out, float *__restrict__ aux_out, int n, int nbg, int E, int Cg,
-    int Tg, float alpha) {
+    int32_t *__restrict__ counts_out, double *__restrict__ loss_part, int n, int nbg, int E, int Cg,
+    int Tg) {
     __shared__ double red[kScanThreads];
     const int tid = threadIdx.x;
     for (int pair = tid; pair < n * E; pair += kScanThreads) {
@@ -309,7 +315,7 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_groups_kernel(
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) aux_out[0] = (float)((double)alpha * (double)E * red[0] / (double)n);
+    if (tid == 0) loss_part[0] = red[0];
 }
 
 // -----------------------------------------------------------------------------
@@ -602,24 +608,30 @@ hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const
     return err;
 }
 
-hipError_t launch_route_scan(const Workspace &w, float alpha, char *ws, int32_t *expert_counts,
-                             float *aux_loss, hipStream_t s) {
+int route_scan_blocks(const Workspace &w) {
+    if (w.n > 1) return 1;
+    return w.E >= 64 ? 8 : 1;
+}
+
+hipError_t launch_route_scan(const Workspace &w, char *ws, int32_t *expert_counts, hipStream_t s) {
     ProfScope ps("route_scan_aux", s);
     if (w.n == 1)
-        hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(kScanThreads), 0, s,
-                           (const int32_t *)(ws + w.block_counts),
+        hipLaunchKernelGGL(route_scan_kernel, dim3((unsigned)route_scan_blocks(w)),
+                           dim3(kScanThreads), 0, s, (const int32_t *)(ws + w.block_counts),
                            (const float *)(ws + w.block_psum), (int32_t *)(ws + w.block_off),
                            (int32_t *)(ws + w.counts), (int32_t *)(ws + w.kept),
                            (int32_t *)(ws + w.counts_g), (int32_t *)(ws + w.grp_off),
-                           expert_counts, aux_loss, (int)w.nb, (int)w.E, (int)w.C, (int)w.T, alpha);
+                           expert_counts, (double *)(ws + w.loss_part), (int)w.nb, (int)w.E,
+                           (int)w.C, (int)w.T);
     else
         hipLaunchKernelGGL(route_scan_groups_kernel, dim3(1), dim3(kScanThreads), 0, s,
                            (const int32_t *)(ws + w.block_counts),
                            (const float *)(ws + w.block_psum), (int32_t *)(ws + w.block_off),
                            (int32_t *)(ws + w.counts), (int32_t *)(ws + w.kept),
                            (int32_t *)(ws + w.counts_g), (float *)(ws + w.psum_g),
-                           (int32_t *)(ws + w.grp_off), expert_counts, aux_loss, (int)w.n,
-                           (int)w.nbg, (int)w.E, (int)w.Cg, (int)w.Tg, alpha);
+                           (int32_t *)(ws + w.grp_off), expert_counts,
+                           (double *)(ws + w.loss_part), (int)w.n, (int)w.nbg, (int)w.E,
+                           (int)w.Cg, (int)w.Tg);
     return hipGetLastError();
 }
 
