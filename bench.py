@@ -56,7 +56,7 @@ def kernel_work(shape, kept, elt):
         "gemm2_wgrad": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "gemm1_dgrad": (gemm, w_bytes + kept * (f + d) * elt, "mfma"),
         "gemm1_wgrad": (gemm, w_bytes + kept * (d + f) * elt, "mfma"),
-        "router_dlogits": (0.0, 2.0 * T * E * 4 + T * 512 + T * 8, "hbm"),
+        "router_dlogits": (0.0, T * E * 4 + T * 512 + T * 8, "hbm"),
         "router_dx_mfma": (6.0 * T * d * E, T * 512 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr_mfma": (4.0 * T * d * E, T * d * elt + T * 512, "hbm"),
         "router_dWr_reduce": (0.0, -(-T // (-(-(-(-T // 85)) // 64) * 64)) * d * 256 * 4.0 + d * E * 4.0, "hbm"),

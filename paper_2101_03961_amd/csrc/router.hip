@@ -324,45 +324,60 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_groups_kernel(
 //   dl[t][j] = p[t][j] (dp[t][j] - sum_i p[t][i] dp[t][i])
 // One wave per token, lanes stride the experts.
 // -----------------------------------------------------------------------------
+// tokens a wave works on at once (their loads overlap); one when the experts fill the registers
+constexpr int dl_tokens(int epl) { return epl <= 4 ? 4 : 1; }
+
 template <int EPL>
 __global__ __launch_bounds__(256) void router_dlogits_kernel(
     const float *__restrict__ probs, const int32_t *__restrict__ idx,
     const float *__restrict__ dgate, const int32_t *__restrict__ counts_g /* [n][E] */,
-    float *__restrict__ dlogits, bf16 *__restrict__ dl_split /* [T][256] hi | lo, or nullptr */,
+    float *__restrict__ dlogits /* [T][E] or nullptr */,
+    bf16 *__restrict__ dl_split /* [T][256] hi | lo, or nullptr */,
     int T, int Tg, int E, float aux_scale /* d_aux*alpha*E/(n Tg^2) */) {
+    constexpr int kDlTokens = dl_tokens(EPL);
     const int lane = threadIdx.x % kWave;
-    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
-    if (t >= T) return;
-    const int me = idx[t];
-    const float dg = dgate[t];
-    const int32_t *counts = counts_g + (size_t)(t / Tg) * E;
-    float p[EPL], dp[EPL];
-    float s = 0.f;
+    const int t_first = (blockIdx.x * (256 / kWave) + threadIdx.x / kWave) * kDlTokens;
+    float p[kDlTokens][EPL], dp[kDlTokens][EPL], s[kDlTokens];
 #pragma unroll
-    for (int j = 0; j < EPL; ++j) {
-        const int e = lane + j * kWave;
-        p[j] = e < E ? probs[(size_t)t * E + e] : 0.f;
-        dp[j] = e < E ? aux_scale * (float)counts[e] : 0.f;
-        if (e == me) dp[j] += dg;
-        s += p[j] * dp[j];
-    }
-    s = wave_sum(s);
+    for (int u = 0; u < kDlTokens; ++u) {
+        const int t = t_first + u;
+        s[u] = 0.f;
+        if (t >= T) continue;
+        const int me = idx[t];
+        const float dg = dgate[t];
+        const int32_t *counts = counts_g + (size_t)(t / Tg) * E;
 #pragma unroll
-    for (int j = 0; j < EPL; ++j) {
-        const int e = lane + j * kWave;
-        const float dl = e < E ? p[j] * (dp[j] - s) : 0.f;
-        if (e < E) dlogits[(size_t)t * E + e] = dl;
-        if (dl_split && e < 128) {   // two bf16 terms (16 mantissa bits) for the MFMA contractions
-            const bf16 hi = (bf16)dl;
-            dl_split[(size_t)t * 256 + e] = hi;
-            dl_split[(size_t)t * 256 + 128 + e] = (bf16)(dl - (float)hi);
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane + j * kWave;
+            p[u][j] = e < E ? probs[(size_t)t * E + e] : 0.f;
+            dp[u][j] = e < E ? aux_scale * (float)counts[e] : 0.f;
+            if (e == me) dp[u][j] += dg;
+            s[u] += p[u][j] * dp[u][j];
         }
     }
-    if (dl_split)   // columns of the 128-wide halves that no lane visited above
-        for (int e = lane + EPL * kWave; e < 128; e += kWave) {
-            dl_split[(size_t)t * 256 + e] = (bf16)0.f;
-            dl_split[(size_t)t * 256 + 128 + e] = (bf16)0.f;
+#pragma unroll
+    for (int u = 0; u < kDlTokens; ++u) s[u] = wave_sum(s[u]);
+#pragma unroll
+    for (int u = 0; u < kDlTokens; ++u) {
+        const int t = t_first + u;
+        if (t >= T) continue;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane + j * kWave;
+            const float dl = e < E ? p[u][j] * (dp[u][j] - s[u]) : 0.f;
+            if (dlogits && e < E) dlogits[(size_t)t * E + e] = dl;
+            if (dl_split && e < 128) {   // two bf16 terms (16 mantissa bits) for the MFMA contractions
+                const bf16 hi = (bf16)dl;
+                dl_split[(size_t)t * 256 + e] = hi;
+                dl_split[(size_t)t * 256 + 128 + e] = (bf16)(dl - (float)hi);
+            }
         }
+        if (dl_split)   // columns of the 128-wide halves that no lane visited above
+            for (int e = lane + EPL * kWave; e < 128; e += kWave) {
+                dl_split[(size_t)t * 256 + e] = (bf16)0.f;
+                dl_split[(size_t)t * 256 + 128 + e] = (bf16)0.f;
+            }
+    }
 }
 
 // dW_r[k][j] = sum over splits of (part[s][k][j] + part[s][k][128 + j]), fixed order
@@ -647,15 +662,18 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
     const bool mfma = router_fwd_mfma_supported(w, sizeof(XT) == 2 ? SW_BF16 : SW_F32) &&
                       (uint64_t)w.T * 512u < 0x7fffffffu;
     bf16 *dl_split = mfma ? (bf16 *)(ws + w.dl_split) : nullptr;
+    // the fp32 copy is read only by the vector-ALU contractions and by the bias gradient
+    float *dlogits_out = (mfma && !db_r) ? nullptr : dlogits;
     {
         ProfScope ps("router_dlogits", s);
         const float aux_scale = (float)((double)d_aux * (double)alpha * (double)w.E /
                                         ((double)w.n * (double)w.Tg * (double)w.Tg));
 #define CALL(N)                                                                                  \
-    hipLaunchKernelGGL(router_dlogits_kernel<N>, dim3((unsigned)ceil_div(w.T, 4)), dim3(256), 0, \
+    hipLaunchKernelGGL(router_dlogits_kernel<N>,                                                  \
+                       dim3((unsigned)ceil_div(w.T, 4 * dl_tokens(N))), dim3(256), 0,             \
                        s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),          \
                        (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts_g),        \
-                       dlogits, dl_split, (int)w.T, (int)w.Tg, (int)w.E, aux_scale)
+                       dlogits_out, dl_split, (int)w.T, (int)w.Tg, (int)w.E, aux_scale)
         SW_DISPATCH_EPL(w.E, CALL);
 #undef CALL
         if ((err = hipGetLastError()) != hipSuccess) return err;
