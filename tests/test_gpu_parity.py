@@ -194,6 +194,46 @@ def test_run_to_run_determinism():
         assert np.array_equal(a[k], b[k]), k
 
 
+def test_step_can_be_captured_in_a_graph():
+    """Forward + backward recorded once and replayed: every replay, with eager work and
+    synchronisation between them, reproduces the eager result bit for bit (the library launches
+    only kernels: no allocation, no memset node, no host synchronisation)."""
+    import torch
+    from paper_2101_03961_amd.layer import SwitchLayer
+    s = SwitchShape("t", 3000, 256, 512, 12, 1.0, dtype="bf16", seed_index=58, n_groups=2)
+    inp = make_inputs(s, _dev())
+    layer = SwitchLayer(s.T, s.d_model, s.d_ff, s.E, s.capacity_factor, s.alpha, s.dtype,
+                        device=_dev(), n_groups=s.n_groups)
+    layer.alloc_grads(with_bias=False)
+    names = ("y", "dx", "dW_r", "dW_in", "dW_out", "aux_loss", "expert_counts", "gate", "dropped")
+
+    def step():
+        layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], None)
+        layer.backward(inp["dy"], inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], None, 1.0)
+
+    step()
+    torch.cuda.synchronize()
+    eager = {k: getattr(layer, k).clone() for k in names}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        for k in names:
+            getattr(layer, k).fill_(3)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in names:
+            assert torch.equal(getattr(layer, k), eager[k]), k
+        assert float(layer.y.float().abs().sum()) > 0   # eager work between replays
+
+
 # ------------------------------------------- full sizes, sampled against oracle
 @pytest.mark.parametrize("name,n_experts", [
     ("base_cf1.0", 3), ("base_cf1.25", 2), ("base_zipf", 3), ("large", 2), ("c_share", 2),
