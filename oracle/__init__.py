@@ -82,8 +82,11 @@ def _load():
     lib.swo_backward.restype = None
     lib.swo_backward.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f32p,
                                  _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, i64, _c_i64p,
-                                 _c_i32p, _c_u8p, _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p,
-                                 _c_f64p, _c_f64p]
+                                 _c_i32p, _c_u8p, i64, _c_i64p, _c_i64p, _c_f64p, _c_f64p, _c_f64p,
+                                 _c_f64p, _c_f64p, _c_f64p, _c_f64p]
+    lib.swo_hidden_near_zero.restype = i64
+    lib.swo_hidden_near_zero.argtypes = [i64, i64, i64, _c_f32p, _c_f32p, _c_i32p, _c_u8p, _c_u8p,
+                                         f64, i64, _c_i64p, _c_i64p, _c_f64p]
     _libs[key] = lib
     return lib
 
@@ -273,15 +276,38 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     return out
 
 
+def hidden_near_zero(x, W_in, expert_index, dropped, rel_eps: float, expert_sel=None,
+                     token_sel=None, max_out: int = 4096):
+    """(t, j, h) for the evaluated kept tokens' hidden units with |h| <= rel_eps * RMS(h_t):
+    pre-activations that are zero to fp32 rounding, where the ReLU decision is not unique."""
+    x32, W_in32 = _f32(x), _f32(W_in)
+    T, d = x32.shape
+    E, _, f = W_in32.shape
+    e = np.ascontiguousarray(expert_index, dtype=np.int32)
+    dr = np.ascontiguousarray(dropped, dtype=np.uint8)
+    sel = _token_mask(e, E, expert_sel, token_sel)
+    ot = np.empty(max_out, dtype=np.int64)
+    oj = np.empty(max_out, dtype=np.int64)
+    oh = np.empty(max_out, dtype=np.float64)
+    n = _load().swo_hidden_near_zero(T, d, f, _ptr(x32, _c_f32p), _ptr(W_in32, _c_f32p),
+                                     _ptr(e, _c_i32p), _ptr(dr, _c_u8p), _ptr(sel, _c_u8p),
+                                     float(rel_eps), max_out, _ptr(ot, _c_i64p),
+                                     _ptr(oj, _c_i64p), _ptr(oh, _c_f64p))
+    assert n <= max_out, "too many near-zero hidden units (%d)" % n
+    return [(int(ot[i]), int(oj[i]), float(oh[i])) for i in range(n)]
+
+
 def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.0,
              expert_sel: Optional[Sequence[int]] = None,
-             token_sel: Optional[Sequence[int]] = None) -> Dict:
+             token_sel: Optional[Sequence[int]] = None,
+             relu_flips: Optional[Sequence] = None) -> Dict:
     """Whole backward pass for L = sum <dy, y> + d_aux * aux_loss.
 
     With expert_sel (and optionally token_sel, extra single tokens), weight
     gradients are returned only for the experts of expert_sel (stacked in the
     given order); dx rows of unselected tokens are NaN and their gate gradient is
     taken as 0 in dW_r / db_r (exact only if dy is zero on those tokens).
+    relu_flips: (token, hidden unit) pairs whose ReLU gate 1[h > 0] is inverted.
     """
     x32, W_r32, W_in32, W_out32, dy32 = _f32(x), _f32(W_r), _f32(W_in), _f32(W_out), _f32(dy)
     T, d = x32.shape
@@ -308,6 +334,9 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
         for s, ex in enumerate(expert_sel):
             sel_slot[ex] = s
         nsel = len(expert_sel)
+    flips = list(relu_flips or [])
+    flip_t = np.ascontiguousarray([p[0] for p in flips], dtype=np.int64)
+    flip_j = np.ascontiguousarray([p[1] for p in flips], dtype=np.int64)
     dx = np.empty((T, d), dtype=np.float64)
     dW_r = np.empty((d, E), dtype=np.float64)
     db_r = np.empty(E, dtype=np.float64)
@@ -319,7 +348,8 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
                          _ptr(W_in32, _c_f32p), _ptr(W_out32, _c_f32p), _ptr(dy32, _c_f32p),
                          float(d_aux), float(alpha), _ptr(e, _c_i32p), _ptr(dr, _c_u8p),
                          _ptr(g, _c_f64p), _ptr(p, _c_f64p), n_groups, _ptr(counts_g, _c_i64p),
-                         _ptr(sel_slot, _c_i32p), _ptr(tmask, _c_u8p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
+                         _ptr(sel_slot, _c_i32p), _ptr(tmask, _c_u8p), len(flips),
+                         _ptr(flip_t, _c_i64p), _ptr(flip_j, _c_i64p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
                          _ptr(db_r, _c_f64p), _ptr(dW_in, _c_f64p), _ptr(dW_out, _c_f64p),
                          _ptr(dgate, _c_f64p), _ptr(dlog, _c_f64p))
     return dict(dx=dx, dW_r=dW_r, db_r=db_r, dW_in=dW_in, dW_out=dW_out, dgate=dgate,

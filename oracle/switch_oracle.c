@@ -229,6 +229,45 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
     (void)E;
 }
 
+/* ---- hidden units whose ReLU decision an fp32 evaluation may take the other way ----
+ * For every evaluated kept token t (token_sel as above) and hidden unit j with
+ *     |h_tj| <= rel_eps * RMS_j(h_t),
+ * (t, j, h_tj) is recorded (up to max_out entries; the return value is the number found).
+ * The layer is discontinuous in its inputs there: an implementation that accumulates h in
+ * fp32 gets the sign of such a sum from its rounding errors.  Single threaded. */
+int64_t swo_hidden_near_zero(int64_t T, int64_t d, int64_t f, const in_t *x, const in_t *W_in,
+                             const int32_t *expert_index, const uint8_t *dropped,
+                             const uint8_t *token_sel, double rel_eps, int64_t max_out,
+                             int64_t *out_t, int64_t *out_j, double *out_h) {
+    double *h = (double *)malloc(sizeof(double) * (size_t)f);
+    int64_t found = 0;
+    for (int64_t t = 0; t < T; ++t) {
+        if ((token_sel && !token_sel[t]) || dropped[t]) continue;
+        const in_t *Wi = W_in + (int64_t)expert_index[t] * d * f;
+        const in_t *xt = x + t * d;
+        for (int64_t j = 0; j < f; ++j) h[j] = 0.0;
+        for (int64_t k = 0; k < d; ++k) {
+            double xk = (double)xt[k];
+            const in_t *row = Wi + k * f;
+            for (int64_t j = 0; j < f; ++j) h[j] += xk * (double)row[j];
+        }
+        double ss = 0.0;
+        for (int64_t j = 0; j < f; ++j) ss += h[j] * h[j];
+        double bound = rel_eps * sqrt(ss / (double)f);
+        for (int64_t j = 0; j < f; ++j)
+            if (fabs(h[j]) <= bound) {
+                if (found < max_out) {
+                    out_t[found] = t;
+                    out_j[found] = j;
+                    out_h[found] = h[j];
+                }
+                ++found;
+            }
+    }
+    free(h);
+    return found;
+}
+
 /* ---- backward ------------------------------------------------------------
  * Scalar objective  L = sum_t <dy_t, y_t> + d_aux * aux_loss.
  * Chain rule through y_t = k_t g_t o_t, o = a W_out, a = ReLU(h), h = x W_in,
@@ -249,6 +288,9 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
  *   sel_slot[e] >= 0 (sel_slot may be NULL = slot e for every expert): expert
  *     e's weight gradients are accumulated into slot sel_slot[e] of dW_in_sel /
  *     dW_out_sel -- complete only if every kept token of e is selected.
+ * ReLU decisions taken the other way: for the n_flip pairs (flip_t[q], flip_j[q]) the gate
+ *   1[h > 0] is inverted (see swo_hidden_near_zero; the tests use it to follow an fp32
+ *   implementation's decision on pre-activations that are zero to rounding).
  */
 void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, const in_t *W_r,
                   const in_t *W_in, const in_t *W_out, const in_t *dy, double d_aux,
@@ -256,7 +298,8 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                   const double *gate, const double *p /* [T][E] */, int64_t n_groups,
                   const int64_t *counts_g /* [n_groups][E] */,
                   const int32_t *sel_slot /* [E] or NULL */,
-                  const uint8_t *token_sel /* [T] or NULL */, double *dx /* [T][d] */,
+                  const uint8_t *token_sel /* [T] or NULL */, int64_t n_flip,
+                  const int64_t *flip_t, const int64_t *flip_j, double *dx /* [T][d] */,
                   double *dW_r /* [d][E] */, double *db_r /* [E] */,
                   double *dW_in_sel /* [nsel][d][f] */, double *dW_out_sel /* [nsel][f][d] */,
                   double *dgate /* [T] */, double *dlogits /* [T][E] */) {
@@ -313,7 +356,10 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                     for (int64_t i = 0; i < d; ++i) grow[i] += aj * dout[i];
                 }
                 for (int64_t i = 0; i < d; ++i) s += dout[i] * (double)row[i];
-                dh[j] = hpre[j] > 0.0 ? s : 0.0;
+                int on = hpre[j] > 0.0;
+                for (int64_t q = 0; q < n_flip; ++q)
+                    if (flip_t[q] == t && flip_j[q] == j) on = !on;
+                dh[j] = on ? s : 0.0;
             }
 #pragma omp barrier
             for (int64_t k = k0; k < k1; ++k) {

@@ -321,6 +321,7 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_groups_kernel(
 // -----------------------------------------------------------------------------
 // Backward, step 1: gradient w.r.t. the logits.
 //   dp[t][i] = dgate[t] [i = e_t] + d_aux * alpha * E * (counts_g[g][i] / Tg) / (n Tg),  t in group g
+//              (evaluated with counts_g - Tg / E: a constant shift of dp leaves dl unchanged)
 //   dl[t][j] = p[t][j] (dp[t][j] - sum_i p[t][i] dp[t][i])
 // One wave per token, lanes stride the experts.
 // -----------------------------------------------------------------------------
@@ -335,6 +336,7 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
     bf16 *__restrict__ dl_split /* [T][256] hi | lo, or nullptr */,
     int T, int Tg, int E, float aux_scale /* d_aux*alpha*E/(n Tg^2) */) {
     constexpr int kDlTokens = dl_tokens(EPL);
+    const float mean_count = (float)Tg / (float)E;
     const int lane = threadIdx.x % kWave;
     const int t_first = (blockIdx.x * (256 / kWave) + threadIdx.x / kWave) * kDlTokens;
     float p[kDlTokens][EPL], dp[kDlTokens][EPL], s[kDlTokens];
@@ -350,7 +352,10 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
         for (int j = 0; j < EPL; ++j) {
             const int e = lane + j * kWave;
             p[u][j] = e < E ? probs[(size_t)t * E + e] : 0.f;
-            dp[u][j] = e < E ? aux_scale * (float)counts[e] : 0.f;
+            // counts enter centred on their mean Tg / E: the softmax backward subtracts the
+            // p-weighted mean of dp anyway (sum_i p_i = 1), and nearly equal counts would
+            // otherwise cancel to a few fp32 digits in dp - s
+            dp[u][j] = e < E ? aux_scale * ((float)counts[e] - mean_count) : 0.f;
             if (e == me) dp[u][j] += dg;
             s[u] += p[u][j] * dp[u][j];
         }

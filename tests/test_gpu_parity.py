@@ -194,6 +194,48 @@ def test_run_to_run_determinism():
         assert np.array_equal(a[k], b[k]), k
 
 
+def test_random_shapes():
+    """Seeded sweep over token counts, widths, expert counts, capacity factors, group counts
+    and both storage types: every tile edge and kernel variant at sizes the full oracle takes
+    a fraction of a second for."""
+    from parity import compare_full
+    rng = np.random.default_rng(20210111)
+    for case in range(36):
+        dtype = "bf16" if rng.random() < 0.75 else "f32"
+        mult = 8 if dtype == "bf16" else 4
+        E = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 20, 32, 64]))
+        n = int(rng.choice([1, 1, 1, 2, 3, 4]))
+        T = int(rng.integers(200, 1400)) * n
+        hi_d, hi_f = (640, 800) if dtype == "bf16" else (400, 400)
+        d = int(rng.integers(32 // mult, hi_d // mult)) * mult
+        f = int(rng.integers(32 // mult, hi_f // mult)) * mult
+        cf = float(rng.choice([0.7, 1.0, 1.25, 2.0, 8.0]))
+        s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=300 + case, n_groups=n)
+        print("[random shape %d] %s T=%d d=%d f=%d E=%d cf=%g groups=%d" %
+              (case, dtype, T, d, f, E, cf, n), flush=True)
+        inp = make_inputs(s, _dev())
+        # few kept tokens per expert: see test_few_tokens
+        widen = ({"dW_r": 5.0, "db_r": 5.0}
+                 if (dtype == "bf16" and T * min(1.0, cf) < 16 * E) else None)
+        compare_full(s, inp, d_aux=0.5, widen=widen)
+
+
+def test_relu_decision_at_a_zero_preactivation():
+    """In this seeded case one pre-activation is -7.5e-9 in fp64 (RMS of its row: 1) and the
+    fp32 sum of the same exact products comes out positive: the unit's gate is a coin flip,
+    the protocol follows the GPU's decision for that one (token, unit) pair."""
+    from parity import compare_full
+    s = SwitchShape("t", 1206, 208, 712, 1, 2.0, dtype="bf16", seed_index=152)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.5)
+    _report("zero pre-activation", errs)
+    import oracle
+    npi = {k: (None if v is None else v.float().cpu().numpy()) for k, v in inp.items()}
+    near = oracle.hidden_near_zero(npi["x"], npi["W_in"], fwd["expert_index"], fwd["dropped"], 1e-6)
+    assert (252, 515) in [(t, j) for t, j, _ in near] and len(near) <= 4, near
+    assert all(abs(h) < 1e-5 for _, _, h in near)
+
+
 def test_step_can_be_captured_in_a_graph():
     """Forward + backward recorded once and replayed: every replay, with eager work and
     synchronisation between them, reproduces the eager result bit for bit (the library launches

@@ -535,3 +535,58 @@ def test_group_capacity_uses_group_size():
     assert oracle.capacity(65536, 128, 1.0, n_groups=8) == 64
     assert oracle.capacity(65536, 128, 1.25, n_groups=8) == 80
     assert oracle.capacity(90, 4, 0.9, n_groups=3) == 6
+
+
+# ---------------------------------------------- ReLU decisions at h = 0 to rounding
+
+def test_hidden_near_zero_matches_direct_evaluation():
+    s = SwitchShape("t", 60, 16, 24, 3, 2.0, dtype="f32", seed_index=24)
+    inp = _np_inputs(s)
+    W_in = inp["W_in"].copy()
+    W_in[1][:, 5] = 0.0                      # unit 5 of expert 1: h = 0 exactly
+    fwd = oracle.forward(inp["x"], inp["W_r"], W_in, inp["W_out"], 2.0, 0.01)
+    eps = 0.05                               # wide band so that ordinary units fall in too
+    got = oracle.hidden_near_zero(inp["x"], W_in, fwd["expert_index"], fwd["dropped"], eps)
+    want = []
+    for t in range(s.T):
+        if fwd["dropped"][t]:
+            continue
+        h = inp["x"][t].astype(np.float64) @ W_in[fwd["expert_index"][t]].astype(np.float64)
+        bound = eps * np.sqrt(np.mean(h * h))
+        want += [(t, j) for j in range(24) if abs(h[j]) <= bound]
+    assert [(t, j) for t, j, _ in got] == want and len(want) > 5
+    zero_units = [(t, j) for t, j, h in got if h == 0.0]
+    assert zero_units == [(t, 5) for t in range(s.T) if fwd["expert_index"][t] == 1]
+
+
+def test_relu_flip_equals_moving_h_across_zero():
+    """Inverting the gate of a unit with h = +delta gives the gradients of the layer whose
+    weights are nudged so that the same h is -delta."""
+    s = SwitchShape("t", 40, 10, 14, 2, 4.0, dtype="f32", seed_index=25)
+    oracle.use_f64_inputs(True)
+    try:
+        inp = {k: (None if v is None else v.astype(np.float64)) for k, v in _np_inputs(s).items()}
+        fwd0 = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 4.0, 0.01)
+        t, j = 7, 3
+        e = int(fwd0["expert_index"][t])
+        xt = inp["x"][t]
+        h = xt @ inp["W_in"][e][:, j]
+        delta = 1e-9
+        W_plus = inp["W_in"].copy()
+        W_plus[e][:, j] -= (h - delta) * xt / (xt @ xt)      # now h_tj = +delta
+        W_minus = inp["W_in"].copy()
+        W_minus[e][:, j] -= (h + delta) * xt / (xt @ xt)     # now h_tj = -delta
+        fp = oracle.forward(inp["x"], inp["W_r"], W_plus, inp["W_out"], 4.0, 0.01)
+        fm = oracle.forward(inp["x"], inp["W_r"], W_minus, inp["W_out"], 4.0, 0.01)
+        near = oracle.hidden_near_zero(inp["x"], W_plus, fp["expert_index"], fp["dropped"], 1e-6)
+        assert [(a, b) for a, b, _ in near] == [(t, j)] and abs(near[0][2] - delta) < 1e-12
+        flipped = oracle.backward(inp["x"], inp["W_r"], W_plus, inp["W_out"], inp["dy"], fp, 0.01,
+                                  1.0, relu_flips=[(t, j)])
+        moved = oracle.backward(inp["x"], inp["W_r"], W_minus, inp["W_out"], inp["dy"], fm, 0.01, 1.0)
+        plain = oracle.backward(inp["x"], inp["W_r"], W_plus, inp["W_out"], inp["dy"], fp, 0.01, 1.0)
+        for k in ("dx", "dW_in", "dW_out", "dW_r"):
+            np.testing.assert_allclose(flipped[k], moved[k], rtol=0, atol=1e-7)
+        assert np.abs(plain["dx"][t] - flipped["dx"][t]).max() > 1e-3     # the flip matters
+        assert np.array_equal(np.delete(plain["dx"], t, axis=0), np.delete(flipped["dx"], t, axis=0))
+    finally:
+        oracle.use_f64_inputs(False)
