@@ -194,6 +194,20 @@ def test_run_to_run_determinism():
         assert np.array_equal(a[k], b[k]), k
 
 
+@pytest.mark.parametrize("dtype,T,d,f,E,cf,n", [
+    ("bf16", 4096, 64, 64, 4096, 2.0, 1),   # the largest expert count the library takes
+    ("f32", 3000, 32, 48, 1000, 3.0, 1),
+    ("bf16", 6000, 72, 64, 513, 1.0, 2),    # nine experts per lane in the softmax kernels
+])
+def test_many_experts(dtype, T, d, f, E, cf, n):
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=59, n_groups=n)
+    inp = make_inputs(s, _dev())
+    widen = {"dW_r": 5.0, "db_r": 5.0} if dtype == "bf16" else None   # a few tokens per expert
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.5, widen=widen)
+    _report("E=%d" % E, errs)
+
+
 def test_random_shapes():
     """Seeded sweep over token counts, widths, expert counts, capacity factors, group counts
     and both storage types: every tile edge and kernel variant at sizes the full oracle takes
