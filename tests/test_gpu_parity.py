@@ -195,7 +195,7 @@ def test_run_to_run_determinism():
 
 
 @pytest.mark.parametrize("dtype,T,d,f,E,cf,n", [
-    ("bf16", 4096, 64, 64, 4096, 2.0, 1),   # the largest expert count the library takes
+    ("bf16", 16384, 64, 64, 4096, 2.0, 1),  # the largest expert count the library takes
     ("f32", 3000, 32, 48, 1000, 3.0, 1),
     ("bf16", 6000, 72, 64, 513, 1.0, 2),    # nine experts per lane in the softmax kernels
 ])
@@ -203,7 +203,8 @@ def test_many_experts(dtype, T, d, f, E, cf, n):
     from parity import compare_full
     s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=59, n_groups=n)
     inp = make_inputs(s, _dev())
-    widen = {"dW_r": 5.0, "db_r": 5.0} if dtype == "bf16" else None   # a few tokens per expert
+    # a few tokens per expert: each element of db_r is a handful of gate gradients
+    widen = {"dW_r": 5.0, "db_r": 10.0} if dtype == "bf16" else None
     errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.5, widen=widen)
     _report("E=%d" % E, errs)
 
