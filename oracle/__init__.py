@@ -30,6 +30,23 @@ _LIB_F64IN = os.path.join(_HERE, "libswitch_oracle_f64in.so")
 _in_dtype = np.float32
 
 _c_f32p = ctypes.c_void_p
+
+
+class Noise(ctypes.Structure):
+    """Training-time noise (mirror of swo_noise): expert dropout rate, jitter eps, seed."""
+    _fields_ = [("expert_dropout", ctypes.c_float), ("jitter_eps", ctypes.c_float),
+                ("seed", ctypes.c_uint64)]
+
+
+def _noise(noise):
+    """None, or a (expert_dropout, jitter_eps, seed) triple -> pointer argument."""
+    if noise is None:
+        return None
+    rate, eps, seed = noise
+    if rate == 0 and eps == 0:
+        return None
+    return ctypes.byref(Noise(float(rate), float(eps), int(seed)))
+
 _c_f64p = ctypes.POINTER(ctypes.c_double)
 _c_i32p = ctypes.POINTER(ctypes.c_int32)
 _c_i64p = ctypes.POINTER(ctypes.c_int64)
@@ -66,7 +83,14 @@ def _load():
     lib.swo_capacity.restype = i64
     lib.swo_capacity.argtypes = [i64, i64, f64]
     lib.swo_logits.restype = None
-    lib.swo_logits.argtypes = [i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f64p]
+    noise_p = ctypes.POINTER(Noise)
+    lib.swo_logits.argtypes = [i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, noise_p, _c_f64p]
+    lib.swo_mix.restype = ctypes.c_uint32
+    lib.swo_mix.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint64]
+    lib.swo_jitter_mult.restype = f64
+    lib.swo_jitter_mult.argtypes = [noise_p, i64, i64, i64]
+    lib.swo_dropout_factor.restype = f64
+    lib.swo_dropout_factor.argtypes = [noise_p, i64, i64, i64]
     lib.swo_softmax.restype = None
     lib.swo_softmax.argtypes = [i64, i64, _c_f64p, _c_f64p]
     lib.swo_top1.restype = None
@@ -78,11 +102,11 @@ def _load():
     lib.swo_positions.argtypes = [i64, i64, i64, i64, _c_i32p, _c_i32p, _c_u8p, _c_i64p]
     lib.swo_expert_ffn.restype = None
     lib.swo_expert_ffn.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_i32p,
-                                   _c_u8p, _c_f64p, _c_u8p, _c_f64p]
+                                   _c_u8p, _c_f64p, _c_u8p, noise_p, _c_f64p]
     lib.swo_backward.restype = None
     lib.swo_backward.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f32p,
                                  _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, i64, _c_i64p,
-                                 _c_i32p, _c_u8p, i64, _c_i64p, _c_i64p, _c_f64p, _c_f64p, _c_f64p,
+                                 _c_i32p, _c_u8p, i64, _c_i64p, _c_i64p, noise_p, _c_f64p, _c_f64p, _c_f64p,
                                  _c_f64p, _c_f64p, _c_f64p, _c_f64p]
     lib.swo_hidden_near_zero.restype = i64
     lib.swo_hidden_near_zero.argtypes = [i64, i64, i64, _c_f32p, _c_f32p, _c_i32p, _c_u8p, _c_u8p,
@@ -131,15 +155,16 @@ def capacity(T: int, E: int, capacity_factor: float, n_groups: int = 1) -> int:
     return int(_load().swo_capacity(T // n_groups, E, float(capacity_factor)))
 
 
-def logits(x, W_r, b_r=None) -> np.ndarray:
-    """h = x W_r (+ b_r), fp64 (Sec. 2.1)."""
+def logits(x, W_r, b_r=None, noise=None) -> np.ndarray:
+    """h = x W_r (+ b_r), fp64 (Sec. 2.1); with noise = (dropout, eps, seed) the router sees the
+    jittered x (App. C)."""
     x, W_r = _f32(x), _f32(W_r)
     T, d = x.shape
     E = W_r.shape[1]
     assert W_r.shape[0] == d
     b = None if b_r is None else _f32(b_r)
     h = np.empty((T, E), dtype=np.float64)
-    _load().swo_logits(T, d, E, _ptr(x, _c_f32p), _ptr(W_r, _c_f32p), _ptr(b, _c_f32p),
+    _load().swo_logits(T, d, E, _ptr(x, _c_f32p), _ptr(W_r, _c_f32p), _ptr(b, _c_f32p), _noise(noise),
                        _ptr(h, _c_f64p))
     return h
 
@@ -212,7 +237,7 @@ def _token_mask(expert_index, E, expert_sel, token_sel):
 
 
 def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None,
-               token_sel=None) -> np.ndarray:
+               token_sel=None, noise=None) -> np.ndarray:
     """y_t = gate_t * ReLU(x_t W_in[e_t]) W_out[e_t] for kept tokens, 0 for dropped.
 
     With expert_sel / token_sel only tokens of those experts / those tokens are
@@ -228,7 +253,7 @@ def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None,
     y = np.empty((T, d), dtype=np.float64)
     _load().swo_expert_ffn(T, d, f, E, _ptr(x, _c_f32p), _ptr(W_in, _c_f32p), _ptr(W_out, _c_f32p),
                            _ptr(e, _c_i32p), _ptr(dr, _c_u8p), _ptr(g, _c_f64p),
-                           _ptr(sel, _c_u8p), _ptr(y, _c_f64p))
+                           _ptr(sel, _c_u8p), _noise(noise), _ptr(y, _c_f64p))
     return y
 
 
@@ -239,11 +264,12 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
             logits_override=None, expert_index_override=None,
             expert_sel: Optional[Sequence[int]] = None,
             token_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False,
-            n_groups: int = 1) -> Dict:
+            n_groups: int = 1, noise=None) -> Dict:
     """Whole forward pass.
 
     n_groups: routing groups of T / n_groups consecutive tokens (capacity, positions and the
         auxiliary loss per group; 1 = the whole batch is one group).
+    noise: None or (expert_dropout, jitter_eps, seed): training-time noise.
     logits_override: use these logits (e.g. another implementation's fp32
         logits, widened) instead of computing them -- for the routing-stage
         comparison, which is defined on identical logits.
@@ -258,7 +284,7 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     E = np.asarray(W_r).shape[1]
     C = capacity(T, E, capacity_factor, n_groups)
     if logits_override is None:
-        h = logits(x32, W_r, b_r)
+        h = logits(x32, W_r, b_r, noise)
     else:
         h = np.ascontiguousarray(logits_override, dtype=np.float64)
     p = softmax(h)
@@ -270,10 +296,24 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     pos, dropped, kept = positions(e, E, C, n_groups)
     out = dict(capacity=C, logits=h, probs=p, expert_index=e, gate=g, aux_loss=loss,
                expert_counts=counts, f=f_vec, P=P_vec, position_in_expert=pos,
-               dropped=dropped, kept_counts=kept, n_groups=n_groups, group_counts=counts_g)
+               dropped=dropped, kept_counts=kept, n_groups=n_groups, group_counts=counts_g,
+               noise=noise)
     if not skip_ffn:
-        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel)
+        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel, noise)
     return out
+
+
+def mix(idx: int, stream: int, seed: int) -> int:
+    """The oracle's counter-based generator: 32 random bits for element idx of a stream."""
+    return int(_load().swo_mix(idx & 0xFFFFFFFF, stream, seed & 0xFFFFFFFFFFFFFFFF))
+
+
+def jitter_mult(noise, t: int, d: int, k: int) -> float:
+    return float(_load().swo_jitter_mult(_noise(noise), t, d, k))
+
+
+def dropout_factor(noise, t: int, f: int, j: int) -> float:
+    return float(_load().swo_dropout_factor(_noise(noise), t, f, j))
 
 
 def hidden_near_zero(x, W_in, expert_index, dropped, rel_eps: float, expert_sel=None,
@@ -349,7 +389,8 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
                          float(d_aux), float(alpha), _ptr(e, _c_i32p), _ptr(dr, _c_u8p),
                          _ptr(g, _c_f64p), _ptr(p, _c_f64p), n_groups, _ptr(counts_g, _c_i64p),
                          _ptr(sel_slot, _c_i32p), _ptr(tmask, _c_u8p), len(flips),
-                         _ptr(flip_t, _c_i64p), _ptr(flip_j, _c_i64p), _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
+                         _ptr(flip_t, _c_i64p), _ptr(flip_j, _c_i64p), _noise(fwd.get("noise")),
+                         _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
                          _ptr(db_r, _c_f64p), _ptr(dW_in, _c_f64p), _ptr(dW_out, _c_f64p),
                          _ptr(dgate, _c_f64p), _ptr(dlog, _c_f64p))
     return dict(dx=dx, dW_r=dW_r, db_r=db_r, dW_in=dW_in, dW_out=dW_out, dgate=dgate,

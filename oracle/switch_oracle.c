@@ -34,6 +34,15 @@
  *   - with several groups the loss is the mean over groups of the one-group
  *     loss (the listing's mean over [num_cores, num_experts] times N^2), and
  *     the capacity is floor(T_group / E * capacity_factor).
+ *   - training-time noise (optional, off by default; swo_noise):
+ *       input jitter (App. C: multiplicative jitter on the router's incoming representation;
+ *       the appendix listing instead adds the noise to the logits -- the text is followed):
+ *       the router sees x[t][k] * m, m uniform in [1 - eps, 1 + eps), the experts see x;
+ *       expert dropout (Sec. 2.4): the hidden activation ReLU(h) of every expert is dropped
+ *       with the given rate and the survivors are scaled by 1 / (1 - rate).
+ *     The random numbers come from a counter-based generator defined here (swo_mix): a
+ *     32-bit mixing function of (seed, stream, element index), so that any implementation
+ *     can reproduce every draw from the element's coordinates alone.
  *   - the residual connection is outside the layer: a dropped token's output
  *     row is zero.
  *   - ReLU'(0) = 0.
@@ -54,6 +63,54 @@
 #endif
 typedef SWO_IN_T in_t;
 
+/* ---- training-time noise ------------------------------------------------- */
+typedef struct {
+    float expert_dropout; /* rate in [0, 1): 0 = off                          */
+    float jitter_eps;     /* eps in [0, 1): 0 = off                           */
+    uint64_t seed;
+} swo_noise;
+
+/* 32 random bits for element `idx` (wrapping 32-bit index) of stream `stream`:
+ * multiply / xor-shift rounds over idx, with the two halves of the seed and the stream
+ * number folded in. */
+uint32_t swo_mix(uint32_t idx, uint32_t stream, uint64_t seed) {
+    uint32_t z = idx ^ (uint32_t)seed;
+    z *= 0x9E3779B1u;
+    z ^= z >> 15;
+    z += (uint32_t)(seed >> 32) + stream * 0x7F4A7C15u;
+    z *= 0x85EBCA77u;
+    z ^= z >> 13;
+    z *= 0xC2B2AE3Du;
+    z ^= z >> 16;
+    return z;
+}
+enum { SWO_STREAM_JITTER = 1, SWO_STREAM_DROPOUT = 2 };
+
+/* jitter multiplier of x[t][k]: (1 - eps) + 2 eps u with u = (top 24 bits) 2^-24, evaluated
+ * in fp32 with one fused multiply-add (so that an fp32 implementation gets the same m) */
+static double jitter_mult(const swo_noise *nz, int64_t t, int64_t d, int64_t k) {
+    if (!nz || nz->jitter_eps <= 0.0f) return 1.0;
+    uint32_t z = swo_mix((uint32_t)((uint64_t)t * (uint64_t)d + (uint64_t)k), SWO_STREAM_JITTER,
+                         nz->seed);
+    float u = (float)(z >> 8) * 0x1p-24f;
+    return (double)fmaf(2.0f * nz->jitter_eps, u, 1.0f - nz->jitter_eps);
+}
+/* dropout factor of hidden unit j of token t: 0 (dropped) or 1 / (1 - rate) */
+static double dropout_factor(const swo_noise *nz, int64_t t, int64_t f, int64_t j) {
+    if (!nz || nz->expert_dropout <= 0.0f) return 1.0;
+    uint32_t thr = (uint32_t)floor((double)nz->expert_dropout * 4294967296.0);
+    uint32_t z = swo_mix((uint32_t)((uint64_t)t * (uint64_t)f + (uint64_t)j), SWO_STREAM_DROPOUT,
+                         nz->seed);
+    return z >= thr ? 1.0 / (1.0 - (double)nz->expert_dropout) : 0.0;
+}
+/* exported for the tests */
+double swo_jitter_mult(const swo_noise *nz, int64_t t, int64_t d, int64_t k) {
+    return jitter_mult(nz, t, d, k);
+}
+double swo_dropout_factor(const swo_noise *nz, int64_t t, int64_t f, int64_t j) {
+    return dropout_factor(nz, t, f, j);
+}
+
 /* ---- Eq. 3: expert capacity -------------------------------------------- */
 int64_t swo_capacity(int64_t T, int64_t E, double capacity_factor) {
     double c = (double)T / (double)E * capacity_factor;
@@ -62,16 +119,24 @@ int64_t swo_capacity(int64_t T, int64_t E, double capacity_factor) {
 
 /* ---- Sec. 2.1: router logits h(x) = W_r . x (+ optional bias) ----------- */
 void swo_logits(int64_t T, int64_t d, int64_t E, const in_t *x, const in_t *W_r,
-                const in_t *b_r /* may be NULL */, double *h /* [T][E] */) {
-#pragma omp parallel for schedule(static)
-    for (int64_t t = 0; t < T; ++t) {
-        for (int64_t i = 0; i < E; ++i) {
-            double s = 0.0;
+                const in_t *b_r /* may be NULL */, const swo_noise *nz /* may be NULL */,
+                double *h /* [T][E] */) {
+#pragma omp parallel
+    {
+        double *xr = (double *)malloc(sizeof(double) * (size_t)(d > 0 ? d : 1));
+#pragma omp for schedule(static)
+        for (int64_t t = 0; t < T; ++t) {
+            /* the router's view of the token: x_t, jittered if asked for */
             for (int64_t k = 0; k < d; ++k)
-                s += (double)x[t * d + k] * (double)W_r[k * E + i];
-            if (b_r) s += (double)b_r[i];
-            h[t * E + i] = s;
+                xr[k] = (double)x[t * d + k] * jitter_mult(nz, t, d, k);
+            for (int64_t i = 0; i < E; ++i) {
+                double s = 0.0;
+                for (int64_t k = 0; k < d; ++k) s += xr[k] * (double)W_r[k * E + i];
+                if (b_r) s += (double)b_r[i];
+                h[t * E + i] = s;
+            }
         }
+        free(xr);
     }
 }
 
@@ -170,7 +235,7 @@ static void my_range(int64_t n, int64_t *lo, int64_t *hi) {
 /* One token through one expert: h = x W_in, a = ReLU(h), o = a W_out (Sec. 5,
  * review of the FFN layer).  Called by every thread of the team. */
 static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, const in_t *Wo,
-                      double *hpre, double *a, double *o) {
+                      const swo_noise *nz, int64_t t, double *hpre, double *a, double *o) {
     int64_t j0, j1, i0, i1;
     my_range(f, &j0, &j1);
     my_range(d, &i0, &i1);
@@ -180,7 +245,8 @@ static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, cons
         const in_t *row = Wi + k * f;
         for (int64_t j = j0; j < j1; ++j) hpre[j] += xk * (double)row[j];
     }
-    for (int64_t j = j0; j < j1; ++j) a[j] = hpre[j] > 0.0 ? hpre[j] : 0.0;
+    for (int64_t j = j0; j < j1; ++j)
+        a[j] = hpre[j] > 0.0 ? hpre[j] * dropout_factor(nz, t, f, j) : 0.0;
 #pragma omp barrier
     for (int64_t i = i0; i < i1; ++i) o[i] = 0.0;
     for (int64_t j = 0; j < f; ++j) {
@@ -198,7 +264,7 @@ static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, cons
 void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
                     const in_t *W_in, const in_t *W_out, const int32_t *expert_index,
                     const uint8_t *dropped, const double *gate, const uint8_t *token_sel,
-                    double *y /* [T][d] */) {
+                    const swo_noise *nz /* may be NULL */, double *y /* [T][d] */) {
     double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
     double *a = (double *)malloc(sizeof(double) * (size_t)f);
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
@@ -217,8 +283,8 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
                 for (int64_t i = i0; i < i1; ++i) yt[i] = 0.0;
                 continue;
             }
-            ffn_token(d, f, x + t * d, W_in + (int64_t)e * d * f, W_out + (int64_t)e * f * d,
-                      hpre, a, o);
+            ffn_token(d, f, x + t * d, W_in + (int64_t)e * d * f, W_out + (int64_t)e * f * d, nz,
+                      t, hpre, a, o);
             for (int64_t i = i0; i < i1; ++i) yt[i] = gate[t] * o[i];
 #pragma omp barrier
         }
@@ -280,6 +346,9 @@ int64_t swo_hidden_near_zero(int64_t T, int64_t d, int64_t f, const in_t *x, con
  *   dp[t,i]  = dg_t 1[i = e_t] + d_aux alpha E f_gi / (n T_g)      (t in group g)
  *   dl[t,j]  = p[t,j] (dp[t,j] - sum_i p[t,i] dp[t,i])         (softmax)
  *   dW_r = x^T dl,  db_r = sum_t dl_t,  dx_t += dl_t W_r^T
+ * With noise: the router's input is x (.) m (jitter multipliers, constants), so x is replaced
+ * by x (.) m in dW_r and the router's share of dx_t is (dl_t W_r^T) (.) m_t; the hidden
+ * activation is ReLU(h) (.) q with q in {0, 1 / (1 - rate)}, so dh_t carries the same q.
  *
  * Partial evaluation (for sampled checks on large layers):
  *   token_sel[t] == 0 (token_sel may be NULL = all selected): the token's expert
@@ -299,7 +368,8 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                   const int64_t *counts_g /* [n_groups][E] */,
                   const int32_t *sel_slot /* [E] or NULL */,
                   const uint8_t *token_sel /* [T] or NULL */, int64_t n_flip,
-                  const int64_t *flip_t, const int64_t *flip_j, double *dx /* [T][d] */,
+                  const int64_t *flip_t, const int64_t *flip_j,
+                  const swo_noise *nz /* may be NULL */, double *dx /* [T][d] */,
                   double *dW_r /* [d][E] */, double *db_r /* [E] */,
                   double *dW_in_sel /* [nsel][d][f] */, double *dW_out_sel /* [nsel][f][d] */,
                   double *dgate /* [T] */, double *dlogits /* [T][E] */) {
@@ -341,7 +411,7 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
             double *gWo = slot >= 0 ? dW_out_sel + slot * f * d : NULL;
             const in_t *xt = x + t * d;
             const in_t *dyt = dy + t * d;
-            ffn_token(d, f, xt, Wi, Wo, hpre, a, o);
+            ffn_token(d, f, xt, Wi, Wo, nz, t, hpre, a, o);
             /* gate gradient: a short dot product, taken whole by every thread */
             double dg = 0.0;
             for (int64_t i = 0; i < d; ++i) dg += (double)dyt[i] * o[i];
@@ -359,7 +429,7 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                 int on = hpre[j] > 0.0;
                 for (int64_t q = 0; q < n_flip; ++q)
                     if (flip_t[q] == t && flip_j[q] == j) on = !on;
-                dh[j] = on ? s : 0.0;
+                dh[j] = on ? s * dropout_factor(nz, t, f, j) : 0.0;
             }
 #pragma omp barrier
             for (int64_t k = k0; k < k1; ++k) {
@@ -402,7 +472,7 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
             for (int64_t k = 0; k < d; ++k) {
                 double r = 0.0;
                 for (int64_t j = 0; j < E; ++j) r += dlogits[t * E + j] * (double)W_r[k * E + j];
-                dxt[k] += r;
+                dxt[k] += r * jitter_mult(nz, t, d, k);   /* the router saw x[t][k] * m */
             }
         }
         free(dp);
@@ -414,7 +484,7 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
         double *row = dW_r + k * E;
         for (int64_t j = 0; j < E; ++j) row[j] = 0.0;
         for (int64_t t = 0; t < T; ++t) {
-            double xk = (double)x[t * d + k];
+            double xk = (double)x[t * d + k] * jitter_mult(nz, t, d, k);
             const double *dl = dlogits + t * E;
             for (int64_t j = 0; j < E; ++j) row[j] += xk * dl[j];
         }

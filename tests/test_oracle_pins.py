@@ -590,3 +590,168 @@ def test_relu_flip_equals_moving_h_across_zero():
         assert np.array_equal(np.delete(plain["dx"], t, axis=0), np.delete(flipped["dx"], t, axis=0))
     finally:
         oracle.use_f64_inputs(False)
+
+
+# ------------------------------------------------------------------ training-time noise
+# The generator's bits cannot be compared with a printed value (the paper fixes no generator),
+# so they are pinned by what any usable generator must satisfy; WHERE the draws enter the
+# layer is pinned against an independent torch forward that takes them as constant matrices.
+def _draws(stream, seed, n, start=0):
+    return np.array([oracle.mix(start + i, stream, seed) for i in range(n)], dtype=np.uint64)
+
+
+def test_generator_is_uniform_and_streams_are_unrelated():
+    n = 60000
+    a = _draws(1, 12345, n)
+    u = a.astype(np.float64) / 2.0 ** 32
+    sigma = 1.0 / np.sqrt(12.0 * n)
+    assert abs(u.mean() - 0.5) < 4 * sigma
+    assert abs(u.var() - 1.0 / 12.0) < 4 * np.sqrt(1.0 / 180.0 / n)
+    # every one of the 32 bits is balanced
+    for b in range(32):
+        ones = int(((a >> np.uint64(b)) & np.uint64(1)).sum())
+        assert abs(ones - n / 2) < 4.5 * np.sqrt(n) / 2, b
+    # 16 equal bins (chi-square, 15 degrees of freedom: 99.99 % point is 44.3)
+    hist = np.bincount((u * 16).astype(np.int64), minlength=16)
+    assert ((hist - n / 16) ** 2 / (n / 16)).sum() < 44.3
+    # neighbouring elements, another stream, another seed (either half), a far-away window:
+    # all uncorrelated with the first sequence
+    others = [np.roll(u, 1), _draws(2, 12345, n) / 2.0 ** 32, _draws(1, 12346, n) / 2.0 ** 32,
+              _draws(1, 12345 + (1 << 32), n) / 2.0 ** 32,
+              _draws(1, 12345, n, start=1 << 31) / 2.0 ** 32]
+    for o in others:
+        assert abs(np.corrcoef(u, o)[0, 1]) < 4.5 / np.sqrt(n)
+        assert (o != u).mean() > 0.999
+    # deterministic, and the element index wraps at 2^32
+    assert oracle.mix(7, 2, 99) == oracle.mix(7, 2, 99) == oracle.mix(7 + (1 << 32), 2, 99)
+    # no two of the first draws collide more often than chance allows (birthday bound ~0.42)
+    assert n - np.unique(a).size <= 6
+
+
+@pytest.mark.parametrize("rate", [0.1, 0.4])
+def test_dropout_factor_values_and_keep_fraction(rate):
+    T, f = 300, 200
+    nz = (rate, 0.0, 77)
+    q = np.array([[oracle.dropout_factor(nz, t, f, j) for j in range(f)] for t in range(T)])
+    scale = 1.0 / (1.0 - float(np.float32(rate)))
+    assert set(np.unique(q)) == {0.0, scale}
+    keep = (q > 0).mean()
+    assert abs(keep - (1 - rate)) < 4 * np.sqrt(rate * (1 - rate) / (T * f))
+    assert abs(q.mean() - 1.0) < 4 * scale * np.sqrt(rate * (1 - rate) / (T * f))   # unbiased
+    # rows and columns are not systematically different
+    assert abs((q > 0).mean(0) - (1 - rate)).max() < 5 * np.sqrt(rate * (1 - rate) / T)
+    assert abs((q > 0).mean(1) - (1 - rate)).max() < 5 * np.sqrt(rate * (1 - rate) / f)
+    # the element's flat index t f + j is what is hashed: a reshape gives the same draws
+    assert oracle.dropout_factor(nz, 3, f, 5) == oracle.dropout_factor(nz, 0, 1, 3 * f + 5)
+    assert oracle.dropout_factor((0.0, 0.0, 77), 3, f, 5) == 1.0
+
+
+@pytest.mark.parametrize("eps", [0.01, 0.25])
+def test_jitter_multiplier_range_and_moments(eps):
+    T, d = 250, 160
+    nz = (0.0, eps, 5)
+    m = np.array([[oracle.jitter_mult(nz, t, d, k) for k in range(d)] for t in range(T)])
+    e32 = float(np.float32(eps))
+    assert m.min() >= 1 - e32 - 1e-7 and m.max() < 1 + e32 + 1e-7
+    assert m.min() < 1 - 0.99 * e32 and m.max() > 1 + 0.99 * e32
+    n = T * d
+    assert abs(m.mean() - 1.0) < 4 * (2 * e32) / np.sqrt(12.0 * n)
+    assert abs(m.var() - (2 * e32) ** 2 / 12) < 5 * (2 * e32) ** 2 * np.sqrt(1.0 / 180.0 / n)
+    assert np.all(m == m.astype(np.float32))       # every multiplier is an fp32 value
+    assert oracle.jitter_mult((0.3, 0.0, 5), 1, d, 2) == 1.0
+    # dropout and jitter draw from different streams
+    q = np.array([oracle.dropout_factor((0.5, 0.0, 5), t, d, k) for t in range(40) for k in range(d)])
+    assert abs(np.corrcoef(q, m[:40].ravel())[0, 1]) < 4.5 / np.sqrt(q.size)
+
+
+def _noise_matrices(nz, T, d, f):
+    M = np.array([[oracle.jitter_mult(nz, t, d, k) for k in range(d)] for t in range(T)])
+    Q = np.array([[oracle.dropout_factor(nz, t, f, j) for j in range(f)] for t in range(T)])
+    return M, Q
+
+
+def test_zero_noise_is_the_plain_layer():
+    s = SwitchShape("t", 64, 16, 24, 4, 1.0, dtype="f32", seed_index=3)
+    inp = _np_inputs(s)
+    a = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha)
+    b = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha,
+                       noise=(0.0, 0.0, 1234))
+    for k in ("logits", "y", "expert_index"):
+        assert np.array_equal(a[k], b[k])
+
+
+@pytest.mark.parametrize("n_groups,bias", [(1, False), (2, True)])
+def test_noisy_layer_against_torch_autograd(n_groups, bias):
+    """Jitter multiplies the router's copy of x only; dropout scales ReLU(h); both are
+    constants under differentiation."""
+    s = SwitchShape("t", 96, 24, 40, 4, 0.75, dtype="f32", zipf_bias=bias, seed_index=23)
+    inp = _np_inputs(s)
+    nz = (0.3, 0.2, 2024)
+    d_aux = 1.3
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.75, s.alpha,
+                         b_r=inp["b_r"], noise=nz, n_groups=n_groups)
+    plain = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.75, s.alpha,
+                           b_r=inp["b_r"], n_groups=n_groups)
+    assert np.abs(fwd["logits"] - plain["logits"]).max() > 1e-3
+    if not bias:
+        assert (fwd["expert_index"] != plain["expert_index"]).any()   # the jitter moved decisions
+    bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd,
+                          s.alpha, d_aux)
+    M, Q = _noise_matrices(nz, s.T, s.d_model, s.d_ff)
+    assert (Q == 0).any() and (M != 1).all()
+    tt = {k: (None if v is None else torch.tensor(v, dtype=torch.float64,
+                                                   requires_grad=(k != "dy")))
+          for k, v in inp.items()}
+    Mt, Qt = torch.tensor(M), torch.tensor(Q)
+    x, E, Tg = tt["x"], s.E, s.T // n_groups
+    h = (x * Mt) @ tt["W_r"]
+    if bias:
+        h = h + tt["b_r"]
+    p = torch.softmax(h, dim=1)
+    e = torch.argmax(h, dim=1)
+    onehot = torch.nn.functional.one_hot(e, E).to(torch.float64)
+    oh_g = onehot.view(n_groups, Tg, E)
+    pos = ((torch.cumsum(oh_g, 1) - 1) * oh_g).sum(2).reshape(-1)
+    kept = (pos < fwd["capacity"]).to(torch.float64)
+    gate = (p * onehot).sum(1)
+    hid = torch.relu(torch.einsum("td,tdf->tf", x, tt["W_in"][e])) * Qt
+    y = (kept * gate)[:, None] * torch.einsum("tf,tfd->td", hid, tt["W_out"][e])
+    aux = s.alpha * E * (oh_g.mean(1).detach() * p.view(n_groups, Tg, E).mean(1)).sum(1).mean()
+    ((y * tt["dy"]).sum() + d_aux * aux).backward()
+    assert np.array_equal(fwd["expert_index"], e.numpy())
+    assert fwd["dropped"].sum() > 0
+    np.testing.assert_allclose(fwd["y"], y.detach().numpy(), rtol=1e-12, atol=1e-14)
+    assert abs(fwd["aux_loss"] - float(aux.detach())) < 1e-15
+    for name in ("x", "W_r", "W_in", "W_out"):
+        g = tt[name].grad.numpy()
+        np.testing.assert_allclose(bwd["d" + name], g, rtol=1e-10,
+                                   atol=1e-12 * max(1.0, np.abs(g).max()), err_msg=name)
+    if bias:
+        np.testing.assert_allclose(bwd["db_r"], tt["b_r"].grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_expert_dropout_is_unbiased_over_seeds():
+    s = SwitchShape("t", 16, 8, 64, 2, 2.0, dtype="f32", seed_index=4)
+    inp = _np_inputs(s)
+    ref = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 2.0, s.alpha)["y"]
+    n = 400
+    ys = np.stack([oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 2.0, s.alpha,
+                                  noise=(0.25, 0.0, 1000 + i))["y"] for i in range(n)])
+    err = ys.mean(0) - ref
+    sem = ys.std(0) / np.sqrt(n)
+    assert (sem > 0).all()
+    assert np.abs(err / sem).max() < 4.5          # 128 outputs, each a mean of 400 draws
+    assert abs((err / sem).mean()) < 4.5 / np.sqrt(err.size)
+
+
+def test_noisy_subsets_match_full_run():
+    """Token / expert subsets draw the same numbers as the full run (the draws depend on the
+    element's coordinates only)."""
+    s = SwitchShape("t", 128, 16, 24, 8, 1.0, dtype="f32", seed_index=9)
+    inp = _np_inputs(s)
+    nz = (0.2, 0.1, 31337)
+    full = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha, noise=nz)
+    sub = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha, noise=nz,
+                         expert_sel=[2], token_sel=[5, 77])
+    rows = np.flatnonzero((full["expert_index"] == 2)).tolist() + [5, 77]
+    assert np.array_equal(full["y"][rows], sub["y"][rows])
