@@ -49,7 +49,8 @@ typedef enum {
     SW_ERR_SHAPE = -2,     /* T, d_model, d_ff, E, n_groups out of range; rows not whole
                               16-byte chunks; bf16: an expert's weight matrix or its
                               slots x max(d_model, d_ff) activations reach 2 GB       */
-    SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite */
+    SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite,
+                              expert_dropout or jitter_eps outside [0, 1)          */
     SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16            */
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
     SW_ERR_ALIGN = -6,     /* a tensor pointer is not 16-byte aligned            */
@@ -72,7 +73,31 @@ typedef struct {
                                 position_in_expert and the two fractions of the loss
                                 are taken per group, the loss is the mean over groups,
                                 the experts are shared.  Must divide T; 0 is read as 1 */
+    /* Training-time noise, both off at 0.  The draws are a pure function of (seed,
+       element): see "Random draws" below.  Forward and backward of one step must be
+       given the same three values; change the seed from step to step. */
+    float expert_dropout;    /* Sec. 2.4: rate in [0, 1) at which the hidden activations
+                                ReLU(x W_in) of every expert are zeroed; survivors are
+                                scaled by 1 / (1 - rate)                             */
+    float jitter_eps;        /* App. C input jitter: the router (and only the router)
+                                sees x[t][k] * m, m uniform in [1 - eps, 1 + eps);
+                                eps in [0, 1)                                         */
+    uint64_t seed;
 } switch_config;
+
+/*
+ * Random draws.  Element number idx (a 32-bit integer that wraps) of stream s gets the
+ * 32 bits
+ *     z = (idx ^ seed_lo) * 0x9E3779B1;  z ^= z >> 15;
+ *     z = (z + seed_hi + s * 0x7F4A7C15) * 0x85EBCA77;  z ^= z >> 13;
+ *     z *= 0xC2B2AE3D;  z ^= z >> 16;            (all arithmetic modulo 2^32)
+ * with seed_lo / seed_hi the two halves of seed.
+ *   jitter  (s = 1, idx = t * d_model + k):  m = fma(2 eps, (z >> 8) * 2^-24, 1 - eps) in fp32
+ *   dropout (s = 2, idx = t * d_ff + j, t the token -- not its slot):  hidden unit j of
+ *           token t is zeroed iff z < floor(rate * 2^32)
+ * With jitter_eps > 0 the router's two contractions run on the vector ALUs in both
+ * precisions (the products x * m are no longer bf16 values).
+ */
 
 /* Expert capacity, Eq. 3, rounded down:
  *   capacity = floor((double)(T / n_groups) / (double)E * capacity_factor)
@@ -93,6 +118,8 @@ int switch_workspace_size(const switch_config *cfg, size_t *bytes_out /* host */
  *   dropped[t] = position_in_expert[t] >= capacity                     (Eq. 3, Fig. 3)
  *   y[t,:] = gate[t] * ReLU(x[t,:] W_in[e]) W_out[e]  if kept, +0 if dropped
  *            (the residual connection is the caller's)
+ *   with noise: h is computed from x * m (Eq. 1 on the jittered input), and
+ *            ReLU(.) above is followed by the dropout factor (0 or 1 / (1 - rate))
  *   aux_loss = alpha * E * sum_i f_i P_i, f_i = expert_counts[i] / T over ALL
  *            tokens (before truncation), P_i = mean_t p[t,i]            (Eqs. 4-6)
  * The workspace keeps what switch_backward needs; it must stay untouched

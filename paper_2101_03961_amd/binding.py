@@ -29,6 +29,9 @@ class SwitchConfig(ctypes.Structure):
         ("act_dtype", ctypes.c_int32),
         ("reserved", ctypes.c_int32),
         ("n_groups", ctypes.c_int64),
+        ("expert_dropout", ctypes.c_float),
+        ("jitter_eps", ctypes.c_float),
+        ("seed", ctypes.c_uint64),
     ]
 
 

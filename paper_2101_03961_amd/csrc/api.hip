@@ -23,6 +23,8 @@ int check_config(const switch_config *cfg) {
     if (cfg->d_model % mult || cfg->d_ff % mult) return SW_ERR_SHAPE;
     if (!(cfg->capacity_factor > 0.0) || !isfinite(cfg->capacity_factor)) return SW_ERR_VALUE;
     if (!isfinite(cfg->alpha)) return SW_ERR_VALUE;
+    if (!(cfg->expert_dropout >= 0.f && cfg->expert_dropout < 1.f)) return SW_ERR_VALUE;
+    if (!(cfg->jitter_eps >= 0.f && cfg->jitter_eps < 1.f)) return SW_ERR_VALUE;
     // slot indices (expert * slots per expert + position) are kept in 32 bits
     const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
     const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
@@ -90,6 +92,16 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
     w.relu_bits = take(E * ceil_div(f, kGemmTile) * ceil_div(C, kGemmTile) * kReluBitsPerTile);
     w.total = off;
+    Noise &nz = w.noise;
+    const uint32_t seed_hi = (uint32_t)(cfg->seed >> 32);
+    nz.seed_lo = (uint32_t)cfg->seed;
+    nz.jitter_term = seed_hi + 1u * 0x7F4A7C15u;
+    nz.dropout_term = seed_hi + 2u * 0x7F4A7C15u;
+    nz.dropout = cfg->expert_dropout > 0.f;
+    nz.jitter = cfg->jitter_eps > 0.f;
+    nz.drop_thr = (uint32_t)floor((double)cfg->expert_dropout * 4294967296.0);
+    nz.drop_scale = (float)(1.0 / (1.0 - (double)cfg->expert_dropout));
+    nz.jitter_eps = cfg->jitter_eps;
     return w;
 }
 
@@ -276,7 +288,9 @@ const char *switch_status_string(int status) {
     case SW_OK: return "ok";
     case SW_ERR_NULL: return "a required pointer is NULL";
     case SW_ERR_SHAPE: return "shape out of range (T, E, d_model, d_ff; 16-byte row chunks)";
-    case SW_ERR_VALUE: return "capacity_factor must be finite and > 0; alpha, d_aux finite";
+    case SW_ERR_VALUE:
+        return "capacity_factor must be finite and > 0; alpha, d_aux finite; expert_dropout and "
+               "jitter_eps in [0, 1)";
     case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16";
     case SW_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";

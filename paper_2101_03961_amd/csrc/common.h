@@ -44,6 +44,37 @@ __device__ __forceinline__ int block_of_token(int t, int nbg, int Tg) {
 }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ---- training-time noise (Sec. 2.4 expert dropout; App. C input jitter) ------
+// Every draw is a function of (seed, stream, element index) only -- 32 bits from
+// multiply / xor-shift rounds, documented in switchffn.h -- so any kernel can
+// reproduce the draw of an element from its coordinates.
+struct Noise {
+    uint32_t seed_lo;
+    uint32_t jitter_term;    // seed_hi + stream constant of the jitter stream
+    uint32_t dropout_term;   // seed_hi + stream constant of the dropout stream
+    uint32_t drop_thr;       // a hidden unit is dropped iff its 32 bits are < drop_thr
+    float drop_scale;        // 1 / (1 - rate); 1 when dropout is off
+    float jitter_eps;
+    int dropout, jitter;     // on / off
+};
+__device__ __forceinline__ uint32_t noise_bits(uint32_t idx, uint32_t seed_lo, uint32_t term) {
+    uint32_t z = (idx ^ seed_lo) * 0x9E3779B1u;
+    z ^= z >> 15;
+    z = (z + term) * 0x85EBCA77u;
+    z ^= z >> 13;
+    z *= 0xC2B2AE3Du;
+    return z ^ (z >> 16);
+}
+// multiplier of element idx = t * d + k of the router's input: uniform in [1 - eps, 1 + eps)
+__device__ __forceinline__ float jitter_of(const Noise &nz, uint32_t idx) {
+    const float u = (float)(noise_bits(idx, nz.seed_lo, nz.jitter_term) >> 8) * 0x1p-24f;
+    return fmaf(2.0f * nz.jitter_eps, u, 1.0f - nz.jitter_eps);
+}
+// hidden unit idx = t * f + j survives expert dropout
+__device__ __forceinline__ bool dropout_keeps(const Noise &nz, uint32_t idx) {
+    return noise_bits(idx, nz.seed_lo, nz.dropout_term) >= nz.drop_thr;
+}
+
 // ---- workspace layout (byte offsets into the caller's workspace) ------------
 struct Workspace {
     int64_t T, d, f, E;
@@ -90,6 +121,7 @@ struct Workspace {
                                 //     A > 0, in the order the bf16 GEMM epilogue visits a tile
     int64_t nsplit;
     size_t total;
+    Noise noise;                // not part of the layout: the call's noise parameters
 };
 
 int check_config(const switch_config *cfg);

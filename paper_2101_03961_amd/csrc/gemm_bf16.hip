@@ -79,6 +79,9 @@ struct GemmArgs {
     int tiles_q, tiles_p, total_tiles;
     int reverse;        // walk the experts from the last to the first (see launch_gemm_bf16)
     // router backward uses of the kernel (see GemmMode)
+    const int32_t *slot_token;          // EPI_DROP: token of each slot, [expert][slots]
+    int slots;                          //           slots per expert
+    Noise nz;                           //           dropout threshold, scale, seed
     const int32_t *tok_slot;            // ROUTER_DX: row of the addend for each token, -1: none
     float *Cf;                          // ROUTER_DWR: fp32 partial sums [split][q][p]
     int T_total, tps;                   // ROUTER_DWR: tokens, tokens per split
@@ -96,7 +99,10 @@ enum GemmMode { MODE_EXPERTS = 0, MODE_ROUTER_DX = 1, MODE_ROUTER_DWR = 2 };
 template <bool TRANS> struct OperandOf { typedef DirectOperand64 type; };
 template <> struct OperandOf<true> { typedef TransOperand64 type; };
 
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2 };
+// EPI_DROP is a flag on top of EPI_RELU / EPI_MASK: expert dropout (Sec. 2.4) zeroes hidden
+// units after the ReLU and scales the survivors; the mask bits then say "active and kept",
+// and the masked gradient is scaled by the same factor.
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_DROP = 4 };
 
 // One output tile of one expert.
 struct Tile {
@@ -150,6 +156,8 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int EPI_BASE = EPI & 3;
+    constexpr bool DROP = (EPI & EPI_DROP) != 0;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -314,7 +322,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             SW_K_STEP(gs + kt);
         }
         // the last two steps load the next tile's first two (after the last tile: zeros)
-        if (EPI == EPI_MASK) {
+        if (EPI_BASE == EPI_MASK) {
             // asked for here so that they are not queued behind the next tile's loads
             const uint32_t *bits = bits_of(lane);
             const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
@@ -365,7 +373,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             char *ep = lds + kRingBytes + wave * kTurnBytes;
             bf16 *Cout = a.Cout + (size_t)cur.e * a.c_batch;
             const int c = ln & 15;
-            uint32_t *bits = EPI == EPI_NONE ? nullptr : bits_of(ln);
+            uint32_t *bits = EPI_BASE == EPI_NONE ? nullptr : bits_of(ln);
             const int p = cur.p0 + wp * 128 + c * 8;
             // ReLU mask: byte j * 8 + i8 of a lane's 32 bytes says which of the eight
             // elements of the 16-byte piece the lane handles in round j, iteration i8 are
@@ -392,6 +400,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int wrow = ln & 31;
+                // expert dropout: the draw of hidden unit p of token t is element t * d_ff + p of
+                // the dropout stream; the lane's accumulators of this round belong to one slot
+                uint32_t drop_row = 0;
+                if (DROP && EPI_BASE == EPI_RELU) {
+                    const int q = cur.q0 + wq * 128 + j * 32 + wrow;
+                    const int tok = q < cur.qlim ? a.slot_token[(size_t)cur.e * a.slots + q] : 0;
+                    drop_row = (uint32_t)tok * (uint32_t)a.Pdim +
+                               (uint32_t)(cur.p0 + wp * 128 + ((ln >> 5) << 2));
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -399,9 +416,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                         float v[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) v[r] = acc[i][j][g * 4 + r];
-                        if (EPI == EPI_RELU) {
+                        if (EPI_BASE == EPI_RELU) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+                            if (DROP) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    v[r] = dropout_keeps(a.nz, drop_row + (uint32_t)(i * 32 + g * 8 + r))
+                                               ? v[r] * a.nz.drop_scale
+                                               : 0.f;
+                            }
+                        }
+                        if (DROP && EPI_BASE == EPI_MASK) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[r] *= a.nz.drop_scale;
                         }
                         bf16x4 o;
 #pragma unroll
@@ -411,14 +439,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                     }
                 }
                 uint32_t m_lo = 0u, m_hi = 0u;
-                if (EPI == EPI_MASK) { m_lo = mb[2 * j]; m_hi = mb[2 * j + 1]; }
+                if (EPI_BASE == EPI_MASK) { m_lo = mb[2 * j]; m_hi = mb[2 * j + 1]; }
 #pragma unroll
                 for (int i8 = 0; i8 < 8; ++i8) {
                     const int rrow = i8 * 4 + (ln >> 4);       // row within the round
                     const int row = j * 32 + rrow;               // row within the wave's sub-tile
                     const int q = cur.q0 + wq * 128 + row;
                     u32x4 val = *(const u32x4 *)(ep + rrow * 256 + ((c ^ (rrow & 15)) << 4));
-                    if (EPI == EPI_RELU) {
+                    if (EPI_BASE == EPI_RELU) {
                         // After ReLU every half word is a non-negative bf16, so adding 0x7fff
                         // carries into its top bit exactly when it is > 0.  Bits 0..3 of the
                         // byte: low halves of the four words, bits 4..7: high halves.
@@ -430,7 +458,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                         if (i8 < 4) m_lo |= byte << (8 * i8);
                         else m_hi |= byte << (8 * (i8 - 4));
                     }
-                    if (EPI == EPI_MASK) {
+                    if (EPI_BASE == EPI_MASK) {
                         uint32_t byte = (i8 < 4 ? m_lo >> (8 * i8) : m_hi >> (8 * (i8 - 4))) & 0xffu;
                         byte |= byte << 12;   // bit w -> bit w, bit 4+w -> bit 16+w
 #pragma unroll
@@ -450,7 +478,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                         *(u32x4 *)(Cout + off) = val;
                     }
                 }
-                if (EPI == EPI_RELU) *(uint2 *)(bits + 2 * j) = make_uint2(m_lo, m_hi);
+                if (EPI_BASE == EPI_RELU) *(uint2 *)(bits + 2 * j) = make_uint2(m_lo, m_hi);
             }
         }
         if (!have_next) break;
@@ -527,6 +555,12 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm1_fwd_relu", s);
+        if (w.noise.dropout) {
+            a.slot_token = (const int32_t *)(ws + w.slot_token);
+            a.slots = C;
+            a.nz = w.noise;
+            return gemm_launch<false, true, EPI_RELU | EPI_DROP, true, false>(a, s);
+        }
         return gemm_launch<false, true, EPI_RELU, true, false>(a, s);
     }
     case GEMM_FWD2: {
@@ -546,6 +580,10 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm2_dgrad_relumask", s);
+        if (w.noise.dropout) {
+            a.nz = w.noise;
+            return gemm_launch<false, false, EPI_MASK | EPI_DROP, true, false>(a, s);
+        }
         return gemm_launch<false, false, EPI_MASK, true, false>(a, s);
     }
     case GEMM_DGRAD1: {

@@ -16,7 +16,11 @@ struct GemmF32Args {
     const int32_t *kept;
     int q_limited;       // rows q >= kept[e] are not computed / stored
     int k_limited;       // reduction runs over k < kept[e]
-    int epi;             // 0 none, 1 ReLU, 2 multiply by [mask > 0]
+    int epi;             // 0 none, 1 ReLU (+ expert dropout), 2 multiply by [mask > 0] (and by
+                         // the dropout scale of the surviving units)
+    const int32_t *slot_token;   // epi 1 with dropout: token of slot e * slots + q
+    long slots;
+    Noise nz;
 };
 
 constexpr int kF32Tile = 64;
@@ -77,13 +81,21 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args a) {
     for (int i = 0; i < 4; ++i) {
         const int q = q0 + ty * 4 + i;
         if (q >= qlim) continue;
+        uint32_t row_idx = 0;   // index of the token's first hidden unit in the dropout stream
+        if (a.epi == 1 && a.nz.dropout)
+            row_idx = (uint32_t)a.slot_token[(size_t)e * a.slots + q] * (uint32_t)a.Pdim;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int p = p0 + tx * 4 + j;
             if (p >= a.Pdim) continue;
             float v = acc[i][j];
-            if (a.epi == 1) v = v > 0.f ? v : 0.f;
-            if (a.epi == 2) v = mask[(long)q * a.ldc + p] > 0.f ? v : 0.f;
+            if (a.epi == 1) {
+                v = v > 0.f ? v : 0.f;
+                if (a.nz.dropout)   // Sec. 2.4: expert dropout on the hidden activation
+                    v = dropout_keeps(a.nz, row_idx + (uint32_t)p) ? v * a.nz.drop_scale : 0.f;
+            }
+            // a unit passes the gradient iff it was active and survived dropout
+            if (a.epi == 2) v = mask[(long)q * a.ldc + p] > 0.f ? v * a.nz.drop_scale : 0.f;
             Cout[(long)q * a.ldc + p] = v;
         }
     }
@@ -94,6 +106,9 @@ hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const vo
     const long d = w.d, f = w.f, C = w.C;
     GemmF32Args a{};
     a.kept = (const int32_t *)(ws + w.kept);
+    a.slot_token = (const int32_t *)(ws + w.slot_token);
+    a.slots = C;
+    a.nz = w.noise;
     const float *Xd = (const float *)(ws + w.Xd);
     float *A = (float *)(ws + w.A);
     float *O = (float *)(ws + w.O);

@@ -9,7 +9,8 @@ namespace sw {
 
 // -----------------------------------------------------------------------------
 // Logits tile kernel:  h[t][e] = sum_k x[t][k] W_r[k][e] (+ b_r[e]), fp32 FMA chain
-// over k ascending.  Block = 256 tokens x 64 experts, thread = 8 tokens x 8 experts.
+// over k ascending (x[t][k] times its jitter multiplier when input jitter is on).
+// Block = 256 tokens x 64 experts, thread = 8 tokens x 8 experts.
 // -----------------------------------------------------------------------------
 constexpr int kLogTB = 256;  // tokens per block
 constexpr int kLogEB = 64;   // experts per block
@@ -20,7 +21,7 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const XT *__restrict
                                                             const float *__restrict__ W_r,
                                                             const float *__restrict__ b_r,
                                                             float *__restrict__ logits, int T,
-                                                            int d, int E) {
+                                                            int d, int E, Noise nz) {
     __shared__ float xs[kLogKC][kLogTB + 4];
     __shared__ float wsm[kLogKC][kLogEB + 4];
     const int tid = threadIdx.x;
@@ -40,7 +41,11 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const XT *__restrict
 #pragma unroll
             for (int kk = 0; kk < kLogKC; ++kk) {
                 float v = 0.f;
-                if (t < T && k0 + kk < d) v = to_f32(x[(size_t)t * d + k0 + kk]);
+                if (t < T && k0 + kk < d) {
+                    v = to_f32(x[(size_t)t * d + k0 + kk]);
+                    // input jitter (App. C): the router sees x * m
+                    if (nz.jitter) v *= jitter_of(nz, (uint32_t)t * (uint32_t)d + (uint32_t)(k0 + kk));
+                }
                 xs[kk][tid] = v;
             }
         }
@@ -402,14 +407,15 @@ __global__ __launch_bounds__(256) void reduce_dWr_split_kernel(const float *__re
 }
 
 // -----------------------------------------------------------------------------
-// Backward, step 2:  dx[t][k] = sum_j dl[t][j] W_r[k][j] + kept_t * dXd[slot_t][k]
+// Backward, step 2:  dx[t][k] = m[t][k] sum_j dl[t][j] W_r[k][j] + kept_t * dXd[slot_t][k]
+// (m: the jitter multiplier the router's input carried, 1 without jitter)
 // Block = 256 tokens x 64 k, thread = 8 tokens x 8 k, reduction over experts.
 // -----------------------------------------------------------------------------
 template <typename XT>
 __global__ __launch_bounds__(256) void router_dx_kernel(
     const float *__restrict__ dlogits, const float *__restrict__ W_r,
     const XT *__restrict__ dXd, const int32_t *__restrict__ tok_slot, XT *__restrict__ dx, int T,
-    int d, int E) {
+    int d, int E, Noise nz) {
     __shared__ float ds[kLogKC][kLogTB + 4];
     __shared__ float wsm[kLogKC][kLogEB + 4];
     const int tid = threadIdx.x;
@@ -468,6 +474,7 @@ __global__ __launch_bounds__(256) void router_dx_kernel(
             const int k = k0 + tx * 8 + j;
             if (k >= d) continue;
             float v = acc[i][j];
+            if (nz.jitter) v *= jitter_of(nz, (uint32_t)t * (uint32_t)d + (uint32_t)k);
             if (kept) v += to_f32(dXd[slot * d + k]);
             dx[(size_t)t * d + k] = from_f32<XT>(v);
         }
@@ -475,7 +482,8 @@ __global__ __launch_bounds__(256) void router_dx_kernel(
 }
 
 // -----------------------------------------------------------------------------
-// Backward, step 3:  dW_r[k][j] = sum_t x[t][k] dl[t][j], split over token ranges.
+// Backward, step 3:  dW_r[k][j] = sum_t x[t][k] dl[t][j] (x times its jitter multiplier
+// when input jitter is on), split over token ranges.
 // Block = 64 k x 64 j output tile over one token range; thread = 4 k x 4 j.
 // Partial sums are combined in split order by reduce_partials_kernel, so the
 // result does not depend on scheduling.
@@ -487,7 +495,7 @@ template <typename XT>
 __global__ __launch_bounds__(256) void router_dWr_kernel(const XT *__restrict__ x,
                                                          const float *__restrict__ dlogits,
                                                          float *__restrict__ part, int T, int d,
-                                                         int E, int tokens_per_split) {
+                                                         int E, int tokens_per_split, Noise nz) {
     __shared__ float xs[kWrTC][kWrTile + 4];
     __shared__ float ls[kWrTC][kWrTile + 4];
     const int tid = threadIdx.x;
@@ -511,7 +519,11 @@ __global__ __launch_bounds__(256) void router_dWr_kernel(const XT *__restrict__ 
             for (int u = 0; u < 4; ++u) {
                 float xv = 0.f, lv = 0.f;
                 if (t < t_hi) {
-                    if (k0 + cc + u < d) xv = to_f32(x[(size_t)t * d + k0 + cc + u]);
+                    if (k0 + cc + u < d) {
+                        xv = to_f32(x[(size_t)t * d + k0 + cc + u]);
+                        if (nz.jitter)
+                            xv *= jitter_of(nz, (uint32_t)t * (uint32_t)d + (uint32_t)(k0 + cc + u));
+                    }
                     if (j0 + cc + u < E) lv = dlogits[(size_t)t * E + j0 + cc + u];
                 }
                 xs[tt][cc + u] = xv;
@@ -612,11 +624,12 @@ hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const
         dim3 grid((unsigned)ceil_div(w.T, kLogTB), (unsigned)ceil_div(w.E, kLogEB));
         if (dtype == SW_BF16)
             hipLaunchKernelGGL(router_logits_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)x,
-                               W_r, b_r, (float *)(ws + w.probs), (int)w.T, (int)w.d, (int)w.E);
+                               W_r, b_r, (float *)(ws + w.probs), (int)w.T, (int)w.d, (int)w.E,
+                               w.noise);
         else
             hipLaunchKernelGGL(router_logits_kernel<float>, grid, dim3(256), 0, s,
                                (const float *)x, W_r, b_r, (float *)(ws + w.probs), (int)w.T,
-                               (int)w.d, (int)w.E);
+                               (int)w.d, (int)w.E, w.noise);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     {
@@ -696,7 +709,7 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
         dim3 grid((unsigned)ceil_div(w.T, kLogTB), (unsigned)ceil_div(w.d, kLogEB));
         hipLaunchKernelGGL(router_dx_kernel<XT>, grid, dim3(256), 0, s, dlogits, W_r,
                            (const XT *)(ws + w.dXd), (const int32_t *)(ws + w.tok_slot), dx,
-                           (int)w.T, (int)w.d, (int)w.E);
+                           (int)w.T, (int)w.d, (int)w.E, w.noise);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     const int tokens_per_split = (int)ceil_div(w.T, w.nsplit);
@@ -706,7 +719,7 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
                   (unsigned)w.nsplit);
         hipLaunchKernelGGL(router_dWr_kernel<XT>, grid, dim3(256), 0, s, x, dlogits,
                            (float *)(ws + w.dWr_part), (int)w.T, (int)w.d, (int)w.E,
-                           tokens_per_split);
+                           tokens_per_split, w.noise);
         if ((err = hipGetLastError()) != hipSuccess) return err;
         const size_t n = (size_t)w.d * w.E;
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0,

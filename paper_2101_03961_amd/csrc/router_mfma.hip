@@ -248,7 +248,8 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
 
 bool router_fwd_mfma_supported(const Workspace &w, int dtype) {
     // x is addressed through one buffer descriptor with 32-bit byte offsets
-    return dtype == SW_BF16 && w.E <= kRmExperts && (w.E % 4) == 0 &&
+    // (with input jitter the router's input x * m is no longer a bf16 value)
+    return dtype == SW_BF16 && !w.noise.jitter && w.E <= kRmExperts && (w.E % 4) == 0 &&
            (uint64_t)w.T * (uint64_t)w.d * 2u < 0x7fffffffu;
 }
 

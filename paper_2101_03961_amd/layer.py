@@ -16,11 +16,13 @@ from . import binding as B
 class SwitchLayer:
     def __init__(self, T: int, d_model: int, d_ff: int, E: int, capacity_factor: float,
                  alpha: float = 0.01, dtype: str = "bf16", device: str = "cuda:0",
-                 want_logits: bool = False, n_groups: int = 1):
+                 want_logits: bool = False, n_groups: int = 1, expert_dropout: float = 0.0,
+                 jitter_eps: float = 0.0, seed: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("SwitchLayer needs a GPU: the layer runs only in the HIP library")
         self.cfg = B.SwitchConfig(T, d_model, d_ff, E, float(capacity_factor), float(alpha),
-                                  B.SW_BF16 if dtype == "bf16" else B.SW_F32, 0, int(n_groups))
+                                  B.SW_BF16 if dtype == "bf16" else B.SW_F32, 0, int(n_groups),
+                                  float(expert_dropout), float(jitter_eps), int(seed))
         self.device = torch.device(device)
         self.act = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.capacity = B.switch_capacity(self.cfg)
@@ -38,6 +40,10 @@ class SwitchLayer:
         self.router_logits = (torch.empty((T, E), dtype=torch.float32, device=dev)
                               if want_logits else None)
         self.dx = self.dW_r = self.db_r = self.dW_in = self.dW_out = None
+
+    def set_seed(self, seed: int) -> None:
+        """Seed of the training-time noise for the next forward + backward pair."""
+        self.cfg.seed = int(seed)
 
     def _stream(self) -> int:
         return torch.cuda.current_stream(self.device).cuda_stream

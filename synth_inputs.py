@@ -46,6 +46,9 @@ class SwitchShape:
     zipf_bias: bool = False      # router bias b_r = 2 ln Zipf(1.1) weights
     seed_index: int = 0
     n_groups: int = 1            # routing groups of T / n_groups consecutive tokens
+    expert_dropout: float = 0.0  # training-time noise: dropout rate of the experts' hidden units,
+    jitter_eps: float = 0.0      # half-width of the multiplicative jitter on the router's input,
+    noise_seed: int = 0          # seed of both
 
     def with_(self, **kw) -> "SwitchShape":
         return replace(self, **kw)

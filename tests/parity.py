@@ -129,11 +129,19 @@ def sum_scale(terms: np.ndarray) -> np.ndarray:
     return np.sqrt(np.sum(np.asarray(terms, dtype=np.float64) ** 2, axis=0))
 
 
+def noise_of(shape):
+    """The shape's training-time noise as the oracle takes it (None when off)."""
+    if shape.expert_dropout == 0 and shape.jitter_eps == 0:
+        return None
+    return (shape.expert_dropout, shape.jitter_eps, shape.noise_seed)
+
+
 def run_gpu(shape, inp, d_aux=1.0, backward=True, dy=None):
     """One forward (+ backward) through the C ABI; returns (layer, numpy dict)."""
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
                         shape.alpha, shape.dtype, device=str(inp["x"].device), want_logits=True,
-                        n_groups=shape.n_groups)
+                        n_groups=shape.n_groups, expert_dropout=shape.expert_dropout,
+                        jitter_eps=shape.jitter_eps, seed=shape.noise_seed)
     out = layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"])
     res = {k: to_np(v) for k, v in out.items() if v is not None}
     if backward:
@@ -151,7 +159,7 @@ def check_routing(shape, npi, gpu):
     # (i) routing stage on identical logits: bit exact
     same = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], shape.capacity_factor,
                           shape.alpha, b_r=npi["b_r"], logits_override=gpu["router_logits"],
-                          skip_ffn=True, n_groups=shape.n_groups)
+                          skip_ffn=True, n_groups=shape.n_groups, noise=noise_of(shape))
     assert np.array_equal(gpu["expert_index"], same["expert_index"]), "expert_index"
     assert np.array_equal(gpu["position_in_expert"], same["position_in_expert"]), "position"
     assert np.array_equal(gpu["dropped"], same["dropped"]), "dropped"
@@ -160,7 +168,7 @@ def check_routing(shape, npi, gpu):
     np.testing.assert_allclose(gpu["gate"], same["gate"], rtol=1e-5, atol=0)
     assert abs(float(gpu["aux_loss"][0]) - same["aux_loss"]) <= 1e-5 * abs(same["aux_loss"])
     # (ii) end to end against fp64 logits
-    h64 = oracle.logits(npi["x"], npi["W_r"], npi["b_r"])
+    h64 = oracle.logits(npi["x"], npi["W_r"], npi["b_r"], noise_of(shape))
     assert np.max(np.abs(gpu["router_logits"] - h64)) <= LOGIT_ATOL * max(1.0, np.abs(h64).max())
     e64 = h64.argmax(axis=1)
     flipped = np.nonzero(e64 != gpu["expert_index"])[0]
@@ -171,7 +179,7 @@ def check_routing(shape, npi, gpu):
     pinned = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"],
                             shape.capacity_factor, shape.alpha, b_r=npi["b_r"],
                             logits_override=h64, expert_index_override=gpu["expert_index"],
-                            skip_ffn=True, n_groups=shape.n_groups)
+                            skip_ffn=True, n_groups=shape.n_groups, noise=noise_of(shape))
     assert np.array_equal(gpu["dropped"], pinned["dropped"])
     np.testing.assert_allclose(gpu["gate"], pinned["gate"], rtol=3e-5, atol=0)
     assert abs(float(gpu["aux_loss"][0]) - pinned["aux_loss"]) <= 1e-5 * abs(pinned["aux_loss"])
@@ -217,7 +225,7 @@ def compare_full(shape, inp, d_aux=1.0, widen=None):
     _, gpu = run_gpu(shape, inp, d_aux)
     fwd, flips = check_routing(shape, npi, gpu)
     fwd["y"] = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
-                                 fwd["dropped"], fwd["gate"])
+                                 fwd["dropped"], fwd["gate"], noise=noise_of(shape))
     errs = {"flips": flips}
     errs["y"] = assert_close("y", gpu["y"], fwd["y"], tol)
     check_dropped_rows_are_zero(gpu, shape.dtype)
@@ -257,7 +265,8 @@ def compare_sampled(shape, inp, n_experts=3, n_tokens=32, d_aux=1.0, seed=0):
     tmask[toks] = True
 
     y_ref = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
-                              fwd["dropped"], fwd["gate"], expert_sel=sel, token_sel=toks)
+                              fwd["dropped"], fwd["gate"], expert_sel=sel, token_sel=toks,
+                              noise=noise_of(shape))
     errs = {"flips": flips, "experts": sel, "tokens_checked": int(tmask.sum())}
     errs["y"] = assert_close("y[sampled]", gpu["y"][tmask], y_ref[tmask], tol)
     check_dropped_rows_are_zero(gpu, shape.dtype)

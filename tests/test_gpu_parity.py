@@ -291,6 +291,72 @@ def test_step_can_be_captured_in_a_graph():
         assert float(layer.y.float().abs().sum()) > 0   # eager work between replays
 
 
+# ------------------------------------------- training-time noise (Sec. 2.4, App. C)
+@pytest.mark.parametrize("dtype,T,d,f,E,cf,n,bias,rate,eps,seed", [
+    ("f32", 700, 96, 200, 6, 1.0, 1, False, 0.1, 0.01, 0x123456789ABC),     # both, 48-bit seed
+    ("f32", 1024, 64, 136, 8, 0.75, 4, True, 0.4, 0.0, 5),                  # dropout only, groups
+    ("f32", 515, 72, 64, 5, 2.0, 1, False, 0.0, 0.25, 2 ** 63 + 11),        # jitter only
+    ("bf16", 1500, 256, 520, 6, 1.25, 1, False, 0.4, 0.1, 7),
+    ("bf16", 2048, 128, 264, 128, 1.5, 2, True, 0.0, 0.01, 99),             # would take the MFMA router
+    ("bf16", 3000, 776, 304, 16, 1.0, 3, False, 0.1, 0.0, 2 ** 40),         # MFMA router + dropout
+])
+def test_training_noise(dtype, T, d, f, E, cf, n, bias, rate, eps, seed):
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=70, n_groups=n, zipf_bias=bias,
+                    expert_dropout=rate, jitter_eps=eps, noise_seed=seed)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.8)
+    _report("noise %s rate %.2f eps %.2f" % (dtype, rate, eps), errs)
+    # the noise did something: outputs differ from the noise-free layer's
+    _, plain = run_gpu_plain(s, inp)
+    assert not np.array_equal(plain["y"], gpu["y"])
+    if eps > 0:
+        assert not np.array_equal(plain["router_logits"], gpu["router_logits"])
+    else:
+        assert np.array_equal(plain["router_logits"], gpu["router_logits"])
+        assert np.array_equal(plain["expert_index"], gpu["expert_index"])
+
+
+def run_gpu_plain(s, inp):
+    from parity import run_gpu
+    return run_gpu(s.with_(expert_dropout=0.0, jitter_eps=0.0), inp, backward=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_training_noise_depends_on_the_seed_only(dtype):
+    from parity import run_gpu
+    s = SwitchShape("t", 2000, 128, 256, 8, 1.25, dtype=dtype, seed_index=71, expert_dropout=0.3,
+                    jitter_eps=0.05, noise_seed=1)
+    inp = make_inputs(s, _dev())
+    _, a = run_gpu(s, inp)
+    _, b = run_gpu(s, inp)
+    _, c = run_gpu(s.with_(noise_seed=2), inp)
+    _, hi = run_gpu(s.with_(noise_seed=1 + (1 << 32)), inp)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    for other in (c, hi):
+        assert not np.array_equal(a["y"], other["y"])
+        assert not np.array_equal(a["router_logits"], other["router_logits"])
+    # zero rates: the seed is not looked at
+    z0 = run_gpu(s.with_(expert_dropout=0.0, jitter_eps=0.0, noise_seed=0), inp)[1]
+    z1 = run_gpu(s.with_(expert_dropout=0.0, jitter_eps=0.0, noise_seed=12345), inp)[1]
+    for k in z0:
+        assert np.array_equal(z0[k], z1[k]), k
+    # dropout keeps about 1 - rate of the active hidden units: dW_out rows of dropped units
+    # are zero for a token; count exact zeros of y instead -- none expected for kept tokens
+    kept = a["dropped"] == 0
+    assert np.all(np.abs(a["y"][kept]).sum(axis=1) > 0)
+
+
+def test_training_noise_full_size_sampled():
+    """Switch-Base shape with the fine-tuning expert dropout of Table 4 and jitter."""
+    from parity import compare_sampled
+    s = CONFIGS["base_cf1.25"].with_(expert_dropout=0.4, jitter_eps=0.01, noise_seed=20210111)
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=2, n_tokens=24)
+    _report("base_cf1.25 + noise", errs)
+
+
 # ------------------------------------------- full sizes, sampled against oracle
 @pytest.mark.parametrize("name,n_experts", [
     ("base_cf1.0", 3), ("base_cf1.25", 2), ("base_zipf", 3), ("large", 2), ("c_share", 2),
