@@ -78,8 +78,11 @@ def cpu_baseline(shape, inp, sample_tokens):
     W_r, b_r, W_in, W_out = (to_np(inp[k]) for k in ("W_r", "b_r", "W_in", "W_out"))
     threads = oracle.max_threads()
     t0 = time.perf_counter()
+    noise = None
+    if shape.expert_dropout or shape.jitter_eps:
+        noise = (shape.expert_dropout, shape.jitter_eps, shape.noise_seed)
     fwd = oracle.forward(x, W_r, W_in, W_out, shape.capacity_factor, shape.alpha, b_r=b_r,
-                         n_groups=shape.n_groups)
+                         n_groups=shape.n_groups, noise=noise)
     oracle.backward(x, W_r, W_in, W_out, dy, fwd, shape.alpha, 1.0)
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
@@ -97,6 +100,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-groups", type=int, default=1,
                     help="routing groups (1 = the benchmark's workload; >1 for experiments)")
+    ap.add_argument("--expert-dropout", type=float, default=0.0,
+                    help="expert dropout rate (0 = the benchmark's workload; >0 for experiments)")
+    ap.add_argument("--jitter-eps", type=float, default=0.0,
+                    help="input jitter on the router (0 = the benchmark's workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
@@ -114,10 +121,16 @@ def main() -> int:
     shape = CONFIGS[args.config]
     if args.n_groups != 1:
         shape = shape.with_(name="%s_x%dgroups" % (shape.name, args.n_groups), n_groups=args.n_groups)
+    if args.expert_dropout or args.jitter_eps:
+        shape = shape.with_(name="%s_drop%g_jit%g" % (shape.name, args.expert_dropout, args.jitter_eps),
+                            expert_dropout=args.expert_dropout, jitter_eps=args.jitter_eps,
+                            noise_seed=2101)
     dev = "cuda:0"
     inp = make_inputs(shape, dev)
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
-                        shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups)
+                        shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups,
+                        expert_dropout=shape.expert_dropout, jitter_eps=shape.jitter_eps,
+                        seed=shape.noise_seed)
     layer.alloc_grads(with_bias=inp["b_r"] is not None)
 
     def step():
@@ -193,7 +206,8 @@ def main() -> int:
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": shape.name, "T": shape.T, "d_model": shape.d_model,
                    "d_ff": shape.d_ff, "E": shape.E, "capacity_factor": shape.capacity_factor,
-                   "n_groups": shape.n_groups,
+                   "n_groups": shape.n_groups, "expert_dropout": shape.expert_dropout,
+                   "jitter_eps": shape.jitter_eps,
                    "capacity": layer.capacity, "kept_tokens": kept,
                    "dropped_frac": 1.0 - kept / shape.T,
                    "count_min_mean_max": [int(counts.min()), float(counts.mean()), int(counts.max())]},
