@@ -102,12 +102,12 @@ def _load():
     lib.swo_positions.argtypes = [i64, i64, i64, i64, _c_i32p, _c_i32p, _c_u8p, _c_i64p]
     lib.swo_expert_ffn.restype = None
     lib.swo_expert_ffn.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_i32p,
-                                   _c_u8p, _c_f64p, _c_u8p, noise_p, _c_f64p]
+                                   _c_u8p, _c_f64p, _c_u8p, noise_p, i64, _c_f64p]
     lib.swo_backward.restype = None
     lib.swo_backward.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_f32p,
                                  _c_f32p, f64, f64, _c_i32p, _c_u8p, _c_f64p, _c_f64p, i64, _c_i64p,
-                                 _c_i32p, _c_u8p, i64, _c_i64p, _c_i64p, noise_p, _c_f64p, _c_f64p, _c_f64p,
-                                 _c_f64p, _c_f64p, _c_f64p, _c_f64p]
+                                 _c_i32p, _c_u8p, i64, _c_i64p, _c_i64p, noise_p, i64, _c_f64p,
+                                 _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p, _c_f64p]
     lib.swo_hidden_near_zero.restype = i64
     lib.swo_hidden_near_zero.argtypes = [i64, i64, i64, _c_f32p, _c_f32p, _c_i32p, _c_u8p, _c_u8p,
                                          f64, i64, _c_i64p, _c_i64p, _c_f64p]
@@ -236,16 +236,29 @@ def _token_mask(expert_index, E, expert_sel, token_sel):
     return mask
 
 
+FFN_KINDS = {"relu": 0, "geglu": 1}
+
+
+def _ffn_dims(W_in, W_out, ffn: str):
+    """(E, d, f) from the weight shapes: W_in is [E, d, f] (relu) or [E, d, 2 f] (geglu: gate
+    columns, then linear columns), W_out is [E, f, d]."""
+    E, d, f1 = W_in.shape
+    f = f1 // 2 if ffn == "geglu" else f1
+    assert ffn in FFN_KINDS and W_out.shape == (E, f, d) and f1 == (2 * f if ffn == "geglu" else f)
+    return E, d, f
+
+
 def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None,
-               token_sel=None, noise=None) -> np.ndarray:
-    """y_t = gate_t * ReLU(x_t W_in[e_t]) W_out[e_t] for kept tokens, 0 for dropped.
+               token_sel=None, noise=None, ffn: str = "relu") -> np.ndarray:
+    """y_t = gate_t * FFN_{e_t}(x_t) for kept tokens, 0 for dropped; FFN = ReLU(x W_in) W_out,
+    or with ffn = "geglu" (GELU(x W_g) * (x W_l)) W_out, W_in = [W_g | W_l].
 
     With expert_sel / token_sel only tokens of those experts / those tokens are
     evaluated; all other rows are NaN."""
     x, W_in, W_out = _f32(x), _f32(W_in), _f32(W_out)
     T, d = x.shape
-    E, d2, f = W_in.shape
-    assert d2 == d and W_out.shape == (E, f, d)
+    E, d2, f = _ffn_dims(W_in, W_out, ffn)
+    assert d2 == d
     e = np.ascontiguousarray(expert_index, dtype=np.int32)
     dr = np.ascontiguousarray(dropped, dtype=np.uint8)
     g = np.ascontiguousarray(gate, dtype=np.float64)
@@ -253,7 +266,7 @@ def expert_ffn(x, W_in, W_out, expert_index, dropped, gate, expert_sel=None,
     y = np.empty((T, d), dtype=np.float64)
     _load().swo_expert_ffn(T, d, f, E, _ptr(x, _c_f32p), _ptr(W_in, _c_f32p), _ptr(W_out, _c_f32p),
                            _ptr(e, _c_i32p), _ptr(dr, _c_u8p), _ptr(g, _c_f64p),
-                           _ptr(sel, _c_u8p), _noise(noise), _ptr(y, _c_f64p))
+                           _ptr(sel, _c_u8p), _noise(noise), FFN_KINDS[ffn], _ptr(y, _c_f64p))
     return y
 
 
@@ -264,12 +277,13 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
             logits_override=None, expert_index_override=None,
             expert_sel: Optional[Sequence[int]] = None,
             token_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False,
-            n_groups: int = 1, noise=None) -> Dict:
+            n_groups: int = 1, noise=None, ffn: str = "relu") -> Dict:
     """Whole forward pass.
 
     n_groups: routing groups of T / n_groups consecutive tokens (capacity, positions and the
         auxiliary loss per group; 1 = the whole batch is one group).
     noise: None or (expert_dropout, jitter_eps, seed): training-time noise.
+    ffn: "relu" or "geglu" (see expert_ffn).
     logits_override: use these logits (e.g. another implementation's fp32
         logits, widened) instead of computing them -- for the routing-stage
         comparison, which is defined on identical logits.
@@ -297,9 +311,9 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
     out = dict(capacity=C, logits=h, probs=p, expert_index=e, gate=g, aux_loss=loss,
                expert_counts=counts, f=f_vec, P=P_vec, position_in_expert=pos,
                dropped=dropped, kept_counts=kept, n_groups=n_groups, group_counts=counts_g,
-               noise=noise)
+               noise=noise, ffn=ffn)
     if not skip_ffn:
-        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel, noise)
+        out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel, noise, ffn)
     return out
 
 
@@ -351,7 +365,9 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
     """
     x32, W_r32, W_in32, W_out32, dy32 = _f32(x), _f32(W_r), _f32(W_in), _f32(W_out), _f32(dy)
     T, d = x32.shape
-    E, _, f = W_in32.shape
+    ffn = fwd.get("ffn", "relu")
+    E, _, f = _ffn_dims(W_in32, W_out32, ffn)
+    f1 = W_in32.shape[2]
     e = np.ascontiguousarray(fwd["expert_index"], dtype=np.int32)
     dr = np.ascontiguousarray(fwd["dropped"], dtype=np.uint8)
     g = np.ascontiguousarray(fwd["gate"], dtype=np.float64)
@@ -380,7 +396,7 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
     dx = np.empty((T, d), dtype=np.float64)
     dW_r = np.empty((d, E), dtype=np.float64)
     db_r = np.empty(E, dtype=np.float64)
-    dW_in = np.empty((nsel, d, f), dtype=np.float64)
+    dW_in = np.empty((nsel, d, f1), dtype=np.float64)
     dW_out = np.empty((nsel, f, d), dtype=np.float64)
     dgate = np.empty(T, dtype=np.float64)
     dlog = np.empty((T, E), dtype=np.float64)
@@ -390,7 +406,7 @@ def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.
                          _ptr(g, _c_f64p), _ptr(p, _c_f64p), n_groups, _ptr(counts_g, _c_i64p),
                          _ptr(sel_slot, _c_i32p), _ptr(tmask, _c_u8p), len(flips),
                          _ptr(flip_t, _c_i64p), _ptr(flip_j, _c_i64p), _noise(fwd.get("noise")),
-                         _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
+                         FFN_KINDS[ffn], _ptr(dx, _c_f64p), _ptr(dW_r, _c_f64p),
                          _ptr(db_r, _c_f64p), _ptr(dW_in, _c_f64p), _ptr(dW_out, _c_f64p),
                          _ptr(dgate, _c_f64p), _ptr(dlog, _c_f64p))
     return dict(dx=dx, dW_r=dW_r, db_r=db_r, dW_in=dW_in, dW_out=dW_out, dgate=dgate,

@@ -43,6 +43,12 @@
  *     The random numbers come from a counter-based generator defined here (swo_mix): a
  *     32-bit mixing function of (seed, stream, element index), so that any implementation
  *     can reproduce every draw from the element's coordinates alone.
+ *   - expert FFN variants (ffn_kind): 0 = the ReLU FFN of Sec. 5's review, ReLU(x W_in) W_out;
+ *     1 = the gated-GELU FFN that App. "Switch models" / Tab. 9 marks as FFN_GEGLU (the
+ *     expansion matrix replaced by two sets of weights combined non-linearly, after Shazeer
+ *     2020): (GELU(x W_g) (.) (x W_l)) W_out with the exact GELU(u) = u Phi(u); W_in then holds
+ *     [W_g | W_l] side by side, [d][2 f].  Expert dropout acts on the combined hidden
+ *     activation.
  *   - the residual connection is outside the layer: a dropped token's output
  *     row is zero.
  *   - ReLU'(0) = 0.
@@ -232,21 +238,40 @@ static void my_range(int64_t n, int64_t *lo, int64_t *hi) {
     *hi = n * (id + 1) / nt;
 }
 
-/* One token through one expert: h = x W_in, a = ReLU(h), o = a W_out (Sec. 5,
- * review of the FFN layer).  Called by every thread of the team. */
-static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, const in_t *Wo,
-                      const swo_noise *nz, int64_t t, double *hpre, double *a, double *o) {
-    int64_t j0, j1, i0, i1;
+enum { SWO_FFN_RELU = 0, SWO_FFN_GEGLU = 1 };
+
+/* Phi(u), the standard normal distribution function, and GELU(u) = u Phi(u) with its derivative
+ * Phi(u) + u phi(u). */
+static double norm_cdf(double u) { return 0.5 * erfc(-u * 0.70710678118654752440); }
+static double gelu(double u) { return u * norm_cdf(u); }
+static double gelu_deriv(double u) {
+    return norm_cdf(u) + u * 0.39894228040143267794 * exp(-0.5 * u * u);
+}
+
+/* One token through one expert (Sec. 5, review of the FFN layer): h = x W_in, the hidden
+ * activation a from h, o = a W_out.  ReLU FFN: W_in is [d][f], a = ReLU(h).  Gated-GELU FFN:
+ * W_in is [d][2 f], a_j = GELU(h_j) h_{f+j}.  hpre has room for 2 f values.  Called by every
+ * thread of the team. */
+static void ffn_token(int kind, int64_t d, int64_t f, const in_t *xt, const in_t *Wi,
+                      const in_t *Wo, const swo_noise *nz, int64_t t, double *hpre, double *a,
+                      double *o) {
+    const int64_t f1 = kind == SWO_FFN_GEGLU ? 2 * f : f;
+    int64_t c0, c1, j0, j1, i0, i1;
+    my_range(f1, &c0, &c1);
     my_range(f, &j0, &j1);
     my_range(d, &i0, &i1);
-    for (int64_t j = j0; j < j1; ++j) hpre[j] = 0.0;
+    for (int64_t j = c0; j < c1; ++j) hpre[j] = 0.0;
     for (int64_t k = 0; k < d; ++k) {
         double xk = (double)xt[k];
-        const in_t *row = Wi + k * f;
-        for (int64_t j = j0; j < j1; ++j) hpre[j] += xk * (double)row[j];
+        const in_t *row = Wi + k * f1;
+        for (int64_t j = c0; j < c1; ++j) hpre[j] += xk * (double)row[j];
     }
-    for (int64_t j = j0; j < j1; ++j)
-        a[j] = hpre[j] > 0.0 ? hpre[j] * dropout_factor(nz, t, f, j) : 0.0;
+#pragma omp barrier
+    for (int64_t j = j0; j < j1; ++j) {
+        double act = kind == SWO_FFN_GEGLU ? gelu(hpre[j]) * hpre[f + j]
+                                           : (hpre[j] > 0.0 ? hpre[j] : 0.0);
+        a[j] = act != 0.0 ? act * dropout_factor(nz, t, f, j) : 0.0;
+    }
 #pragma omp barrier
     for (int64_t i = i0; i < i1; ++i) o[i] = 0.0;
     for (int64_t j = 0; j < f; ++j) {
@@ -264,8 +289,10 @@ static void ffn_token(int64_t d, int64_t f, const in_t *xt, const in_t *Wi, cons
 void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
                     const in_t *W_in, const in_t *W_out, const int32_t *expert_index,
                     const uint8_t *dropped, const double *gate, const uint8_t *token_sel,
-                    const swo_noise *nz /* may be NULL */, double *y /* [T][d] */) {
-    double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
+                    const swo_noise *nz /* may be NULL */, int64_t ffn_kind,
+                    double *y /* [T][d] */) {
+    const int64_t f1 = ffn_kind == SWO_FFN_GEGLU ? 2 * f : f;
+    double *hpre = (double *)malloc(sizeof(double) * (size_t)f1);
     double *a = (double *)malloc(sizeof(double) * (size_t)f);
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
 #pragma omp parallel
@@ -283,8 +310,8 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
                 for (int64_t i = i0; i < i1; ++i) yt[i] = 0.0;
                 continue;
             }
-            ffn_token(d, f, x + t * d, W_in + (int64_t)e * d * f, W_out + (int64_t)e * f * d, nz,
-                      t, hpre, a, o);
+            ffn_token((int)ffn_kind, d, f, x + t * d, W_in + (int64_t)e * d * f1,
+                      W_out + (int64_t)e * f * d, nz, t, hpre, a, o);
             for (int64_t i = i0; i < i1; ++i) yt[i] = gate[t] * o[i];
 #pragma omp barrier
         }
@@ -349,6 +376,9 @@ int64_t swo_hidden_near_zero(int64_t T, int64_t d, int64_t f, const in_t *x, con
  * With noise: the router's input is x (.) m (jitter multipliers, constants), so x is replaced
  * by x (.) m in dW_r and the router's share of dx_t is (dl_t W_r^T) (.) m_t; the hidden
  * activation is ReLU(h) (.) q with q in {0, 1 / (1 - rate)}, so dh_t carries the same q.
+ * Gated-GELU FFN (h = [u | v], a = GELU(u) (.) v (.) q): with da_t = dout_t W_out[e]^T,
+ *   du_t = da_t (.) q (.) v (.) GELU'(u),  dv_t = da_t (.) q (.) GELU(u),  dh_t = [du_t | dv_t],
+ * and dW_in, dx_t as above with the [d][2 f] matrix.
  *
  * Partial evaluation (for sampled checks on large layers):
  *   token_sel[t] == 0 (token_sel may be NULL = all selected): the token's expert
@@ -369,16 +399,18 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                   const int32_t *sel_slot /* [E] or NULL */,
                   const uint8_t *token_sel /* [T] or NULL */, int64_t n_flip,
                   const int64_t *flip_t, const int64_t *flip_j,
-                  const swo_noise *nz /* may be NULL */, double *dx /* [T][d] */,
+                  const swo_noise *nz /* may be NULL */, int64_t ffn_kind,
+                  double *dx /* [T][d] */,
                   double *dW_r /* [d][E] */, double *db_r /* [E] */,
-                  double *dW_in_sel /* [nsel][d][f] */, double *dW_out_sel /* [nsel][f][d] */,
+                  double *dW_in_sel /* [nsel][d][f1] */, double *dW_out_sel /* [nsel][f][d] */,
                   double *dgate /* [T] */, double *dlogits /* [T][E] */) {
     /* expert part: tokens in sequence order, see "Work sharing" above */
-    double *hpre = (double *)malloc(sizeof(double) * (size_t)f);
+    const int64_t f1 = ffn_kind == SWO_FFN_GEGLU ? 2 * f : f;   /* columns of W_in */
+    double *hpre = (double *)malloc(sizeof(double) * (size_t)f1);
     double *a = (double *)malloc(sizeof(double) * (size_t)f);
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
     double *dout = (double *)malloc(sizeof(double) * (size_t)d);
-    double *dh = (double *)malloc(sizeof(double) * (size_t)f);
+    double *dh = (double *)malloc(sizeof(double) * (size_t)f1);
 #pragma omp parallel
     {
         int64_t j0, j1, k0, k1;
@@ -387,10 +419,10 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
         for (int64_t e = 0; e < E; ++e) {
             int64_t slot = sel_slot ? sel_slot[e] : e;
             if (slot < 0) continue;
-            double *gWi = dW_in_sel + slot * d * f;
+            double *gWi = dW_in_sel + slot * d * f1;
             double *gWo = dW_out_sel + slot * f * d;
             for (int64_t k = k0; k < k1; ++k)
-                for (int64_t j = 0; j < f; ++j) gWi[k * f + j] = 0.0;
+                for (int64_t j = 0; j < f1; ++j) gWi[k * f1 + j] = 0.0;
             for (int64_t j = j0; j < j1; ++j)
                 for (int64_t i = 0; i < d; ++i) gWo[j * d + i] = 0.0;
         }
@@ -405,13 +437,13 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                 if (omp_get_thread_num() == 0) dgate[t] = 0.0;
                 continue;
             }
-            const in_t *Wi = W_in + e * d * f;
+            const in_t *Wi = W_in + e * d * f1;
             const in_t *Wo = W_out + e * f * d;
-            double *gWi = slot >= 0 ? dW_in_sel + slot * d * f : NULL;
+            double *gWi = slot >= 0 ? dW_in_sel + slot * d * f1 : NULL;
             double *gWo = slot >= 0 ? dW_out_sel + slot * f * d : NULL;
             const in_t *xt = x + t * d;
             const in_t *dyt = dy + t * d;
-            ffn_token(d, f, xt, Wi, Wo, nz, t, hpre, a, o);
+            ffn_token((int)ffn_kind, d, f, xt, Wi, Wo, nz, t, hpre, a, o);
             /* gate gradient: a short dot product, taken whole by every thread */
             double dg = 0.0;
             for (int64_t i = 0; i < d; ++i) dg += (double)dyt[i] * o[i];
@@ -426,6 +458,12 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
                     for (int64_t i = 0; i < d; ++i) grow[i] += aj * dout[i];
                 }
                 for (int64_t i = 0; i < d; ++i) s += dout[i] * (double)row[i];
+                if (ffn_kind == SWO_FFN_GEGLU) {
+                    double sq = s * dropout_factor(nz, t, f, j);
+                    dh[j] = sq * hpre[f + j] * gelu_deriv(hpre[j]);
+                    dh[f + j] = sq * gelu(hpre[j]);
+                    continue;
+                }
                 int on = hpre[j] > 0.0;
                 for (int64_t q = 0; q < n_flip; ++q)
                     if (flip_t[q] == t && flip_j[q] == j) on = !on;
@@ -433,13 +471,13 @@ void swo_backward(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x, con
             }
 #pragma omp barrier
             for (int64_t k = k0; k < k1; ++k) {
-                const in_t *row = Wi + k * f;
+                const in_t *row = Wi + k * f1;
                 double xk = (double)xt[k], s = 0.0;
                 if (gWi) {
-                    double *grow = gWi + k * f;
-                    for (int64_t j = 0; j < f; ++j) grow[j] += xk * dh[j];
+                    double *grow = gWi + k * f1;
+                    for (int64_t j = 0; j < f1; ++j) grow[j] += xk * dh[j];
                 }
-                for (int64_t j = 0; j < f; ++j) s += dh[j] * (double)row[j];
+                for (int64_t j = 0; j < f1; ++j) s += dh[j] * (double)row[j];
                 dxt[k] = s;
             }
 #pragma omp barrier

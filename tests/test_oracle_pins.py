@@ -755,3 +755,113 @@ def test_noisy_subsets_match_full_run():
                          expert_sel=[2], token_sel=[5, 77])
     rows = np.flatnonzero((full["expert_index"] == 2)).tolist() + [5, 77]
     assert np.array_equal(full["y"][rows], sub["y"][rows])
+
+
+# ------------------------------------------------------------------ gated-GELU experts
+def _geglu_inputs(s, seed=0):
+    """The shape's synthetic inputs with a second, independent set of first-layer columns:
+    W_in = [W_g | W_l], [E, d, 2 f]."""
+    inp = _np_inputs(s)
+    rng = np.random.default_rng(1000 + seed)
+    W_l = (rng.standard_normal(inp["W_in"].shape) / np.sqrt(s.d_model)).astype(np.float32)
+    inp["W_in"] = np.ascontiguousarray(np.concatenate([inp["W_in"], W_l], axis=2))
+    assert inp["W_in"].dtype == np.float32
+    return inp
+
+
+def test_geglu_single_expert_is_the_textbook_layer():
+    """E = 1, nothing dropped: y = (GELU(x W_g) * (x W_l)) W_out with the exact (erf) GELU."""
+    s = SwitchShape("t", 40, 12, 20, 1, 1.0, dtype="f32", seed_index=31)
+    inp = _geglu_inputs(s)
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha, ffn="geglu")
+    x = inp["x"].astype(np.float64)
+    u = x @ inp["W_in"][0, :, :20].astype(np.float64)
+    v = x @ inp["W_in"][0, :, 20:].astype(np.float64)
+    ref = (u * scipy.special.ndtr(u) * v) @ inp["W_out"][0].astype(np.float64)
+    np.testing.assert_allclose(fwd["y"], ref, rtol=1e-12, atol=1e-15)
+    t_ref = (torch.nn.functional.gelu(torch.tensor(u)) * torch.tensor(v)).numpy() @ inp["W_out"][0].astype(np.float64)
+    np.testing.assert_allclose(fwd["y"], t_ref, rtol=1e-12, atol=1e-15)
+    # and it is not the tanh approximation
+    t_tanh = (torch.nn.functional.gelu(torch.tensor(u), approximate="tanh") * torch.tensor(v)).numpy() \
+        @ inp["W_out"][0].astype(np.float64)
+    assert np.abs(fwd["y"] - t_tanh).max() > 1e-6
+
+
+def test_geglu_limits():
+    s = SwitchShape("t", 16, 8, 6, 2, 2.0, dtype="f32", seed_index=32)
+    inp = _geglu_inputs(s)
+    # zero gate columns: GELU(0) = 0, so the layer's output vanishes
+    z = inp["W_in"].copy()
+    z[:, :, :6] = 0
+    y0 = oracle.forward(inp["x"], inp["W_r"], z, inp["W_out"], 2.0, s.alpha, ffn="geglu")["y"]
+    assert np.all(y0 == 0)
+    # far on the positive side GELU is the identity, far on the negative side zero: with
+    # constant gate pre-activations +-40 the layer is +-linear / zero
+    big = inp["W_in"].copy()
+    x = np.abs(inp["x"]) + 0.5
+    big[:, :, :6] = 40.0 / x.sum(1).min()
+    fwd = oracle.forward(x, inp["W_r"], big, inp["W_out"], 2.0, s.alpha, ffn="geglu")
+    e, g = fwd["expert_index"], fwd["gate"]
+    x64 = x.astype(np.float64)
+    for t in range(16):
+        u = x64[t] @ big[e[t], :, :6].astype(np.float64)
+        v = x64[t] @ big[e[t], :, 6:].astype(np.float64)
+        assert u.min() >= 39.9
+        np.testing.assert_allclose(fwd["y"][t], g[t] * ((u * v) @ inp["W_out"][e[t]].astype(np.float64)),
+                                   rtol=1e-12, atol=1e-14)
+    neg = big.copy()
+    neg[:, :, :6] *= -1
+    yn = oracle.forward(x, inp["W_r"], neg, inp["W_out"], 2.0, s.alpha, ffn="geglu")["y"]
+    assert np.abs(yn).max() < 1e-300
+
+
+@pytest.mark.parametrize("n_groups,noise", [(1, None), (2, (0.25, 0.1, 77))])
+def test_geglu_backward_against_torch_autograd(n_groups, noise):
+    s = SwitchShape("t", 96, 24, 20, 4, 0.75, dtype="f32", seed_index=33)
+    inp = _geglu_inputs(s)
+    d_aux, f = 0.6, s.d_ff
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 0.75, s.alpha,
+                         n_groups=n_groups, noise=noise, ffn="geglu")
+    bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd,
+                          s.alpha, d_aux)
+    assert bwd["dW_in"].shape == (s.E, s.d_model, 2 * f)
+    M, Q = (np.ones((s.T, s.d_model)), np.ones((s.T, f))) if noise is None else \
+        _noise_matrices(noise, s.T, s.d_model, f)
+    tt = {k: (None if v is None else torch.tensor(v, dtype=torch.float64,
+                                                   requires_grad=(k != "dy")))
+          for k, v in inp.items()}
+    x, E, Tg = tt["x"], s.E, s.T // n_groups
+    h = (x * torch.tensor(M)) @ tt["W_r"]
+    p = torch.softmax(h, dim=1)
+    e = torch.argmax(h, dim=1)
+    onehot = torch.nn.functional.one_hot(e, E).to(torch.float64)
+    oh_g = onehot.view(n_groups, Tg, E)
+    pos = ((torch.cumsum(oh_g, 1) - 1) * oh_g).sum(2).reshape(-1)
+    kept = (pos < fwd["capacity"]).to(torch.float64)
+    gate = (p * onehot).sum(1)
+    pre = torch.einsum("td,tdf->tf", x, tt["W_in"][e])
+    hid = torch.nn.functional.gelu(pre[:, :f]) * pre[:, f:] * torch.tensor(Q)
+    y = (kept * gate)[:, None] * torch.einsum("tf,tfd->td", hid, tt["W_out"][e])
+    aux = s.alpha * E * (oh_g.mean(1).detach() * p.view(n_groups, Tg, E).mean(1)).sum(1).mean()
+    ((y * tt["dy"]).sum() + d_aux * aux).backward()
+    assert np.array_equal(fwd["expert_index"], e.numpy()) and fwd["dropped"].sum() > 0
+    np.testing.assert_allclose(fwd["y"], y.detach().numpy(), rtol=1e-12, atol=1e-14)
+    for name in ("x", "W_r", "W_in", "W_out"):
+        g = tt[name].grad.numpy()
+        np.testing.assert_allclose(bwd["d" + name], g, rtol=1e-10,
+                                   atol=1e-12 * max(1.0, np.abs(g).max()), err_msg=name)
+
+
+def test_geglu_subsets_match_full_run():
+    s = SwitchShape("t", 128, 16, 12, 8, 1.0, dtype="f32", seed_index=34)
+    inp = _geglu_inputs(s)
+    full = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha, ffn="geglu")
+    fb = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], full, s.alpha)
+    sub = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha, ffn="geglu",
+                         expert_sel=[3], token_sel=[5])
+    sb = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], sub, s.alpha,
+                         expert_sel=[3], token_sel=[5])
+    rows = np.flatnonzero(full["expert_index"] == 3).tolist() + [5]
+    assert np.array_equal(full["y"][rows], sub["y"][rows])
+    assert np.array_equal(fb["dW_in"][3], sb["dW_in"][0])
+    assert np.array_equal(fb["dW_out"][3], sb["dW_out"][0])
