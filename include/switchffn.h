@@ -43,6 +43,13 @@ extern "C" {
 
 typedef enum { SW_F32 = 0, SW_BF16 = 1 } sw_dtype;
 
+/* Expert FFN variants.  SW_FFN_RELU: ReLU(x W_in) W_out, W_in [E, d_model, d_ff] (Sec. 5's
+ * review of the FFN layer).  SW_FFN_GEGLU: the FFN_GEGLU of the model tables (App. "Switch
+ * models"): the expansion matrix is replaced by two, combined as GELU(x W_g) * (x W_l) with
+ * the exact GELU(u) = u Phi(u); W_in is then [E, d_model, 2 d_ff] with the d_ff gate columns
+ * W_g first and the d_ff linear columns W_l after them, and dW_in has the same shape. */
+typedef enum { SW_FFN_RELU = 0, SW_FFN_GEGLU = 1 } sw_ffn_kind;
+
 typedef enum {
     SW_OK = 0,
     SW_ERR_NULL = -1,      /* a required pointer is NULL                         */
@@ -51,7 +58,8 @@ typedef enum {
                               slots x max(d_model, d_ff) activations reach 2 GB       */
     SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite,
                               expert_dropout or jitter_eps outside [0, 1)          */
-    SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16            */
+    SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16, or ffn_kind
+                              is not a sw_ffn_kind                               */
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
     SW_ERR_ALIGN = -6,     /* a tensor pointer is not 16-byte aligned            */
     SW_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch (see hipGetLastError) */
@@ -67,7 +75,7 @@ typedef struct {
     double capacity_factor;  /* > 0; Eq. 3                                          */
     float alpha;             /* auxiliary-loss coefficient (Sec. 2.2; paper: 1e-2)  */
     int32_t act_dtype;       /* sw_dtype of activations and expert weights          */
-    int32_t reserved;        /* set to 0                                            */
+    int32_t ffn_kind;        /* sw_ffn_kind; 0 = the ReLU FFN                       */
     int64_t n_groups;        /* routing groups of T / n_groups consecutive tokens:
                                 capacity (Eq. 3 with the group's token count),
                                 position_in_expert and the two fractions of the loss
@@ -120,6 +128,7 @@ int switch_workspace_size(const switch_config *cfg, size_t *bytes_out /* host */
  *            (the residual connection is the caller's)
  *   with noise: h is computed from x * m (Eq. 1 on the jittered input), and
  *            ReLU(.) above is followed by the dropout factor (0 or 1 / (1 - rate))
+ *   SW_FFN_GEGLU: ReLU(x W_in[e]) is replaced by GELU(x W_g[e]) * (x W_l[e])
  *   aux_loss = alpha * E * sum_i f_i P_i, f_i = expert_counts[i] / T over ALL
  *            tokens (before truncation), P_i = mean_t p[t,i]            (Eqs. 4-6)
  * The workspace keeps what switch_backward needs; it must stay untouched
@@ -129,7 +138,7 @@ int switch_forward(const switch_config *cfg,
                    const void *x,               /* [T, d_model]        act_dtype            */
                    const float *W_r,            /* [d_model, E]        fp32                 */
                    const float *b_r,            /* [E] fp32 or NULL (the paper has no router bias) */
-                   const void *W_in,            /* [E, d_model, d_ff]  act_dtype            */
+                   const void *W_in,            /* [E, d_model, d_ff]  act_dtype ([.., 2 d_ff] for SW_FFN_GEGLU) */
                    const void *W_out,           /* [E, d_ff, d_model]  act_dtype            */
                    void *y,                     /* [T, d_model]        act_dtype  (out)     */
                    int32_t *expert_index,       /* [T]   (out)                              */
@@ -157,7 +166,7 @@ int switch_backward(const switch_config *cfg,
                     void *dx,            /* [T, d_model]       act_dtype (out)           */
                     float *dW_r,         /* [d_model, E]       fp32      (out)           */
                     float *db_r,         /* [E] fp32 (out) or NULL                       */
-                    void *dW_in,         /* [E, d_model, d_ff] act_dtype (out)           */
+                    void *dW_in,         /* [E, d_model, d_ff] act_dtype (out); same shape as W_in */
                     void *dW_out,        /* [E, d_ff, d_model] act_dtype (out)           */
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 

@@ -8,6 +8,8 @@ library is missing or cannot be loaded, importing the binding raises.
 from .binding import (  # noqa: F401
     SW_BF16,
     SW_F32,
+    SW_FFN_GEGLU,
+    SW_FFN_RELU,
     SwitchConfig,
     SwitchError,
     library_path,

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libswitchffn.so")
 
 SW_F32, SW_BF16 = 0, 1
+SW_FFN_RELU, SW_FFN_GEGLU = 0, 1
 
 
 class SwitchError(RuntimeError):
@@ -27,7 +28,7 @@ class SwitchConfig(ctypes.Structure):
         ("capacity_factor", ctypes.c_double),
         ("alpha", ctypes.c_float),
         ("act_dtype", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("ffn_kind", ctypes.c_int32),
         ("n_groups", ctypes.c_int64),
         ("expert_dropout", ctypes.c_float),
         ("jitter_eps", ctypes.c_float),

@@ -13,6 +13,7 @@ namespace sw {
 int check_config(const switch_config *cfg) {
     if (!cfg) return SW_ERR_NULL;
     if (cfg->act_dtype != SW_F32 && cfg->act_dtype != SW_BF16) return SW_ERR_DTYPE;
+    if (cfg->ffn_kind != SW_FFN_RELU && cfg->ffn_kind != SW_FFN_GEGLU) return SW_ERR_DTYPE;
     if (cfg->T < 0 || cfg->T >= (int64_t)1 << 31) return SW_ERR_SHAPE;
     if (cfg->n_groups < 0 || cfg->n_groups > 65536) return SW_ERR_SHAPE;
     if (cfg->n_groups > 1 && (cfg->T % cfg->n_groups) != 0) return SW_ERR_SHAPE;
@@ -31,8 +32,9 @@ int check_config(const switch_config *cfg) {
     if (c * n * (double)cfg->E >= 2147483647.0) return SW_ERR_SHAPE;
     if (cfg->act_dtype == SW_BF16) {
         // the bf16 GEMMs address one expert's matrices through 32-bit buffer descriptors
-        const double wide = (double)(cfg->d_model > cfg->d_ff ? cfg->d_model : cfg->d_ff);
-        if ((double)cfg->d_model * (double)cfg->d_ff * 2.0 >= 2147483647.0) return SW_ERR_SHAPE;
+        const double f1 = (double)cfg->d_ff * (cfg->ffn_kind == SW_FFN_GEGLU ? 2.0 : 1.0);
+        const double wide = (double)cfg->d_model > f1 ? (double)cfg->d_model : f1;
+        if ((double)cfg->d_model * f1 * 2.0 >= 2147483647.0) return SW_ERR_SHAPE;
         if (c * n * wide * 2.0 >= 2147483647.0) return SW_ERR_SHAPE;
     }
     return SW_OK;
@@ -46,6 +48,8 @@ int64_t capacity_of(const switch_config *cfg) {
 Workspace layout_workspace(const switch_config *cfg) {
     Workspace w{};
     w.T = cfg->T; w.d = cfg->d_model; w.f = cfg->d_ff; w.E = cfg->E;
+    w.geglu = cfg->ffn_kind == SW_FFN_GEGLU;
+    w.f1 = w.geglu ? 2 * w.f : w.f;
     w.n = cfg->n_groups > 1 ? cfg->n_groups : 1;
     w.Tg = w.T / w.n;
     w.Cg = capacity_of(cfg);
@@ -56,7 +60,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.nsplit = w.nb < 64 ? w.nb : 64;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    const size_t T = w.T, E = w.E, C = w.C, d = w.d, f = w.f, nb = w.nb;
+    const size_t T = w.T, E = w.E, C = w.C, d = w.d, f = w.f, f1 = w.f1, nb = w.nb;
     w.probs = take(T * E * 4);
     w.idx = take(T * 4);
     w.gate = take(T * 4);
@@ -73,10 +77,12 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.slot_token = take(E * C * 4);
     w.tok_slot = take(T * 4);
     w.Xd = take(E * C * d * w.elt);
+    w.H = take(w.geglu ? E * C * f1 * w.elt : 0);
     w.A = take(E * C * f * w.elt);
     w.O = take(E * C * d * w.elt);
     w.dO = take(E * C * d * w.elt);
-    w.dH = take(E * C * f * w.elt);
+    w.dA = take(w.geglu ? E * C * f * w.elt : 0);
+    w.dH = take(E * C * f1 * w.elt);
     w.dXd = take(E * C * d * w.elt);
     w.dgate = take(T * 4);
     w.dlogits = take(T * E * 4);
@@ -233,6 +239,7 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
                                         aux_loss, s))))
         return st;
     if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
+    if (w.geglu && (st = status_of(launch_geglu_fwd(w, dt, ws, s)))) return st;
     if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
     if ((st = status_of(launch_combine(w, dt, ws, y, s)))) return st;
     return SW_OK;
@@ -252,9 +259,10 @@ int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const
         hipStream_t s0 = (hipStream_t)hip_stream;
         const size_t elt = cfg->act_dtype == SW_BF16 ? 2 : 4;
         const size_t wbytes = (size_t)cfg->E * cfg->d_model * cfg->d_ff * elt;
+        const size_t in_mult = cfg->ffn_kind == SW_FFN_GEGLU ? 2 : 1;
         if ((st = fill_zero(dW_r, (size_t)cfg->d_model * cfg->E * 4, s0))) return st;
         if (db_r && (st = fill_zero(db_r, (size_t)cfg->E * 4, s0))) return st;
-        if ((st = fill_zero(dW_in, wbytes, s0))) return st;
+        if ((st = fill_zero(dW_in, wbytes * in_mult, s0))) return st;
         return fill_zero(dW_out, wbytes, s0);
     }
     if (!dy || !x || !W_r || !W_in || !W_out || !dx || !dW_r || !dW_in || !dW_out)
@@ -273,6 +281,7 @@ int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const
 
     if ((st = status_of(launch_combine_bwd(w, dt, dy, ws, s)))) return st;
     if ((st = status_of(gemm(GEMM_DGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if (w.geglu && (st = status_of(launch_geglu_bwd(w, dt, ws, s)))) return st;
     // dH is consumed right after it is produced (the first-layer data gradient walks the
     // experts backwards, see launch_gemm_bf16), then the two weight gradients
     if ((st = status_of(gemm(GEMM_DGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
@@ -291,7 +300,7 @@ const char *switch_status_string(int status) {
     case SW_ERR_VALUE:
         return "capacity_factor must be finite and > 0; alpha, d_aux finite; expert_dropout and "
                "jitter_eps in [0, 1)";
-    case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16";
+    case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16, ffn_kind SW_FFN_RELU or SW_FFN_GEGLU";
     case SW_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
     case SW_ERR_LAUNCH: return "HIP launch failed";

@@ -78,6 +78,8 @@ __device__ __forceinline__ bool dropout_keeps(const Noise &nz, uint32_t idx) {
 // ---- workspace layout (byte offsets into the caller's workspace) ------------
 struct Workspace {
     int64_t T, d, f, E;
+    int64_t f1;                 // columns of W_in: f (ReLU FFN) or 2 f (gated-GELU FFN: gate | linear)
+    int geglu;                  // gated-GELU FFN
     int64_t n;                  // routing groups
     int64_t Tg;                 // tokens per group (T / n)
     int64_t Cg;                 // capacity: slots per expert and group (Eq. 3 on Tg tokens)
@@ -102,10 +104,12 @@ struct Workspace {
     size_t tok_slot;            // i32 [T]      slot (e * C + grp_off[g][e] + pos) of each kept token,
                                 //              -1 for dropped ones
     size_t Xd;                  // act [E][C][d]   dispatched tokens
-    size_t A;                   // act [E][C][f]   ReLU(Xd W_in)
+    size_t H;                   // act [E][C][2f]  Xd W_in = [u | v] (gated-GELU FFN only)
+    size_t A;                   // act [E][C][f]   ReLU(Xd W_in), or GELU(u) v; after expert dropout
     size_t O;                   // act [E][C][d]   A W_out
     size_t dO;                  // act [E][C][d]
-    size_t dH;                  // act [E][C][f]
+    size_t dA;                  // act [E][C][f]   dO W_out^T (gated-GELU FFN only)
+    size_t dH;                  // act [E][C][f1]  gradient of Xd W_in
     size_t dXd;                 // act [E][C][d]
     size_t dgate;               // f32 [T]
     size_t dlogits;             // f32 [T][E]
@@ -157,6 +161,9 @@ int route_scan_blocks(const Workspace &w);
 hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
                            hipStream_t s);
+// Gated-GELU FFN: A = GELU(u) v (and expert dropout) from H = [u | v]; dH = [du | dv] from dA, H.
+hipError_t launch_geglu_fwd(const Workspace &w, int dtype, char *ws, hipStream_t s);
+hipError_t launch_geglu_bwd(const Workspace &w, int dtype, char *ws, hipStream_t s);
 hipError_t launch_combine(const Workspace &w, int dtype, char *ws, void *y, hipStream_t s);
 hipError_t launch_combine_bwd(const Workspace &w, int dtype, const void *dy, char *ws,
                               hipStream_t s);
@@ -170,13 +177,16 @@ hipError_t launch_router_dWr_mfma(const Workspace &w, const void *x, char *ws, h
 // Grouped GEMMs over experts.  Each computes, for every expert e,
 //   C_e[q][p] = sum_k Q_e(q,k) * P_e(p,k)
 // where C_e is row-major with p contiguous.
+// (f1 = columns of W_in.  With the gated-GELU FFN the first GEMM stores the plain product
+// H = Xd W_in and the second-layer data gradient the plain dA = dO W_out^T; the activation
+// and its derivative are applied by the kernels of geglu.hip.)
 enum GemmKind {
-    GEMM_FWD1,   // A  = relu(Xd W_in)            q: slot  p: d_ff     k: d_model
+    GEMM_FWD1,   // A  = relu(Xd W_in) | H = Xd W_in  q: slot  p: f1       k: d_model
     GEMM_FWD2,   // O  = A W_out                  q: slot  p: d_model  k: d_ff
-    GEMM_DGRAD2, // dH = (dO W_out^T) * [A > 0]   q: slot  p: d_ff     k: d_model
-    GEMM_DGRAD1, // dXd = dH W_in^T               q: slot  p: d_model  k: d_ff
+    GEMM_DGRAD2, // dH = (dO W_out^T) * [A > 0] | dA = dO W_out^T   q: slot  p: d_ff  k: d_model
+    GEMM_DGRAD1, // dXd = dH W_in^T               q: slot  p: d_model  k: f1
     GEMM_WGRAD2, // dW_out = A^T dO               q: d_ff  p: d_model  k: slot (< kept)
-    GEMM_WGRAD1  // dW_in = Xd^T dH               q: d_model p: d_ff   k: slot (< kept)
+    GEMM_WGRAD1  // dW_in = Xd^T dH               q: d_model p: f1     k: slot (< kept)
 };
 hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
                             const void *W_out, void *dW_in, void *dW_out, hipStream_t s);

@@ -1,0 +1,107 @@
+// Gated-GELU expert FFN (the FFN_GEGLU variant of the paper's model tables): the
+// element-wise half of the first layer.  The first GEMM leaves H = Xd W_in = [u | v]
+// (gate pre-activations, linear part; f columns each), these kernels turn it into
+//   forward   A  = GELU(u) v q                       GELU(u) = u Phi(u), exact
+//   backward  du = dA q v GELU'(u),  dv = dA q GELU(u),  dH = [du | dv]
+// with q the expert-dropout factor of the hidden unit (1 without dropout; Sec. 2.4).
+// Both are streaming kernels: one lane handles 16 bytes of consecutive hidden units of
+// one slot row (eight bf16 or four fp32), rows past an expert's kept tokens are skipped.
+// Arithmetic is fp32, one rounding at the store.
+#include "common.h"
+
+namespace sw {
+
+// Phi(u) = erfc(-u / sqrt 2) / 2: erfc keeps its relative accuracy in the lower tail, where
+// 1 + erf(.) would cancel.
+__device__ __forceinline__ float norm_cdf(float u) { return 0.5f * erfcf(-u * 0.70710678f); }
+__device__ __forceinline__ float gelu_of(float u) { return u * norm_cdf(u); }
+__device__ __forceinline__ float gelu_deriv(float u) {
+    return norm_cdf(u) + u * 0.3989422804f * __expf(-0.5f * u * u);
+}
+
+// 16 bytes of hidden units
+template <typename XT> struct Chunk;
+template <> struct Chunk<bf16> {
+    typedef bf16 type __attribute__((ext_vector_type(8)));
+    static constexpr int n = 8;
+};
+template <> struct Chunk<float> {
+    typedef float type __attribute__((ext_vector_type(4)));
+    static constexpr int n = 4;
+};
+
+template <typename XT, bool BACKWARD>
+__global__ __launch_bounds__(256) void geglu_kernel(const XT *__restrict__ H,
+                                                    const XT *__restrict__ dA,
+                                                    XT *__restrict__ out,   // A (forward) or dH
+                                                    const int32_t *__restrict__ kept,
+                                                    const int32_t *__restrict__ slot_token,
+                                                    int slots, int f, Noise nz) {
+    typedef typename Chunk<XT>::type V;
+    constexpr int kGegluChunk = Chunk<XT>::n;
+    const int e = blockIdx.y;
+    const int chunks_per_row = f / kGegluChunk;
+    const long chunk = (long)blockIdx.x * 256 + threadIdx.x;
+    const int row = (int)(chunk / chunks_per_row);
+    if (row >= kept[e]) return;
+    const int j0 = (int)(chunk - (long)row * chunks_per_row) * kGegluChunk;
+    const size_t slot = (size_t)e * slots + row;
+    const XT *h = H + slot * 2 * f;
+    const V u = *(const V *)(h + j0);
+    const V v = *(const V *)(h + f + j0);
+    float q[kGegluChunk];
+#pragma unroll
+    for (int i = 0; i < kGegluChunk; ++i) q[i] = 1.f;
+    if (nz.dropout) {
+        const uint32_t idx = (uint32_t)slot_token[slot] * (uint32_t)f + (uint32_t)j0;
+#pragma unroll
+        for (int i = 0; i < kGegluChunk; ++i)
+            q[i] = dropout_keeps(nz, idx + (uint32_t)i) ? nz.drop_scale : 0.f;
+    }
+    if (!BACKWARD) {
+        V a;
+#pragma unroll
+        for (int i = 0; i < kGegluChunk; ++i)
+            a[i] = from_f32<XT>(gelu_of(to_f32(u[i])) * to_f32(v[i]) * q[i]);
+        *(V *)(out + slot * f + j0) = a;
+    } else {
+        const V da = *(const V *)(dA + slot * f + j0);
+        V du, dv;
+#pragma unroll
+        for (int i = 0; i < kGegluChunk; ++i) {
+            const float s = to_f32(da[i]) * q[i];
+            const float ui = to_f32(u[i]);
+            du[i] = from_f32<XT>(s * to_f32(v[i]) * gelu_deriv(ui));
+            dv[i] = from_f32<XT>(s * gelu_of(ui));
+        }
+        XT *o = out + slot * 2 * f;
+        *(V *)(o + j0) = du;
+        *(V *)(o + f + j0) = dv;
+    }
+}
+
+template <typename XT, bool BACKWARD>
+static hipError_t geglu_launch(const Workspace &w, char *ws, hipStream_t s) {
+    if (w.C == 0) return hipSuccess;
+    const long chunks = (long)w.C * (w.f / Chunk<XT>::n);
+    dim3 grid((unsigned)ceil_div(chunks, 256), (unsigned)w.E);
+    hipLaunchKernelGGL((geglu_kernel<XT, BACKWARD>), grid, dim3(256), 0, s,
+                       (const XT *)(ws + w.H), (const XT *)(ws + w.dA),
+                       (XT *)(ws + (BACKWARD ? w.dH : w.A)), (const int32_t *)(ws + w.kept),
+                       (const int32_t *)(ws + w.slot_token), (int)w.C, (int)w.f, w.noise);
+    return hipGetLastError();
+}
+
+hipError_t launch_geglu_fwd(const Workspace &w, int dtype, char *ws, hipStream_t s) {
+    ProfScope ps("geglu_fwd", s);
+    return dtype == SW_BF16 ? geglu_launch<bf16, false>(w, ws, s)
+                            : geglu_launch<float, false>(w, ws, s);
+}
+
+hipError_t launch_geglu_bwd(const Workspace &w, int dtype, char *ws, hipStream_t s) {
+    ProfScope ps("geglu_bwd", s);
+    return dtype == SW_BF16 ? geglu_launch<bf16, true>(w, ws, s)
+                            : geglu_launch<float, true>(w, ws, s);
+}
+
+}  // namespace sw

@@ -527,7 +527,7 @@ static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
 
 hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
                             const void *W_out, void *dW_in, void *dW_out, hipStream_t s) {
-    const int d = (int)w.d, f = (int)w.f, C = (int)w.C, E = (int)w.E;
+    const int d = (int)w.d, f = (int)w.f, f1 = (int)w.f1, C = (int)w.C, E = (int)w.E;
     GemmArgs a{};
     a.kept = (const int32_t *)(ws + w.kept);
     const bf16 *Xd = (const bf16 *)(ws + w.Xd);
@@ -549,11 +549,15 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     switch (kind) {
     case GEMM_FWD1: {
         a.Q = Xd; a.q_batch = (size_t)C * d; a.ldq = d;
-        a.P = (const bf16 *)W_in; a.p_batch = (size_t)d * f; a.ldp = f;
-        a.Cout = A; a.c_batch = (size_t)C * f; a.ldc = f;
+        a.P = (const bf16 *)W_in; a.p_batch = (size_t)d * f1; a.ldp = f1;
+        a.Cout = w.geglu ? (bf16 *)(ws + w.H) : A; a.c_batch = (size_t)C * f1; a.ldc = f1;
         a.relu_bits = (uint8_t *)(ws + w.relu_bits);
-        finish(C, f, d);
+        finish(C, f1, d);
         if (a.total_tiles == 0) return hipSuccess;
+        if (w.geglu) {   // the plain product; activation and dropout follow in geglu_fwd
+            ProfScope ps("gemm1_fwd", s);
+            return gemm_launch<false, true, EPI_NONE, true, false>(a, s);
+        }
         ProfScope ps("gemm1_fwd_relu", s);
         if (w.noise.dropout) {
             a.slot_token = (const int32_t *)(ws + w.slot_token);
@@ -575,10 +579,14 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     case GEMM_DGRAD2: {
         a.Q = dO; a.q_batch = (size_t)C * d; a.ldq = d;
         a.P = (const bf16 *)W_out; a.p_batch = (size_t)f * d; a.ldp = d;   // [p = f][k = d]
-        a.Cout = dH; a.c_batch = (size_t)C * f; a.ldc = f;
+        a.Cout = w.geglu ? (bf16 *)(ws + w.dA) : dH; a.c_batch = (size_t)C * f; a.ldc = f;
         a.relu_bits = (uint8_t *)(ws + w.relu_bits);
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
+        if (w.geglu) {
+            ProfScope ps("gemm2_dgrad", s);
+            return gemm_launch<false, false, EPI_NONE, true, false>(a, s);
+        }
         ProfScope ps("gemm2_dgrad_relumask", s);
         if (w.noise.dropout) {
             a.nz = w.noise;
@@ -587,10 +595,10 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         return gemm_launch<false, false, EPI_MASK, true, false>(a, s);
     }
     case GEMM_DGRAD1: {
-        a.Q = dH; a.q_batch = (size_t)C * f; a.ldq = f;
-        a.P = (const bf16 *)W_in; a.p_batch = (size_t)d * f; a.ldp = f;    // [p = d][k = f]
+        a.Q = dH; a.q_batch = (size_t)C * f1; a.ldq = f1;
+        a.P = (const bf16 *)W_in; a.p_batch = (size_t)d * f1; a.ldp = f1;    // [p = d][k = f1]
         a.Cout = dXd; a.c_batch = (size_t)C * d; a.ldc = d;
-        finish(C, d, f);
+        finish(C, d, f1);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm1_dgrad", s);
         return gemm_launch<false, false, EPI_NONE, true, false>(a, s);
@@ -605,9 +613,9 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     }
     case GEMM_WGRAD1: {
         a.Q = Xd; a.q_batch = (size_t)C * d; a.ldq = d;     // [k = slot][q = d]
-        a.P = dH; a.p_batch = (size_t)C * f; a.ldp = f;     // [k = slot][p = f]
-        a.Cout = (bf16 *)dW_in; a.c_batch = (size_t)d * f; a.ldc = f;
-        finish(d, f, C);
+        a.P = dH; a.p_batch = (size_t)C * f1; a.ldp = f1;     // [k = slot][p = f1]
+        a.Cout = (bf16 *)dW_in; a.c_batch = (size_t)d * f1; a.ldc = f1;
+        finish(d, f1, C);
         ProfScope ps("gemm1_wgrad", s);
         return gemm_launch<true, true, EPI_NONE, false, true>(a, s);
     }

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args a) {
 
 hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
                            const void *W_out, void *dW_in, void *dW_out, hipStream_t s) {
-    const long d = w.d, f = w.f, C = w.C;
+    const long d = w.d, f = w.f, f1 = w.f1, C = w.C;
     GemmF32Args a{};
     a.kept = (const int32_t *)(ws + w.kept);
     a.slot_token = (const int32_t *)(ws + w.slot_token);
@@ -118,11 +118,11 @@ hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const vo
     const char *name = "";
     switch (kind) {
     case GEMM_FWD1:
-        name = "gemm1_fwd_relu";
+        name = w.geglu ? "gemm1_fwd" : "gemm1_fwd_relu";
         a.Q = Xd; a.q_batch = C * d; a.q_rs = d; a.q_ks = 1;
-        a.P = (const float *)W_in; a.p_batch = d * f; a.p_rs = 1; a.p_ks = f;
-        a.Cout = A; a.c_batch = C * f; a.ldc = f;
-        a.Qdim = C; a.Pdim = f; a.Kdim = d; a.q_limited = 1; a.epi = 1;
+        a.P = (const float *)W_in; a.p_batch = d * f1; a.p_rs = 1; a.p_ks = f1;
+        a.Cout = w.geglu ? (float *)(ws + w.H) : A; a.c_batch = C * f1; a.ldc = f1;
+        a.Qdim = C; a.Pdim = f1; a.Kdim = d; a.q_limited = 1; a.epi = w.geglu ? 0 : 1;
         break;
     case GEMM_FWD2:
         name = "gemm2_fwd";
@@ -132,18 +132,18 @@ hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const vo
         a.Qdim = C; a.Pdim = d; a.Kdim = f; a.q_limited = 1;
         break;
     case GEMM_DGRAD2:
-        name = "gemm2_dgrad_relumask";
+        name = w.geglu ? "gemm2_dgrad" : "gemm2_dgrad_relumask";
         a.Q = dO; a.q_batch = C * d; a.q_rs = d; a.q_ks = 1;
         a.P = (const float *)W_out; a.p_batch = f * d; a.p_rs = d; a.p_ks = 1;
-        a.Cout = dH; a.c_batch = C * f; a.ldc = f; a.mask = A;
-        a.Qdim = C; a.Pdim = f; a.Kdim = d; a.q_limited = 1; a.epi = 2;
+        a.Cout = w.geglu ? (float *)(ws + w.dA) : dH; a.c_batch = C * f; a.ldc = f; a.mask = A;
+        a.Qdim = C; a.Pdim = f; a.Kdim = d; a.q_limited = 1; a.epi = w.geglu ? 0 : 2;
         break;
     case GEMM_DGRAD1:
         name = "gemm1_dgrad";
-        a.Q = dH; a.q_batch = C * f; a.q_rs = f; a.q_ks = 1;
-        a.P = (const float *)W_in; a.p_batch = d * f; a.p_rs = f; a.p_ks = 1;
+        a.Q = dH; a.q_batch = C * f1; a.q_rs = f1; a.q_ks = 1;
+        a.P = (const float *)W_in; a.p_batch = d * f1; a.p_rs = f1; a.p_ks = 1;
         a.Cout = dXd; a.c_batch = C * d; a.ldc = d;
-        a.Qdim = C; a.Pdim = d; a.Kdim = f; a.q_limited = 1;
+        a.Qdim = C; a.Pdim = d; a.Kdim = f1; a.q_limited = 1;
         break;
     case GEMM_WGRAD2:
         name = "gemm2_wgrad";
@@ -155,9 +155,9 @@ hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const vo
     case GEMM_WGRAD1:
         name = "gemm1_wgrad";
         a.Q = Xd; a.q_batch = C * d; a.q_rs = 1; a.q_ks = d;
-        a.P = dH; a.p_batch = C * f; a.p_rs = 1; a.p_ks = f;
-        a.Cout = (float *)dW_in; a.c_batch = d * f; a.ldc = f;
-        a.Qdim = d; a.Pdim = f; a.Kdim = C; a.k_limited = 1;
+        a.P = dH; a.p_batch = C * f1; a.p_rs = 1; a.p_ks = f1;
+        a.Cout = (float *)dW_in; a.c_batch = d * f1; a.ldc = f1;
+        a.Qdim = d; a.Pdim = f1; a.Kdim = C; a.k_limited = 1;
         break;
     }
     if (a.Qdim == 0) return hipSuccess;   // capacity 0 and a slot-indexed output: nothing to do

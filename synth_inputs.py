@@ -49,6 +49,7 @@ class SwitchShape:
     expert_dropout: float = 0.0  # training-time noise: dropout rate of the experts' hidden units,
     jitter_eps: float = 0.0      # half-width of the multiplicative jitter on the router's input,
     noise_seed: int = 0          # seed of both
+    ffn: str = "relu"            # expert FFN: "relu", or "geglu" (W_in = [W_g | W_l], [E, d, 2 d_ff])
 
     def with_(self, **kw) -> "SwitchShape":
         return replace(self, **kw)
@@ -64,6 +65,9 @@ CONFIGS: Dict[str, SwitchShape] = {
         SwitchShape("large", 65536, 1024, 2816, 128, 1.25, seed_index=4),
         SwitchShape("xxl", 16384, 4096, 10240, 64, 1.25, seed_index=5),
         SwitchShape("c_share", 32768, 2080, 6144, 64, 1.0, seed_index=6),
+        # the model table's own Switch-Base layer: d_ff 2048 with the gated-GELU FFN
+        # (three 768 x 2048 matrices per expert, FLOP-matched to base_cf1.0's two 768 x 3072)
+        SwitchShape("base_geglu", 65536, 768, 2048, 128, 1.0, seed_index=7, ffn="geglu"),
     ]
 }
 
@@ -108,7 +112,8 @@ def make_inputs(shape: SwitchShape, device: str = "cpu",
     T, d, f, E = shape.T, shape.d_model, shape.d_ff, shape.E
     x = _normal(gen, (T, d), 1.0, dev).to(dt)
     W_r = _normal(gen, (d, E), 0.02, dev)
-    W_in = _trunc_normal(gen, (E, d, f), 1.0 / math.sqrt(d), dev).to(dt)
+    f_in = 2 * f if shape.ffn == "geglu" else f
+    W_in = _trunc_normal(gen, (E, d, f_in), 1.0 / math.sqrt(d), dev).to(dt)
     W_out = _trunc_normal(gen, (E, f, d), 1.0 / math.sqrt(f), dev).to(dt)
     dy = _normal(gen, (T, d), 1.0, dev).to(dt)
     b_r = zipf_router_bias(E).to(dev) if shape.zipf_bias else None

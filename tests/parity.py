@@ -141,7 +141,7 @@ def run_gpu(shape, inp, d_aux=1.0, backward=True, dy=None):
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
                         shape.alpha, shape.dtype, device=str(inp["x"].device), want_logits=True,
                         n_groups=shape.n_groups, expert_dropout=shape.expert_dropout,
-                        jitter_eps=shape.jitter_eps, seed=shape.noise_seed)
+                        jitter_eps=shape.jitter_eps, seed=shape.noise_seed, ffn=shape.ffn)
     out = layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"])
     res = {k: to_np(v) for k, v in out.items() if v is not None}
     if backward:
@@ -159,7 +159,7 @@ def check_routing(shape, npi, gpu):
     # (i) routing stage on identical logits: bit exact
     same = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"], shape.capacity_factor,
                           shape.alpha, b_r=npi["b_r"], logits_override=gpu["router_logits"],
-                          skip_ffn=True, n_groups=shape.n_groups, noise=noise_of(shape))
+                          skip_ffn=True, n_groups=shape.n_groups, noise=noise_of(shape), ffn=shape.ffn)
     assert np.array_equal(gpu["expert_index"], same["expert_index"]), "expert_index"
     assert np.array_equal(gpu["position_in_expert"], same["position_in_expert"]), "position"
     assert np.array_equal(gpu["dropped"], same["dropped"]), "dropped"
@@ -179,7 +179,7 @@ def check_routing(shape, npi, gpu):
     pinned = oracle.forward(npi["x"], npi["W_r"], npi["W_in"], npi["W_out"],
                             shape.capacity_factor, shape.alpha, b_r=npi["b_r"],
                             logits_override=h64, expert_index_override=gpu["expert_index"],
-                            skip_ffn=True, n_groups=shape.n_groups, noise=noise_of(shape))
+                            skip_ffn=True, n_groups=shape.n_groups, noise=noise_of(shape), ffn=shape.ffn)
     assert np.array_equal(gpu["dropped"], pinned["dropped"])
     np.testing.assert_allclose(gpu["gate"], pinned["gate"], rtol=3e-5, atol=0)
     assert abs(float(gpu["aux_loss"][0]) - pinned["aux_loss"]) <= 1e-5 * abs(pinned["aux_loss"])
@@ -195,7 +195,9 @@ def check_dropped_rows_are_zero(gpu, dtype):
 def resolve_relu_ties(shape, npi, fwd, gpu_dx, d_aux, expert_sel=None, token_sel=None):
     """(token, unit) pairs, among the evaluated tokens' pre-activations that are zero to fp32
     rounding, whose ReLU gate the GPU took the other way: decided per token by which choice
-    reproduces the GPU's dx row.  Almost always empty."""
+    reproduces the GPU's dx row.  Almost always empty.  (The gated-GELU FFN is smooth: none.)"""
+    if shape.ffn != "relu":
+        return []
     near = oracle.hidden_near_zero(npi["x"], npi["W_in"], fwd["expert_index"], fwd["dropped"],
                                    RELU_TIE, expert_sel=expert_sel, token_sel=token_sel)
     by_token = {}
@@ -225,7 +227,7 @@ def compare_full(shape, inp, d_aux=1.0, widen=None):
     _, gpu = run_gpu(shape, inp, d_aux)
     fwd, flips = check_routing(shape, npi, gpu)
     fwd["y"] = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
-                                 fwd["dropped"], fwd["gate"], noise=noise_of(shape))
+                                 fwd["dropped"], fwd["gate"], noise=noise_of(shape), ffn=shape.ffn)
     errs = {"flips": flips}
     errs["y"] = assert_close("y", gpu["y"], fwd["y"], tol)
     check_dropped_rows_are_zero(gpu, shape.dtype)
@@ -266,7 +268,7 @@ def compare_sampled(shape, inp, n_experts=3, n_tokens=32, d_aux=1.0, seed=0):
 
     y_ref = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
                               fwd["dropped"], fwd["gate"], expert_sel=sel, token_sel=toks,
-                              noise=noise_of(shape))
+                              noise=noise_of(shape), ffn=shape.ffn)
     errs = {"flips": flips, "experts": sel, "tokens_checked": int(tmask.sum())}
     errs["y"] = assert_close("y[sampled]", gpu["y"][tmask], y_ref[tmask], tol)
     check_dropped_rows_are_zero(gpu, shape.dtype)

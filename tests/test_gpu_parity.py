@@ -357,6 +357,66 @@ def test_training_noise_full_size_sampled():
     _report("base_cf1.25 + noise", errs)
 
 
+# ------------------------------------------- gated-GELU experts (model tables, FFN_GEGLU)
+@pytest.mark.parametrize("dtype,T,d,f,E,cf,n,rate,eps", [
+    ("f32", 700, 96, 100, 6, 1.0, 1, 0.0, 0.0),
+    ("f32", 1024, 64, 36, 8, 0.75, 4, 0.25, 0.05),
+    ("bf16", 1500, 256, 520, 6, 1.25, 1, 0.0, 0.0),     # ragged tiles in every GEMM
+    ("bf16", 4096, 128, 264, 16, 1.0, 2, 0.1, 0.0),
+    ("bf16", 3000, 776, 128, 5, 2.0, 1, 0.0, 0.01),
+    ("bf16", 600, 64, 8, 3, 1.0, 1, 0.0, 0.0),          # the narrowest hidden layer
+])
+def test_geglu_experts(dtype, T, d, f, E, cf, n, rate, eps):
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=80, n_groups=n, ffn="geglu",
+                    expert_dropout=rate, jitter_eps=eps, noise_seed=31)
+    inp = make_inputs(s, _dev())
+    assert inp["W_in"].shape == (E, d, 2 * f)
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.8)
+    assert gpu["dW_in"].shape == (E, d, 2 * f)
+    _report("geglu %s f=%d" % (dtype, f), errs)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_geglu_capacity_zero_and_empty_batch(dtype):
+    from parity import run_gpu
+    from paper_2101_03961_amd.layer import SwitchLayer
+    s = SwitchShape("t", 64, 64, 72, 128, 1.0, dtype=dtype, seed_index=81, ffn="geglu")  # capacity 0
+    inp = make_inputs(s, _dev())
+    _, gpu = run_gpu(s, inp)
+    assert np.all(gpu["dropped"] == 1) and np.all(gpu["y"] == 0)
+    assert np.all(gpu["dW_in"] == 0) and np.all(gpu["dW_out"] == 0)
+    layer = SwitchLayer(0, 64, 72, 4, 1.0, s.alpha, dtype, device=_dev(), ffn="geglu")
+    e = lambda *shape: torch.empty(shape, dtype=layer.act, device=_dev())
+    W_r = torch.zeros((64, 4), device=_dev())
+    layer.forward(e(0, 64), W_r, e(4, 64, 144), e(4, 72, 64))
+    layer.alloc_grads(with_bias=False)
+    layer.dW_in.fill_(1.0)
+    layer.dW_out.fill_(1.0)
+    g = layer.backward(e(0, 64), e(0, 64), W_r, e(4, 64, 144), e(4, 72, 64))
+    torch.cuda.synchronize()
+    assert g["dW_in"].shape == (4, 64, 144) and float(g["dW_in"].float().abs().sum()) == 0.0
+    assert float(g["dW_out"].float().abs().sum()) == 0.0
+
+
+def test_layer_refuses_wrong_weight_shape():
+    """The ReLU layout handed to a gated-GELU layer must not reach the kernels."""
+    from paper_2101_03961_amd.layer import SwitchLayer
+    s = SwitchShape("t", 256, 64, 72, 4, 1.0, dtype="bf16", seed_index=82)
+    inp = make_inputs(s, _dev())
+    layer = SwitchLayer(s.T, s.d_model, s.d_ff, s.E, 1.0, s.alpha, "bf16", device=_dev(), ffn="geglu")
+    with pytest.raises(ValueError):
+        layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"])
+
+
+def test_geglu_switch_base_sampled():
+    from parity import compare_sampled
+    s = CONFIGS["base_geglu"]
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=2, n_tokens=24)
+    _report("base_geglu", errs)
+
+
 # ------------------------------------------- full sizes, sampled against oracle
 @pytest.mark.parametrize("name,n_experts", [
     ("base_cf1.0", 3), ("base_cf1.25", 2), ("base_zipf", 3), ("large", 2), ("c_share", 2),
