@@ -40,7 +40,19 @@ def kernel_work(shape, kept, elt):
     T, d, f, E = shape.T, shape.d_model, shape.d_ff, shape.E
     gemm = 2.0 * kept * d * f
     w_bytes = float(E) * d * f * elt
-    return {
+    f1 = 2 * f if shape.ffn == "geglu" else f          # columns of W_in
+    gemm_in = 2.0 * kept * d * f1
+    w_in_bytes = float(E) * d * f1 * elt
+    geglu = {
+        # gated-GELU FFN: plain first-layer product, streaming activation kernels
+        "gemm1_fwd": (gemm_in, w_in_bytes + kept * (d + f1) * elt, "mfma"),
+        "geglu_fwd": (0.0, kept * (f1 + f) * elt, "hbm"),
+        "gemm2_dgrad": (gemm, w_bytes + kept * (d + f) * elt, "mfma"),
+        "geglu_bwd": (0.0, kept * (f1 + f + f1) * elt, "hbm"),
+        "gemm1_dgrad": (gemm_in, w_in_bytes + kept * (f1 + d) * elt, "mfma"),
+        "gemm1_wgrad": (gemm_in, w_in_bytes + kept * (d + f1) * elt, "mfma"),
+    } if shape.ffn == "geglu" else {}
+    return {**{
         "router_split_weights": (0.0, d * E * 4 + 3 * 128 * d * 2 + d * 512, "hbm"),
         "router_fwd_mfma": (6.0 * T * d * E, T * d * elt + T * E * 4 + T * 12, "hbm"),
         "router_logits": (2.0 * T * d * E, T * d * elt + T * E * 4 + d * E * 4, "hbm"),
@@ -63,7 +75,7 @@ def kernel_work(shape, kept, elt):
         "router_dx": (2.0 * T * d * E, T * E * 4 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr": (2.0 * T * d * E, T * d * elt + T * E * 4, "hbm"),
         "router_dbr": (0.0, T * E * 4.0, "hbm"),
-    }
+    }, **geglu}
 
 
 def cpu_baseline(shape, inp, sample_tokens):
@@ -82,7 +94,7 @@ def cpu_baseline(shape, inp, sample_tokens):
     if shape.expert_dropout or shape.jitter_eps:
         noise = (shape.expert_dropout, shape.jitter_eps, shape.noise_seed)
     fwd = oracle.forward(x, W_r, W_in, W_out, shape.capacity_factor, shape.alpha, b_r=b_r,
-                         n_groups=shape.n_groups, noise=noise)
+                         n_groups=shape.n_groups, noise=noise, ffn=shape.ffn)
     oracle.backward(x, W_r, W_in, W_out, dy, fwd, shape.alpha, 1.0)
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
@@ -130,7 +142,7 @@ def main() -> int:
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
                         shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups,
                         expert_dropout=shape.expert_dropout, jitter_eps=shape.jitter_eps,
-                        seed=shape.noise_seed)
+                        seed=shape.noise_seed, ffn=shape.ffn)
     layer.alloc_grads(with_bias=inp["b_r"] is not None)
 
     def step():
@@ -205,7 +217,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": shape.name, "T": shape.T, "d_model": shape.d_model,
-                   "d_ff": shape.d_ff, "E": shape.E, "capacity_factor": shape.capacity_factor,
+                   "d_ff": shape.d_ff, "ffn": shape.ffn, "E": shape.E,
+                   "capacity_factor": shape.capacity_factor,
                    "n_groups": shape.n_groups, "expert_dropout": shape.expert_dropout,
                    "jitter_eps": shape.jitter_eps,
                    "capacity": layer.capacity, "kept_tokens": kept,
