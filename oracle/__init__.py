@@ -100,6 +100,9 @@ def _load():
                                  _c_f64p]
     lib.swo_positions.restype = None
     lib.swo_positions.argtypes = [i64, i64, i64, i64, _c_i32p, _c_i32p, _c_u8p, _c_i64p]
+    lib.swo_ntlb.restype = None
+    lib.swo_ntlb.argtypes = [i64, i64, i64, i64, i64, _c_f64p, _c_i32p, _c_i32p, _c_i32p, _c_u8p,
+                             _c_i64p, _c_i32p]
     lib.swo_expert_ffn.restype = None
     lib.swo_expert_ffn.argtypes = [i64, i64, i64, i64, _c_f32p, _c_f32p, _c_f32p, _c_i32p,
                                    _c_u8p, _c_f64p, _c_u8p, noise_p, i64, _c_f64p]
@@ -223,6 +226,27 @@ def positions(expert_index, E: int, C: int, n_groups: int = 1):
     return pos, dropped, (kept[0] if n_groups == 1 else kept)
 
 
+def ntlb(h, expert_index, pos, dropped, kept, C: int, n_groups: int, rounds: int,
+         choices_override=None):
+    """No-Token-Left-Behind stages after the Switch routing (App. B): returns updated copies
+    (expert_index, position_in_expert, dropped, kept) and the experts asked for, [T][rounds]."""
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    T, E = h.shape
+    e = np.array(expert_index, dtype=np.int32)
+    pos = np.array(pos, dtype=np.int32)
+    dropped = np.array(dropped, dtype=np.uint8)
+    kept = np.array(kept, dtype=np.int64).reshape(n_groups, E)
+    choices = np.empty((T, rounds), dtype=np.int32)
+    ov = None
+    if choices_override is not None:
+        ov = np.ascontiguousarray(choices_override, dtype=np.int32)
+        assert ov.shape == (T, rounds)
+    _load().swo_ntlb(T, E, C, n_groups, rounds, _ptr(h, _c_f64p), _ptr(ov, _c_i32p),
+                     _ptr(e, _c_i32p), _ptr(pos, _c_i32p), _ptr(dropped, _c_u8p),
+                     _ptr(kept, _c_i64p), _ptr(choices, _c_i32p))
+    return e, pos, dropped, (kept[0] if n_groups == 1 else kept), choices
+
+
 def _token_mask(expert_index, E, expert_sel, token_sel):
     """uint8[T] mask of the tokens to evaluate, or None for all of them."""
     if expert_sel is None and token_sel is None:
@@ -277,13 +301,19 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
             logits_override=None, expert_index_override=None,
             expert_sel: Optional[Sequence[int]] = None,
             token_sel: Optional[Sequence[int]] = None, skip_ffn: bool = False,
-            n_groups: int = 1, noise=None, ffn: str = "relu") -> Dict:
+            n_groups: int = 1, noise=None, ffn: str = "relu", ntlb_rounds: int = 0,
+            ntlb_choices_override=None) -> Dict:
     """Whole forward pass.
 
     n_groups: routing groups of T / n_groups consecutive tokens (capacity, positions and the
         auxiliary loss per group; 1 = the whole batch is one group).
     noise: None or (expert_dropout, jitter_eps, seed): training-time noise.
     ffn: "relu" or "geglu" (see expert_ffn).
+    ntlb_rounds: No-Token-Left-Behind re-routing stages after the Switch routing (App. B).
+        Then expert_index / gate / position_in_expert describe the expert that processes the
+        token (for tokens without a slot: the arg max, its probability and raw rank),
+        first_choice is the arg max, and expert_counts / the loss keep counting arg max
+        decisions.  ntlb_choices_override ([T][rounds]) forces what each token asks for.
     logits_override: use these logits (e.g. another implementation's fp32
         logits, widened) instead of computing them -- for the routing-stage
         comparison, which is defined on identical logits.
@@ -308,10 +338,15 @@ def forward(x, W_r, W_in, W_out, capacity_factor: float, alpha: float, b_r=None,
         g = p[np.arange(T), e].copy()
     loss, counts, f_vec, P_vec, counts_g = aux_loss(e, p, alpha, n_groups, with_group_counts=True)
     pos, dropped, kept = positions(e, E, C, n_groups)
+    first_choice, choices = e, None
+    if ntlb_rounds > 0:
+        e, pos, dropped, kept, choices = ntlb(h, e, pos, dropped, kept, C, n_groups, ntlb_rounds,
+                                              ntlb_choices_override)
+        g = p[np.arange(T), e].copy()
     out = dict(capacity=C, logits=h, probs=p, expert_index=e, gate=g, aux_loss=loss,
                expert_counts=counts, f=f_vec, P=P_vec, position_in_expert=pos,
                dropped=dropped, kept_counts=kept, n_groups=n_groups, group_counts=counts_g,
-               noise=noise, ffn=ffn)
+               noise=noise, ffn=ffn, first_choice=first_choice, ntlb_choices=choices)
     if not skip_ffn:
         out["y"] = expert_ffn(x32, W_in, W_out, e, dropped, g, expert_sel, token_sel, noise, ffn)
     return out

@@ -49,6 +49,9 @@
  *     2020): (GELU(x W_g) (.) (x W_l)) W_out with the exact GELU(u) = u Phi(u); W_in then holds
  *     [W_g | W_l] side by side, [d][2 f].  Expert dropout acts on the combined hidden
  *     activation.
+ *   - No-Token-Left-Behind (App. B), optional: see swo_ntlb.  A re-routed token's output is
+ *     scaled by the router probability of the expert that processes it; the auxiliary loss
+ *     keeps counting the arg max decisions.
  *   - the residual connection is outside the layer: a dropped token's output
  *     row is zero.
  *   - ReLU'(0) = 0.
@@ -225,6 +228,57 @@ void swo_positions(int64_t T, int64_t E, int64_t C, int64_t n_groups,
         }
     }
     free(seen);
+}
+
+/* ---- No-Token-Left-Behind (App. B): after the Switch routing above (stage 1), `rounds`
+ * further stages re-route the tokens that are still without a slot.  In stage r + 1 every
+ * such token, in sequence order inside its group, asks for its next-best expert -- experts
+ * ranked by logit, highest first, equal logits by lower index; softmax is monotone, so this
+ * is the ranking by router probability -- and gets that expert's next free slot if the
+ * group's capacity is not used up; otherwise it stays without one (and may try again in
+ * the next stage).  Inputs: the stage-1 result (expert_index, position_in_expert, dropped,
+ * kept as left by swo_positions).  choice_override ([T][rounds], may be NULL): the expert a
+ * token asks for in stage r + 1 instead of the ranking's.
+ * Outputs, for tokens that found a slot in a later stage: expert_index = that expert,
+ * position_in_expert = its slot number within the (group, expert) capacity, dropped = 0; all
+ * other entries are left as they are.  choices ([T][rounds], may be NULL) records what each
+ * token asked for (-1: it already had a slot, or no expert was left to ask). */
+void swo_ntlb(int64_t T, int64_t E, int64_t C, int64_t n_groups, int64_t rounds,
+              const double *logits /* [T][E] */, const int32_t *choice_override,
+              int32_t *expert_index, int32_t *position_in_expert, uint8_t *dropped,
+              int64_t *kept /* [n_groups][E] */, int32_t *choices) {
+    const int64_t Tg = T / n_groups;
+    int32_t *asked = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    for (int64_t t = 0; t < T; ++t) asked[t] = expert_index[t];   /* the last expert asked */
+    for (int64_t r = 0; r < rounds; ++r) {
+        for (int64_t t = 0; t < T; ++t) {
+            if (choices) choices[t * rounds + r] = -1;
+            if (!dropped[t]) continue;
+            const int64_t g = t / Tg;
+            const double *h = logits + t * E;
+            int32_t next = -1;
+            if (choice_override) {
+                next = choice_override[t * rounds + r];
+            } else if (asked[t] >= 0) {
+                /* the best expert that ranks strictly after the one asked last */
+                const int32_t a = asked[t];
+                for (int32_t i = 0; i < (int32_t)E; ++i) {
+                    const int after = h[i] < h[a] || (h[i] == h[a] && i > a);
+                    if (after && (next < 0 || h[i] > h[next])) next = i;
+                }
+            }
+            asked[t] = next;
+            if (choices) choices[t * rounds + r] = next;
+            if (next < 0) continue;
+            if (kept[g * E + next] < C) {
+                expert_index[t] = next;
+                position_in_expert[t] = (int32_t)kept[g * E + next];
+                dropped[t] = 0;
+                kept[g * E + next] += 1;
+            }
+        }
+    }
+    free(asked);
 }
 
 /* Work sharing.  The expert part is evaluated token by token, in sequence

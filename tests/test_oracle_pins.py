@@ -865,3 +865,140 @@ def test_geglu_subsets_match_full_run():
     assert np.array_equal(full["y"][rows], sub["y"][rows])
     assert np.array_equal(fb["dW_in"][3], sb["dW_in"][0])
     assert np.array_equal(fb["dW_out"][3], sb["dW_out"][0])
+
+
+# ------------------------------------------------------------------ No-Token-Left-Behind (App. B)
+def _ntlb_by_definition(h, C, n_groups, rounds):
+    """Stage by stage with whole-array operations, in the style of the appendix listing: the
+    candidates of a stage as a one-hot matrix, their rank by a cumulative sum, kept iff the
+    rank is below the capacity still free when the stage starts."""
+    T, E = h.shape
+    Tg = T // n_groups
+    order = np.lexsort((np.arange(E)[None, :].repeat(T, 0), -h), axis=1)    # best first, low index first
+    final = np.full(T, -1)
+    slot = np.full(T, -1)
+    used = np.zeros((n_groups, E), dtype=np.int64)
+    for stage in range(rounds + 1):
+        if stage >= E:
+            break
+        cand = order[:, stage]
+        for g in range(n_groups):
+            sl = slice(g * Tg, (g + 1) * Tg)
+            waiting = final[sl] < 0
+            onehot = (np.arange(E)[None, :] == cand[sl, None]) & waiting[:, None]
+            rank = (np.cumsum(onehot, axis=0) - 1)[np.arange(Tg), cand[sl]]
+            free = C - used[g]
+            ok = waiting & (rank < free[cand[sl]])
+            idx = np.flatnonzero(ok) + g * Tg
+            final[idx] = cand[idx]
+            slot[idx] = used[g][cand[idx]] + rank[ok]
+            used[g] += onehot[ok].sum(axis=0)
+    return final, slot, used
+
+
+@pytest.mark.parametrize("T,E,cf,n,rounds", [
+    (24, 3, 0.5, 1, 1), (24, 3, 1.0, 1, 2), (40, 4, 0.8, 2, 1), (60, 5, 1.0, 3, 4),
+    (64, 8, 0.6, 1, 3), (30, 2, 1.0, 1, 5), (48, 6, 0.3, 2, 2),
+])
+def test_ntlb_matches_stagewise_definition(T, E, cf, n, rounds):
+    rng = np.random.default_rng(T * 31 + E)
+    for trial in range(20):
+        h = rng.standard_normal((T, E)) + np.linspace(0.8, 0, E)[None, :]    # skewed: overflow
+        if trial % 4 == 0:
+            h = np.round(h * 2) / 2                                          # many exact ties
+        C = oracle.capacity(T, E, cf, n)
+        p = oracle.softmax(h)
+        e1, _ = oracle.top1(h, p)
+        pos, dropped, kept = oracle.positions(e1, E, C, n)
+        e, pos2, dr2, kept2, choices = oracle.ntlb(h, e1, pos, dropped, kept, C, n, rounds)
+        final, slot, used = _ntlb_by_definition(h, C, n, rounds)
+        has = final >= 0
+        assert np.array_equal(dr2 == 0, has)
+        assert np.array_equal(e[has], final[has]) and np.array_equal(pos2[has], slot[has])
+        assert np.array_equal(np.asarray(kept2).reshape(n, E), used)
+        # tokens without a slot keep reporting the arg max and their raw stage-1 rank
+        assert np.array_equal(e[~has], e1[~has]) and np.array_equal(pos2[~has], pos[~has])
+        assert np.all(pos2[~has] >= C)
+        # stage 1 is the Switch routing, untouched
+        k1 = dropped == 0
+        assert np.array_equal(e[k1], e1[k1]) and np.array_equal(pos2[k1], pos[k1])
+        assert used.max() <= C
+        # every slot of a (group, expert) is taken exactly once
+        Tg = T // n
+        keys = (np.arange(T) // Tg)[has] * E * (C + 1) + final[has] * (C + 1) + slot[has]
+        assert np.unique(keys).size == keys.size
+
+
+def test_ntlb_worked_example():
+    """Six tokens, two experts, capacity 3, every token prefers expert 0 (Fig. 11's situation):
+    stage 1 keeps tokens 0-2 at expert 0, stage 2 sends tokens 3-5 to expert 1."""
+    h = np.array([[2.0, 1.0]] * 6)
+    p = oracle.softmax(h)
+    e1, _ = oracle.top1(h, p)
+    pos, dropped, kept = oracle.positions(e1, 2, 3, 1)
+    assert dropped.tolist() == [0, 0, 0, 1, 1, 1]
+    e, pos2, dr2, kept2, choices = oracle.ntlb(h, e1, pos, dropped, kept, 3, 1, 1)
+    assert e.tolist() == [0, 0, 0, 1, 1, 1] and pos2.tolist() == [0, 1, 2, 0, 1, 2]
+    assert dr2.tolist() == [0] * 6 and kept2.tolist() == [3, 3]
+    assert choices[:, 0].tolist() == [-1, -1, -1, 1, 1, 1]
+    # capacity 2: expert 1 takes tokens 2 and 3, tokens 4 and 5 stay without a slot
+    pos, dropped, kept = oracle.positions(e1, 2, 2, 1)
+    e, pos2, dr2, kept2, _ = oracle.ntlb(h, e1, pos, dropped, kept, 2, 1, 3)
+    assert e.tolist() == [0, 0, 1, 1, 0, 0] and dr2.tolist() == [0, 0, 0, 0, 1, 1]
+    assert pos2.tolist() == [0, 1, 0, 1, 4, 5]
+
+
+def test_ntlb_with_enough_rounds_fills_the_whole_capacity():
+    s = SwitchShape("t", 96, 12, 16, 6, 1.0, dtype="f32", zipf_bias=True, seed_index=41)
+    inp = _np_inputs(s)
+    kw = dict(b_r=inp["b_r"], skip_ffn=True)
+    base = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha, **kw)
+    assert base["dropped"].sum() > 20
+    prev = base["dropped"].sum()
+    for r in range(1, 6):
+        f = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha,
+                           ntlb_rounds=r, **kw)
+        assert f["dropped"].sum() <= prev
+        prev = f["dropped"].sum()
+        assert f["aux_loss"] == base["aux_loss"]                    # the loss counts arg max decisions
+        assert np.array_equal(f["expert_counts"], base["expert_counts"])
+        assert np.array_equal(f["first_choice"], base["expert_index"])
+        moved = f["expert_index"] != base["expert_index"]
+        assert np.all(base["dropped"][moved] == 1)
+        t = np.flatnonzero(moved)
+        np.testing.assert_array_equal(f["gate"][t], f["probs"][t, f["expert_index"][t]])
+    assert prev == 0 and np.all(np.asarray(f["kept_counts"]) == 16)   # capacity 16 x 6 experts = 96 tokens
+
+
+@pytest.mark.parametrize("ffn", ["relu", "geglu"])
+def test_ntlb_layer_against_torch_autograd(ffn):
+    s = SwitchShape("t", 96, 24, 20, 4, 1.0, dtype="f32", zipf_bias=True, seed_index=42)
+    inp = _geglu_inputs(s) if ffn == "geglu" else _np_inputs(s)
+    d_aux, f = 0.9, s.d_ff
+    fwd = oracle.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], 1.0, s.alpha,
+                         b_r=inp["b_r"], n_groups=2, ntlb_rounds=2, ffn=ffn)
+    moved = fwd["expert_index"] != fwd["first_choice"]
+    assert moved.sum() > 5 and fwd["dropped"].sum() > 0
+    bwd = oracle.backward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["dy"], fwd,
+                          s.alpha, d_aux)
+    tt = {k: (None if v is None else torch.tensor(v, dtype=torch.float64,
+                                                   requires_grad=(k != "dy")))
+          for k, v in inp.items()}
+    x, E, Tg = tt["x"], s.E, s.T // 2
+    p = torch.softmax(x @ tt["W_r"] + tt["b_r"], dim=1)
+    e = torch.tensor(fwd["expert_index"].astype(np.int64))          # the routing is a constant
+    kept = torch.tensor(1.0 - fwd["dropped"].astype(np.float64))
+    gate = p[torch.arange(s.T), e]
+    pre = torch.einsum("td,tdf->tf", x, tt["W_in"][e])
+    hid = torch.nn.functional.gelu(pre[:, :f]) * pre[:, f:] if ffn == "geglu" else torch.relu(pre)
+    y = (kept * gate)[:, None] * torch.einsum("tf,tfd->td", hid, tt["W_out"][e])
+    first = torch.nn.functional.one_hot(torch.tensor(fwd["first_choice"].astype(np.int64)), E)
+    f_g = first.to(torch.float64).view(2, Tg, E).mean(1)
+    aux = s.alpha * E * (f_g * p.view(2, Tg, E).mean(1)).sum(1).mean()
+    ((y * tt["dy"]).sum() + d_aux * aux).backward()
+    np.testing.assert_allclose(fwd["y"], y.detach().numpy(), rtol=1e-12, atol=1e-14)
+    assert abs(fwd["aux_loss"] - float(aux.detach())) < 1e-15
+    for name in ("x", "W_r", "W_in", "W_out", "b_r"):
+        g = tt[name].grad.numpy()
+        np.testing.assert_allclose(bwd["d" + name], g, rtol=1e-10,
+                                   atol=1e-12 * max(1.0, np.abs(g).max()), err_msg=name)
