@@ -75,6 +75,9 @@ def kernel_work(shape, kept, elt):
         "router_dx": (2.0 * T * d * E, T * E * 4 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr": (2.0 * T * d * E, T * d * elt + T * E * 4, "hbm"),
         "router_dbr": (0.0, T * E * 4.0, "hbm"),
+        # per stage: the logits rows of the waiting tokens are not known in advance; priced
+        # with the token-sized tables the four kernels always stream
+        "ntlb_stages": (0.0, shape.ntlb_rounds * T * 4.0 * 6, "hbm"),
     }, **geglu}
 
 
@@ -94,7 +97,8 @@ def cpu_baseline(shape, inp, sample_tokens):
     if shape.expert_dropout or shape.jitter_eps:
         noise = (shape.expert_dropout, shape.jitter_eps, shape.noise_seed)
     fwd = oracle.forward(x, W_r, W_in, W_out, shape.capacity_factor, shape.alpha, b_r=b_r,
-                         n_groups=shape.n_groups, noise=noise, ffn=shape.ffn)
+                         n_groups=shape.n_groups, noise=noise, ffn=shape.ffn,
+                         ntlb_rounds=shape.ntlb_rounds)
     oracle.backward(x, W_r, W_in, W_out, dy, fwd, shape.alpha, 1.0)
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
@@ -116,6 +120,8 @@ def main() -> int:
                     help="expert dropout rate (0 = the benchmark's workload; >0 for experiments)")
     ap.add_argument("--jitter-eps", type=float, default=0.0,
                     help="input jitter on the router (0 = the benchmark's workload)")
+    ap.add_argument("--ntlb-rounds", type=int, default=0,
+                    help="No-Token-Left-Behind re-routing stages (0 = the benchmark's workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path "
@@ -137,12 +143,15 @@ def main() -> int:
         shape = shape.with_(name="%s_drop%g_jit%g" % (shape.name, args.expert_dropout, args.jitter_eps),
                             expert_dropout=args.expert_dropout, jitter_eps=args.jitter_eps,
                             noise_seed=2101)
+    if args.ntlb_rounds:
+        shape = shape.with_(name="%s_ntlb%d" % (shape.name, args.ntlb_rounds),
+                            ntlb_rounds=args.ntlb_rounds)
     dev = "cuda:0"
     inp = make_inputs(shape, dev)
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
                         shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups,
                         expert_dropout=shape.expert_dropout, jitter_eps=shape.jitter_eps,
-                        seed=shape.noise_seed, ffn=shape.ffn)
+                        seed=shape.noise_seed, ffn=shape.ffn, ntlb_rounds=shape.ntlb_rounds)
     layer.alloc_grads(with_bias=inp["b_r"] is not None)
 
     def step():
@@ -220,7 +229,7 @@ def main() -> int:
                    "d_ff": shape.d_ff, "ffn": shape.ffn, "E": shape.E,
                    "capacity_factor": shape.capacity_factor,
                    "n_groups": shape.n_groups, "expert_dropout": shape.expert_dropout,
-                   "jitter_eps": shape.jitter_eps,
+                   "jitter_eps": shape.jitter_eps, "ntlb_rounds": shape.ntlb_rounds,
                    "capacity": layer.capacity, "kept_tokens": kept,
                    "dropped_frac": 1.0 - kept / shape.T,
                    "count_min_mean_max": [int(counts.min()), float(counts.mean()), int(counts.max())]},

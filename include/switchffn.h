@@ -57,7 +57,8 @@ typedef enum {
                               16-byte chunks; bf16: an expert's weight matrix or its
                               slots x max(d_model, d_ff) activations reach 2 GB       */
     SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite,
-                              expert_dropout or jitter_eps outside [0, 1)          */
+                              expert_dropout or jitter_eps outside [0, 1), ntlb_rounds
+                              outside 0 .. 16                                       */
     SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16, or ffn_kind
                               is not a sw_ffn_kind                               */
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
@@ -91,6 +92,12 @@ typedef struct {
                                 sees x[t][k] * m, m uniform in [1 - eps, 1 + eps);
                                 eps in [0, 1)                                         */
     uint64_t seed;
+    int32_t ntlb_rounds;     /* No-Token-Left-Behind (App. B): re-routing stages after the
+                                Switch routing, 0 (off) .. 16.  In each stage the tokens
+                                still without a slot ask their next-best expert (by logit;
+                                equal logits: lower index first) for the capacity it has
+                                left, in sequence order inside the routing group.       */
+    int32_t reserved;        /* set to 0                                            */
 } switch_config;
 
 /*
@@ -129,6 +136,12 @@ int switch_workspace_size(const switch_config *cfg, size_t *bytes_out /* host */
  *   with noise: h is computed from x * m (Eq. 1 on the jittered input), and
  *            ReLU(.) above is followed by the dropout factor (0 or 1 / (1 - rate))
  *   SW_FFN_GEGLU: ReLU(x W_in[e]) is replaced by GELU(x W_g[e]) * (x W_l[e])
+ *   ntlb_rounds > 0: for a token placed by a re-routing stage, expert_index is the expert
+ *            that processes it, gate that expert's probability (which scales y),
+ *            position_in_expert its slot number within the (group, expert) capacity, and
+ *            dropped 0; tokens that never find a slot report the arg max, its probability
+ *            and their raw rank as without re-routing.  expert_counts and aux_loss keep
+ *            counting arg max decisions.
  *   aux_loss = alpha * E * sum_i f_i P_i, f_i = expert_counts[i] / T over ALL
  *            tokens (before truncation), P_i = mean_t p[t,i]            (Eqs. 4-6)
  * The workspace keeps what switch_backward needs; it must stay untouched

@@ -33,6 +33,8 @@ class SwitchConfig(ctypes.Structure):
         ("expert_dropout", ctypes.c_float),
         ("jitter_eps", ctypes.c_float),
         ("seed", ctypes.c_uint64),
+        ("ntlb_rounds", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libswitchffn.so")
-SOURCES = ["api.hip", "router.hip", "router_mfma.hip", "dispatch_combine.hip", "geglu.hip", "gemm_f32.hip",
+SOURCES = ["api.hip", "router.hip", "router_mfma.hip", "dispatch_combine.hip", "geglu.hip", "ntlb.hip", "gemm_f32.hip",
            "gemm_bf16.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

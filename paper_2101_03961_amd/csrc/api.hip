@@ -26,6 +26,7 @@ int check_config(const switch_config *cfg) {
     if (!isfinite(cfg->alpha)) return SW_ERR_VALUE;
     if (!(cfg->expert_dropout >= 0.f && cfg->expert_dropout < 1.f)) return SW_ERR_VALUE;
     if (!(cfg->jitter_eps >= 0.f && cfg->jitter_eps < 1.f)) return SW_ERR_VALUE;
+    if (cfg->ntlb_rounds < 0 || cfg->ntlb_rounds > 16) return SW_ERR_VALUE;
     // slot indices (expert * slots per expert + position) are kept in 32 bits
     const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
     const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
@@ -97,6 +98,16 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.nsplit_m = ceil_div(w.T, w.tps_m);
     w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
     w.relu_bits = take(E * ceil_div(f, kGemmTile) * ceil_div(C, kGemmTile) * kReluBitsPerTile);
+    w.ntlb_rounds = cfg->ntlb_rounds;
+    if (w.ntlb_rounds > 0) {
+        const size_t nE = (size_t)w.n * E * 4;
+        w.ntlb_logits = take(T * E * 4);
+        w.ntlb_asked = take(T * 4);
+        w.ntlb_cnt = take(nE);
+        w.ntlb_used = take(nE);
+        w.ntlb_free = take(nE);
+        w.ntlb_base = take(nE);
+    }
     w.total = off;
     Noise &nz = w.noise;
     const uint32_t seed_hi = (uint32_t)(cfg->seed >> 32);
@@ -226,6 +237,8 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
     hipStream_t s = (hipStream_t)hip_stream;
     const int dt = cfg->act_dtype;
     auto gemm = dt == SW_BF16 ? launch_gemm_bf16 : launch_gemm_f32;
+    // the re-routing stages rank the experts by logit: keep the logits if the caller does not
+    if (w.ntlb_rounds > 0 && !router_logits) router_logits = (float *)(ws + w.ntlb_logits);
 
     if (router_fwd_mfma_supported(w, dt))
         st = status_of(launch_router_fwd_mfma(w, x, W_r, b_r, ws, expert_index, gate,
@@ -236,7 +249,7 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
     if (st) return st;
     if ((st = status_of(launch_route_scan(w, ws, expert_counts, s)))) return st;
     if ((st = status_of(launch_dispatch(w, dt, cfg->alpha, x, ws, position_in_expert, dropped,
-                                        aux_loss, s))))
+                                        aux_loss, router_logits, expert_index, gate, s))))
         return st;
     if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
     if (w.geglu && (st = status_of(launch_geglu_fwd(w, dt, ws, s)))) return st;
@@ -299,7 +312,7 @@ const char *switch_status_string(int status) {
     case SW_ERR_SHAPE: return "shape out of range (T, E, d_model, d_ff; 16-byte row chunks)";
     case SW_ERR_VALUE:
         return "capacity_factor must be finite and > 0; alpha, d_aux finite; expert_dropout and "
-               "jitter_eps in [0, 1)";
+               "jitter_eps in [0, 1); ntlb_rounds in 0..16";
     case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16, ffn_kind SW_FFN_RELU or SW_FFN_GEGLU";
     case SW_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";

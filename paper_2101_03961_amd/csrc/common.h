@@ -124,6 +124,14 @@ struct Workspace {
     size_t relu_bits;           // u8  [E][f tiles][slot tiles][kReluBitsPerTile]  one bit per element of A:
                                 //     A > 0, in the order the bf16 GEMM epilogue visits a tile
     int64_t nsplit;
+    // No-Token-Left-Behind (only laid out when ntlb_rounds > 0)
+    int ntlb_rounds;
+    size_t ntlb_logits;         // f32 [T][E]   logits, when the caller asks for none
+    size_t ntlb_asked;          // i32 [T]      expert a waiting token asked last (-1: none left)
+    size_t ntlb_cnt;            // i32 [n][E]   candidates of the current stage
+    size_t ntlb_used;           // i32 [n][E]   slots handed out so far
+    size_t ntlb_free;           // i32 [n][E]   capacity free when the current stage starts
+    size_t ntlb_base;           // i32 [n][E]   first slot of the current stage's tokens
     size_t total;
     Noise noise;                // not part of the layout: the call's noise parameters
 };
@@ -158,9 +166,15 @@ hipError_t launch_route_scan(const Workspace &w, char *ws, int32_t *expert_count
 // number of blocks of that launch = parts of the loss that positions_kernel adds up
 int route_scan_blocks(const Workspace &w);
 // Positions, dropped mask, the loss from its parts, gather of kept tokens into expert-major slots.
+// With No-Token-Left-Behind stages (logits != nullptr) between the two, which also update
+// expert_index and gate of the tokens they place.
 hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
+                           const float *logits, int32_t *expert_index, float *gate,
                            hipStream_t s);
+hipError_t launch_ntlb(const Workspace &w, char *ws, const float *logits, int32_t *expert_index,
+                       float *gate, int32_t *position_in_expert, uint8_t *dropped,
+                       hipStream_t s);
 // Gated-GELU FFN: A = GELU(u) v (and expert dropout) from H = [u | v]; dH = [du | dv] from dA, H.
 hipError_t launch_geglu_fwd(const Workspace &w, int dtype, char *ws, hipStream_t s);
 hipError_t launch_geglu_bwd(const Workspace &w, int dtype, char *ws, hipStream_t s);

@@ -169,6 +169,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
 // -----------------------------------------------------------------------------
 hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
+                           const float *logits, int32_t *expert_index, float *gate,
                            hipStream_t s) {
     hipError_t err;
     {
@@ -184,6 +185,10 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const voi
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (w.C == 0) return hipSuccess;
+    if (w.ntlb_rounds > 0 &&
+        (err = launch_ntlb(w, ws, logits, expert_index, gate, position_in_expert, dropped, s)) !=
+            hipSuccess)
+        return err;
     {
         ProfScope ps("dispatch_gather", s);
         const int vec = dtype == SW_BF16 ? 8 : 4;

@@ -49,6 +49,7 @@ class SwitchShape:
     expert_dropout: float = 0.0  # training-time noise: dropout rate of the experts' hidden units,
     jitter_eps: float = 0.0      # half-width of the multiplicative jitter on the router's input,
     noise_seed: int = 0          # seed of both
+    ntlb_rounds: int = 0         # No-Token-Left-Behind re-routing stages
     ffn: str = "relu"            # expert FFN: "relu", or "geglu" (W_in = [W_g | W_l], [E, d, 2 d_ff])
 
     def with_(self, **kw) -> "SwitchShape":

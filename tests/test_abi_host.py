@@ -57,19 +57,21 @@ def test_capacity_and_workspace_host_functions():
     (dict(n_groups=-1), -2),
     (dict(ffn_kind=2), -4), (dict(ffn_kind=-1), -4),
     (dict(ffn_kind=1, d_model=32768, d_ff=16384), -2),   # [W_g | W_l] of one expert reaches 2 GB
+    (dict(ntlb_rounds=-1), -3), (dict(ntlb_rounds=17), -3),
     (dict(expert_dropout=1.0), -3), (dict(expert_dropout=-0.1), -3),
     (dict(expert_dropout=float("nan")), -3),
     (dict(jitter_eps=1.0), -3), (dict(jitter_eps=-1e-3), -3), (dict(jitter_eps=float("nan")), -3),
 ])
 def test_bad_config_is_refused(kw, status):
-    assert ctypes.sizeof(sw.SwitchConfig) == 80       # the header's struct: 64 bytes + noise
+    assert ctypes.sizeof(sw.SwitchConfig) == 88       # the header's struct
     base = dict(T=256, d_model=64, d_ff=256, E=4, capacity_factor=1.25, alpha=0.01,
                 act_dtype=sw.SW_BF16, ffn_kind=0, n_groups=1, expert_dropout=0.0, jitter_eps=0.0,
-                seed=0)
+                seed=0, ntlb_rounds=0, reserved=0)
     base.update(kw)
     cfg = sw.SwitchConfig(*[base[k] for k in ("T", "d_model", "d_ff", "E", "capacity_factor",
                                               "alpha", "act_dtype", "ffn_kind", "n_groups",
-                                              "expert_dropout", "jitter_eps", "seed")])
+                                              "expert_dropout", "jitter_eps", "seed", "ntlb_rounds",
+                                              "reserved")])
     with pytest.raises(sw.SwitchError) as ei:
         sw.switch_capacity(cfg)
     assert ei.value.status == status

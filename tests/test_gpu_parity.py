@@ -417,6 +417,47 @@ def test_geglu_switch_base_sampled():
     _report("base_geglu", errs)
 
 
+# ------------------------------------------- No-Token-Left-Behind (App. B)
+@pytest.mark.parametrize("dtype,T,d,f,E,cf,n,bias,rounds,ffn", [
+    ("f32", 700, 64, 96, 6, 1.0, 1, True, 1, "relu"),
+    ("f32", 1024, 64, 40, 8, 0.75, 4, True, 3, "geglu"),
+    ("bf16", 3000, 128, 264, 16, 1.0, 1, False, 1, "relu"),     # MFMA router, mild overflow
+    ("bf16", 4096, 128, 264, 128, 1.0, 2, True, 2, "relu"),     # heavy skew, 128 experts
+    ("bf16", 2500, 72, 64, 513, 2.0, 1, False, 2, "relu"),      # nine experts per lane, ragged
+    ("f32", 600, 32, 32, 3, 1.0, 1, True, 16, "relu"),          # more rounds than experts
+])
+def test_no_token_left_behind(dtype, T, d, f, E, cf, n, bias, rounds, ffn):
+    from parity import compare_full, run_gpu
+    s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=90, n_groups=n, zipf_bias=bias,
+                    ntlb_rounds=rounds, ffn=ffn)
+    inp = make_inputs(s, _dev())
+    widen = {"dW_r": 5.0, "db_r": 10.0} if E > 256 else None
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.7, widen=widen)
+    _, plain = run_gpu(s.with_(ntlb_rounds=0), inp, backward=False)
+    rescued = int(plain["dropped"].sum()) - int(gpu["dropped"].sum())
+    errs["rescued"], errs["still_dropped"] = rescued, int(gpu["dropped"].sum())
+    _report("ntlb %s E=%d rounds=%d" % (dtype, E, rounds), errs)
+    assert rescued > 0
+    # tokens that had a slot keep it; the loss and the counts do not change
+    k1 = plain["dropped"] == 0
+    assert np.array_equal(plain["expert_index"][k1], gpu["expert_index"][k1])
+    assert np.array_equal(plain["position_in_expert"][k1], gpu["position_in_expert"][k1])
+    assert np.array_equal(plain["expert_counts"], gpu["expert_counts"])
+    assert np.array_equal(plain["aux_loss"], gpu["aux_loss"])
+    # no (group, expert) pair exceeds its capacity
+    kept = gpu["dropped"] == 0
+    key = (np.arange(T) // (T // n))[kept] * E + gpu["expert_index"][kept]
+    assert np.bincount(key, minlength=n * E).max() <= fwd["capacity"]
+
+
+def test_no_token_left_behind_full_size():
+    from parity import compare_sampled
+    s = CONFIGS["base_cf1.0"].with_(ntlb_rounds=2)
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=2, n_tokens=24)
+    _report("base_cf1.0 + 2 re-routing stages", errs)
+
+
 # ------------------------------------------- full sizes, sampled against oracle
 @pytest.mark.parametrize("name,n_experts", [
     ("base_cf1.0", 3), ("base_cf1.25", 2), ("base_zipf", 3), ("large", 2), ("c_share", 2),
