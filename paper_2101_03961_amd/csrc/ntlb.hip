@@ -5,8 +5,9 @@
 // equal logits by lower index -- and hands out that expert's remaining capacity in sequence
 // order inside the routing group.  A stage is the stage-1 machinery once more, on the
 // stage's candidates only:
-//   ntlb_choice      per 256-token block: the expert each waiting token asks for, its rank
-//                    among the block's earlier candidates for the same expert, block histogram
+//   ntlb_choice      the expert each waiting token asks for
+//   ntlb_rank        per 256-token block: a candidate's rank among the block's earlier
+//                    candidates for the same expert, block histogram
 //   ntlb_block_scan  per (group, expert): exclusive prefix of the histograms over the blocks
 //   ntlb_expert_scan per expert: capacity still free per group, where the stage's tokens go in
 //                    the expert's slot range (behind everything placed before), new totals
@@ -17,44 +18,40 @@
 namespace sw {
 
 // -----------------------------------------------------------------------------
-// A wave owns 64 tokens; it visits those still waiting one at a time: the lanes stride the
-// experts and the wave reduces to the best expert ranking strictly after the one asked last.
+// The expert each waiting token asks for.  Tokens without a slot sit at the end of their
+// group's sequence (they are the ones whose rank passed the capacity), so a wave does not
+// own consecutive tokens but every W-th one (W = number of waves): lane k looks at token
+// k W + w, and the waiting tokens spread evenly over the waves.  A wave then visits its waiting
+// tokens four at a time (their row loads overlap): the lanes stride the experts and the wave
+// reduces to the best expert ranking strictly after the one asked last.
 // -----------------------------------------------------------------------------
-__global__ __launch_bounds__(kRouteTB) void ntlb_choice_kernel(
+__global__ __launch_bounds__(256) void ntlb_choice_kernel(
     const float *__restrict__ logits, const int32_t *__restrict__ tok_slot,
-    const int32_t *__restrict__ first_choice, int32_t *__restrict__ asked,
-    int32_t *__restrict__ local_rank, int32_t *__restrict__ block_counts, int nbg, int Tg, int E,
+    const int32_t *__restrict__ first_choice, int32_t *__restrict__ asked, int T, int E, int W,
     int round) {
-    extern __shared__ int32_t sm[];
-    int32_t *list = sm;                  // [kRouteTB] experts asked for, candidates in token order
-    int32_t *wave_n = sm + kRouteTB;     // [4] candidates per wave
-    int32_t *hist = sm + kRouteTB + 4;   // [E]
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int b = blockIdx.x;
-    int t0, tend;
-    block_token_range(b, nbg, Tg, t0, tend);
-    for (int i = tid; i < E; i += kRouteTB) hist[i] = 0;
-    // lane l holds token tw's state; the wave then visits only its waiting tokens, four at a
-    // time so that their row loads overlap
-    const int tw = t0 + tid;
-    const bool unplaced = tw < tend && tok_slot[tw] < 0;
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= W) return;
+    const long tl_ = (long)lane * W + w;
+    const int tw = tl_ < T ? (int)tl_ : -1;
+    const bool unplaced = tw >= 0 && tok_slot[tw] < 0;
     const int last = unplaced ? (round == 0 ? first_choice[tw] : asked[tw]) : -1;
     const float last_h = last >= 0 ? logits[(size_t)tw * E + last] : 0.f;
     int next = -1;
     unsigned long long todo = __ballot(unplaced && last >= 0);
     while (todo) {
-        int tl[4], a[4], be[4];
+        int src[4], a[4], be[4];
+        bool live[4];
         float ha[4], bh[4];
         const float *h[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            tl[k] = todo ? __ffsll(todo) - 1 : -1;   // wave-uniform
-            if (todo) todo &= todo - 1;
-            const int src = tl[k] >= 0 ? tl[k] : 0;
-            a[k] = __shfl(last, src, kWave);
-            ha[k] = __shfl(last_h, src, kWave);
-            h[k] = logits + (size_t)(t0 + wave * kWave + src) * E;
+            live[k] = todo != 0;                         // wave-uniform
+            src[k] = live[k] ? __ffsll(todo) - 1 : src[0];
+            if (live[k]) todo &= todo - 1;
+            a[k] = __shfl(last, src[k], kWave);
+            ha[k] = __shfl(last_h, src[k], kWave);
+            h[k] = logits + (size_t)__shfl(tw, src[k], kWave) * E;
             bh[k] = -INFINITY;
             be[k] = 0x7fffffff;
         }
@@ -79,12 +76,34 @@ __global__ __launch_bounds__(kRouteTB) void ntlb_choice_kernel(
                     be[k] = oe;
                 }
             }
-            if (lane == tl[k]) next = be[k] == 0x7fffffff ? -1 : be[k];
+            if (live[k] && lane == src[k]) next = be[k] == 0x7fffffff ? -1 : be[k];
         }
     }
     if (unplaced) asked[tw] = next;
-    // candidates in token order: position in the block's list = candidates in earlier waves +
-    // earlier lanes; rank = earlier list entries asking for the same expert
+}
+
+// -----------------------------------------------------------------------------
+// Per 256-token block (never across routing groups): the stage's candidates in token order,
+// each one's rank among the block's earlier candidates for the same expert, and the block's
+// histogram of experts asked for.
+// -----------------------------------------------------------------------------
+__global__ __launch_bounds__(kRouteTB) void ntlb_rank_kernel(
+    const int32_t *__restrict__ tok_slot, const int32_t *__restrict__ asked,
+    int32_t *__restrict__ local_rank, int32_t *__restrict__ block_counts, int nbg, int Tg, int E) {
+    extern __shared__ int32_t sm[];
+    int32_t *list = sm;                  // [kRouteTB] experts asked for, candidates in token order
+    int32_t *wave_n = sm + kRouteTB;     // [4] candidates per wave
+    int32_t *hist = sm + kRouteTB + 4;   // [E]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x;
+    int t0, tend;
+    block_token_range(b, nbg, Tg, t0, tend);
+    for (int i = tid; i < E; i += kRouteTB) hist[i] = 0;
+    const int tw = t0 + tid;
+    const int next = (tw < tend && tok_slot[tw] < 0) ? asked[tw] : -1;
+    // position in the block's list = candidates in earlier waves + in earlier lanes;
+    // rank = earlier list entries asking for the same expert
     const unsigned long long cmask = __ballot(next >= 0);
     if (lane == 0) wave_n[wave] = __popcll(cmask);
     __syncthreads();
@@ -194,10 +213,14 @@ hipError_t launch_ntlb(const Workspace &w, char *ws, const float *logits, int32_
     ProfScope ps("ntlb_stages", s);
     const size_t smem = sizeof(int32_t) * (kRouteTB + 4 + (size_t)w.E);
     for (int round = 0; round < w.ntlb_rounds; ++round) {
-        hipLaunchKernelGGL(ntlb_choice_kernel, dim3((unsigned)w.nb), dim3(kRouteTB), smem, s, logits,
+        const int W = (int)ceil_div(w.T, kWave);   // waves of the choice kernel
+        hipLaunchKernelGGL(ntlb_choice_kernel, dim3((unsigned)ceil_div(W, 4)), dim3(256), 0, s, logits,
                            (const int32_t *)(ws + w.tok_slot), (const int32_t *)(ws + w.idx),
-                           (int32_t *)(ws + w.ntlb_asked), (int32_t *)(ws + w.local_rank),
-                           (int32_t *)(ws + w.block_counts), (int)w.nbg, (int)w.Tg, (int)w.E, round);
+                           (int32_t *)(ws + w.ntlb_asked), (int)w.T, (int)w.E, W, round);
+        hipLaunchKernelGGL(ntlb_rank_kernel, dim3((unsigned)w.nb), dim3(kRouteTB), smem, s,
+                           (const int32_t *)(ws + w.tok_slot), (const int32_t *)(ws + w.ntlb_asked),
+                           (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
+                           (int)w.nbg, (int)w.Tg, (int)w.E);
         hipLaunchKernelGGL(ntlb_block_scan_kernel, dim3((unsigned)ceil_div(w.n * w.E, 4)), dim3(256),
                            0, s, (const int32_t *)(ws + w.block_counts),
                            (int32_t *)(ws + w.block_off), (int32_t *)(ws + w.ntlb_cnt), (int)w.n,
