@@ -235,6 +235,37 @@ def test_random_shapes():
         compare_full(s, inp, d_aux=0.5, widen=widen)
 
 
+def test_random_shapes_with_options():
+    """The same sweep with the optional parts switched on at random: gated-GELU experts,
+    expert dropout, input jitter, re-routing stages, router bias."""
+    from parity import compare_full
+    rng = np.random.default_rng(20210112)
+    for case in range(30):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        mult = 8 if dtype == "bf16" else 4
+        E = int(rng.choice([2, 3, 4, 6, 8, 16, 32, 128]))
+        n = int(rng.choice([1, 1, 2, 4]))
+        T = int(rng.integers(300, 1400)) * n
+        hi_d, hi_f = (520, 400) if dtype == "bf16" else (300, 200)
+        d = int(rng.integers(32 // mult, hi_d // mult)) * mult
+        f = int(rng.integers(32 // mult, hi_f // mult)) * mult
+        cf = float(rng.choice([0.7, 1.0, 1.25, 2.0]))
+        ffn = "geglu" if rng.random() < 0.5 else "relu"
+        rate = float(rng.choice([0.0, 0.1, 0.4]))
+        eps = float(rng.choice([0.0, 0.0, 0.01, 0.1]))
+        rounds = int(rng.choice([0, 0, 1, 2, 4]))
+        bias = bool(rng.random() < 0.4)
+        s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=400 + case, n_groups=n,
+                        ffn=ffn, expert_dropout=rate, jitter_eps=eps,
+                        noise_seed=int(rng.integers(0, 2 ** 62)), ntlb_rounds=rounds, zipf_bias=bias)
+        print("[random options %d] %s T=%d d=%d f=%d E=%d cf=%g groups=%d %s drop=%g jitter=%g "
+              "stages=%d bias=%d" % (case, dtype, T, d, f, E, cf, n, ffn, rate, eps, rounds, bias),
+              flush=True)
+        inp = make_inputs(s, _dev())
+        few = dtype == "bf16" and T * min(1.0, cf) < 16 * E
+        compare_full(s, inp, d_aux=0.5, widen={"dW_r": 5.0, "db_r": 5.0} if few else None)
+
+
 def test_relu_decision_at_a_zero_preactivation():
     """In this seeded case one pre-activation is -7.5e-9 in fp64 (RMS of its row: 1) and the
     fp32 sum of the same exact products comes out positive: the unit's gate is a coin flip,
