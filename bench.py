@@ -52,9 +52,14 @@ def kernel_work(shape, kept, elt):
         "gemm1_dgrad": (gemm_in, w_in_bytes + kept * (f1 + d) * elt, "mfma"),
         "gemm1_wgrad": (gemm_in, w_in_bytes + kept * (d + f1) * elt, "mfma"),
     } if shape.ffn == "geglu" else {}
+    jit = shape.jitter_eps > 0
+    dpad = -(-d // 32) * 32
+    x_router = T * 3 * dpad * 2 if jit else T * d * elt     # bytes of the router's input operand
     return {**{
+        "router_jitter_split": (0.0, T * d * elt + T * 3 * dpad * 2, "hbm"),
+        "router_dx_jitter": (0.0, 2.0 * T * d * elt + kept * d * elt + T * 4, "hbm"),
         "router_split_weights": (0.0, d * E * 4 + 3 * 128 * d * 2 + d * 512, "hbm"),
-        "router_fwd_mfma": (6.0 * T * d * E, T * d * elt + T * E * 4 + T * 12, "hbm"),
+        "router_fwd_mfma": (6.0 * T * d * E, x_router + T * E * 4 + T * 12, "hbm"),
         "router_logits": (2.0 * T * d * E, T * d * elt + T * E * 4 + d * E * 4, "hbm"),
         "router_softmax_top1": (0.0, 2.0 * T * E * 4 + T * 8, "hbm"),
         "route_scan_aux": (0.0, 3.0 * (T / 256.0) * E * 4, "hbm"),
@@ -70,7 +75,7 @@ def kernel_work(shape, kept, elt):
         "gemm1_wgrad": (gemm, w_bytes + kept * (d + f) * elt, "mfma"),
         "router_dlogits": (0.0, T * E * 4 + T * 512 + T * 8, "hbm"),
         "router_dx_mfma": (6.0 * T * d * E, T * 512 + kept * d * elt + T * d * elt, "hbm"),
-        "router_dWr_mfma": (4.0 * T * d * E, T * d * elt + T * 512, "hbm"),
+        "router_dWr_mfma": (4.0 * T * d * E, (T * 2 * dpad * 2 if jit else T * d * elt) + T * 512, "hbm"),
         "router_dWr_reduce": (0.0, -(-T // (-(-(-(-T // 85)) // 64) * 64)) * d * 256 * 4.0 + d * E * 4.0, "hbm"),
         "router_dx": (2.0 * T * d * E, T * E * 4 + kept * d * elt + T * d * elt, "hbm"),
         "router_dWr": (2.0 * T * d * E, T * d * elt + T * E * 4, "hbm"),

@@ -90,13 +90,28 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.dWr_part = take((size_t)w.nsplit * d * E * 4);
     w.dbr_part = take((size_t)ceil_div(w.T, kRouteTB) * E * 4);
     w.dpad = ceil_div(w.d, 32) * 32;
-    w.wsplit = take((size_t)3 * 128 * w.dpad * 2);
+    // noise parameters first: the router's layout depends on the jitter
+    Noise &nz = w.noise;
+    const uint32_t seed_hi = (uint32_t)(cfg->seed >> 32);
+    nz.seed_lo = (uint32_t)cfg->seed;
+    nz.jitter_term = seed_hi + 1u * 0x7F4A7C15u;
+    nz.dropout_term = seed_hi + 2u * 0x7F4A7C15u;
+    nz.dropout = cfg->expert_dropout > 0.f;
+    nz.jitter = cfg->jitter_eps > 0.f;
+    nz.drop_thr = (uint32_t)floor((double)cfg->expert_dropout * 4294967296.0);
+    nz.drop_scale = (float)(1.0 / (1.0 - (double)cfg->expert_dropout));
+    nz.jitter_eps = cfg->jitter_eps;
+    const bool jit_mfma = nz.jitter && cfg->act_dtype == SW_BF16;
+    w.dpad_r = jit_mfma ? 3 * w.dpad : w.dpad;
+    w.wsplit = take((size_t)3 * 128 * w.dpad_r * 2);
     w.wsplit_b = take(d * 256 * 2);
     w.dl_split = take(T * 256 * 2);
+    w.xj = take(jit_mfma ? T * (size_t)w.dpad_r * 2 : 0);
+    w.no_slot = take(jit_mfma ? T * 4 : 0);
     w.tps_m = ceil_div(ceil_div(w.T, 85), 64) * 64;
     if (w.tps_m < 64) w.tps_m = 64;   // empty batch
     w.nsplit_m = ceil_div(w.T, w.tps_m);
-    w.dWr_part_m = take((size_t)w.nsplit_m * d * 256 * 4);
+    w.dWr_part_m = take((size_t)w.nsplit_m * (jit_mfma ? 2 * (size_t)w.dpad : d) * 256 * 4);
     w.relu_bits = take(E * ceil_div(f, kGemmTile) * ceil_div(C, kGemmTile) * kReluBitsPerTile);
     w.ntlb_rounds = cfg->ntlb_rounds;
     if (w.ntlb_rounds > 0) {
@@ -109,16 +124,6 @@ Workspace layout_workspace(const switch_config *cfg) {
         w.ntlb_base = take(nE);
     }
     w.total = off;
-    Noise &nz = w.noise;
-    const uint32_t seed_hi = (uint32_t)(cfg->seed >> 32);
-    nz.seed_lo = (uint32_t)cfg->seed;
-    nz.jitter_term = seed_hi + 1u * 0x7F4A7C15u;
-    nz.dropout_term = seed_hi + 2u * 0x7F4A7C15u;
-    nz.dropout = cfg->expert_dropout > 0.f;
-    nz.jitter = cfg->jitter_eps > 0.f;
-    nz.drop_thr = (uint32_t)floor((double)cfg->expert_dropout * 4294967296.0);
-    nz.drop_scale = (float)(1.0 / (1.0 - (double)cfg->expert_dropout));
-    nz.jitter_eps = cfg->jitter_eps;
     return w;
 }
 

@@ -115,11 +115,16 @@ struct Workspace {
     size_t dlogits;             // f32 [T][E]
     size_t dWr_part;            // f32 [nsplit][d][E]  split-T partial sums of dW_r
     size_t dbr_part;            // f32 [ceil(T / 256)][E]  per-256-token sums of dlogits
-    size_t wsplit;              // bf16 [3][128][dpad]  W_r^T as three bf16 terms (MFMA router)
+    size_t wsplit;              // bf16 [3][128][dpad_r]  W_r^T as three bf16 terms (MFMA router)
     int64_t dpad;               // d rounded up to a multiple of 32
+    int64_t dpad_r;             // k extent of the MFMA router: dpad, or 3 dpad with input jitter
+                                // (the jittered input as three bf16 planes side by side)
+    size_t xj;                  // bf16 [T][3 dpad]  x * m as hi | mid | lo planes (jitter + MFMA router)
+    size_t no_slot;             // i32 [T]  all -1 (jitter + MFMA router backward)
     size_t wsplit_b;            // bf16 [d][256]   W_r rows as hi | lo halves (MFMA router backward)
     size_t dl_split;            // bf16 [T][256]   dlogits rows as hi | lo halves
     size_t dWr_part_m;          // f32 [nsplit_m][d][256]  partial sums of x^T [dl_hi | dl_lo]
+                                //     (with jitter: [nsplit_m][2 dpad][256], hi and mid plane of x * m)
     int64_t tps_m, nsplit_m;    // tokens per split (multiple of 32), number of splits
     size_t relu_bits;           // u8  [E][f tiles][slot tiles][kReluBitsPerTile]  one bit per element of A:
                                 //     A > 0, in the order the bf16 GEMM epilogue visits a tile

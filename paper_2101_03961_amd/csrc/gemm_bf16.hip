@@ -624,14 +624,15 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
 }
 
 // dx = dl W_r^T + (kept) dXd[slot]: dl as bf16 hi|lo rows [T][256], W_r^T as bf16 hi|lo rows
-// [d][256]; see GemmMode.
+// [d][256]; see GemmMode.  With input jitter the product alone is written (no token has an
+// addend row); router_dx_jitter_kernel then scales it by the multipliers and adds the rows.
 hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStream_t s) {
     GemmArgs a{};
     a.Q = (const bf16 *)(ws + w.dl_split); a.q_batch = 0; a.ldq = 256;
     a.P = (const bf16 *)(ws + w.wsplit_b); a.p_batch = 0; a.ldp = 256;
     a.Cout = (bf16 *)dx; a.c_batch = 0; a.ldc = (int)w.d;
     a.mask = (const bf16 *)(ws + w.dXd);
-    a.tok_slot = (const int32_t *)(ws + w.tok_slot);
+    a.tok_slot = (const int32_t *)(ws + (w.noise.jitter ? w.no_slot : w.tok_slot));
     a.Qdim = (int)w.T; a.Pdim = (int)w.d; a.Kdim = 384;
     a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
     a.tiles_p = (int)ceil_div(a.Pdim, kBP);
@@ -641,13 +642,19 @@ hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStre
 }
 
 // Partial sums over token ranges of x^T [dl_hi | dl_lo]  ->  part[split][d][256] (fp32).
+// With input jitter x is replaced by the hi and mid planes of x * m, taken as one operand of
+// 2 dpad rows: part[split][2 dpad][256], row k from the hi plane, row dpad + k from the mid plane.
 hipError_t launch_router_dWr_mfma(const Workspace &w, const void *x, char *ws, hipStream_t s) {
     GemmArgs a{};
-    a.Q = (const bf16 *)x; a.q_batch = (size_t)w.tps_m * w.d; a.ldq = (int)w.d;          // [k = token][q = d]
+    const bool jitter = w.noise.jitter;
+    const int ldx = jitter ? (int)w.dpad_r : (int)w.d;
+    const int rows = jitter ? 2 * (int)w.dpad : (int)w.d;
+    a.Q = jitter ? (const bf16 *)(ws + w.xj) : (const bf16 *)x;                  // [k = token][q]
+    a.q_batch = (size_t)w.tps_m * ldx; a.ldq = ldx;
     a.P = (const bf16 *)(ws + w.dl_split); a.p_batch = (size_t)w.tps_m * 256; a.ldp = 256;  // [k = token][p]
-    a.Cf = (float *)(ws + w.dWr_part_m); a.c_batch = (size_t)w.d * 256; a.ldc = 256;
+    a.Cf = (float *)(ws + w.dWr_part_m); a.c_batch = (size_t)rows * 256; a.ldc = 256;
     a.T_total = (int)w.T; a.tps = (int)w.tps_m;
-    a.Qdim = (int)w.d; a.Pdim = 256; a.Kdim = (int)w.tps_m;
+    a.Qdim = rows; a.Pdim = 256; a.Kdim = (int)w.tps_m;
     a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
     a.tiles_p = 1;
     a.total_tiles = a.tiles_q * a.tiles_p * (int)w.nsplit_m;

@@ -390,20 +390,64 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
     }
 }
 
-// dW_r[k][j] = sum over splits of (part[s][k][j] + part[s][k][128 + j]), fixed order
+// dW_r[k][j] = sum over splits of (part[s][k][j] + part[s][k][128 + j]), fixed order.
+// rows = rows of one split's part; second > 0: the operand had a second plane (input jitter:
+// x * m as hi + mid), whose rows start at `second` and are added in.
 __global__ __launch_bounds__(256) void reduce_dWr_split_kernel(const float *__restrict__ part,
                                                                float *__restrict__ dW_r, int d,
-                                                               int E, int nsplit) {
+                                                               int E, int nsplit, int rows,
+                                                               int second) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= d * E) return;
     const int k = i / E, j = i - k * E;
     float s = 0.f;
 #pragma unroll 8
     for (int q = 0; q < nsplit; ++q) {   // unrolled: eight splits' loads in flight, same order of sums
-        const float *row = part + ((size_t)q * d + k) * 256;
+        const float *row = part + ((size_t)q * rows + k) * 256;
         s += row[j] + row[128 + j];
     }
+    if (second > 0) {
+        float s2 = 0.f;
+#pragma unroll 8
+        for (int q = 0; q < nsplit; ++q) {
+            const float *row = part + ((size_t)q * rows + second + k) * 256;
+            s2 += row[j] + row[128 + j];
+        }
+        s += s2;
+    }
     dW_r[i] = s;
+}
+
+// Input jitter with the matrix-core router backward: dx holds the router's product
+// dl W_r^T (rounded to bf16); finish  dx[t][k] = m[t][k] * dx[t][k] + dXd[slot_t][k].
+__global__ __launch_bounds__(256) void router_dx_jitter_kernel(bf16 *__restrict__ dx,
+                                                               const bf16 *__restrict__ dXd,
+                                                               const int32_t *__restrict__ tok_slot,
+                                                               int T, int d, Noise nz) {
+    typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    const int cpr = d / 8;
+    const long chunk = (long)blockIdx.x * 256 + threadIdx.x;
+    if (chunk >= (long)T * cpr) return;
+    const int t = (int)(chunk / cpr);
+    const int k0 = (int)(chunk - (long)t * cpr) * 8;
+    bf16x8 v = *(const bf16x8 *)(dx + (size_t)t * d + k0);
+    const int slot = tok_slot[t];
+    bf16x8 add;
+    if (slot >= 0) add = *(const bf16x8 *)(dXd + (size_t)slot * d + k0);
+    const uint32_t idx = (uint32_t)t * (uint32_t)d + (uint32_t)k0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float r = (float)v[i] * jitter_of(nz, idx + (uint32_t)i);
+        if (slot >= 0) r += (float)add[i];
+        v[i] = (bf16)r;
+    }
+    *(bf16x8 *)(dx + (size_t)t * d + k0) = v;
+}
+
+// 4-byte words set to -1
+__global__ __launch_bounds__(256) void fill_minus_one_kernel(int32_t *__restrict__ p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = -1;
 }
 
 // -----------------------------------------------------------------------------
@@ -697,12 +741,27 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (mfma) {
+        const bool jitter = w.noise.jitter;
+        if (jitter) {   // the matrix-core kernel writes the bare product: no token has an addend
+            hipLaunchKernelGGL(fill_minus_one_kernel, dim3((unsigned)ceil_div(w.T, 256)), dim3(256),
+                               0, s, (int32_t *)(ws + w.no_slot), (int)w.T);
+            if ((err = hipGetLastError()) != hipSuccess) return err;
+        }
         if ((err = launch_router_dx_mfma(w, ws, dx, s)) != hipSuccess) return err;
+        if (jitter) {
+            ProfScope ps("router_dx_jitter", s);
+            const long chunks = (long)w.T * (w.d / 8);
+            hipLaunchKernelGGL(router_dx_jitter_kernel, dim3((unsigned)ceil_div(chunks, 256)),
+                               dim3(256), 0, s, (bf16 *)dx, (const bf16 *)(ws + w.dXd),
+                               (const int32_t *)(ws + w.tok_slot), (int)w.T, (int)w.d, w.noise);
+            if ((err = hipGetLastError()) != hipSuccess) return err;
+        }
         if ((err = launch_router_dWr_mfma(w, x, ws, s)) != hipSuccess) return err;
         ProfScope ps("router_dWr_reduce", s);
         hipLaunchKernelGGL(reduce_dWr_split_kernel, dim3((unsigned)ceil_div(w.d * w.E, 256)),
                            dim3(256), 0, s, (const float *)(ws + w.dWr_part_m), dW_r, (int)w.d,
-                           (int)w.E, (int)w.nsplit_m);
+                           (int)w.E, (int)w.nsplit_m, jitter ? 2 * (int)w.dpad : (int)w.d,
+                           jitter ? (int)w.dpad : 0);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     } else {
         ProfScope ps("router_dx", s);

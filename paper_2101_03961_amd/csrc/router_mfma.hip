@@ -29,14 +29,19 @@ constexpr int kRmPitch = kRmExperts + 4;               // floats per row of the 
 constexpr int kRmTileBytes = kRmTokens * kRmPitch * 4; // 132 KB
 constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + 4 * kRmExperts * 4;
 
-// W_r [d][E] fp32 -> wsplit [3][128][dpad] bf16: term s of expert e, k contiguous;
+// W_r [d][E] fp32 -> wsplit [3][128][planes * dpad] bf16: term s of expert e, k contiguous;
 // rows of absent experts and columns past d are zero.  Also, for the backward
 // pass, wsplit_b [d][256] bf16: row k holds hi(W_r[k][0..127]) | lo(...), where
 // hi + lo carries 16 mantissa bits.
+// planes = 3 (input jitter): the router's input x * m is no bf16 value any more and comes as
+// three bf16 planes hi | mid | lo side by side, [T][3 dpad] (jitter_split_kernel).  The
+// weight terms are then laid out against all three planes, with zeros where plane p meets a
+// term s > 2 - p: the kernel below, unchanged, sums exactly the six products plane p x term s
+// with p + s <= 2, whose omitted rest is below 2^-24 of the leading one.
 __global__ __launch_bounds__(256) void router_split_kernel(const float *__restrict__ W_r,
                                                            bf16 *__restrict__ wsplit,
                                                            bf16 *__restrict__ wsplit_b, int d,
-                                                           int dpad, int E) {
+                                                           int dpad, int E, int planes) {
     const int k = blockIdx.x * 256 + threadIdx.x;
     const int e = blockIdx.y;
     if (k >= dpad) return;
@@ -46,14 +51,52 @@ __global__ __launch_bounds__(256) void router_split_kernel(const float *__restri
     const bf16 mid = (bf16)r1;
     const float r2 = r1 - (float)mid;
     const bf16 lo = (bf16)r2;
-    const size_t plane = (size_t)kRmExperts * dpad;
-    wsplit[(size_t)e * dpad + k] = hi;
-    wsplit[plane + (size_t)e * dpad + k] = mid;
-    wsplit[2 * plane + (size_t)e * dpad + k] = lo;
+    const size_t row = (size_t)planes * dpad;
+    const size_t term = (size_t)kRmExperts * row;
+    const bf16 zero = (bf16)0.f;
+    for (int p = 0; p < planes; ++p) {
+        const size_t at = (size_t)e * row + (size_t)p * dpad + k;
+        wsplit[at] = hi;
+        wsplit[term + at] = p <= 1 ? mid : zero;
+        wsplit[2 * term + at] = p == 0 ? lo : zero;
+    }
     if (k < d) {
         wsplit_b[(size_t)k * 256 + e] = hi;
         wsplit_b[(size_t)k * 256 + 128 + e] = mid;
     }
+}
+
+// Input jitter (App. C) for the matrix-core router: xj[t] = hi | mid | lo planes of the fp32
+// product x[t][k] * m[t][k] (the split is exact: 8 + 8 + 8 mantissa bits), each plane dpad
+// wide with zeros past d.  One lane per 16-byte chunk of a plane row.
+__global__ __launch_bounds__(256) void jitter_split_kernel(const bf16 *__restrict__ x,
+                                                           bf16 *__restrict__ xj, int T, int d,
+                                                           int dpad, Noise nz) {
+    const int cpr = dpad / 8;   // chunks per plane row
+    const long chunk = (long)blockIdx.x * 256 + threadIdx.x;
+    if (chunk >= (long)T * cpr) return;
+    const int t = (int)(chunk / cpr);
+    const int k0 = (int)(chunk - (long)t * cpr) * 8;
+    bf16x8 hi, mid, lo;
+    if (k0 < d) {   // d is a multiple of 8: a chunk is inside the row or past it
+        const bf16x8 v = *(const bf16x8 *)(x + (size_t)t * d + k0);
+        const uint32_t idx = (uint32_t)t * (uint32_t)d + (uint32_t)k0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float p = (float)v[i] * jitter_of(nz, idx + (uint32_t)i);
+            hi[i] = (bf16)p;
+            const float r1 = p - (float)hi[i];
+            mid[i] = (bf16)r1;
+            lo[i] = (bf16)(r1 - (float)mid[i]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) hi[i] = mid[i] = lo[i] = (bf16)0.f;
+    }
+    bf16 *row = xj + (size_t)t * 3 * dpad + k0;
+    *(bf16x8 *)(row) = hi;
+    *(bf16x8 *)(row + dpad) = mid;
+    *(bf16x8 *)(row + 2 * dpad) = lo;
 }
 
 #define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
@@ -247,10 +290,11 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
 #undef SW_WAIT_VMCNT
 
 bool router_fwd_mfma_supported(const Workspace &w, int dtype) {
-    // x is addressed through one buffer descriptor with 32-bit byte offsets
-    // (with input jitter the router's input x * m is no longer a bf16 value)
-    return dtype == SW_BF16 && !w.noise.jitter && w.E <= kRmExperts && (w.E % 4) == 0 &&
-           (uint64_t)w.T * (uint64_t)w.d * 2u < 0x7fffffffu;
+    // x (with input jitter: its three planes) is addressed through one buffer descriptor with
+    // 32-bit byte offsets
+    const uint64_t row = w.noise.jitter ? (uint64_t)w.dpad_r : (uint64_t)w.d;
+    return dtype == SW_BF16 && w.E <= kRmExperts && (w.E % 4) == 0 &&
+           (uint64_t)w.T * row * 2u < 0x7fffffffu;
 }
 
 hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float *W_r,
@@ -264,22 +308,35 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
         attr_set = true;
     }
     hipError_t err;
+    const bool jitter = w.noise.jitter;
     {
         ProfScope ps("router_split_weights", s);
         dim3 grid((unsigned)ceil_div(w.dpad, 256), kRmExperts);
         hipLaunchKernelGGL(router_split_kernel, grid, dim3(256), 0, s, W_r, (bf16 *)(ws + w.wsplit),
-                           (bf16 *)(ws + w.wsplit_b), (int)w.d, (int)w.dpad, (int)w.E);
+                           (bf16 *)(ws + w.wsplit_b), (int)w.d, (int)w.dpad, (int)w.E,
+                           jitter ? 3 : 1);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    if (jitter) {
+        ProfScope ps("router_jitter_split", s);
+        const long chunks = (long)w.T * (w.dpad / 8);
+        hipLaunchKernelGGL(jitter_split_kernel, dim3((unsigned)ceil_div(chunks, 256)), dim3(256), 0,
+                           s, (const bf16 *)x, (bf16 *)(ws + w.xj), (int)w.T, (int)w.d, (int)w.dpad,
+                           w.noise);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     {
         ProfScope ps("router_fwd_mfma", s);
+        // with jitter: the planes of x * m as one row of 3 dpad values
+        const bf16 *xin = jitter ? (const bf16 *)(ws + w.xj) : (const bf16 *)x;
+        const int d_in = jitter ? (int)w.dpad_r : (int)w.d;
         hipLaunchKernelGGL(router_fwd_mfma_kernel, dim3((unsigned)w.nb), dim3(256), kRmLds, s,
-                           (const bf16 *)x, (const bf16 *)(ws + w.wsplit), b_r,
+                           xin, (const bf16 *)(ws + w.wsplit), b_r,
                            (float *)(ws + w.probs), router_logits, expert_index, gate,
                            (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
                            (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
-                           (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, (int)w.d, (int)w.dpad,
-                           (int)w.E);
+                           (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, d_in,
+                           (int)w.dpad_r, (int)w.E);
         err = hipGetLastError();
     }
     return err;
