@@ -110,8 +110,8 @@ typedef struct {
  *   jitter  (s = 1, idx = t * d_model + k):  m = fma(2 eps, (z >> 8) * 2^-24, 1 - eps) in fp32
  *   dropout (s = 2, idx = t * d_ff + j, t the token -- not its slot):  hidden unit j of
  *           token t is zeroed iff z < floor(rate * 2^32)
- * With jitter_eps > 0 the router's two contractions run on the vector ALUs in both
- * precisions (the products x * m are no longer bf16 values).
+ * With jitter_eps > 0 and bf16 tokens the workspace also holds x * m as three bf16 planes
+ * (6 * T * d_model bytes, d_model rounded up to a multiple of 32).
  */
 
 /* Expert capacity, Eq. 3, rounded down:
