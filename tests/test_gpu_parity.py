@@ -481,6 +481,21 @@ def test_no_token_left_behind(dtype, T, d, f, E, cf, n, bias, rounds, ffn):
     assert np.bincount(key, minlength=n * E).max() <= fwd["capacity"]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_groups_of_two_tokens(dtype):
+    """The smallest routing groups: two tokens each, one slot per (group, expert); with a
+    re-routing stage the second token of a pair that collides moves to the other expert."""
+    from parity import compare_full
+    s = SwitchShape("t", 2048, 64, 72, 2, 1.0, dtype=dtype, seed_index=91, n_groups=1024)
+    inp = make_inputs(s, _dev())
+    errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.6)
+    assert fwd["capacity"] == 1 and 0 < gpu["dropped"].sum() < 1024
+    _report("groups of two", errs)
+    errs, gpu2, _, _ = compare_full(s.with_(ntlb_rounds=1), inp, d_aux=0.6)
+    assert gpu2["dropped"].sum() == 0          # two tokens, two experts with one slot each
+    _report("groups of two + re-routing", errs)
+
+
 def test_no_token_left_behind_full_size():
     from parity import compare_sampled
     s = CONFIGS["base_cf1.0"].with_(ntlb_rounds=2)
