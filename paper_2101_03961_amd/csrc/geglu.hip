@@ -22,7 +22,7 @@ struct NormalOf {
 };
 __device__ __forceinline__ NormalOf normal_of(float u) {
     const float z = fabsf(u) * 0.70710678f;
-    const float t = __frcp_rn(fmaf(0.3275911f, z, 1.0f));
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));   // 1 ulp: far inside the error of the fit
     const float e = __expf(-z * z);
     float poly = fmaf(1.061405429f, t, -1.453152027f);
     poly = fmaf(poly, t, 1.421413741f);
