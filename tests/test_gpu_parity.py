@@ -282,16 +282,23 @@ def test_relu_decision_at_a_zero_preactivation():
     assert all(abs(h) < 1e-5 for _, _, h in near)
 
 
-def test_step_can_be_captured_in_a_graph():
+@pytest.mark.parametrize("options", [
+    {},
+    dict(ffn="geglu", expert_dropout=0.1, jitter_eps=0.01, noise_seed=3, ntlb_rounds=2),
+])
+def test_step_can_be_captured_in_a_graph(options):
     """Forward + backward recorded once and replayed: every replay, with eager work and
     synchronisation between them, reproduces the eager result bit for bit (the library launches
     only kernels: no allocation, no memset node, no host synchronisation)."""
     import torch
     from paper_2101_03961_amd.layer import SwitchLayer
-    s = SwitchShape("t", 3000, 256, 512, 12, 1.0, dtype="bf16", seed_index=58, n_groups=2)
+    s = SwitchShape("t", 3000, 256, 512, 12, 1.0, dtype="bf16", seed_index=58, n_groups=2,
+                    **options)
     inp = make_inputs(s, _dev())
     layer = SwitchLayer(s.T, s.d_model, s.d_ff, s.E, s.capacity_factor, s.alpha, s.dtype,
-                        device=_dev(), n_groups=s.n_groups)
+                        device=_dev(), n_groups=s.n_groups, ffn=s.ffn,
+                        expert_dropout=s.expert_dropout, jitter_eps=s.jitter_eps,
+                        seed=s.noise_seed, ntlb_rounds=s.ntlb_rounds)
     layer.alloc_grads(with_bias=False)
     names = ("y", "dx", "dW_r", "dW_in", "dW_out", "aux_loss", "expert_counts", "gate", "dropped")
 
