@@ -87,7 +87,8 @@ typedef struct {
        given the same three values; change the seed from step to step. */
     float expert_dropout;    /* Sec. 2.4: rate in [0, 1) at which the hidden activations
                                 ReLU(x W_in) of every expert are zeroed; survivors are
-                                scaled by 1 / (1 - rate)                             */
+                                scaled by 1 / (1 - rate).  Takes effect rounded down to a
+                                multiple of 2^-16                                     */
     float jitter_eps;        /* App. C input jitter: the router (and only the router)
                                 sees x[t][k] * m, m uniform in [1 - eps, 1 + eps);
                                 eps in [0, 1)                                         */
@@ -108,8 +109,10 @@ typedef struct {
  *     z *= 0xC2B2AE3D;  z ^= z >> 16;            (all arithmetic modulo 2^32)
  * with seed_lo / seed_hi the two halves of seed.
  *   jitter  (s = 1, idx = t * d_model + k):  m = fma(2 eps, (z >> 8) * 2^-24, 1 - eps) in fp32
- *   dropout (s = 2, idx = t * d_ff + j, t the token -- not its slot):  hidden unit j of
- *           token t is zeroed iff z < floor(rate * 2^32)
+ *   dropout (s = 2):  hidden unit j of token t (the token -- not its slot) is element
+ *           i = t * d_ff + j; it takes 16 bits of the z drawn for idx = i / 2 -- z & 0xFFFF if
+ *           i is even, z >> 16 if odd -- and is zeroed iff they are < thr = floor(rate * 2^16);
+ *           survivors are scaled by 2^16 / (2^16 - thr)
  * With jitter_eps > 0 and bf16 tokens the workspace also holds x * m as three bf16 planes
  * (6 * T * d_model bytes, d_model rounded up to a multiple of 32).
  */

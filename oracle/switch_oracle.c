@@ -39,7 +39,8 @@
  *       the appendix listing instead adds the noise to the logits -- the text is followed):
  *       the router sees x[t][k] * m, m uniform in [1 - eps, 1 + eps), the experts see x;
  *       expert dropout (Sec. 2.4): the hidden activation ReLU(h) of every expert is dropped
- *       with the given rate and the survivors are scaled by 1 / (1 - rate).
+ *       with the given rate (rounded down to a multiple of 2^-16) and the survivors are
+ *       scaled by 1 / (1 - that rate).
  *     The random numbers come from a counter-based generator defined here (swo_mix): a
  *     32-bit mixing function of (seed, stream, element index), so that any implementation
  *     can reproduce every draw from the element's coordinates alone.
@@ -104,13 +105,18 @@ static double jitter_mult(const swo_noise *nz, int64_t t, int64_t d, int64_t k) 
     float u = (float)(z >> 8) * 0x1p-24f;
     return (double)fmaf(2.0f * nz->jitter_eps, u, 1.0f - nz->jitter_eps);
 }
-/* dropout factor of hidden unit j of token t: 0 (dropped) or 1 / (1 - rate) */
+/* dropout factor of hidden unit j of token t: 0 (dropped) or 1 / (1 - rate'), rate' = the
+ * rate rounded down to a multiple of 2^-16.  Element idx = t f + j (wrapping 32-bit) takes 16
+ * of the 32 bits drawn for the pair idx / 2 -- the low half if idx is even, the high half if
+ * odd -- and is dropped iff they are below rate' 2^16; survivors are scaled so that the
+ * expectation is exactly the undropped value. */
 static double dropout_factor(const swo_noise *nz, int64_t t, int64_t f, int64_t j) {
     if (!nz || nz->expert_dropout <= 0.0f) return 1.0;
-    uint32_t thr = (uint32_t)floor((double)nz->expert_dropout * 4294967296.0);
-    uint32_t z = swo_mix((uint32_t)((uint64_t)t * (uint64_t)f + (uint64_t)j), SWO_STREAM_DROPOUT,
-                         nz->seed);
-    return z >= thr ? 1.0 / (1.0 - (double)nz->expert_dropout) : 0.0;
+    uint32_t thr = (uint32_t)floor((double)nz->expert_dropout * 65536.0);
+    uint32_t idx = (uint32_t)((uint64_t)t * (uint64_t)f + (uint64_t)j);
+    uint32_t z = swo_mix(idx >> 1, SWO_STREAM_DROPOUT, nz->seed);
+    uint32_t h = (idx & 1u) ? z >> 16 : z & 0xFFFFu;
+    return h >= thr ? 65536.0 / (65536.0 - (double)thr) : 0.0;
 }
 /* exported for the tests */
 double swo_jitter_mult(const swo_noise *nz, int64_t t, int64_t d, int64_t k) {

@@ -633,11 +633,17 @@ def test_dropout_factor_values_and_keep_fraction(rate):
     T, f = 300, 200
     nz = (rate, 0.0, 77)
     q = np.array([[oracle.dropout_factor(nz, t, f, j) for j in range(f)] for t in range(T)])
-    scale = 1.0 / (1.0 - float(np.float32(rate)))
+    thr = int(np.floor(float(np.float32(rate)) * 65536.0))       # the rate takes effect in steps of 2^-16
+    eff = thr / 65536.0
+    assert abs(eff - rate) < 2.0 ** -16
+    scale = 65536.0 / (65536.0 - thr)
     assert set(np.unique(q)) == {0.0, scale}
     keep = (q > 0).mean()
-    assert abs(keep - (1 - rate)) < 4 * np.sqrt(rate * (1 - rate) / (T * f))
-    assert abs(q.mean() - 1.0) < 4 * scale * np.sqrt(rate * (1 - rate) / (T * f))   # unbiased
+    assert abs(keep - (1 - eff)) < 4 * np.sqrt(eff * (1 - eff) / (T * f))
+    assert abs(q.mean() - 1.0) < 4 * scale * np.sqrt(eff * (1 - eff) / (T * f))   # unbiased
+    # the two units of a pair (they share one 32-bit draw) are independent
+    k = (q > 0).astype(np.float64)
+    assert abs(np.corrcoef(k[:, 0::2].ravel(), k[:, 1::2].ravel())[0, 1]) < 4.5 / np.sqrt(T * f / 2)
     # rows and columns are not systematically different
     assert abs((q > 0).mean(0) - (1 - rate)).max() < 5 * np.sqrt(rate * (1 - rate) / T)
     assert abs((q > 0).mean(1) - (1 - rate)).max() < 5 * np.sqrt(rate * (1 - rate) / f)
