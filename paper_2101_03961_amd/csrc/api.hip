@@ -98,8 +98,8 @@ Workspace layout_workspace(const switch_config *cfg) {
     nz.dropout_term = seed_hi + 2u * 0x7F4A7C15u;
     nz.dropout = cfg->expert_dropout > 0.f;
     nz.jitter = cfg->jitter_eps > 0.f;
-    nz.drop_thr = (uint32_t)floor((double)cfg->expert_dropout * 4294967296.0);
-    nz.drop_scale = (float)(1.0 / (1.0 - (double)cfg->expert_dropout));
+    nz.drop_thr = (uint32_t)floor((double)cfg->expert_dropout * 65536.0);
+    nz.drop_scale = (float)(65536.0 / (65536.0 - (double)nz.drop_thr));
     nz.jitter_eps = cfg->jitter_eps;
     const bool jit_mfma = nz.jitter && cfg->act_dtype == SW_BF16;
     w.dpad_r = jit_mfma ? 3 * w.dpad : w.dpad;

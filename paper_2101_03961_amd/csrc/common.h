@@ -52,8 +52,8 @@ struct Noise {
     uint32_t seed_lo;
     uint32_t jitter_term;    // seed_hi + stream constant of the jitter stream
     uint32_t dropout_term;   // seed_hi + stream constant of the dropout stream
-    uint32_t drop_thr;       // a hidden unit is dropped iff its 32 bits are < drop_thr
-    float drop_scale;        // 1 / (1 - rate); 1 when dropout is off
+    uint32_t drop_thr;       // a hidden unit is dropped iff its 16 bits are < drop_thr = floor(rate 2^16)
+    float drop_scale;        // 2^16 / (2^16 - drop_thr); 1 when dropout is off
     float jitter_eps;
     int dropout, jitter;     // on / off
 };
@@ -70,9 +70,21 @@ __device__ __forceinline__ float jitter_of(const Noise &nz, uint32_t idx) {
     const float u = (float)(noise_bits(idx, nz.seed_lo, nz.jitter_term) >> 8) * 0x1p-24f;
     return fmaf(2.0f * nz.jitter_eps, u, 1.0f - nz.jitter_eps);
 }
+// Expert dropout: the 32 bits drawn for pair i (hidden units 2 i and 2 i + 1 of the flattened
+// [token][unit] index) decide both, 16 bits each
+__device__ __forceinline__ uint32_t dropout_pair_bits(const Noise &nz, uint32_t pair) {
+    return noise_bits(pair, nz.seed_lo, nz.dropout_term);
+}
+__device__ __forceinline__ bool dropout_keeps_even(const Noise &nz, uint32_t z) {
+    return (z & 0xFFFFu) >= nz.drop_thr;
+}
+__device__ __forceinline__ bool dropout_keeps_odd(const Noise &nz, uint32_t z) {
+    return (z >> 16) >= nz.drop_thr;
+}
 // hidden unit idx = t * f + j survives expert dropout
 __device__ __forceinline__ bool dropout_keeps(const Noise &nz, uint32_t idx) {
-    return noise_bits(idx, nz.seed_lo, nz.dropout_term) >= nz.drop_thr;
+    const uint32_t z = dropout_pair_bits(nz, idx >> 1);
+    return (idx & 1u) ? dropout_keeps_odd(nz, z) : dropout_keeps_even(nz, z);
 }
 
 // ---- workspace layout (byte offsets into the caller's workspace) ------------

@@ -70,9 +70,13 @@ __global__ __launch_bounds__(256) void geglu_kernel(const XT *__restrict__ H,
     for (int i = 0; i < kGegluChunk; ++i) q[i] = 1.f;
     if (nz.dropout) {
         const uint32_t idx = (uint32_t)slot_token[slot] * (uint32_t)f + (uint32_t)j0;
+        // j0 is a multiple of the chunk and f is even: the chunk is whole aligned pairs
 #pragma unroll
-        for (int i = 0; i < kGegluChunk; ++i)
-            q[i] = dropout_keeps(nz, idx + (uint32_t)i) ? nz.drop_scale : 0.f;
+        for (int i = 0; i < kGegluChunk; i += 2) {
+            const uint32_t z = dropout_pair_bits(nz, (idx + (uint32_t)i) >> 1);
+            q[i] = dropout_keeps_even(nz, z) ? nz.drop_scale : 0.f;
+            q[i + 1] = dropout_keeps_odd(nz, z) ? nz.drop_scale : 0.f;
+        }
     }
     if (!BACKWARD) {
         V a;

@@ -419,12 +419,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                         if (EPI_BASE == EPI_RELU) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
-                            if (DROP) {
+                            if (DROP) {   // the lane's four units are two aligned pairs
+                                const uint32_t first = drop_row + (uint32_t)(i * 32 + g * 8);
 #pragma unroll
-                                for (int r = 0; r < 4; ++r)
-                                    v[r] = dropout_keeps(a.nz, drop_row + (uint32_t)(i * 32 + g * 8 + r))
-                                               ? v[r] * a.nz.drop_scale
-                                               : 0.f;
+                                for (int h = 0; h < 2; ++h) {
+                                    const uint32_t z = dropout_pair_bits(a.nz, (first >> 1) + (uint32_t)h);
+                                    v[2 * h] = dropout_keeps_even(a.nz, z) ? v[2 * h] * a.nz.drop_scale : 0.f;
+                                    v[2 * h + 1] =
+                                        dropout_keeps_odd(a.nz, z) ? v[2 * h + 1] * a.nz.drop_scale : 0.f;
+                                }
                             }
                         }
                         if (DROP && EPI_BASE == EPI_MASK) {
