@@ -106,7 +106,8 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     float *__restrict__ probs, float *__restrict__ logits_out, int32_t *__restrict__ idx_out,
     float *__restrict__ gate_out, int32_t *__restrict__ idx_ws, float *__restrict__ gate_ws,
     int32_t *__restrict__ local_rank, int32_t *__restrict__ block_counts,
-    float *__restrict__ block_psum, int nbg, int Tg, int d, int dpad, int E) {
+    float *__restrict__ block_psum, int nbg, int Tg, int d, int dpad, int E,
+    int plane_steps /* k steps per plane of the input: dpad / 32, or a third of it with jitter */) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -143,13 +144,17 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const char *st = lds + (kt % kRmStages) * kRmStageBytes;
+        // plane p of a jittered input meets only the weight terms s <= 2 - p (the others are
+        // stored as zeros); without jitter there is one plane and all three terms count
+        const int last_term = 2 - kt / plane_steps;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             bf16x8 fx[2];
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) fx[tt] = ox.read_frag(st, tt, ks);
 #pragma unroll
-            for (int s = 0; s < 3; ++s)
+            for (int s = 0; s < 3; ++s) {
+                if (s > last_term) continue;   // uniform
 #pragma unroll
                 for (int et = 0; et < 4; ++et) {
                     const bf16x8 fw = ow.read_frag(st + kRmXBytes, s * 4 + et, ks);
@@ -157,6 +162,7 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
                     for (int tt = 0; tt < 2; ++tt)
                         acc[tt][et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx[tt], acc[tt][et], 0, 0, 0);
                 }
+            }
         }
         // step kt+1 has landed (step kt+2 may still fly); after the barrier stage kt is free
         SW_WAIT_VMCNT(10);
@@ -336,7 +342,7 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
                            (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
                            (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
                            (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, d_in,
-                           (int)w.dpad_r, (int)w.E);
+                           (int)w.dpad_r, (int)w.E, (int)(w.dpad / 32));
         err = hipGetLastError();
     }
     return err;
