@@ -21,6 +21,10 @@
  *     detected on the host before anything is launched; nothing is thrown
  *     across the ABI.  Inputs must be finite (NaN/Inf behaviour unspecified).
  *   - Gradients are overwritten, not accumulated.
+ *   - The library keeps no state between calls apart from what the workspace holds; with
+ *     profiling off, calls from several host threads may run at once if each has its own
+ *     workspace, outputs and stream.  One device per process is assumed (the launch width
+ *     is taken from the device that is current at the first call).
  *   - An empty batch (T = 0) is legal: forward writes expert_counts = 0 and
  *     aux_loss = 0 (both fractions of Eq. 4 are empty sums), backward writes
  *     zeros to dW_r, db_r, dW_in, dW_out; the per-token arguments and the
