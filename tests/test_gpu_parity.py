@@ -194,6 +194,36 @@ def test_run_to_run_determinism():
         assert np.array_equal(a[k], b[k]), k
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scaling_and_expert_permutation_properties(dtype):
+    """Properties of the GPU path alone.  Doubling W_out doubles y exactly (a power of two
+    changes no rounding).  Renumbering the experts (columns of W_r, blocks of W_in / W_out)
+    renumbers expert_index and the counts and leaves every token's slot; gate and output move
+    only by the rounding of the softmax sum taken in another order."""
+    from parity import run_gpu
+    s = SwitchShape("t", 3000, 128, 264, 12, 1.0, dtype=dtype, seed_index=92)
+    inp = make_inputs(s, _dev())
+    _, a = run_gpu(s, inp, backward=False)
+    doubled = dict(inp, W_out=inp["W_out"] * 2)
+    _, b = run_gpu(s, doubled, backward=False)
+    assert np.array_equal(b["y"], 2 * a["y"])
+    for k in ("expert_index", "gate", "dropped", "position_in_expert", "aux_loss"):
+        assert np.array_equal(a[k], b[k]), k
+    perm = torch.randperm(s.E, generator=torch.Generator().manual_seed(5)).to(_dev())
+    shuffled = dict(inp, W_r=inp["W_r"][:, perm].contiguous(), W_in=inp["W_in"][perm].contiguous(),
+                    W_out=inp["W_out"][perm].contiguous())
+    _, c = run_gpu(s, shuffled, backward=False)
+    p = perm.cpu().numpy()
+    assert np.array_equal(p[c["expert_index"]], a["expert_index"])
+    assert np.array_equal(c["expert_counts"], a["expert_counts"][p])
+    for k in ("dropped", "position_in_expert"):
+        assert np.array_equal(a[k], c[k]), k
+    np.testing.assert_allclose(c["gate"], a["gate"], rtol=5e-7, atol=0)
+    ulp = 2.0 ** -7 if dtype == "bf16" else 1e-6          # one rounding step of the storage type
+    np.testing.assert_allclose(c["y"], a["y"], rtol=ulp, atol=1e-30)
+    assert abs(float(a["aux_loss"][0]) - float(c["aux_loss"][0])) <= 1e-6 * abs(float(a["aux_loss"][0]))
+
+
 @pytest.mark.parametrize("dtype,T,d,f,E,cf,n", [
     ("bf16", 16384, 64, 64, 4096, 2.0, 1),  # the largest expert count the library takes
     ("f32", 3000, 32, 48, 1000, 3.0, 1),
