@@ -25,6 +25,7 @@ struct GemmF32Args {
 
 constexpr int kF32Tile = 64;
 constexpr int kF32KC = 16;
+constexpr int kF32Flush = 256;   // products per chain of the two-level sum
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args a) {
     __shared__ float qs[kF32KC][kF32Tile + 4];
@@ -40,12 +41,24 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args a) {
     const float *P = a.P + (size_t)e * a.p_batch;
     const int tid = threadIdx.x;
     const int tx = tid % 16, ty = tid / 16;
-    float acc[4][4];
+    // Two-level sums: a running chain of at most kF32Flush products is folded into a total, so
+    // that the rounding error of a long reduction (thousands of slots in a weight gradient)
+    // grows with the square roots of the two lengths instead of with the whole length.
+    float acc[4][4], total[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        for (int j = 0; j < 4; ++j) acc[i][j] = total[i][j] = 0.f;
     for (int k0 = 0; k0 < klim; k0 += kF32KC) {
+        if (k0 != 0 && k0 % kF32Flush == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    total[i][j] += acc[i][j];
+                    acc[i][j] = 0.f;
+                }
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int id = tid + i * 256;
@@ -88,7 +101,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args a) {
         for (int j = 0; j < 4; ++j) {
             const int p = p0 + tx * 4 + j;
             if (p >= a.Pdim) continue;
-            float v = acc[i][j];
+            float v = total[i][j] + acc[i][j];
             if (a.epi == 1) {
                 v = v > 0.f ? v : 0.f;
                 if (a.nz.dropout)   // Sec. 2.4: expert dropout on the hidden activation

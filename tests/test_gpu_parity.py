@@ -239,6 +239,16 @@ def test_many_experts(dtype, T, d, f, E, cf, n):
     _report("E=%d" % E, errs)
 
 
+def test_fp32_long_reduction():
+    """One expert holding 17 576 tokens: each weight-gradient element is a sum over all of them,
+    which the fp32 path takes in two levels (a single fp32 chain drifts past 1e-5 here)."""
+    from parity import compare_full
+    s = SwitchShape("t", 17576, 292, 152, 1, 1.25, dtype="f32", seed_index=61, n_groups=8)
+    errs = compare_full(s, make_inputs(s, _dev()), d_aux=0.5)[0]
+    _report("fp32, 17576 tokens in one expert", errs)
+    assert errs["dW_in"] < 2e-6 and errs["dW_out"] < 2e-6
+
+
 def test_random_shapes():
     """Seeded sweep over token counts, widths, expert counts, capacity factors, group counts
     and both storage types: every tile edge and kernel variant at sizes the full oracle takes
