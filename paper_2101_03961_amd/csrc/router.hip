@@ -390,6 +390,55 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
     }
 }
 
+// The same for the matrix-core backward (E <= 128, E % 4 == 0): a lane owns the two adjacent
+// experts 2 lane and 2 lane + 1, so a wave reads a probability row with one 8-byte load per
+// lane and writes the bf16 hi | lo halves as 4-byte pairs; four tokens per wave at once.
+__global__ __launch_bounds__(256) void router_dlogits_pair_kernel(
+    const float *__restrict__ probs, const int32_t *__restrict__ idx,
+    const float *__restrict__ dgate, const int32_t *__restrict__ counts_g /* [n][E] */,
+    float *__restrict__ dlogits /* [T][E] or nullptr */, bf16 *__restrict__ dl_split /* [T][256] */,
+    int T, int Tg, int E, float aux_scale) {
+    typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    constexpr int kTok = 4;
+    const float mean_count = (float)Tg / (float)E;
+    const int lane = threadIdx.x % kWave;
+    const int t_first = (blockIdx.x * (256 / kWave) + threadIdx.x / kWave) * kTok;
+    const int e0 = 2 * lane;
+    const bool live = e0 < E;   // E is even: both experts of the lane or neither
+    float2 p[kTok], dp[kTok];
+    float s[kTok];
+#pragma unroll
+    for (int u = 0; u < kTok; ++u) {
+        const int t = t_first + u;
+        s[u] = 0.f;
+        p[u] = dp[u] = make_float2(0.f, 0.f);
+        if (t >= T || !live) continue;
+        const int me = idx[t];
+        const float dg = dgate[t];
+        const int2 c = *(const int2 *)(counts_g + (size_t)(t / Tg) * E + e0);
+        p[u] = *(const float2 *)(probs + (size_t)t * E + e0);
+        dp[u].x = aux_scale * ((float)c.x - mean_count) + (me == e0 ? dg : 0.f);
+        dp[u].y = aux_scale * ((float)c.y - mean_count) + (me == e0 + 1 ? dg : 0.f);
+        s[u] = p[u].x * dp[u].x + p[u].y * dp[u].y;
+    }
+#pragma unroll
+    for (int u = 0; u < kTok; ++u) s[u] = wave_sum(s[u]);
+#pragma unroll
+    for (int u = 0; u < kTok; ++u) {
+        const int t = t_first + u;
+        if (t >= T) continue;
+        const float2 dl = make_float2(p[u].x * (dp[u].x - s[u]), p[u].y * (dp[u].y - s[u]));   // 0 past E
+        if (dlogits && live) *(float2 *)(dlogits + (size_t)t * E + e0) = dl;
+        bf16x2 hi, lo;
+        hi[0] = (bf16)dl.x;
+        hi[1] = (bf16)dl.y;
+        lo[0] = (bf16)(dl.x - (float)hi[0]);
+        lo[1] = (bf16)(dl.y - (float)hi[1]);
+        *(bf16x2 *)(dl_split + (size_t)t * 256 + e0) = hi;        // all 128 columns of each half
+        *(bf16x2 *)(dl_split + (size_t)t * 256 + 128 + e0) = lo;
+    }
+}
+
 // dW_r[k][j] = sum over splits of (part[s][k][j] + part[s][k][128 + j]), fixed order.
 // rows = rows of one split's part; second > 0: the operand had a second plane (input jitter:
 // x * m as hi + mid), whose rows start at `second` and are added in.
@@ -736,7 +785,13 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
                        s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),          \
                        (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts_g),        \
                        dlogits_out, dl_split, (int)w.T, (int)w.Tg, (int)w.E, aux_scale)
-        SW_DISPATCH_EPL(w.E, CALL);
+        if (mfma)
+            hipLaunchKernelGGL(router_dlogits_pair_kernel, dim3((unsigned)ceil_div(w.T, 16)), dim3(256),
+                               0, s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),
+                               (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts_g),
+                               dlogits_out, dl_split, (int)w.T, (int)w.Tg, (int)w.E, aux_scale);
+        else
+            SW_DISPATCH_EPL(w.E, CALL);
 #undef CALL
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
