@@ -103,7 +103,8 @@ Workspace layout_workspace(const switch_config *cfg) {
     nz.jitter_eps = cfg->jitter_eps;
     const bool jit_mfma = nz.jitter && cfg->act_dtype == SW_BF16;
     w.dpad_r = jit_mfma ? 3 * w.dpad : w.dpad;
-    w.wsplit = take((size_t)3 * 128 * w.dpad_r * 2);
+    w.etiles = ceil_div(w.E, 128);
+    w.wsplit = take((size_t)w.etiles * 3 * 128 * w.dpad_r * 2);
     w.wsplit_b = take(d * 256 * 2);
     w.dl_split = take(T * 256 * 2);
     w.xj = take(jit_mfma ? T * (size_t)w.dpad_r * 2 : 0);

@@ -127,7 +127,8 @@ struct Workspace {
     size_t dlogits;             // f32 [T][E]
     size_t dWr_part;            // f32 [nsplit][d][E]  split-T partial sums of dW_r
     size_t dbr_part;            // f32 [ceil(T / 256)][E]  per-256-token sums of dlogits
-    size_t wsplit;              // bf16 [3][128][dpad_r]  W_r^T as three bf16 terms (MFMA router)
+    int64_t etiles;             // tiles of 128 experts: ceil(E / 128)
+    size_t wsplit;              // bf16 [etiles][3][128][dpad_r]  W_r^T as three bf16 terms (MFMA router)
     int64_t dpad;               // d rounded up to a multiple of 32
     int64_t dpad_r;             // k extent of the MFMA router: dpad, or 3 dpad with input jitter
                                 // (the jittered input as three bf16 planes side by side)
@@ -175,6 +176,11 @@ hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const
                              float *router_logits, hipStream_t s);
 // The same on bf16 MFMA (bf16 x, E <= 128, E % 4 == 0): see router_mfma.hip.
 bool router_fwd_mfma_supported(const Workspace &w, int dtype);
+bool router_bwd_mfma_supported(const Workspace &w, int dtype);
+// softmax, arg max, gate, ranks and block statistics from the logits left in the
+// probability buffer (the second half of launch_router_fwd)
+hipError_t launch_router_softmax(const Workspace &w, char *ws, int32_t *expert_index, float *gate,
+                                 float *router_logits, hipStream_t s);
 hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float *W_r,
                                   const float *b_r, char *ws, int32_t *expert_index, float *gate,
                                   float *router_logits, hipStream_t s);

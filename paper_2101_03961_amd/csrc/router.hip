@@ -725,12 +725,16 @@ hipError_t launch_router_fwd(const Workspace &w, int dtype, const void *x, const
                                (int)w.d, (int)w.E, w.noise);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
-    {
-        ProfScope ps("router_softmax_top1", s);
+    return launch_router_softmax(w, ws, expert_index, gate, router_logits, s);
+}
+
+hipError_t launch_router_softmax(const Workspace &w, char *ws, int32_t *expert_index, float *gate,
+                                 float *router_logits, hipStream_t s) {
+    hipError_t err = hipSuccess;
+    ProfScope ps("router_softmax_top1", s);
 #define CALL(N) err = softmax_launch<N>(w, ws, expert_index, gate, router_logits, s)
-        SW_DISPATCH_EPL(w.E, CALL);
+    SW_DISPATCH_EPL(w.E, CALL);
 #undef CALL
-    }
     return err;
 }
 
@@ -770,8 +774,7 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
     // bf16 tokens and up to 128 experts: the two contractions run on the matrix cores
     // (dl and W_r as two bf16 terms each; x is bf16 already)
     // (the forward pass took the same path and left W_r's bf16 terms in the workspace)
-    const bool mfma = router_fwd_mfma_supported(w, sizeof(XT) == 2 ? SW_BF16 : SW_F32) &&
-                      (uint64_t)w.T * 512u < 0x7fffffffu;
+    const bool mfma = router_bwd_mfma_supported(w, sizeof(XT) == 2 ? SW_BF16 : SW_F32);
     bf16 *dl_split = mfma ? (bf16 *)(ws + w.dl_split) : nullptr;
     // the fp32 copy is read only by the vector-ALU contractions and by the bias gradient
     float *dlogits_out = (mfma && !db_r) ? nullptr : dlogits;

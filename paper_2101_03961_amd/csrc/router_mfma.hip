@@ -29,8 +29,8 @@ constexpr int kRmPitch = kRmExperts + 4;               // floats per row of the 
 constexpr int kRmTileBytes = kRmTokens * kRmPitch * 4; // 132 KB
 constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + 4 * kRmExperts * 4;
 
-// W_r [d][E] fp32 -> wsplit [3][128][planes * dpad] bf16: term s of expert e, k contiguous;
-// rows of absent experts and columns past d are zero.  Also, for the backward
+// W_r [d][E] fp32 -> wsplit [tiles][3][128][planes * dpad] bf16: per tile of 128 experts, term
+// s of expert e, k contiguous; rows of absent experts and columns past d are zero.  Also, for the backward
 // pass, wsplit_b [d][256] bf16: row k holds hi(W_r[k][0..127]) | lo(...), where
 // hi + lo carries 16 mantissa bits.
 // planes = 3 (input jitter): the router's input x * m is no bf16 value any more and comes as
@@ -43,7 +43,8 @@ __global__ __launch_bounds__(256) void router_split_kernel(const float *__restri
                                                            bf16 *__restrict__ wsplit_b, int d,
                                                            int dpad, int E, int planes) {
     const int k = blockIdx.x * 256 + threadIdx.x;
-    const int e = blockIdx.y;
+    const int e = blockIdx.y;                 // 0 .. 128 * expert tiles
+    const int tile = e / kRmExperts, el = e - tile * kRmExperts;
     if (k >= dpad) return;
     float w = (k < d && e < E) ? W_r[(size_t)k * E + e] : 0.f;
     const bf16 hi = (bf16)w;
@@ -53,16 +54,17 @@ __global__ __launch_bounds__(256) void router_split_kernel(const float *__restri
     const bf16 lo = (bf16)r2;
     const size_t row = (size_t)planes * dpad;
     const size_t term = (size_t)kRmExperts * row;
+    bf16 *wt = wsplit + (size_t)tile * 3 * term;   // this expert tile's [3][128][row]
     const bf16 zero = (bf16)0.f;
     for (int p = 0; p < planes; ++p) {
-        const size_t at = (size_t)e * row + (size_t)p * dpad + k;
-        wsplit[at] = hi;
-        wsplit[term + at] = p <= 1 ? mid : zero;
-        wsplit[2 * term + at] = p == 0 ? lo : zero;
+        const size_t at = (size_t)el * row + (size_t)p * dpad + k;
+        wt[at] = hi;
+        wt[term + at] = p <= 1 ? mid : zero;
+        wt[2 * term + at] = p == 0 ? lo : zero;
     }
-    if (k < d) {
-        wsplit_b[(size_t)k * 256 + e] = hi;
-        wsplit_b[(size_t)k * 256 + 128 + e] = mid;
+    if (k < d && tile == 0) {   // the backward operand exists for one expert tile only
+        wsplit_b[(size_t)k * 256 + el] = hi;
+        wsplit_b[(size_t)k * 256 + 128 + el] = mid;
     }
 }
 
@@ -101,6 +103,11 @@ __global__ __launch_bounds__(256) void jitter_split_kernel(const bf16 *__restric
 
 #define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
 
+// FUSED (up to 128 experts): softmax, arg max, gate, ranks and block statistics follow in the
+// same kernel.  Otherwise the block computes the logits of expert tile blockIdx.y only and
+// writes them (plus bias) into the probability buffer, [T][E]; the softmax kernel of the
+// vector-ALU path takes over from there.
+template <bool FUSED>
 __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     const bf16 *__restrict__ x, const bf16 *__restrict__ wsplit, const float *__restrict__ b_r,
     float *__restrict__ probs, float *__restrict__ logits_out, int32_t *__restrict__ idx_out,
@@ -117,9 +124,11 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     int t0, tend;   // the block's tokens: [t0, tend), inside one routing group
     block_token_range(b, nbg, Tg, t0, tend);
 
+    const int e_base = FUSED ? 0 : (int)blockIdx.y * kRmExperts;   // first expert of the tile
     DirectOperand ox, ow;
     ox.init(x, d, t0, tend, d, lane, wave, wave * 64);
-    ow.init(wsplit, dpad, 0, 3 * kRmExperts, dpad, lane, wave, 0);
+    ow.init(wsplit + (size_t)(FUSED ? 0 : blockIdx.y) * 3 * kRmExperts * dpad, dpad, 0,
+            3 * kRmExperts, dpad, lane, wave, 0);
     const int nk = dpad / 32;
 
     f32x16 acc[2][4];
@@ -172,8 +181,36 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
     SW_WAIT_VMCNT(0);
     __syncthreads();
 
-    // ---- softmax, arg max, gate: lane and lane ^ 32 share a token -----------------
     float *ptile = (float *)lds;                                   // [256][kRmPitch]
+    if (!FUSED) {
+        // logits tile -> LDS -> whole 512-byte row segments of [T][E]
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const int tl = wave * 64 + tt * 32 + (lane & 31);
+#pragma unroll
+            for (int et = 0; et < 4; ++et)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int el = et * 32 + 8 * g + 4 * (lane >> 5);
+                    float4 v = make_float4(acc[tt][et][4 * g], acc[tt][et][4 * g + 1],
+                                           acc[tt][et][4 * g + 2], acc[tt][et][4 * g + 3]);
+                    if (b_r && e_base + el < E) {   // E is a multiple of 4: a group is in or out
+                        const float4 b = *(const float4 *)(b_r + e_base + el);
+                        v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+                    }
+                    *(float4 *)(ptile + tl * kRmPitch + el) = v;
+                }
+        }
+        __syncthreads();
+        const int nvalid = tend - t0;
+        const int c4 = (tid & 31) * 4;
+        for (int row = tid >> 5; row < nvalid; row += 8)
+            if (e_base + c4 < E)
+                *(float4 *)(probs + (size_t)(t0 + row) * E + e_base + c4) =
+                    *(const float4 *)(ptile + row * kRmPitch + c4);
+        return;
+    }
+    // ---- softmax, arg max, gate: lane and lane ^ 32 share a token -----------------
     int32_t *idx_s = (int32_t *)(lds + kRmTileBytes);              // [256]
     int32_t *hist = idx_s + kRmTokens;                             // [4][128]
     for (int i = tid; i < 4 * kRmExperts; i += 256) hist[i] = 0;   // one histogram per wave
@@ -295,12 +332,17 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
 }
 #undef SW_WAIT_VMCNT
 
+// The backward contractions on the matrix cores exist for one expert tile.
+bool router_bwd_mfma_supported(const Workspace &w, int dtype) {
+    return router_fwd_mfma_supported(w, dtype) && w.E <= kRmExperts &&
+           (uint64_t)w.T * 512u < 0x7fffffffu;
+}
+
 bool router_fwd_mfma_supported(const Workspace &w, int dtype) {
     // x (with input jitter: its three planes) is addressed through one buffer descriptor with
     // 32-bit byte offsets
     const uint64_t row = w.noise.jitter ? (uint64_t)w.dpad_r : (uint64_t)w.d;
-    return dtype == SW_BF16 && w.E <= kRmExperts && (w.E % 4) == 0 &&
-           (uint64_t)w.T * row * 2u < 0x7fffffffu;
+    return dtype == SW_BF16 && (w.E % 4) == 0 && (uint64_t)w.T * row * 2u < 0x7fffffffu;
 }
 
 hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float *W_r,
@@ -308,8 +350,11 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
                                   float *router_logits, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel,
+        hipError_t err = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel<true>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
+        if (err != hipSuccess) return err;
+        err = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel<false>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
         if (err != hipSuccess) return err;
         attr_set = true;
     }
@@ -317,7 +362,7 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
     const bool jitter = w.noise.jitter;
     {
         ProfScope ps("router_split_weights", s);
-        dim3 grid((unsigned)ceil_div(w.dpad, 256), kRmExperts);
+        dim3 grid((unsigned)ceil_div(w.dpad, 256), (unsigned)(kRmExperts * w.etiles));
         hipLaunchKernelGGL(router_split_kernel, grid, dim3(256), 0, s, W_r, (bf16 *)(ws + w.wsplit),
                            (bf16 *)(ws + w.wsplit_b), (int)w.d, (int)w.dpad, (int)w.E,
                            jitter ? 3 : 1);
@@ -336,15 +381,29 @@ hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float
         // with jitter: the planes of x * m as one row of 3 dpad values
         const bf16 *xin = jitter ? (const bf16 *)(ws + w.xj) : (const bf16 *)x;
         const int d_in = jitter ? (int)w.dpad_r : (int)w.d;
-        hipLaunchKernelGGL(router_fwd_mfma_kernel, dim3((unsigned)w.nb), dim3(256), kRmLds, s,
-                           xin, (const bf16 *)(ws + w.wsplit), b_r,
-                           (float *)(ws + w.probs), router_logits, expert_index, gate,
-                           (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
-                           (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
-                           (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, d_in,
-                           (int)w.dpad_r, (int)w.E, (int)(w.dpad / 32));
-        err = hipGetLastError();
+        if (w.etiles == 1) {
+            hipLaunchKernelGGL(router_fwd_mfma_kernel<true>, dim3((unsigned)w.nb), dim3(256), kRmLds,
+                               s, xin, (const bf16 *)(ws + w.wsplit), b_r, (float *)(ws + w.probs),
+                               router_logits, expert_index, gate, (int32_t *)(ws + w.idx),
+                               (float *)(ws + w.gate), (int32_t *)(ws + w.local_rank),
+                               (int32_t *)(ws + w.block_counts), (float *)(ws + w.block_psum),
+                               (int)w.nbg, (int)w.Tg, d_in, (int)w.dpad_r, (int)w.E,
+                               (int)(w.dpad / 32));
+            err = hipGetLastError();
+        } else {
+            hipLaunchKernelGGL(router_fwd_mfma_kernel<false>,
+                               dim3((unsigned)w.nb, (unsigned)w.etiles), dim3(256), kRmLds, s, xin,
+                               (const bf16 *)(ws + w.wsplit), b_r, (float *)(ws + w.probs),
+                               router_logits, expert_index, gate, (int32_t *)(ws + w.idx),
+                               (float *)(ws + w.gate), (int32_t *)(ws + w.local_rank),
+                               (int32_t *)(ws + w.block_counts), (float *)(ws + w.block_psum),
+                               (int)w.nbg, (int)w.Tg, d_in, (int)w.dpad_r, (int)w.E,
+                               (int)(w.dpad / 32));
+            err = hipGetLastError();
+        }
     }
+    if (err == hipSuccess && w.etiles > 1)
+        err = launch_router_softmax(w, ws, expert_index, gate, router_logits, s);
     return err;
 }
 

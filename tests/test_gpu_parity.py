@@ -239,6 +239,24 @@ def test_many_experts(dtype, T, d, f, E, cf, n):
     _report("E=%d" % E, errs)
 
 
+@pytest.mark.parametrize("T,d,f,E,cf,n,bias,eps,rounds", [
+    (4096, 128, 72, 256, 2.0, 1, False, 0.0, 0),      # two full expert tiles
+    (3000, 200, 64, 200, 1.0, 2, True, 0.0, 1),       # second tile partly filled, ragged d
+    (2048, 776, 64, 1024, 4.0, 1, False, 0.01, 0),    # eight tiles, jittered input planes
+    (5000, 96, 64, 132, 1.5, 1, True, 0.0, 2),        # four experts in the second tile
+])
+def test_bf16_router_on_matrix_cores_beyond_128_experts(T, d, f, E, cf, n, bias, eps, rounds):
+    """More than 128 experts (a multiple of 4): the logits come from the matrix-core kernel, one
+    tile of 128 experts per block, softmax and the rest from the vector-ALU path's kernel."""
+    from parity import compare_full
+    s = SwitchShape("t", T, d, f, E, cf, dtype="bf16", seed_index=62, n_groups=n, zipf_bias=bias,
+                    jitter_eps=eps, noise_seed=17, ntlb_rounds=rounds)
+    few = T * min(1.0, cf) < 16 * E
+    errs = compare_full(s, make_inputs(s, _dev()), d_aux=0.5,
+                        widen={"dW_r": 5.0, "db_r": 10.0} if few else None)[0]
+    _report("bf16 router, E=%d" % E, errs)
+
+
 def test_fp32_long_reduction():
     """One expert holding 17 576 tokens: each weight-gradient element is a sum over all of them,
     which the fp32 path takes in two levels (a single fp32 chain drifts past 1e-5 here)."""
