@@ -105,14 +105,14 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.dpad_r = jit_mfma ? 3 * w.dpad : w.dpad;
     w.etiles = ceil_div(w.E, 128);
     w.wsplit = take((size_t)w.etiles * 3 * 128 * w.dpad_r * 2);
-    w.wsplit_b = take(d * 256 * 2);
-    w.dl_split = take(T * 256 * 2);
+    w.wsplit_b = take((size_t)w.etiles * d * 256 * 2);
+    w.dl_split = take((size_t)w.etiles * T * 256 * 2);
     w.xj = take(jit_mfma ? T * (size_t)w.dpad_r * 2 : 0);
     w.no_slot = take(jit_mfma ? T * 4 : 0);
     w.tps_m = ceil_div(ceil_div(w.T, 85), 64) * 64;
     if (w.tps_m < 64) w.tps_m = 64;   // empty batch
     w.nsplit_m = ceil_div(w.T, w.tps_m);
-    w.dWr_part_m = take((size_t)w.nsplit_m * (jit_mfma ? 2 * (size_t)w.dpad : d) * 256 * 4);
+    w.dWr_part_m = take((size_t)w.etiles * w.nsplit_m * (jit_mfma ? 2 * (size_t)w.dpad : d) * 256 * 4);
     w.relu_bits = take(E * ceil_div(f, kGemmTile) * ceil_div(C, kGemmTile) * kReluBitsPerTile);
     w.ntlb_rounds = cfg->ntlb_rounds;
     if (w.ntlb_rounds > 0) {

@@ -134,9 +134,9 @@ struct Workspace {
                                 // (the jittered input as three bf16 planes side by side)
     size_t xj;                  // bf16 [T][3 dpad]  x * m as hi | mid | lo planes (jitter + MFMA router)
     size_t no_slot;             // i32 [T]  all -1 (jitter + MFMA router backward)
-    size_t wsplit_b;            // bf16 [d][256]   W_r rows as hi | lo halves (MFMA router backward)
-    size_t dl_split;            // bf16 [T][256]   dlogits rows as hi | lo halves
-    size_t dWr_part_m;          // f32 [nsplit_m][d][256]  partial sums of x^T [dl_hi | dl_lo]
+    size_t wsplit_b;            // bf16 [etiles][d][256]   W_r rows as hi | lo halves (MFMA router backward)
+    size_t dl_split;            // bf16 [etiles][T][256]   dlogits rows as hi | lo halves
+    size_t dWr_part_m;          // f32 [etiles][nsplit_m][d][256]  partial sums of x^T [dl_hi | dl_lo]
                                 //     (with jitter: [nsplit_m][2 dpad][256], hi and mid plane of x * m)
     int64_t tps_m, nsplit_m;    // tokens per split (multiple of 32), number of splits
     size_t relu_bits;           // u8  [E][f tiles][slot tiles][kReluBitsPerTile]  one bit per element of A:

@@ -83,6 +83,8 @@ struct GemmArgs {
     int slots;                          //           slots per expert
     Noise nz;                           //           dropout threshold, scale, seed
     const int32_t *tok_slot;            // ROUTER_DX: row of the addend for each token, -1: none
+    int router_tiles;                   // ROUTER_DX: tiles of 128 experts; operands are planes
+    int q_plane, p_plane;               //   [tile][row][256], plane sizes in elements
     float *Cf;                          // ROUTER_DWR: fp32 partial sums [split][q][p]
     int T_total, tps;                   // ROUTER_DWR: tokens, tokens per split
 };
@@ -187,11 +189,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     oq.init_frag(lane, wq * 128);
     int ld_nk = 0;      // k steps (with data) of the tile the loads are in
     auto begin_loads = [&](const Tile &t) {
-        // width of the operand rows in k: the reduction length, except for ROUTER_DX
-        // whose 384 k values are read from 256-wide (hi | lo) rows
-        const int kwidth = MODE == MODE_ROUTER_DX ? 256 : t.klim;
-        op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, kwidth, lane, wave);
-        oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, kwidth, lane, wave);
+        if (MODE == MODE_ROUTER_DX) {
+            // the 384 k values of an expert tile are read from 256-wide (hi | lo) rows of that
+            // tile's plane; k offsets address across planes, so the bounds span all of them (a
+            // ragged last row tile then reads rows of the next plane: finite, and never stored)
+            op.init_load(a.P, a.ldp, t.p0, a.router_tiles * a.Pdim, a.router_tiles * a.p_plane, lane,
+                         wave);
+            oq.init_load(a.Q, a.ldq, t.q0, a.router_tiles * a.Qdim, a.router_tiles * a.q_plane, lane,
+                         wave);
+        } else {
+            op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave);
+            oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave);
+        }
         ld_nk = steps_of(t);
     };
     // k offsets (P, Q) of step j of the tile the loads are in; steps past its range read zeros
@@ -199,9 +208,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     auto k_of = [&](int j) {
         const int r = j < ld_nk ? j : ld_nk;
         if (MODE == MODE_ROUTER_DX) {
-            // steps 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi; 6: past the end
-            k0q_ = r < 4 ? 64 * (r & 1) : (r < 6 ? 128 + 64 * (r - 4) : 256);
-            k0p_ = r < 2 ? 64 * r : (r < 4 ? 128 + 64 * (r - 2) : (r < 6 ? 64 * (r - 4) : 256));
+            // six steps per expert tile -- 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi --
+            // in that tile's planes; past the last tile: beyond the k limit (zeros)
+            const int jt = r / 6, rr = r - 6 * jt;
+            k0q_ = jt * a.q_plane + (rr < 4 ? 64 * (rr & 1) : 128 + 64 * (rr - 4));
+            k0p_ = jt * a.p_plane + (rr < 2 ? 64 * rr : (rr < 4 ? 128 + 64 * (rr - 2) : 64 * (rr - 4)));
+            if (r >= ld_nk) {
+                k0q_ = a.router_tiles * a.q_plane;
+                k0p_ = a.router_tiles * a.p_plane;
+            }
         } else {
             k0p_ = k0q_ = r * kBK;
         }
@@ -626,8 +641,8 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     return hipErrorInvalidValue;
 }
 
-// dx = dl W_r^T + (kept) dXd[slot]: dl as bf16 hi|lo rows [T][256], W_r^T as bf16 hi|lo rows
-// [d][256]; see GemmMode.  With input jitter the product alone is written (no token has an
+// dx = dl W_r^T + (kept) dXd[slot]: dl as bf16 hi|lo rows [tile][T][256], W_r^T as bf16 hi|lo
+// rows [tile][d][256], one plane per tile of 128 experts; see GemmMode.  With input jitter the product alone is written (no token has an
 // addend row); router_dx_jitter_kernel then scales it by the multipliers and adds the rows.
 hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStream_t s) {
     GemmArgs a{};
@@ -636,7 +651,10 @@ hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStre
     a.Cout = (bf16 *)dx; a.c_batch = 0; a.ldc = (int)w.d;
     a.mask = (const bf16 *)(ws + w.dXd);
     a.tok_slot = (const int32_t *)(ws + (w.noise.jitter ? w.no_slot : w.tok_slot));
-    a.Qdim = (int)w.T; a.Pdim = (int)w.d; a.Kdim = 384;
+    a.router_tiles = (int)w.etiles;
+    a.q_plane = (int)(w.T * 256);
+    a.p_plane = (int)(w.d * 256);
+    a.Qdim = (int)w.T; a.Pdim = (int)w.d; a.Kdim = 384 * (int)w.etiles;
     a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
     a.tiles_p = (int)ceil_div(a.Pdim, kBP);
     a.total_tiles = a.tiles_q * a.tiles_p;
@@ -648,21 +666,28 @@ hipError_t launch_router_dx_mfma(const Workspace &w, char *ws, void *dx, hipStre
 // With input jitter x is replaced by the hi and mid planes of x * m, taken as one operand of
 // 2 dpad rows: part[split][2 dpad][256], row k from the hi plane, row dpad + k from the mid plane.
 hipError_t launch_router_dWr_mfma(const Workspace &w, const void *x, char *ws, hipStream_t s) {
-    GemmArgs a{};
     const bool jitter = w.noise.jitter;
     const int ldx = jitter ? (int)w.dpad_r : (int)w.d;
     const int rows = jitter ? 2 * (int)w.dpad : (int)w.d;
-    a.Q = jitter ? (const bf16 *)(ws + w.xj) : (const bf16 *)x;                  // [k = token][q]
-    a.q_batch = (size_t)w.tps_m * ldx; a.ldq = ldx;
-    a.P = (const bf16 *)(ws + w.dl_split); a.p_batch = (size_t)w.tps_m * 256; a.ldp = 256;  // [k = token][p]
-    a.Cf = (float *)(ws + w.dWr_part_m); a.c_batch = (size_t)rows * 256; a.ldc = 256;
-    a.T_total = (int)w.T; a.tps = (int)w.tps_m;
-    a.Qdim = rows; a.Pdim = 256; a.Kdim = (int)w.tps_m;
-    a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
-    a.tiles_p = 1;
-    a.total_tiles = a.tiles_q * a.tiles_p * (int)w.nsplit_m;
     ProfScope ps("router_dWr_mfma", s);
-    return gemm_launch<true, true, EPI_NONE, false, true, MODE_ROUTER_DWR>(a, s);
+    // one launch per tile of 128 experts: part[tile][split][rows][256]
+    for (int tile = 0; tile < (int)w.etiles; ++tile) {
+        GemmArgs a{};
+        a.Q = jitter ? (const bf16 *)(ws + w.xj) : (const bf16 *)x;                  // [k = token][q]
+        a.q_batch = (size_t)w.tps_m * ldx; a.ldq = ldx;
+        a.P = (const bf16 *)(ws + w.dl_split) + (size_t)tile * w.T * 256;           // [k = token][p]
+        a.p_batch = (size_t)w.tps_m * 256; a.ldp = 256;
+        a.Cf = (float *)(ws + w.dWr_part_m) + (size_t)tile * w.nsplit_m * rows * 256;
+        a.c_batch = (size_t)rows * 256; a.ldc = 256;
+        a.T_total = (int)w.T; a.tps = (int)w.tps_m;
+        a.Qdim = rows; a.Pdim = 256; a.Kdim = (int)w.tps_m;
+        a.tiles_q = (int)ceil_div(a.Qdim, kBQ);
+        a.tiles_p = 1;
+        a.total_tiles = a.tiles_q * a.tiles_p * (int)w.nsplit_m;
+        hipError_t err = gemm_launch<true, true, EPI_NONE, false, true, MODE_ROUTER_DWR>(a, s);
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
 }
 
 }  // namespace sw

@@ -341,6 +341,7 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
     bf16 *__restrict__ dl_split /* [T][256] hi | lo, or nullptr */,
     int T, int Tg, int E, float aux_scale /* d_aux*alpha*E/(n Tg^2) */) {
     constexpr int kDlTokens = dl_tokens(EPL);
+    const int epad = (E + 127) / 128 * 128;
     const float mean_count = (float)Tg / (float)E;
     const int lane = threadIdx.x % kWave;
     const int t_first = (blockIdx.x * (256 / kWave) + threadIdx.x / kWave) * kDlTokens;
@@ -376,16 +377,18 @@ __global__ __launch_bounds__(256) void router_dlogits_kernel(
             const int e = lane + j * kWave;
             const float dl = e < E ? p[u][j] * (dp[u][j] - s[u]) : 0.f;
             if (dlogits && e < E) dlogits[(size_t)t * E + e] = dl;
-            if (dl_split && e < 128) {   // two bf16 terms (16 mantissa bits) for the MFMA contractions
-                const bf16 hi = (bf16)dl;
-                dl_split[(size_t)t * 256 + e] = hi;
-                dl_split[(size_t)t * 256 + 128 + e] = (bf16)(dl - (float)hi);
+            if (dl_split && e < epad) {   // two bf16 terms (16 mantissa bits) for the MFMA contractions,
+                const bf16 hi = (bf16)dl;  // one [T][hi 128 | lo 128] plane per tile of 128 experts
+                bf16 *row = dl_split + ((size_t)(e >> 7) * T + t) * 256 + (e & 127);
+                row[0] = hi;
+                row[128] = (bf16)(dl - (float)hi);
             }
         }
         if (dl_split)   // columns of the 128-wide halves that no lane visited above
-            for (int e = lane + EPL * kWave; e < 128; e += kWave) {
-                dl_split[(size_t)t * 256 + e] = (bf16)0.f;
-                dl_split[(size_t)t * 256 + 128 + e] = (bf16)0.f;
+            for (int e = lane + EPL * kWave; e < epad; e += kWave) {
+                bf16 *row = dl_split + ((size_t)(e >> 7) * T + t) * 256 + (e & 127);
+                row[0] = (bf16)0.f;
+                row[128] = (bf16)0.f;
             }
     }
 }
@@ -449,18 +452,20 @@ __global__ __launch_bounds__(256) void reduce_dWr_split_kernel(const float *__re
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= d * E) return;
     const int k = i / E, j = i - k * E;
+    // the parts of expert j's tile of 128 experts: [tile][split][rows][hi 128 | lo 128]
+    const float *tile_part = part + (size_t)(j >> 7) * nsplit * rows * 256 + (j & 127);
     float s = 0.f;
 #pragma unroll 8
     for (int q = 0; q < nsplit; ++q) {   // unrolled: eight splits' loads in flight, same order of sums
-        const float *row = part + ((size_t)q * rows + k) * 256;
-        s += row[j] + row[128 + j];
+        const float *row = tile_part + ((size_t)q * rows + k) * 256;
+        s += row[0] + row[128];
     }
     if (second > 0) {
         float s2 = 0.f;
 #pragma unroll 8
         for (int q = 0; q < nsplit; ++q) {
-            const float *row = part + ((size_t)q * rows + second + k) * 256;
-            s2 += row[j] + row[128 + j];
+            const float *row = tile_part + ((size_t)q * rows + second + k) * 256;
+            s2 += row[0] + row[128];
         }
         s += s2;
     }
@@ -788,7 +793,7 @@ static hipError_t router_bwd_typed(const Workspace &w, float alpha, float d_aux,
                        s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),          \
                        (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts_g),        \
                        dlogits_out, dl_split, (int)w.T, (int)w.Tg, (int)w.E, aux_scale)
-        if (mfma)
+        if (mfma && w.etiles == 1)
             hipLaunchKernelGGL(router_dlogits_pair_kernel, dim3((unsigned)ceil_div(w.T, 16)), dim3(256),
                                0, s, (const float *)(ws + w.probs), (const int32_t *)(ws + w.idx),
                                (const float *)(ws + w.dgate), (const int32_t *)(ws + w.counts_g),

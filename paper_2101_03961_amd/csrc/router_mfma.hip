@@ -31,8 +31,8 @@ constexpr int kRmLds = kRmTileBytes + kRmTokens * 4 + 4 * kRmExperts * 4;
 
 // W_r [d][E] fp32 -> wsplit [tiles][3][128][planes * dpad] bf16: per tile of 128 experts, term
 // s of expert e, k contiguous; rows of absent experts and columns past d are zero.  Also, for the backward
-// pass, wsplit_b [d][256] bf16: row k holds hi(W_r[k][0..127]) | lo(...), where
-// hi + lo carries 16 mantissa bits.
+// pass, wsplit_b [tiles][d][256] bf16: row k of a tile's plane holds hi(W_r[k][its 128
+// experts]) | lo(...), where hi + lo carries 16 mantissa bits.
 // planes = 3 (input jitter): the router's input x * m is no bf16 value any more and comes as
 // three bf16 planes hi | mid | lo side by side, [T][3 dpad] (jitter_split_kernel).  The
 // weight terms are then laid out against all three planes, with zeros where plane p meets a
@@ -62,9 +62,10 @@ __global__ __launch_bounds__(256) void router_split_kernel(const float *__restri
         wt[term + at] = p <= 1 ? mid : zero;
         wt[2 * term + at] = p == 0 ? lo : zero;
     }
-    if (k < d && tile == 0) {   // the backward operand exists for one expert tile only
-        wsplit_b[(size_t)k * 256 + el] = hi;
-        wsplit_b[(size_t)k * 256 + 128 + el] = mid;
+    if (k < d) {   // the backward operand: one [d][hi 128 | lo 128] plane per expert tile
+        bf16 *row = wsplit_b + ((size_t)tile * d + k) * 256 + el;
+        row[0] = hi;
+        row[128] = mid;
     }
 }
 
@@ -332,10 +333,12 @@ __global__ __launch_bounds__(256) void router_fwd_mfma_kernel(
 }
 #undef SW_WAIT_VMCNT
 
-// The backward contractions on the matrix cores exist for one expert tile.
+// The backward contractions address all expert tiles' planes of dl and of W_r through one
+// buffer descriptor each.
 bool router_bwd_mfma_supported(const Workspace &w, int dtype) {
-    return router_fwd_mfma_supported(w, dtype) && w.E <= kRmExperts &&
-           (uint64_t)w.T * 512u < 0x7fffffffu;
+    return router_fwd_mfma_supported(w, dtype) &&
+           (uint64_t)w.etiles * (uint64_t)w.T * 512u < 0x7fffffffu &&
+           (uint64_t)w.etiles * (uint64_t)w.d * 512u < 0x7fffffffu;
 }
 
 bool router_fwd_mfma_supported(const Workspace &w, int dtype) {

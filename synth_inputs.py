@@ -69,6 +69,9 @@ CONFIGS: Dict[str, SwitchShape] = {
         # the model table's own Switch-Base layer: d_ff 2048 with the gated-GELU FFN
         # (three 768 x 2048 matrices per expert, FLOP-matched to base_cf1.0's two 768 x 3072)
         SwitchShape("base_geglu", 65536, 768, 2048, 128, 1.0, seed_index=7, ffn="geglu"),
+        # twice the experts of Switch-Base (the paper's scaling runs go to 256): the router
+        # beyond one tile of 128 experts
+        SwitchShape("base_e256", 65536, 768, 3072, 256, 1.0, seed_index=8),
     ]
 }
 
