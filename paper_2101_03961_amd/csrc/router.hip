@@ -121,53 +121,85 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
 #pragma unroll
     for (int j = 0; j < EPL; ++j) pacc[j] = 0.f;
 
-    for (int i = 0; i < kWave; ++i) {
-        const int tl = wave * kWave + i;
-        const int t = t0 + tl;
-        if (t >= tend) {
-            if (lane == 0) idx_s[tl] = -1;
-            continue;
-        }
-        float *row = probs + (size_t)t * E;
-        float h[EPL];
-        float best = -INFINITY;
-        int besti = 0x7fffffff;
+    // kU tokens at a time (their loads and reductions overlap); every token's arithmetic, and the
+    // order in which the tokens enter the probability sums, is that of a one-by-one walk
+    constexpr int kU = EPL <= 4 ? 4 : (EPL <= 8 ? 2 : 1);
+    for (int i0 = 0; i0 < kWave; i0 += kU) {
+        float h[kU][EPL], best[kU], z[kU];
+        int besti[kU];
+        bool live[kU];
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const int e = lane + j * kWave;
-            h[j] = e < E ? row[e] : -INFINITY;
-            if (logits_copy && e < E) logits_copy[(size_t)t * E + e] = h[j];
-            if (h[j] > best) { best = h[j]; besti = e; }   // ascending e: lowest index kept on ties
+        for (int u = 0; u < kU; ++u) {
+            const int t = t0 + wave * kWave + i0 + u;
+            live[u] = t < tend;
+            best[u] = -INFINITY;
+            besti[u] = 0x7fffffff;
+            const float *row = probs + (size_t)(live[u] ? t : t0) * E;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                const int e = lane + j * kWave;
+                h[u][j] = (live[u] && e < E) ? row[e] : -INFINITY;
+                if (h[u][j] > best[u]) { best[u] = h[u][j]; besti[u] = e; }   // ascending e: lowest index kept on ties
+            }
+        }
+        if (logits_copy) {
+#pragma unroll
+            for (int u = 0; u < kU; ++u)
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) {
+                    const int e = lane + j * kWave;
+                    if (live[u] && e < E)
+                        logits_copy[(size_t)(t0 + wave * kWave + i0 + u) * E + e] = h[u][j];
+                }
         }
 #pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            const float ov = __shfl_xor(best, m, kWave);
-            const int oi = __shfl_xor(besti, m, kWave);
-            if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
-        }
-        float ex[EPL];
-        float z = 0.f;
+        for (int m = 32; m >= 1; m >>= 1)
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const int e = lane + j * kWave;
-            ex[j] = e < E ? expf(h[j] - best) : 0.f;
-            z += ex[j];
-        }
-        z = wave_sum(z);
+            for (int u = 0; u < kU; ++u) {
+                const float ov = __shfl_xor(best[u], m, kWave);
+                const int oi = __shfl_xor(besti[u], m, kWave);
+                if (ov > best[u] || (ov == best[u] && oi < besti[u])) { best[u] = ov; besti[u] = oi; }
+            }
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const int e = lane + j * kWave;
-            const float p = ex[j] / z;
-            if (e < E) row[e] = p;
-            pacc[j] += p;   // padded experts add 0
+        for (int u = 0; u < kU; ++u) {
+            z[u] = 0.f;
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                const int e = lane + j * kWave;
+                // the hardware exp2 is accurate to about one ulp, the scaled argument adds
+                // |h - best| 2^-24: far inside the 1e-5 budget
+                h[u][j] = (live[u] && e < E) ? __expf(h[u][j] - best[u]) : 0.f;
+                z[u] += h[u][j];
+            }
         }
-        if (lane == 0) {
-            const float g = 1.0f / z;   // exp(0) / z: probability of the arg max
-            idx_s[tl] = besti;
-            idx_out[t] = besti;
-            idx_ws[t] = besti;
-            gate_out[t] = g;
-            gate_ws[t] = g;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1)
+#pragma unroll
+            for (int u = 0; u < kU; ++u) z[u] += __shfl_xor(z[u], m, kWave);
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int tl = wave * kWave + i0 + u;
+            const int t = t0 + tl;
+            if (!live[u]) {
+                if (lane == 0) idx_s[tl] = -1;
+                continue;
+            }
+            float *row = probs + (size_t)t * E;
+            const float g = 1.0f / z[u];   // exp(0) / z: also the probability of the arg max
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                const int e = lane + j * kWave;
+                const float p = h[u][j] * g;
+                if (e < E) row[e] = p;
+                pacc[j] += p;   // padded experts add 0
+            }
+            if (lane == 0) {
+                idx_s[tl] = besti[u];
+                idx_out[t] = besti[u];
+                idx_ws[t] = besti[u];
+                gate_out[t] = g;
+                gate_ws[t] = g;
+            }
         }
     }
 #pragma unroll
