@@ -572,6 +572,7 @@ def test_no_token_left_behind_full_size():
 # ------------------------------------------- full sizes, sampled against oracle
 @pytest.mark.parametrize("name,n_experts", [
     ("base_cf1.0", 3), ("base_cf1.25", 2), ("base_zipf", 3), ("large", 2), ("c_share", 2),
+    ("base_e256", 3),
 ])
 def test_full_size_sampled_parity(name, n_experts):
     from parity import compare_sampled
