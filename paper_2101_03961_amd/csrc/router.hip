@@ -97,14 +97,16 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <int EPL>
-__global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
+// WAVES waves share the block's kRouteTB tokens (16 when the per-wave probability sums fit
+// the LDS: few waves per CU leave this kernel waiting on its own loads).
+template <int EPL, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void router_softmax_kernel(
     float *__restrict__ probs /* in: logits, out: p */, float *__restrict__ logits_copy,
     int32_t *__restrict__ idx_out, float *__restrict__ gate_out, int32_t *__restrict__ idx_ws,
     float *__restrict__ gate_ws, int32_t *__restrict__ local_rank,
     int32_t *__restrict__ block_counts, float *__restrict__ block_psum, int nbg, int Tg, int E) {
     extern __shared__ char smem_raw[];
-    // layout: idx_s[kRouteTB] | hist[E] | psum_w[4][E]
+    // layout: idx_s[kRouteTB] | hist[E] | psum_w[WAVES][E]
     int32_t *idx_s = (int32_t *)smem_raw;
     int32_t *hist = idx_s + kRouteTB;
     float *psum_w = (float *)(hist + E);
@@ -115,7 +117,9 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
     const int b = blockIdx.x;
     int t0, tend;
     block_token_range(b, nbg, Tg, t0, tend);
-    for (int e = tid; e < E; e += kRouteTB) hist[e] = 0;
+    constexpr int kThreads = WAVES * kWave;
+    constexpr int kTokPerWave = kRouteTB / WAVES;
+    for (int e = tid; e < E; e += kThreads) hist[e] = 0;
 
     float pacc[EPL];
 #pragma unroll
@@ -124,13 +128,14 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
     // kU tokens at a time (their loads and reductions overlap); every token's arithmetic, and the
     // order in which the tokens enter the probability sums, is that of a one-by-one walk
     constexpr int kU = EPL <= 4 ? 4 : (EPL <= 8 ? 2 : 1);
-    for (int i0 = 0; i0 < kWave; i0 += kU) {
+    static_assert(kTokPerWave % kU == 0, "tokens per wave");
+    for (int i0 = 0; i0 < kTokPerWave; i0 += kU) {
         float h[kU][EPL], best[kU], z[kU];
         int besti[kU];
         bool live[kU];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            const int t = t0 + wave * kWave + i0 + u;
+            const int t = t0 + wave * kTokPerWave + i0 + u;
             live[u] = t < tend;
             best[u] = -INFINITY;
             besti[u] = 0x7fffffff;
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
                 for (int j = 0; j < EPL; ++j) {
                     const int e = lane + j * kWave;
                     if (live[u] && e < E)
-                        logits_copy[(size_t)(t0 + wave * kWave + i0 + u) * E + e] = h[u][j];
+                        logits_copy[(size_t)(t0 + wave * kTokPerWave + i0 + u) * E + e] = h[u][j];
                 }
         }
 #pragma unroll
@@ -178,7 +183,7 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
             for (int u = 0; u < kU; ++u) z[u] += __shfl_xor(z[u], m, kWave);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            const int tl = wave * kWave + i0 + u;
+            const int tl = wave * kTokPerWave + i0 + u;
             const int t = t0 + tl;
             if (!live[u]) {
                 if (lane == 0) idx_s[tl] = -1;
@@ -209,7 +214,7 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
     }
     __syncthreads();
     // rank of each token among the block's earlier tokens with the same expert
-    {
+    if (tid < kRouteTB) {
         const int me = idx_s[tid];
         if (me >= 0) {
             int r = 0;
@@ -219,11 +224,12 @@ __global__ __launch_bounds__(kRouteTB) void router_softmax_kernel(
         }
     }
     __syncthreads();
-    for (int e = tid; e < E; e += kRouteTB) {
+    for (int e = tid; e < E; e += kThreads) {
         block_counts[(size_t)b * E + e] = hist[e];
-        // fixed order over the four waves
-        block_psum[(size_t)b * E + e] =
-            ((psum_w[e] + psum_w[E + e]) + psum_w[2 * E + e]) + psum_w[3 * E + e];
+        float ps = psum_w[e];   // fixed order over the waves
+#pragma unroll
+        for (int q = 1; q < WAVES; ++q) ps += psum_w[q * E + e];
+        block_psum[(size_t)b * E + e] = ps;
     }
 }
 
@@ -725,9 +731,10 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 template <int EPL>
 static hipError_t softmax_launch(const Workspace &w, char *ws, int32_t *expert_index, float *gate,
                                  float *router_logits, hipStream_t s) {
-    const size_t smem = sizeof(int32_t) * kRouteTB + sizeof(int32_t) * w.E + sizeof(float) * 4 * w.E;
-    hipLaunchKernelGGL(router_softmax_kernel<EPL>, dim3((unsigned)w.nb), dim3(kRouteTB), smem, s,
-                       (float *)(ws + w.probs), router_logits, expert_index, gate,
+    constexpr int kWaves = EPL <= 8 ? 16 : 4;   // 16 x 512 experts x 4 bytes = 32 KB of sums at most
+    const size_t smem = sizeof(int32_t) * kRouteTB + sizeof(int32_t) * w.E + sizeof(float) * kWaves * w.E;
+    hipLaunchKernelGGL((router_softmax_kernel<EPL, kWaves>), dim3((unsigned)w.nb), dim3(kWaves * kWave),
+                       smem, s, (float *)(ws + w.probs), router_logits, expert_index, gate,
                        (int32_t *)(ws + w.idx), (float *)(ws + w.gate),
                        (int32_t *)(ws + w.local_rank), (int32_t *)(ws + w.block_counts),
                        (float *)(ws + w.block_psum), (int)w.nbg, (int)w.Tg, (int)w.E);
