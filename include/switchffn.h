@@ -34,6 +34,9 @@
  *     fp32 and rounded once (nearest-even) at each store.  SW_F32: the same
  *     tensors are fp32.  The router (W_r, b_r, logits, softmax, gate, aux loss,
  *     dW_r, db_r) is fp32 in both cases ("selective precision", Sec. 2.4).
+ *     With bf16 tokens and E a multiple of 4 its contractions run on the
+ *     matrix cores (fp32 weights as exact sums of bf16 terms); otherwise on the
+ *     vector ALUs, with the same results to rounding and several times slower.
  */
 #ifndef SWITCHFFN_H
 #define SWITCHFFN_H
