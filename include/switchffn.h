@@ -21,10 +21,11 @@
  *     detected on the host before anything is launched; nothing is thrown
  *     across the ABI.  Inputs must be finite (NaN/Inf behaviour unspecified).
  *   - Gradients are overwritten, not accumulated.
- *   - The library keeps no state between calls apart from what the workspace holds; with
- *     profiling off, calls from several host threads may run at once if each has its own
- *     workspace, outputs and stream.  One device per process is assumed (the launch width
- *     is taken from the device that is current at the first call).
+ *   - The library keeps no state between calls apart from what the workspace holds (and
+ *     one-time kernel attributes, set under std::call_once); with profiling off, calls from
+ *     several host threads may run at once if each has its own workspace, outputs and
+ *     stream.  One device per process is assumed for switch_forward / switch_backward (the
+ *     launch width is taken from the device that is current at the first call).
  *   - An empty batch (T = 0) is legal: forward writes expert_counts = 0 and
  *     aux_loss = 0 (both fractions of Eq. 4 are empty sums), backward writes
  *     zeros to dW_r, db_r, dW_in, dW_out; the per-token arguments and the
@@ -65,7 +66,7 @@ typedef enum {
                               slots x max(d_model, d_ff) activations reach 2 GB       */
     SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite,
                               expert_dropout or jitter_eps outside [0, 1), ntlb_rounds
-                              outside 0 .. 16                                       */
+                              outside 0 .. 16, reserved not 0                       */
     SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16, or ffn_kind
                               is not a sw_ffn_kind                               */
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
@@ -105,7 +106,7 @@ typedef struct {
                                 still without a slot ask their next-best expert (by logit;
                                 equal logits: lower index first) for the capacity it has
                                 left, in sequence order inside the routing group.       */
-    int32_t reserved;        /* set to 0                                            */
+    int32_t reserved;        /* must be 0 (anything else is refused with SW_ERR_VALUE) */
 } switch_config;
 
 /*
@@ -197,7 +198,8 @@ int switch_backward(const switch_config *cfg,
 const char *switch_status_string(int status);
 
 /*
- * Per-kernel timing with HIP events, for measurement.  While enabled, every
+ * Per-kernel timing with HIP events: for measurement only, not part of the layer's interface
+ * (bench.py uses it).  While enabled, every
  * kernel the library launches is bracketed by two events recorded on the
  * call's stream.  switch_profile_collect synchronises those events and adds
  * the elapsed times to per-kernel totals; switch_profile_get reads them.

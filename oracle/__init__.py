@@ -383,7 +383,7 @@ def hidden_near_zero(x, W_in, expert_index, dropped, rel_eps: float, expert_sel=
                                      float(rel_eps), max_out, _ptr(ot, _c_i64p),
                                      _ptr(oj, _c_i64p), _ptr(oh, _c_f64p))
     assert n <= max_out, "too many near-zero hidden units (%d)" % n
-    return [(int(ot[i]), int(oj[i]), float(oh[i])) for i in range(n)]
+    return sorted((int(ot[i]), int(oj[i]), float(oh[i])) for i in range(n))
 
 
 def backward(x, W_r, W_in, W_out, dy, fwd: Dict, alpha: float, d_aux: float = 1.0,

@@ -387,37 +387,46 @@ void swo_expert_ffn(int64_t T, int64_t d, int64_t f, int64_t E, const in_t *x,
  *     |h_tj| <= rel_eps * RMS_j(h_t),
  * (t, j, h_tj) is recorded (up to max_out entries; the return value is the number found).
  * The layer is discontinuous in its inputs there: an implementation that accumulates h in
- * fp32 gets the sign of such a sum from its rounding errors.  Single threaded. */
+ * fp32 gets the sign of such a sum from its rounding errors.  Tokens are shared out over
+ * the OpenMP threads (each token's sums are taken by one thread, k ascending); the entries
+ * come out in no particular order. */
 int64_t swo_hidden_near_zero(int64_t T, int64_t d, int64_t f, const in_t *x, const in_t *W_in,
                              const int32_t *expert_index, const uint8_t *dropped,
                              const uint8_t *token_sel, double rel_eps, int64_t max_out,
                              int64_t *out_t, int64_t *out_j, double *out_h) {
-    double *h = (double *)malloc(sizeof(double) * (size_t)f);
     int64_t found = 0;
-    for (int64_t t = 0; t < T; ++t) {
-        if ((token_sel && !token_sel[t]) || dropped[t]) continue;
-        const in_t *Wi = W_in + (int64_t)expert_index[t] * d * f;
-        const in_t *xt = x + t * d;
-        for (int64_t j = 0; j < f; ++j) h[j] = 0.0;
-        for (int64_t k = 0; k < d; ++k) {
-            double xk = (double)xt[k];
-            const in_t *row = Wi + k * f;
-            for (int64_t j = 0; j < f; ++j) h[j] += xk * (double)row[j];
-        }
-        double ss = 0.0;
-        for (int64_t j = 0; j < f; ++j) ss += h[j] * h[j];
-        double bound = rel_eps * sqrt(ss / (double)f);
-        for (int64_t j = 0; j < f; ++j)
-            if (fabs(h[j]) <= bound) {
-                if (found < max_out) {
-                    out_t[found] = t;
-                    out_j[found] = j;
-                    out_h[found] = h[j];
-                }
-                ++found;
+#pragma omp parallel
+    {
+        double *h = (double *)malloc(sizeof(double) * (size_t)f);
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t t = 0; t < T; ++t) {
+            if ((token_sel && !token_sel[t]) || dropped[t]) continue;
+            const in_t *Wi = W_in + (int64_t)expert_index[t] * d * f;
+            const in_t *xt = x + t * d;
+            for (int64_t j = 0; j < f; ++j) h[j] = 0.0;
+            for (int64_t k = 0; k < d; ++k) {
+                double xk = (double)xt[k];
+                const in_t *row = Wi + k * f;
+                for (int64_t j = 0; j < f; ++j) h[j] += xk * (double)row[j];
             }
+            double ss = 0.0;
+            for (int64_t j = 0; j < f; ++j) ss += h[j] * h[j];
+            double bound = rel_eps * sqrt(ss / (double)f);
+            for (int64_t j = 0; j < f; ++j)
+                if (fabs(h[j]) <= bound) {
+#pragma omp critical(swo_near_zero)
+                    {
+                        if (found < max_out) {
+                            out_t[found] = t;
+                            out_j[found] = j;
+                            out_h[found] = h[j];
+                        }
+                        ++found;
+                    }
+                }
+        }
+        free(h);
     }
-    free(h);
     return found;
 }
 

@@ -27,6 +27,7 @@ int check_config(const switch_config *cfg) {
     if (!(cfg->expert_dropout >= 0.f && cfg->expert_dropout < 1.f)) return SW_ERR_VALUE;
     if (!(cfg->jitter_eps >= 0.f && cfg->jitter_eps < 1.f)) return SW_ERR_VALUE;
     if (cfg->ntlb_rounds < 0 || cfg->ntlb_rounds > 16) return SW_ERR_VALUE;
+    if (cfg->reserved != 0) return SW_ERR_VALUE;
     // slot indices (expert * slots per expert + position) are kept in 32 bits
     const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
     const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
@@ -218,29 +219,13 @@ static int fill_zero(void *p, size_t bytes, hipStream_t s) {
     return status_of(hipGetLastError());
 }
 
-int switch_forward(const switch_config *cfg, const void *x, const float *W_r, const float *b_r,
-                   const void *W_in, const void *W_out, void *y, int32_t *expert_index,
-                   float *gate, int32_t *position_in_expert, uint8_t *dropped,
-                   int32_t *expert_counts, float *aux_loss, float *router_logits, void *workspace,
-                   size_t workspace_bytes, void *hip_stream) {
-    int st = check_config(cfg);
-    if (st != SW_OK) return st;
-    if (cfg->T == 0) {   // empty batch: no token, no routing; counts and loss are zero
-        if (!expert_counts || !aux_loss) return SW_ERR_NULL;
-        if ((st = fill_zero(expert_counts, (size_t)cfg->E * 4, (hipStream_t)hip_stream))) return st;
-        return fill_zero(aux_loss, 4, (hipStream_t)hip_stream);
-    }
-    if (!x || !W_r || !W_in || !W_out || !y || !expert_index || !gate || !position_in_expert ||
-        !dropped || !expert_counts || !aux_loss)
-        return SW_ERR_NULL;
-    if (!aligned16(x) || !aligned16(W_r) || !aligned16(W_in) || !aligned16(W_out) ||
-        !aligned16(y) || (router_logits && !aligned16(router_logits)))
-        return SW_ERR_ALIGN;
-    const Workspace w = layout_workspace(cfg);
-    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < w.total)
-        return SW_ERR_WORKSPACE;
-    char *ws = (char *)workspace;
-    hipStream_t s = (hipStream_t)hip_stream;
+// The forward pass on a workspace that has been checked: argument checks, then launches only.
+static int forward_on(const switch_config *cfg, const Workspace &w, const void *x, const float *W_r,
+                      const float *b_r, const void *W_in, const void *W_out, void *y,
+                      int32_t *expert_index, float *gate, int32_t *position_in_expert,
+                      uint8_t *dropped, int32_t *expert_counts, float *aux_loss,
+                      float *router_logits, char *ws, hipStream_t s) {
+    int st;
     const int dt = cfg->act_dtype;
     auto gemm = dt == SW_BF16 ? launch_gemm_bf16 : launch_gemm_f32;
     // the re-routing stages rank the experts by logit: keep the logits if the caller does not
@@ -262,6 +247,45 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
     if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
     if ((st = status_of(launch_combine(w, dt, ws, y, s)))) return st;
     return SW_OK;
+}
+
+// pointer checks of the forward pass (T > 0)
+static int check_forward_pointers(const void *x, const float *W_r, const float *b_r,
+                                  const void *W_in, const void *W_out, void *y,
+                                  int32_t *expert_index, float *gate, int32_t *position_in_expert,
+                                  uint8_t *dropped, int32_t *expert_counts, float *aux_loss,
+                                  float *router_logits) {
+    if (!x || !W_r || !W_in || !W_out || !y || !expert_index || !gate || !position_in_expert ||
+        !dropped || !expert_counts || !aux_loss)
+        return SW_ERR_NULL;
+    if (!aligned16(x) || !aligned16(W_r) || !aligned16(W_in) || !aligned16(W_out) ||
+        !aligned16(y) || (b_r && !aligned16(b_r)) || (router_logits && !aligned16(router_logits)))
+        return SW_ERR_ALIGN;
+    return SW_OK;
+}
+
+int switch_forward(const switch_config *cfg, const void *x, const float *W_r, const float *b_r,
+                   const void *W_in, const void *W_out, void *y, int32_t *expert_index,
+                   float *gate, int32_t *position_in_expert, uint8_t *dropped,
+                   int32_t *expert_counts, float *aux_loss, float *router_logits, void *workspace,
+                   size_t workspace_bytes, void *hip_stream) {
+    int st = check_config(cfg);
+    if (st != SW_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (cfg->T == 0) {   // empty batch: no token, no routing; counts and loss are zero
+        if (!expert_counts || !aux_loss) return SW_ERR_NULL;
+        if ((st = fill_zero(expert_counts, (size_t)cfg->E * 4, s))) return st;
+        return fill_zero(aux_loss, 4, s);
+    }
+    if ((st = check_forward_pointers(x, W_r, b_r, W_in, W_out, y, expert_index, gate,
+                                     position_in_expert, dropped, expert_counts, aux_loss,
+                                     router_logits)))
+        return st;
+    const Workspace w = layout_workspace(cfg);
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < w.total)
+        return SW_ERR_WORKSPACE;
+    return forward_on(cfg, w, x, W_r, b_r, W_in, W_out, y, expert_index, gate, position_in_expert,
+                      dropped, expert_counts, aux_loss, router_logits, (char *)workspace, s);
 }
 
 int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const void *x,
@@ -288,7 +312,7 @@ int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const
         return SW_ERR_NULL;
     if (!aligned16(dy) || !aligned16(x) || !aligned16(W_r) || !aligned16(W_in) ||
         !aligned16(W_out) || !aligned16(dx) || !aligned16(dW_r) || !aligned16(dW_in) ||
-        !aligned16(dW_out))
+        !aligned16(dW_out) || (db_r && !aligned16(db_r)))
         return SW_ERR_ALIGN;
     const Workspace w = layout_workspace(cfg);
     if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < w.total)
@@ -318,7 +342,7 @@ const char *switch_status_string(int status) {
     case SW_ERR_SHAPE: return "shape out of range (T, E, d_model, d_ff; 16-byte row chunks)";
     case SW_ERR_VALUE:
         return "capacity_factor must be finite and > 0; alpha, d_aux finite; expert_dropout and "
-               "jitter_eps in [0, 1); ntlb_rounds in 0..16";
+               "jitter_eps in [0, 1); ntlb_rounds in 0..16; reserved 0";
     case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16, ffn_kind SW_FFN_RELU or SW_FFN_GEGLU";
     case SW_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";

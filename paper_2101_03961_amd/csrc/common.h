@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "switchffn.h"
 
 namespace sw {
@@ -157,6 +159,22 @@ struct Workspace {
 int check_config(const switch_config *cfg);
 int64_t capacity_of(const switch_config *cfg);
 Workspace layout_workspace(const switch_config *cfg);
+
+// ---- one-time set-up per device ------------------------------------------------------
+// Kernel attributes (dynamic LDS size) and the CU count belong to a device: each is set or
+// read once per device, under std::call_once, by whichever host thread comes first.
+constexpr int kMaxDevices = 64;
+struct PerDeviceOnce {
+    std::once_flag flag[kMaxDevices];
+    hipError_t err[kMaxDevices];
+};
+template <typename F> static inline hipError_t once_per_device(PerDeviceOnce &o, F fn) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    std::call_once(o.flag[dev], [&] { o.err[dev] = fn(); });
+    return o.err[dev];
+}
 
 // ---- profiling hooks ---------------------------------------------------------
 void prof_begin(const char *name, hipStream_t s);

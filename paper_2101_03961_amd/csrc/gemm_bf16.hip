@@ -512,29 +512,31 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 
 // Number of CUs of the current device, rounded down to a multiple of kXcds.
 static int persistent_blocks() {
-    static int blocks = 0;
-    if (blocks == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+    static PerDeviceOnce once;
+    static int blocks[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    (void)once_per_device(once, [&] {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             cus < kXcds)
             cus = 256;
-        blocks = cus / kXcds * kXcds;
-    }
-    return blocks;
+        blocks[dev] = cus / kXcds * kXcds;
+        return hipSuccess;
+    });
+    return blocks[dev];
 }
 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED,
           int MODE = MODE_EXPERTS>
 static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
     auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED, MODE>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute((const void *)kern,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
+    static PerDeviceOnce once;   // one per template instantiation
+    hipError_t attr_err = once_per_device(once, [&] {
+        return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kGemmLds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     // one block per CU (the 128 KB of LDS and 512 registers per lane allow no more)
     int blocks = persistent_blocks();
     const int needed = (int)(ceil_div(a.total_tiles, kXcds) * kXcds);

@@ -351,17 +351,15 @@ bool router_fwd_mfma_supported(const Workspace &w, int dtype) {
 hipError_t launch_router_fwd_mfma(const Workspace &w, const void *x, const float *W_r,
                                   const float *b_r, char *ws, int32_t *expert_index, float *gate,
                                   float *router_logits, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel<true>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
-        if (err != hipSuccess) return err;
-        err = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel<false>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    hipError_t err;
+    static PerDeviceOnce once;
+    hipError_t err = once_per_device(once, [&] {
+        hipError_t e = hipFuncSetAttribute((const void *)router_fwd_mfma_kernel<true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute((const void *)router_fwd_mfma_kernel<false>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kRmLds);
+    });
+    if (err != hipSuccess) return err;
     const bool jitter = w.noise.jitter;
     {
         ProfScope ps("router_split_weights", s);

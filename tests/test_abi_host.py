@@ -61,6 +61,7 @@ def test_capacity_and_workspace_host_functions():
     (dict(expert_dropout=1.0), -3), (dict(expert_dropout=-0.1), -3),
     (dict(expert_dropout=float("nan")), -3),
     (dict(jitter_eps=1.0), -3), (dict(jitter_eps=-1e-3), -3), (dict(jitter_eps=float("nan")), -3),
+    (dict(reserved=1), -3),            # the header says "must be 0"
 ])
 def test_bad_config_is_refused(kw, status):
     assert ctypes.sizeof(sw.SwitchConfig) == 88       # the header's struct
@@ -98,6 +99,20 @@ def test_null_misaligned_and_small_workspace_are_refused():
     assert sw.switch_backward(cfg, None, 1.0, *bargs, ok, need, check=False) == -1
     assert sw.switch_backward(cfg, ok, float("nan"), *bargs, ok, need, check=False) == -3
     assert sw.switch_backward(cfg, ok, 1.0, *bargs, ok, 16, check=False) == -5
+
+
+def test_vector_read_pointers_must_be_aligned():
+    """b_r is read 16 bytes at a time by the matrix-core router beyond 128 experts, db_r is
+    written by whole chunks: both are covered by the alignment check."""
+    cfg = sw.SwitchConfig(256, 64, 256, 4, 1.25, 0.01, sw.SW_F32)
+    need = sw.switch_workspace_size(cfg)
+    ok = 0x1000
+    args = [ok] * 13
+    args[2] = ok + 4                                                                    # b_r
+    assert sw.switch_forward(cfg, *args, ok, need, check=False) == -6
+    bargs = [ok] * 10
+    bargs[7] = ok + 8                                                                   # db_r
+    assert sw.switch_backward(cfg, ok, 1.0, *bargs, ok, need, check=False) == -6
 
 
 def test_status_strings():
