@@ -72,7 +72,9 @@ typedef enum {
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
     SW_ERR_ALIGN = -6,     /* a tensor pointer is not 16-byte aligned            */
     SW_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch (see hipGetLastError) */
-    SW_ERR_STATE = -8      /* profiling calls out of order                       */
+    SW_ERR_STATE = -8,     /* profiling calls out of order                       */
+    SW_ERR_STATIC_LIMIT = -9 /* switch_forward_static: the configuration's workspace
+                              exceeds SW_STATIC_SCRATCH_BYTES                      */
 } sw_status;
 
 /* Layer description (host struct, passed by pointer, copied by the callee). */
@@ -193,6 +195,29 @@ int switch_backward(const switch_config *cfg,
                     void *dW_in,         /* [E, d_model, d_ff] act_dtype (out); same shape as W_in */
                     void *dW_out,        /* [E, d_ff, d_model] act_dtype (out)           */
                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Forward pass without a caller workspace, for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * Same arguments, outputs and results as switch_forward, bit for bit; the workspace is a
+ * fixed array of SW_STATIC_SCRATCH_BYTES of device memory inside the library (one copy per
+ * GPU, held from library load until the process ends).  The call allocates and frees
+ * nothing, on the device or through any library (with profiling off: switch_profile_enable
+ * creates events).  A configuration whose switch_workspace_size exceeds
+ * SW_STATIC_SCRATCH_BYTES is refused with SW_ERR_STATIC_LIMIT before anything else is looked
+ * at.  The array keeps the previous call's contents (the forward pass reads no word of it
+ * that the same call has not written, so nothing is cleared) and every call on one GPU uses
+ * the same array: two such calls that overlap in time on one GPU -- different streams or
+ * host threads -- race and give undefined results; calls on one stream are ordered and safe.
+ * There is no backward pass on this array: switch_backward needs the workspace of a
+ * switch_forward.
+ */
+#define SW_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int switch_forward_static(const switch_config *cfg, const void *x, const float *W_r,
+                          const float *b_r /* or NULL */, const void *W_in, const void *W_out,
+                          void *y, int32_t *expert_index, float *gate,
+                          int32_t *position_in_expert, uint8_t *dropped, int32_t *expert_counts,
+                          float *aux_loss, float *router_logits /* or NULL */, void *hip_stream);
 
 /* Human-readable name of a status code.  Host; static storage. */
 const char *switch_status_string(int status);

@@ -15,7 +15,9 @@ from .binding import (  # noqa: F401
     library_path,
     switch_backward,
     switch_capacity,
+    SW_STATIC_SCRATCH_BYTES,
     switch_forward,
+    switch_forward_static,
     switch_profile_collect,
     switch_profile_enable,
     switch_profile_read,

@@ -61,6 +61,8 @@ def _load():
     lib.switch_workspace_size.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t)]
     lib.switch_forward.restype = ctypes.c_int
     lib.switch_forward.argtypes = [cfgp] + [vp] * 13 + [vp, ctypes.c_size_t, vp]
+    lib.switch_forward_static.restype = ctypes.c_int
+    lib.switch_forward_static.argtypes = [cfgp] + [vp] * 13 + [vp]
     lib.switch_backward.restype = ctypes.c_int
     lib.switch_backward.argtypes = [cfgp, vp, ctypes.c_float] + [vp] * 10 + [vp, ctypes.c_size_t, vp]
     lib.switch_status_string.restype = ctypes.c_char_p
@@ -117,6 +119,22 @@ def switch_forward(cfg: SwitchConfig, x, W_r, b_r, W_in, W_out, y, expert_index,
                                 _p(workspace), int(workspace_bytes), hip_stream or None)
     if check and st != 0:
         raise SwitchError(st, "switch_forward")
+    return st
+
+
+SW_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024   # include/switchffn.h
+
+
+def switch_forward_static(cfg: SwitchConfig, x, W_r, b_r, W_in, W_out, y, expert_index, gate,
+                          position_in_expert, dropped, expert_counts, aux_loss, router_logits,
+                          hip_stream: int = 0, check: bool = True) -> int:
+    """switch_forward on the library's own fixed scratch array: no workspace argument."""
+    st = _load().switch_forward_static(ctypes.byref(cfg), _p(x), _p(W_r), _p(b_r), _p(W_in),
+                                       _p(W_out), _p(y), _p(expert_index), _p(gate),
+                                       _p(position_in_expert), _p(dropped), _p(expert_counts),
+                                       _p(aux_loss), _p(router_logits), hip_stream or None)
+    if check and st != 0:
+        raise SwitchError(st, "switch_forward_static")
     return st
 
 

@@ -184,6 +184,31 @@ static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace sw
 
+// ---- library-owned scratch for callers that cannot allocate --------------------
+// One copy per GPU (device memory of the loaded code object, held until the process ends).
+// In host code the array's name is only a handle: the device address is asked for once per
+// device, with that device current, and only that address is ever passed on.
+static __device__ __align__(256) unsigned char scratch[SW_STATIC_SCRATCH_BYTES];
+
+namespace sw {
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+// device address of `scratch` on the current device
+static int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SW_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SW_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SW_OK;
+}
+}  // namespace sw
+
 using namespace sw;
 
 extern "C" {
@@ -288,6 +313,34 @@ int switch_forward(const switch_config *cfg, const void *x, const float *W_r, co
                       dropped, expert_counts, aux_loss, router_logits, (char *)workspace, s);
 }
 
+int switch_forward_static(const switch_config *cfg, const void *x, const float *W_r,
+                          const float *b_r, const void *W_in, const void *W_out, void *y,
+                          int32_t *expert_index, float *gate, int32_t *position_in_expert,
+                          uint8_t *dropped, int32_t *expert_counts, float *aux_loss,
+                          float *router_logits, void *hip_stream) {
+    int st = check_config(cfg);
+    if (st != SW_OK) return st;
+    // the size limit comes first: it depends on the configuration alone
+    const Workspace w = layout_workspace(cfg);
+    if (w.total > (size_t)SW_STATIC_SCRATCH_BYTES) return SW_ERR_STATIC_LIMIT;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (cfg->T == 0) {
+        if (!expert_counts || !aux_loss) return SW_ERR_NULL;
+        if ((st = fill_zero(expert_counts, (size_t)cfg->E * 4, s))) return st;
+        return fill_zero(aux_loss, 4, s);
+    }
+    if ((st = check_forward_pointers(x, W_r, b_r, W_in, W_out, y, expert_index, gate,
+                                     position_in_expert, dropped, expert_counts, aux_loss,
+                                     router_logits)))
+        return st;
+    void *ws = nullptr;
+    if ((st = static_scratch(&ws))) return st;
+    // Nothing in the forward pass reads a workspace word before a kernel of the same call has
+    // written it, so what an earlier call left in the array needs no clearing.
+    return forward_on(cfg, w, x, W_r, b_r, W_in, W_out, y, expert_index, gate, position_in_expert,
+                      dropped, expert_counts, aux_loss, router_logits, (char *)ws, s);
+}
+
 int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const void *x,
                     const float *W_r, const float *b_r, const void *W_in, const void *W_out,
                     void *dx, float *dW_r, float *db_r, void *dW_in, void *dW_out, void *workspace,
@@ -348,6 +401,9 @@ const char *switch_status_string(int status) {
     case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
     case SW_ERR_LAUNCH: return "HIP launch failed";
     case SW_ERR_STATE: return "profiling call out of order";
+    case SW_ERR_STATIC_LIMIT:
+        return "configuration needs more workspace than the library's static scratch "
+               "(SW_STATIC_SCRATCH_BYTES); use switch_forward with a caller workspace";
     default: return "unknown status";
     }
 }

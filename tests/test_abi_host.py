@@ -81,6 +81,7 @@ def test_bad_config_is_refused(kw, status):
     # forward / backward refuse the same configuration before looking at pointers
     assert sw.switch_forward(cfg, *([None] * 13), None, 0, check=False) == status
     assert sw.switch_backward(cfg, None, 1.0, *([None] * 10), None, 0, check=False) == status
+    assert sw.switch_forward_static(cfg, *([None] * 13), check=False) == status
 
 
 def test_null_misaligned_and_small_workspace_are_refused():
@@ -110,15 +111,33 @@ def test_vector_read_pointers_must_be_aligned():
     args = [ok] * 13
     args[2] = ok + 4                                                                    # b_r
     assert sw.switch_forward(cfg, *args, ok, need, check=False) == -6
+    assert sw.switch_forward_static(cfg, *args, check=False) == -6
     bargs = [ok] * 10
     bargs[7] = ok + 8                                                                   # db_r
     assert sw.switch_backward(cfg, ok, 1.0, *bargs, ok, need, check=False) == -6
 
 
+def test_static_scratch_variant_refuses_what_does_not_fit():
+    """The size limit depends on the configuration alone and is checked first; NULL and
+    misaligned pointers are refused like in switch_forward; all before any launch."""
+    big = sw.SwitchConfig(65536, 768, 3072, 128, 1.0, 0.01, sw.SW_BF16)
+    assert sw.switch_workspace_size(big) > sw.SW_STATIC_SCRATCH_BYTES
+    assert sw.switch_forward_static(big, *([None] * 13), check=False) == -9
+    text = open(HEADER).read()
+    m = re.search(r"#define SW_STATIC_SCRATCH_BYTES \((\d+)u \* 1024u \* 1024u\)", text)
+    assert m and int(m.group(1)) * 1024 * 1024 == sw.SW_STATIC_SCRATCH_BYTES
+    small = sw.SwitchConfig(256, 64, 256, 4, 1.25, 0.01, sw.SW_F32)
+    assert sw.switch_workspace_size(small) <= sw.SW_STATIC_SCRATCH_BYTES
+    ok = 0x1000
+    assert sw.switch_forward_static(small, *([None] + [ok] * 12), check=False) == -1
+    assert sw.switch_forward_static(small, *([ok + 4] + [ok] * 12), check=False) == -6
+    assert "static scratch" in sw.switch_status_string(-9)
+
+
 def test_status_strings():
     assert sw.switch_status_string(0) == "ok"
-    seen = {sw.switch_status_string(s) for s in range(-8, 1)}
-    assert len(seen) == 9
+    seen = {sw.switch_status_string(s) for s in range(-9, 1)}
+    assert len(seen) == 10
     assert "unknown" in sw.switch_status_string(-99)
 
 
