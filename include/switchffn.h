@@ -66,7 +66,7 @@ typedef enum {
                               slots x max(d_model, d_ff) activations reach 2 GB       */
     SW_ERR_VALUE = -3,     /* capacity_factor not finite or <= 0, alpha not finite,
                               expert_dropout or jitter_eps outside [0, 1), ntlb_rounds
-                              outside 0 .. 16, reserved not 0                       */
+                              outside 0 .. 16, unknown bits in flags                */
     SW_ERR_DTYPE = -4,     /* act_dtype is neither SW_F32 nor SW_BF16, or ffn_kind
                               is not a sw_ffn_kind                               */
     SW_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small            */
@@ -108,8 +108,16 @@ typedef struct {
                                 still without a slot ask their next-best expert (by logit;
                                 equal logits: lower index first) for the capacity it has
                                 left, in sequence order inside the routing group.       */
-    int32_t reserved;        /* must be 0 (anything else is refused with SW_ERR_VALUE) */
+    int32_t flags;           /* 0, or SW_FLAG_SEPARATE_DISPATCH; other bits are refused
+                                with SW_ERR_VALUE                                       */
 } switch_config;
+
+/* bf16 layers run the dispatch and the combine of Sec. 5.4 inside the expert GEMMs (token rows
+ * are gathered by the operand loads, output rows are written to their tokens by the second
+ * GEMM's epilogue).  With this flag they run as separate passes over an expert-major copy of
+ * the tokens instead, as fp32 layers always do and as bf16 layers do by themselves when x
+ * reaches 2 GB.  Same results up to rounding (the gate is applied at a different place). */
+#define SW_FLAG_SEPARATE_DISPATCH 1
 
 /*
  * Random draws.  Element number idx (a 32-bit integer that wraps) of stream s gets the

@@ -10,6 +10,7 @@ _LIB_PATH = os.path.join(HERE, "libswitchffn.so")
 
 SW_F32, SW_BF16 = 0, 1
 SW_FFN_RELU, SW_FFN_GEGLU = 0, 1
+SW_FLAG_SEPARATE_DISPATCH = 1
 
 
 class SwitchError(RuntimeError):
@@ -34,7 +35,7 @@ class SwitchConfig(ctypes.Structure):
         ("jitter_eps", ctypes.c_float),
         ("seed", ctypes.c_uint64),
         ("ntlb_rounds", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("flags", ctypes.c_int32),
     ]
 
 

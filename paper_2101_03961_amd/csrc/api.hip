@@ -27,7 +27,7 @@ int check_config(const switch_config *cfg) {
     if (!(cfg->expert_dropout >= 0.f && cfg->expert_dropout < 1.f)) return SW_ERR_VALUE;
     if (!(cfg->jitter_eps >= 0.f && cfg->jitter_eps < 1.f)) return SW_ERR_VALUE;
     if (cfg->ntlb_rounds < 0 || cfg->ntlb_rounds > 16) return SW_ERR_VALUE;
-    if (cfg->reserved != 0) return SW_ERR_VALUE;
+    if (cfg->flags & ~SW_FLAG_SEPARATE_DISPATCH) return SW_ERR_VALUE;
     // slot indices (expert * slots per expert + position) are kept in 32 bits
     const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
     const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
@@ -76,7 +76,15 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.grp_off = take((size_t)w.n * E * 4);
     w.loss_part = take(8 * 8);
     w.kept = take(E * 4);
-    w.slot_token = take(E * C * 4);
+    // 128 entries of padding: the GEMMs that gather k-rows read the table a step past an
+    // expert's last slot (and mask what they read)
+    w.slot_token = take((E * C + 128) * 4);
+    w.slot_gate = take(E * C * 4);
+    w.slot_off = take((E * C + 128) * 4);
+    // dispatch and combine inside the GEMMs: bf16, and x / dy / y addressed through one buffer
+    // descriptor with 32-bit byte offsets
+    w.fused = cfg->act_dtype == SW_BF16 && !(cfg->flags & SW_FLAG_SEPARATE_DISPATCH) &&
+              (double)T * (double)d * 2.0 < 2147483647.0;
     w.tok_slot = take(T * 4);
     w.Xd = take(E * C * d * w.elt);
     w.H = take(w.geglu ? E * C * f1 * w.elt : 0);
@@ -267,10 +275,13 @@ static int forward_on(const switch_config *cfg, const Workspace &w, const void *
     if ((st = status_of(launch_dispatch(w, dt, cfg->alpha, x, ws, position_in_expert, dropped,
                                         aux_loss, router_logits, expert_index, gate, s))))
         return st;
-    if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
+    const TokenMajor tm{x, nullptr, y};
+    // fused: rows of tokens without a slot are +0, all others are written by the second GEMM
+    if (w.fused && (st = status_of(launch_zero_dropped(w, ws, y, s)))) return st;
+    if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, tm, s)))) return st;
     if (w.geglu && (st = status_of(launch_geglu_fwd(w, dt, ws, s)))) return st;
-    if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, s)))) return st;
-    if ((st = status_of(launch_combine(w, dt, ws, y, s)))) return st;
+    if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, tm, s)))) return st;
+    if (!w.fused && (st = status_of(launch_combine(w, dt, ws, y, s)))) return st;
     return SW_OK;
 }
 
@@ -375,14 +386,21 @@ int switch_backward(const switch_config *cfg, const void *dy, float d_aux, const
     const int dt = cfg->act_dtype;
     auto gemm = dt == SW_BF16 ? launch_gemm_bf16 : launch_gemm_f32;
 
-    if ((st = status_of(launch_combine_bwd(w, dt, dy, ws, s)))) return st;
-    if ((st = status_of(gemm(GEMM_DGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    const TokenMajor tm{x, dy, nullptr};
+    // fused: only the gate gradient is left of the combine's backward pass (dy is read by the
+    // GEMMs through the slot -> token table)
+    if (w.fused)
+        st = status_of(launch_gate_grad(w, dy, ws, s));
+    else
+        st = status_of(launch_combine_bwd(w, dt, dy, ws, s));
+    if (st) return st;
+    if ((st = status_of(gemm(GEMM_DGRAD2, w, ws, W_in, W_out, dW_in, dW_out, tm, s)))) return st;
     if (w.geglu && (st = status_of(launch_geglu_bwd(w, dt, ws, s)))) return st;
     // dH is consumed right after it is produced (the first-layer data gradient walks the
     // experts backwards, see launch_gemm_bf16), then the two weight gradients
-    if ((st = status_of(gemm(GEMM_DGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
-    if ((st = status_of(gemm(GEMM_WGRAD1, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
-    if ((st = status_of(gemm(GEMM_WGRAD2, w, ws, W_in, W_out, dW_in, dW_out, s)))) return st;
+    if ((st = status_of(gemm(GEMM_DGRAD1, w, ws, W_in, W_out, dW_in, dW_out, tm, s)))) return st;
+    if ((st = status_of(gemm(GEMM_WGRAD1, w, ws, W_in, W_out, dW_in, dW_out, tm, s)))) return st;
+    if ((st = status_of(gemm(GEMM_WGRAD2, w, ws, W_in, W_out, dW_in, dW_out, tm, s)))) return st;
     if ((st = status_of(launch_router_bwd(w, dt, cfg->alpha, d_aux, x, W_r, ws, dx, dW_r, db_r, s))))
         return st;
     return SW_OK;
@@ -395,7 +413,7 @@ const char *switch_status_string(int status) {
     case SW_ERR_SHAPE: return "shape out of range (T, E, d_model, d_ff; 16-byte row chunks)";
     case SW_ERR_VALUE:
         return "capacity_factor must be finite and > 0; alpha, d_aux finite; expert_dropout and "
-               "jitter_eps in [0, 1); ntlb_rounds in 0..16; reserved 0";
+               "jitter_eps in [0, 1); ntlb_rounds in 0..16; flags: known bits only";
     case SW_ERR_DTYPE: return "act_dtype must be SW_F32 or SW_BF16, ffn_kind SW_FFN_RELU or SW_FFN_GEGLU";
     case SW_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SW_ERR_ALIGN: return "tensor pointer not 16-byte aligned";

@@ -22,6 +22,10 @@ template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf
 
 constexpr int kWave = 64;
 
+// Entry of the slot -> row-offset table for a slot without a token: as a buffer offset it lies
+// beyond every descriptor (all are kept below 2 GB), so loads through it read zeros.
+constexpr uint32_t kNoRow = 0x80000000u;
+
 // Token block of the router / position kernels: one block of kRouteTB threads
 // owns kRouteTB consecutive tokens.
 constexpr int kRouteTB = 256;
@@ -114,7 +118,12 @@ struct Workspace {
     size_t grp_off;             // i32 [n][E]   first slot of group g inside expert e's slots:
                                 //              sum of min(counts_g, Cg) over earlier groups
     size_t kept;                // i32 [E]      kept tokens per expert: sum over groups of min(count, Cg)
-    size_t slot_token;          // i32 [E][C]   token held by each slot (valid for slot < kept[e])
+    int fused;                  // bf16: dispatch and combine run inside the GEMMs (x, dy gathered by
+                                //   the slot -> token table, y written by the second GEMM)
+    size_t slot_token;          // i32 [E][C] + 128  token held by each slot (valid for slot < kept[e])
+    size_t slot_gate;           // f32 [E][C]   gate of that token (the probability that scales its output)
+    size_t slot_off;            // u32 [E][C] + 128  byte offset of that token's row in x / dy / y:
+                                //              token * d * 2 (only kept when `fused`)
     size_t tok_slot;            // i32 [T]      slot (e * C + grp_off[g][e] + pos) of each kept token,
                                 //              -1 for dropped ones
     size_t Xd;                  // act [E][C][d]   dispatched tokens
@@ -243,9 +252,21 @@ enum GemmKind {
     GEMM_WGRAD2, // dW_out = A^T dO               q: d_ff  p: d_model  k: slot (< kept)
     GEMM_WGRAD1  // dW_in = Xd^T dH               q: d_model p: f1     k: slot (< kept)
 };
+// The caller's token-major tensors, [T][d_model]: what the GEMMs gather from and scatter to
+// when dispatch and combine run inside them (Workspace::fused).
+struct TokenMajor {
+    const void *x;    // layer input
+    const void *dy;   // gradient of the output (backward only)
+    void *y;          // layer output (forward only)
+};
 hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
-                            const void *W_out, void *dW_in, void *dW_out, hipStream_t s);
+                            const void *W_out, void *dW_in, void *dW_out, const TokenMajor &tm,
+                            hipStream_t s);
 hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
-                           const void *W_out, void *dW_in, void *dW_out, hipStream_t s);
+                           const void *W_out, void *dW_in, void *dW_out, const TokenMajor &tm,
+                           hipStream_t s);
+// fused path: +0 rows of y for the tokens without a slot; gate gradient from the saved outputs
+hipError_t launch_zero_dropped(const Workspace &w, char *ws, void *y, hipStream_t s);
+hipError_t launch_gate_grad(const Workspace &w, const void *dy, char *ws, hipStream_t s);
 
 }  // namespace sw

@@ -49,15 +49,16 @@ template <> __device__ __forceinline__ Chunk16 pack<bf16>(const float *v) {
 // -----------------------------------------------------------------------------
 // position_in_expert[t] = block_off[block(t)][e_t] + local_rank[t] (rank inside the token's
 // routing group); dropped mask (position >= Cg); slot of each kept token,
-// e * C + grp_off[g][e] + position, and the slot -> token table.  Thread 0 also finishes
-// the auxiliary loss.
+// e * C + grp_off[g][e] + position, the slot -> token table and the gate of each slot's token.
+// Thread 0 also finishes the auxiliary loss.
 // -----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void positions_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ local_rank,
     const int32_t *__restrict__ block_off, const int32_t *__restrict__ grp_off,
-    int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out,
-    int32_t *__restrict__ slot_token,
-    int32_t *__restrict__ tok_slot, const double *__restrict__ loss_part, int loss_parts,
+    const float *__restrict__ gate, int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out,
+    int32_t *__restrict__ slot_token, float *__restrict__ slot_gate, uint32_t *__restrict__ slot_off,
+    uint32_t row_bytes, int32_t *__restrict__ tok_slot, const double *__restrict__ loss_part,
+    int loss_parts,
     double loss_scale /* alpha E / n */, float *__restrict__ aux_out, int T, int Tg, int nbg, int E,
     int C, int Cg) {
     const int t = blockIdx.x * 256 + threadIdx.x;
@@ -73,7 +74,11 @@ __global__ __launch_bounds__(256) void positions_kernel(
     pos_out[t] = p;
     dropped_out[t] = dr;
     const int slot = e * C + grp_off[(size_t)(t / Tg) * E + e] + p;
-    if (!dr) slot_token[slot] = t;
+    if (!dr) {
+        slot_token[slot] = t;
+        slot_gate[slot] = gate[t];
+        slot_off[slot] = (uint32_t)t * row_bytes;   // used only where it cannot overflow
+    }
     tok_slot[t] = dr ? -1 : slot;
 }
 
@@ -165,8 +170,75 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
 }
 
 // -----------------------------------------------------------------------------
+// Dispatch and combine inside the GEMMs: what is left of the two passes.
+//   zero_dropped: y[t][:] = +0 for the tokens without a slot (the second GEMM's epilogue writes
+//                 the rows of all others).  One wave per token.
+//   gate_grad:    dgate[t] = <dy[t], o_t> for kept tokens, 0 for dropped ones, from the saved
+//                 slot-major copy of the output rows Y[slot_t] = gate[t] o_t: <dy[t], Y[slot_t]> /
+//                 gate[t] (a gate that underflowed to 0 gets gradient 0: its probability is 0
+//                 and so is every term the gradient would enter).  One wave per token.
+// -----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zero_dropped_kernel(Chunk16 *__restrict__ y,
+                                                           const int32_t *__restrict__ tok_slot,
+                                                           int T, int cpr) {
+    const int lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T || tok_slot[t] >= 0) return;
+    const Chunk16 zero = {{0u, 0u, 0u, 0u}};
+    for (int col = lane; col < cpr; col += kWave) y[(size_t)t * cpr + col] = zero;
+}
+
+template <typename XT>
+__global__ __launch_bounds__(256) void gate_grad_kernel(const Chunk16 *__restrict__ dy,
+                                                        const Chunk16 *__restrict__ Y,
+                                                        const int32_t *__restrict__ tok_slot,
+                                                        const float *__restrict__ gate,
+                                                        float *__restrict__ dgate, int T, int cpr) {
+    const int lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    const int slot_or_none = tok_slot[t];
+    if (slot_or_none < 0) {
+        if (lane == 0) dgate[t] = 0.f;
+        return;
+    }
+    const size_t slot = (size_t)slot_or_none;
+    float dot = 0.f;
+    for (int col = lane; col < cpr; col += kWave) {
+        float av[Vec<XT>::N], bv[Vec<XT>::N];
+        unpack<XT>(dy[(size_t)t * cpr + col], av);
+        unpack<XT>(Y[slot * cpr + col], bv);
+#pragma unroll
+        for (int i = 0; i < Vec<XT>::N; ++i) dot = fmaf(av[i], bv[i], dot);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, kWave);
+    if (lane == 0) {
+        const float g = gate[t];
+        dgate[t] = g > 0.f ? dot / g : 0.f;
+    }
+}
+
+// -----------------------------------------------------------------------------
 // launchers
 // -----------------------------------------------------------------------------
+hipError_t launch_zero_dropped(const Workspace &w, char *ws, void *y, hipStream_t s) {
+    ProfScope ps("zero_dropped", s);
+    hipLaunchKernelGGL(zero_dropped_kernel, dim3((unsigned)ceil_div(w.T, 256 / kWave)), dim3(256), 0,
+                       s, (Chunk16 *)y, (const int32_t *)(ws + w.tok_slot), (int)w.T,
+                       (int)(w.d / 8));
+    return hipGetLastError();
+}
+
+hipError_t launch_gate_grad(const Workspace &w, const void *dy, char *ws, hipStream_t s) {
+    ProfScope ps("gate_grad", s);
+    hipLaunchKernelGGL(gate_grad_kernel<bf16>, dim3((unsigned)ceil_div(w.T, 256 / kWave)), dim3(256),
+                       0, s, (const Chunk16 *)dy, (const Chunk16 *)(ws + w.O),
+                       (const int32_t *)(ws + w.tok_slot), (const float *)(ws + w.gate),
+                       (float *)(ws + w.dgate), (int)w.T, (int)(w.d / 8));
+    return hipGetLastError();
+}
+
 hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
                            const float *logits, int32_t *expert_index, float *gate,
@@ -177,7 +249,9 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const voi
         hipLaunchKernelGGL(positions_kernel, dim3((unsigned)ceil_div(w.T, 256)), dim3(256), 0, s,
                            (const int32_t *)(ws + w.idx), (const int32_t *)(ws + w.local_rank),
                            (const int32_t *)(ws + w.block_off), (const int32_t *)(ws + w.grp_off),
-                           position_in_expert, dropped, (int32_t *)(ws + w.slot_token),
+                           (const float *)(ws + w.gate), position_in_expert, dropped,
+                           (int32_t *)(ws + w.slot_token), (float *)(ws + w.slot_gate),
+                           (uint32_t *)(ws + w.slot_off), (uint32_t)(w.d * w.elt),
                            (int32_t *)(ws + w.tok_slot), (const double *)(ws + w.loss_part),
                            route_scan_blocks(w), (double)alpha * (double)w.E / (double)w.n,
                            aux_loss, (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E, (int)w.C,
@@ -189,6 +263,7 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const voi
         (err = launch_ntlb(w, ws, logits, expert_index, gate, position_in_expert, dropped, s)) !=
             hipSuccess)
         return err;
+    if (w.fused) return hipSuccess;   // the GEMMs read x through the slot -> token table
     {
         ProfScope ps("dispatch_gather", s);
         const int vec = dtype == SW_BF16 ? 8 : 4;

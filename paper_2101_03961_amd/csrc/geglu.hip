@@ -1,7 +1,8 @@
 // Gated-GELU expert FFN (the FFN_GEGLU variant of the paper's model tables): the
 // element-wise half of the first layer.  The first GEMM leaves H = Xd W_in = [u | v]
 // (gate pre-activations, linear part; f columns each), these kernels turn it into
-//   forward   A  = GELU(u) v q                       GELU(u) = u Phi(u), exact
+//   forward   A  = GELU(u) v q  (times the token's gate when the combine runs inside the GEMMs)
+//                                                    GELU(u) = u Phi(u), exact
 //   backward  du = dA q v GELU'(u),  dv = dA q GELU(u),  dH = [du | dv]
 // with q the expert-dropout factor of the hidden unit (1 without dropout; Sec. 2.4).
 // Both are streaming kernels: one lane handles 16 bytes of consecutive hidden units of
@@ -52,6 +53,7 @@ __global__ __launch_bounds__(256) void geglu_kernel(const XT *__restrict__ H,
                                                     XT *__restrict__ out,   // A (forward) or dH
                                                     const int32_t *__restrict__ kept,
                                                     const int32_t *__restrict__ slot_token,
+                                                    const float *__restrict__ slot_gate,
                                                     int slots, int f, Noise nz) {
     typedef typename Chunk<XT>::type V;
     constexpr int kGegluChunk = Chunk<XT>::n;
@@ -79,10 +81,13 @@ __global__ __launch_bounds__(256) void geglu_kernel(const XT *__restrict__ H,
         }
     }
     if (!BACKWARD) {
+        // slot_gate set: the hidden row is stored times its token's gate, so that the second
+        // GEMM's rows are the layer's output rows (combine inside the GEMMs)
+        const float g = slot_gate ? slot_gate[slot] : 1.f;
         V a;
 #pragma unroll
         for (int i = 0; i < kGegluChunk; ++i)
-            a[i] = from_f32<XT>(to_f32(u[i]) * normal_of(to_f32(u[i])).cdf * to_f32(v[i]) * q[i]);
+            a[i] = from_f32<XT>(to_f32(u[i]) * normal_of(to_f32(u[i])).cdf * to_f32(v[i]) * q[i] * g);
         *(V *)(out + slot * f + j0) = a;
     } else {
         const V da = *(const V *)(dA + slot * f + j0);
@@ -109,7 +114,9 @@ static hipError_t geglu_launch(const Workspace &w, char *ws, hipStream_t s) {
     hipLaunchKernelGGL((geglu_kernel<XT, BACKWARD>), grid, dim3(256), 0, s,
                        (const XT *)(ws + w.H), (const XT *)(ws + w.dA),
                        (XT *)(ws + (BACKWARD ? w.dH : w.A)), (const int32_t *)(ws + w.kept),
-                       (const int32_t *)(ws + w.slot_token), (int)w.C, (int)w.f, w.noise);
+                       (const int32_t *)(ws + w.slot_token),
+                       (!BACKWARD && w.fused) ? (const float *)(ws + w.slot_gate) : nullptr, (int)w.C,
+                       (int)w.f, w.noise);
     return hipGetLastError();
 }
 

@@ -49,6 +49,15 @@
 // in whole 256-byte row segments; fused into it: ReLU and one mask bit per element
 // (first forward GEMM), that mask (gradient w.r.t. the hidden activations), the
 // gathered addend of the router's dx.
+//
+// Dispatch and combine (Sec. 5.4) without a pass of their own.  With GATHER set an operand's
+// rows are fetched from the token-major tensors by the slot -> token table: the first forward
+// GEMM and the first-layer weight gradient read x, the second-layer data and weight gradients
+// read dy.  The first GEMM's epilogue scales each hidden row by its token's gate (EPI_SCALE) so
+// that the second GEMM's rows are the layer's output rows, which its epilogue writes straight
+// to y[token] (EPI_SCATTER, next to the slot-major copy the gate gradient reads); the second-
+// layer data gradient applies the gate as a row scale likewise, (g dy) W^T = g (dy W^T), and
+// the second-layer weight gradient needs no scaled dy at all: (g A)^T dy = A^T (g dy).
 #include "common.h"
 #include "lds_operands.h"
 
@@ -87,6 +96,11 @@ struct GemmArgs {
     int q_plane, p_plane;               //   [tile][row][256], plane sizes in elements
     float *Cf;                          // ROUTER_DWR: fp32 partial sums [split][q][p]
     int T_total, tps;                   // ROUTER_DWR: tokens, tokens per split
+    // dispatch / combine inside the GEMM (see GATHER, EPI_SCALE, EPI_SCATTER)
+    uint32_t gather_bytes;              // bytes of the token-major matrix a gathered operand points at
+    const uint32_t *slot_off;           // byte offset of each slot's token row in the token-major tensors
+    const float *row_scale;             // EPI_SCALE: gate of each slot's token, [expert][slots]
+    bf16 *Cscatter;                     // EPI_SCATTER: token-major output, row token(slot)
 };
 
 // What the "experts" and the k dimension of a launch are.
@@ -98,13 +112,20 @@ struct GemmArgs {
 //               range, k = tokens of the range, fp32 output.
 enum GemmMode { MODE_EXPERTS = 0, MODE_ROUTER_DX = 1, MODE_ROUTER_DWR = 2 };
 
-template <bool TRANS> struct OperandOf { typedef DirectOperand64 type; };
-template <> struct OperandOf<true> { typedef TransOperand64 type; };
+template <bool TRANS, bool GATHER> struct OperandOf { typedef DirectOperand64 type; };
+template <> struct OperandOf<true, false> { typedef TransOperand64 type; };
+template <> struct OperandOf<false, true> { typedef DirectGather64 type; };
+template <> struct OperandOf<true, true> { typedef TransGather64 type; };
+// which operands are gathered by the slot -> token table
+enum { GATHER_NONE = 0, GATHER_Q = 1, GATHER_P = 2 };
 
 // EPI_DROP is a flag on top of EPI_RELU / EPI_MASK: expert dropout (Sec. 2.4) zeroes hidden
 // units after the ReLU and scales the survivors; the mask bits then say "active and kept",
 // and the masked gradient is scaled by the same factor.
-enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_DROP = 4 };
+// EPI_SCALE multiplies every output row by its slot's gate before the store (after ReLU and
+// dropout; the mask bits are taken from the stored values, and gate > 0).  EPI_SCATTER also
+// writes every output row to row token(slot) of a token-major tensor.
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_MASK = 2, EPI_DROP = 4, EPI_SCALE = 8, EPI_SCATTER = 16 };
 
 // One output tile of one expert.
 struct Tile {
@@ -155,16 +176,35 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
 // wait until at most N of this wave's direct loads are still in flight
 #define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
 
-template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE>
+template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE, int GATHER>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int EPI_BASE = EPI & 3;
     constexpr bool DROP = (EPI & EPI_DROP) != 0;
+    constexpr bool SCALE = (EPI & EPI_SCALE) != 0;
+    constexpr bool SCATTER = (EPI & EPI_SCATTER) != 0;
+    constexpr bool GQ = (GATHER & GATHER_Q) != 0, GP = (GATHER & GATHER_P) != 0;
+    constexpr bool GQ_ROWS = GQ && !Q_TRANS;            // Q's tile rows are gathered (per tile)
+    constexpr bool G_STEPS = (GQ && Q_TRANS) || GP;     // an operand's k-rows are gathered (per step)
+    // Ragged row tiles.  Where q runs over an expert's slots (Q_LIMITED, Q stored [row][k]) the
+    // tile's 32-row blocks are dealt out to the two wave rows alternately -- block b goes to wave
+    // row b % 2 as its block b / 2 -- so that a tile with few rows keeps both wave rows busy
+    // and each wave multiplies only its first nj = ceil(rows / 64) blocks: a last tile of 40
+    // rows costs a quarter of the MFMAs of a full one instead of all of them.  LDS row
+    // 128 wq + 32 j + r holds tile row 32 (2 j + wq) + r; blocks without rows are not loaded.
+    constexpr bool DEAL = Q_LIMITED && !Q_TRANS && MODE == MODE_EXPERTS;
+    static_assert(!(GP && !P_TRANS), "P is gathered only along k");
+    static_assert(!(SCALE && SCATTER), "one per-row table per launch");
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave & 1;
     const int wq = wave >> 1;
+    // tile row of row r of block j of wave row w (see DEAL below)
+    auto row_of = [](int w, int j, int r) {
+        return (Q_LIMITED && !Q_TRANS && MODE == MODE_EXPERTS) ? (2 * j + w) * 32 + r
+                                                                : w * 128 + j * 32 + r;
+    };
     // LDS address of the ring (the dynamic segment starts the block's allocation)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
 
@@ -183,11 +223,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     // under way, and they stay in flight during the epilogue (which has its own LDS).
     // A tile takes at least two steps (steps past its k range read zeros).
     auto steps_of = [&](const Tile &t) { return (t.klim + kBK - 1) / kBK; };
-    typename OperandOf<P_TRANS>::type op;
-    typename OperandOf<Q_TRANS>::type oq;
+    typename OperandOf<P_TRANS, GP>::type op;
+    typename OperandOf<Q_TRANS, GQ>::type oq;
     op.init_frag(lane, wp * 128);
     oq.init_frag(lane, wq * 128);
     int ld_nk = 0;      // k steps (with data) of the tile the loads are in
+    int ld_e = 0;       // its expert
+    int ld_rows = kBQ;  // DEAL: its q rows
+    // Values fetched with ordinary loads long before their use, and "pinned" (passed through an
+    // empty asm) right after a k step's barrier, where every load of the wave has completed
+    // anyway: the wait the compiler puts before their first use then costs nothing, while a
+    // wait in front of the epilogue or of the next tile's loads would also sit out the direct
+    // loads in flight, which the compiler does not count.
+    // (row offsets: byte offset of a slot's token row in the token-major tensors, slot_off)
+    uint32_t off_rows = kOobOffset;  // GQ_ROWS: offset of row 8 wave + (lane & 7) + 32 (lane >> 3) of the next tile
+    // G_STEPS: offsets of the lane's k-rows 16 wave + 2 i + lane / 32 of the step to be loaded
+    uint32_t off_step[8] = {kOobOffset, kOobOffset, kOobOffset, kOobOffset,
+                            kOobOffset, kOobOffset, kOobOffset, kOobOffset};
+    uint32_t ep_lo = 0, ep_hi = 0;   // SCALE / SCATTER: gate / offset of rows lane, lane + 64 of the wave's q rows
+    auto rows_offsets = [&](const Tile &t) {
+        const int row = t.q0 + 8 * wave + (lane & 7) + 32 * (lane >> 3);
+        return row < t.qlim ? a.slot_off[(size_t)t.e * a.slots + row] : kOobOffset;
+    };
     auto begin_loads = [&](const Tile &t) {
         if (MODE == MODE_ROUTER_DX) {
             // the 384 k values of an expert tile are read from 256-wide (hi | lo) rows of that
@@ -198,15 +255,32 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             oq.init_load(a.Q, a.ldq, t.q0, a.router_tiles * a.Qdim, a.router_tiles * a.q_plane, lane,
                          wave);
         } else {
-            op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave);
-            oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave);
+            if constexpr (GP)
+                op.init_gather(a.P, a.gather_bytes, t.p0, a.Pdim, lane, wave);
+            else
+                op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave);
+            if constexpr (GQ_ROWS)
+                oq.init_gather(a.Q, a.gather_bytes, t.klim, lane, wave, off_rows, DEAL);
+            else if constexpr (GQ)
+                oq.init_gather(a.Q, a.gather_bytes, t.q0, t.qlim, lane, wave);
+            else
+                oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave);
         }
         ld_nk = steps_of(t);
+        ld_e = t.e;
+        ld_rows = t.qlim - t.q0;
     };
     // k offsets (P, Q) of step j of the tile the loads are in; steps past its range read zeros
     int k0p_ = 0, k0q_ = 0;
     auto k_of = [&](int j) {
         const int r = j < ld_nk ? j : ld_nk;
+        if (G_STEPS) {
+            // row offsets of the lane's k-rows of the step: two addresses per load instruction.
+            // Slots without a token hold kOobOffset, and the table is padded for steps past the end.
+            const uint32_t *row = a.slot_off + (size_t)ld_e * a.slots + r * kBK + 16 * wave + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) off_step[i] = row[2 * i];
+        }
         if (MODE == MODE_ROUTER_DX) {
             // six steps per expert tile -- 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi --
             // in that tile's planes; past the last tile: beyond the k limit (zeros)
@@ -222,17 +296,42 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         }
     };
 
+    uint32_t mb[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // EPI_MASK: the lane's 32 bytes of ReLU bits of the tile
+    int slot_lo = -1, slot_hi = -1;   // ROUTER_DX: slot of the addend of rows lane, lane + 64 (-1: none)
+    auto pin_values = [&]() {
+        if (GQ_ROWS) asm volatile("" : "+v"(off_rows));
+        if (G_STEPS)
+            asm volatile("" : "+v"(off_step[0]), "+v"(off_step[1]), "+v"(off_step[2]), "+v"(off_step[3]),
+                              "+v"(off_step[4]), "+v"(off_step[5]), "+v"(off_step[6]), "+v"(off_step[7]));
+        if (SCALE || SCATTER) asm volatile("" : "+v"(ep_lo), "+v"(ep_hi));
+        if (EPI_BASE == EPI_MASK)
+            asm volatile("" : "+v"(mb[0]), "+v"(mb[1]), "+v"(mb[2]), "+v"(mb[3]), "+v"(mb[4]),
+                              "+v"(mb[5]), "+v"(mb[6]), "+v"(mb[7]));
+        if (MODE == MODE_ROUTER_DX) asm volatile("" : "+v"(slot_lo), "+v"(slot_hi));
+    };
+
     // fragments: two register sets, each fragment as two 8-byte halves
     s16x4 fa[2][4][2], fb[2][4][2];
-    constexpr int kNP = OperandOf<P_TRANS>::type::kPieces;
-    constexpr int kNR = kNP + OperandOf<Q_TRANS>::type::kPieces;   // LDS reads per sub-step
+    constexpr int kNP = OperandOf<P_TRANS, GP>::type::kPieces;
+    constexpr int kNR = kNP + OperandOf<Q_TRANS, GQ>::type::kPieces;   // LDS reads per sub-step
 
 // direct loads into the stage of pipeline step GS, load G of sixteen (P: 0..7, Q: 8..15)
 #define SW_ISSUE_ONE(GS, G)                                                           \
     do {                                                                              \
         const uint32_t st_ = lds0 + (uint32_t)(((GS) & (kStages - 1)) * kStageBytes); \
-        if ((G) < 8) op.issue_one(st_, k0p_, wave, (G));                              \
-        else oq.issue_one(st_ + kOpBytes64, k0q_, wave, (G)-8);                       \
+        if ((G) < 8) {                                                                \
+            if constexpr (GP) op.issue_one(st_, wave, (G), off_step[(G)]);            \
+            else if constexpr (P_TRANS) op.issue_one(st_, k0p_, wave, (G));           \
+            else op.issue_one(st_, k0p_, wave, (G), (G));                             \
+        } else {                                                                      \
+            const int i_ = ((G)-8) & 7;                                               \
+            const int blk_ = DEAL ? 2 * (i_ & 3) + (i_ >> 2) : i_;                    \
+            if constexpr (GQ && Q_TRANS)                                              \
+                oq.issue_one(st_ + kOpBytes64, wave, i_, off_step[i_]);               \
+            else if constexpr (Q_TRANS) oq.issue_one(st_ + kOpBytes64, k0q_, wave, i_); \
+            else if (!DEAL || blk_ * 32 < ld_rows)                                    \
+                oq.issue_one(st_ + kOpBytes64, k0q_, wave, i_, blk_);                 \
+        }                                                                             \
     } while (0)
 // LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of pipeline step GS, sub-step KS into SET
 #define SW_READ_GROUP(SET, GS, KS, G)                                                 \
@@ -247,6 +346,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #define SW_MFMA_PAIR(SET, G)                                                          \
     _Pragma("unroll") for (int m_ = 2 * (G); m_ < 2 * (G) + 2; ++m_) {                \
         const int i_ = m_ >> 2, j_ = m_ & 3;                                          \
+        if (DEAL && j_ >= nj) continue;                                               \
         const s16x8 a8_ = __builtin_shufflevector(fa[SET][i_][0], fa[SET][i_][1], 0, 1, 2, 3, 4, 5, 6, 7); \
         const s16x8 b8_ = __builtin_shufflevector(fb[SET][j_][0], fb[SET][j_][1], 0, 1, 2, 3, 4, 5, 6, 7); \
         acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
@@ -278,6 +378,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         }                                                                             \
         SW_WAIT_VMCNT(0); /* the next step has landed */                              \
         __syncthreads();                                                              \
+        pin_values();                                                                 \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
             SW_ISSUE_ONE(GS, 2 * g);                                                  \
             SW_ISSUE_ONE(GS, 2 * g + 1);                                              \
@@ -289,6 +390,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 
     // Start of the pipeline: both stages are filled with the first tile's steps 0 and 1,
     // then step 0 is awaited.
+    if (GQ_ROWS) off_rows = rows_offsets(cur);
     begin_loads(cur);
 #pragma unroll
     for (int st = 0; st < kStages; ++st) {
@@ -296,28 +398,52 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
         for (int g = 0; g < 16; ++g) SW_ISSUE_ONE(st, g);
     }
-    SW_WAIT_VMCNT(16);
+    // (step 0 has landed; with dealt row blocks a step may be fewer than sixteen loads, so all
+    // are awaited rather than all but the last sixteen)
+    if (DEAL) SW_WAIT_VMCNT(0); else SW_WAIT_VMCNT(16);
     __syncthreads();
 
     int gs = 0;   // pipeline step of the current tile's first k step
     while (true) {
         const int nsteps = steps_of(cur) > 2 ? steps_of(cur) : 2;
+        // DEAL: 32-row blocks with work per wave row (see above)
+        const int nj = DEAL ? (min(cur.qlim - cur.q0, kBQ) + 63) / 64 : 4;
         const bool have_next = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, nxt);
 
-        // ROUTER_DX: slot of the addend of rows lane and lane + 64 of the wave's 128 rows
-        // (-1: dropped token or past the end: nothing to add)
-        int slot_lo = -1, slot_hi = -1;
+        // Per-tile values of the epilogue and of the next tile's loads, asked for here and
+        // pinned after the first barrier of the tile (see pin_values).
         if (MODE == MODE_ROUTER_DX) {
-            // (asked for here, used only in the epilogue: nothing waits for them before)
+            // slot of the addend of rows lane and lane + 64 of the wave's 128 rows
+            // (-1: dropped token or past the end: nothing to add)
             const int q = cur.q0 + wq * 128 + lane;
-            if (q < cur.qlim) slot_lo = a.tok_slot[q];
-            if (q + 64 < cur.qlim) slot_hi = a.tok_slot[q + 64];
+            slot_lo = q < cur.qlim ? a.tok_slot[q] : -1;
+            slot_hi = q + 64 < cur.qlim ? a.tok_slot[q + 64] : -1;
         }
-        uint32_t mb[8];   // EPI_MASK: the lane's 32 bytes of ReLU bits of this tile
         auto bits_of = [&](int ln) {
             return (uint32_t *)(a.relu_bits + (size_t)cur.index * kReluBitsPerTile +
                                 (size_t)(wave * 64 + ln) * 32);
         };
+        if (EPI_BASE == EPI_MASK) {
+            const uint32_t *bits = bits_of(lane);
+            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mb[w] = b0[w]; mb[4 + w] = b1[w]; }
+        }
+        if (SCALE || SCATTER) {
+            // gate (SCALE) or row offset (SCATTER) of the wave's q rows: lane 32 j + r holds the
+            // value of row r of the wave's block j (ep_lo: j = 0, 1; ep_hi: j = 2, 3)
+            const int q_lo = cur.q0 + row_of(wq, lane >> 5, lane & 31);
+            const int q_hi = cur.q0 + row_of(wq, 2 + (lane >> 5), lane & 31);
+            const size_t at = (size_t)cur.e * a.slots;
+            if (SCALE) {
+                ep_lo = q_lo < cur.qlim ? __float_as_uint(a.row_scale[at + q_lo]) : 0u;
+                ep_hi = q_hi < cur.qlim ? __float_as_uint(a.row_scale[at + q_hi]) : 0u;
+            } else {
+                ep_lo = q_lo < cur.qlim ? a.slot_off[at + q_lo] : 0u;
+                ep_hi = q_hi < cur.qlim ? a.slot_off[at + q_hi] : 0u;
+            }
+        }
+        if (GQ_ROWS && have_next) off_rows = rows_offsets(nxt);
 
         f32x16 acc[4][4];
 #pragma unroll
@@ -337,13 +463,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             SW_K_STEP(gs + kt);
         }
         // the last two steps load the next tile's first two (after the last tile: zeros)
-        if (EPI_BASE == EPI_MASK) {
-            // asked for here so that they are not queued behind the next tile's loads
-            const uint32_t *bits = bits_of(lane);
-            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) { mb[w] = b0[w]; mb[4 + w] = b1[w]; }
-        }
         if (have_next) {
             begin_loads(nxt);
         } else {
@@ -388,6 +507,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             char *ep = lds + kRingBytes + wave * kTurnBytes;
             bf16 *Cout = a.Cout + (size_t)cur.e * a.c_batch;
             const int c = ln & 15;
+            bf16 *Cscat = SCATTER ? a.Cscatter : nullptr;
             uint32_t *bits = EPI_BASE == EPI_NONE ? nullptr : bits_of(ln);
             const int p = cur.p0 + wp * 128 + c * 8;
             // ReLU mask: byte j * 8 + i8 of a lane's 32 bytes says which of the eight
@@ -414,16 +534,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                if (DEAL && j >= nj) continue;   // blocks without rows
                 const int wrow = ln & 31;
                 // expert dropout: the draw of hidden unit p of token t is element t * d_ff + p of
                 // the dropout stream; the lane's accumulators of this round belong to one slot
                 uint32_t drop_row = 0;
                 if (DROP && EPI_BASE == EPI_RELU) {
-                    const int q = cur.q0 + wq * 128 + j * 32 + wrow;
+                    const int q = cur.q0 + row_of(wq, j, wrow);
                     const int tok = q < cur.qlim ? a.slot_token[(size_t)cur.e * a.slots + q] : 0;
                     drop_row = (uint32_t)tok * (uint32_t)a.Pdim +
                                (uint32_t)(cur.p0 + wp * 128 + ((ln >> 5) << 2));
                 }
+                // the gate of the slot whose accumulators the lane holds in this round
+                float row_gate = 1.f;
+                if (SCALE)
+                    row_gate = __uint_as_float(
+                        (uint32_t)__shfl((int)(j < 2 ? ep_lo : ep_hi), (j & 1) * 32 + wrow, kWave));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -449,6 +575,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] *= a.nz.drop_scale;
                         }
+                        if (SCALE) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[r] *= row_gate;
+                        }
                         bf16x4 o;
 #pragma unroll
                         for (int r = 0; r < 4; ++r) o[r] = (bf16)v[r];
@@ -462,8 +592,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                 for (int i8 = 0; i8 < 8; ++i8) {
                     const int rrow = i8 * 4 + (ln >> 4);       // row within the round
                     const int row = j * 32 + rrow;               // row within the wave's sub-tile
-                    const int q = cur.q0 + wq * 128 + row;
+                    const int q = cur.q0 + row_of(wq, j, rrow);
                     u32x4 val = *(const u32x4 *)(ep + rrow * 256 + ((c ^ (rrow & 15)) << 4));
+                    uint32_t row_off = 0;   // SCATTER: the row's place (asked of the lane that holds it, by all lanes)
+                    if (SCATTER) row_off = (uint32_t)__shfl((int)(j < 2 ? ep_lo : ep_hi), row & 63, kWave);
                     if (EPI_BASE == EPI_RELU) {
                         // After ReLU every half word is a non-negative bf16, so adding 0x7fff
                         // carries into its top bit exactly when it is > 0.  Bits 0..3 of the
@@ -494,6 +626,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                             val = __builtin_bit_cast(u32x4, vo);
                         }
                         *(u32x4 *)(Cout + off) = val;
+                        // the same row, at its token's place in the token-major output
+                        if (SCATTER) *(u32x4 *)((char *)Cscat + row_off + (size_t)p * 2) = val;
                     }
                 }
                 if (EPI_BASE == EPI_RELU) *(uint2 *)(bits + 2 * j) = make_uint2(m_lo, m_hi);
@@ -528,9 +662,9 @@ static int persistent_blocks() {
 }
 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED,
-          int MODE = MODE_EXPERTS>
+          int MODE = MODE_EXPERTS, int GATHER = GATHER_NONE>
 static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
-    auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED, MODE>;
+    auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED, MODE, GATHER>;
     static PerDeviceOnce once;   // one per template instantiation
     hipError_t attr_err = once_per_device(once, [&] {
         return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -546,7 +680,8 @@ static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
-                            const void *W_out, void *dW_in, void *dW_out, hipStream_t s) {
+                            const void *W_out, void *dW_in, void *dW_out, const TokenMajor &tm,
+                            hipStream_t s) {
     const int d = (int)w.d, f = (int)w.f, f1 = (int)w.f1, C = (int)w.C, E = (int)w.E;
     GemmArgs a{};
     a.kept = (const int32_t *)(ws + w.kept);
@@ -562,56 +697,81 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         a.tiles_p = (int)ceil_div(Pdim, kBP);
         a.total_tiles = a.tiles_q * a.tiles_p * E;
     };
+    // With w.fused the token-major tensors take the place of the dispatched copies: x for Xd,
+    // dy for dO (the gate moves into A and into the row scales), y is written by the second
+    // GEMM (see the head of this file).
+    const bool fused = w.fused;
+    a.slot_token = (const int32_t *)(ws + w.slot_token);
+    a.slots = C;
+    a.row_scale = (const float *)(ws + w.slot_gate);
+    a.slot_off = (const uint32_t *)(ws + w.slot_off);
+    a.gather_bytes = (uint32_t)((size_t)w.T * d * 2);
     // A GEMM that follows the producer of its large activation operand walks the experts in
     // the opposite order: the producer's last-written experts are the ones still in the
     // memory-side cache (measured: 2-3 % of those kernels' time).
     a.reverse = kind == GEMM_FWD2 || kind == GEMM_DGRAD1;
     switch (kind) {
     case GEMM_FWD1: {
-        a.Q = Xd; a.q_batch = (size_t)C * d; a.ldq = d;
+        a.Q = fused ? (const bf16 *)tm.x : Xd; a.q_batch = fused ? 0 : (size_t)C * d; a.ldq = d;
         a.P = (const bf16 *)W_in; a.p_batch = (size_t)d * f1; a.ldp = f1;
         a.Cout = w.geglu ? (bf16 *)(ws + w.H) : A; a.c_batch = (size_t)C * f1; a.ldc = f1;
         a.relu_bits = (uint8_t *)(ws + w.relu_bits);
         finish(C, f1, d);
         if (a.total_tiles == 0) return hipSuccess;
-        if (w.geglu) {   // the plain product; activation and dropout follow in geglu_fwd
+        if (w.geglu) {   // the plain product; activation, dropout and gate follow in geglu_fwd
             ProfScope ps("gemm1_fwd", s);
+            if (fused)
+                return gemm_launch<false, true, EPI_NONE, true, false, MODE_EXPERTS, GATHER_Q>(a, s);
             return gemm_launch<false, true, EPI_NONE, true, false>(a, s);
         }
         ProfScope ps("gemm1_fwd_relu", s);
-        if (w.noise.dropout) {
-            a.slot_token = (const int32_t *)(ws + w.slot_token);
-            a.slots = C;
-            a.nz = w.noise;
-            return gemm_launch<false, true, EPI_RELU | EPI_DROP, true, false>(a, s);
+        a.nz = w.noise;
+        if (fused) {
+            if (w.noise.dropout)
+                return gemm_launch<false, true, EPI_RELU | EPI_DROP | EPI_SCALE, true, false,
+                                   MODE_EXPERTS, GATHER_Q>(a, s);
+            return gemm_launch<false, true, EPI_RELU | EPI_SCALE, true, false, MODE_EXPERTS,
+                               GATHER_Q>(a, s);
         }
+        if (w.noise.dropout)
+            return gemm_launch<false, true, EPI_RELU | EPI_DROP, true, false>(a, s);
         return gemm_launch<false, true, EPI_RELU, true, false>(a, s);
     }
     case GEMM_FWD2: {
         a.Q = A; a.q_batch = (size_t)C * f; a.ldq = f;
         a.P = (const bf16 *)W_out; a.p_batch = (size_t)f * d; a.ldp = d;
         a.Cout = O; a.c_batch = (size_t)C * d; a.ldc = d;
+        a.Cscatter = (bf16 *)tm.y;
         finish(C, d, f);
         if (a.total_tiles == 0) return hipSuccess;
         ProfScope ps("gemm2_fwd", s);
+        if (fused) return gemm_launch<false, true, EPI_SCATTER, true, false>(a, s);
         return gemm_launch<false, true, EPI_NONE, true, false>(a, s);
     }
     case GEMM_DGRAD2: {
-        a.Q = dO; a.q_batch = (size_t)C * d; a.ldq = d;
+        a.Q = fused ? (const bf16 *)tm.dy : dO; a.q_batch = fused ? 0 : (size_t)C * d; a.ldq = d;
         a.P = (const bf16 *)W_out; a.p_batch = (size_t)f * d; a.ldp = d;   // [p = f][k = d]
         a.Cout = w.geglu ? (bf16 *)(ws + w.dA) : dH; a.c_batch = (size_t)C * f; a.ldc = f;
         a.relu_bits = (uint8_t *)(ws + w.relu_bits);
         finish(C, f, d);
         if (a.total_tiles == 0) return hipSuccess;
+        a.nz = w.noise;
         if (w.geglu) {
             ProfScope ps("gemm2_dgrad", s);
+            if (fused)
+                return gemm_launch<false, false, EPI_SCALE, true, false, MODE_EXPERTS, GATHER_Q>(a, s);
             return gemm_launch<false, false, EPI_NONE, true, false>(a, s);
         }
         ProfScope ps("gemm2_dgrad_relumask", s);
-        if (w.noise.dropout) {
-            a.nz = w.noise;
-            return gemm_launch<false, false, EPI_MASK | EPI_DROP, true, false>(a, s);
+        if (fused) {
+            if (w.noise.dropout)
+                return gemm_launch<false, false, EPI_MASK | EPI_DROP | EPI_SCALE, true, false,
+                                   MODE_EXPERTS, GATHER_Q>(a, s);
+            return gemm_launch<false, false, EPI_MASK | EPI_SCALE, true, false, MODE_EXPERTS,
+                               GATHER_Q>(a, s);
         }
+        if (w.noise.dropout)
+            return gemm_launch<false, false, EPI_MASK | EPI_DROP, true, false>(a, s);
         return gemm_launch<false, false, EPI_MASK, true, false>(a, s);
     }
     case GEMM_DGRAD1: {
@@ -625,18 +785,24 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
     }
     case GEMM_WGRAD2: {
         a.Q = A; a.q_batch = (size_t)C * f; a.ldq = f;      // [k = slot][q = f]
-        a.P = dO; a.p_batch = (size_t)C * d; a.ldp = d;     // [k = slot][p = d]
+        a.P = fused ? (const bf16 *)tm.dy : dO;             // [k = slot][p = d]
+        a.p_batch = fused ? 0 : (size_t)C * d; a.ldp = d;
         a.Cout = (bf16 *)dW_out; a.c_batch = (size_t)f * d; a.ldc = d;
         finish(f, d, C);
         ProfScope ps("gemm2_wgrad", s);
+        if (fused)
+            return gemm_launch<true, true, EPI_NONE, false, true, MODE_EXPERTS, GATHER_P>(a, s);
         return gemm_launch<true, true, EPI_NONE, false, true>(a, s);
     }
     case GEMM_WGRAD1: {
-        a.Q = Xd; a.q_batch = (size_t)C * d; a.ldq = d;     // [k = slot][q = d]
+        a.Q = fused ? (const bf16 *)tm.x : Xd;              // [k = slot][q = d]
+        a.q_batch = fused ? 0 : (size_t)C * d; a.ldq = d;
         a.P = dH; a.p_batch = (size_t)C * f1; a.ldp = f1;     // [k = slot][p = f1]
         a.Cout = (bf16 *)dW_in; a.c_batch = (size_t)d * f1; a.ldc = f1;
         finish(d, f1, C);
         ProfScope ps("gemm1_wgrad", s);
+        if (fused)
+            return gemm_launch<true, true, EPI_NONE, false, true, MODE_EXPERTS, GATHER_Q>(a, s);
         return gemm_launch<true, true, EPI_NONE, false, true>(a, s);
     }
     }

@@ -115,7 +115,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args a) {
 }
 
 hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
-                           const void *W_out, void *dW_in, void *dW_out, hipStream_t s) {
+                           const void *W_out, void *dW_in, void *dW_out, const TokenMajor &,
+                           hipStream_t s) {
     const long d = w.d, f = w.f, f1 = w.f1, C = w.C;
     GemmF32Args a{};
     a.kept = (const int32_t *)(ws + w.kept);

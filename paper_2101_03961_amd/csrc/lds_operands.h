@@ -129,10 +129,11 @@ struct DirectOperand64 {
         frag0 = (uint32_t)(fr * 128 + (((lane >> 5) ^ ((fr >> 1) & 7)) << 4));
     }
     static constexpr int kPieces = 4;   // LDS reads per k sub-step: one per fragment
-    // load i of eight: rows 32 i + [8 wave, 8 wave + 8)
-    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
+    // load i of eight: LDS rows 32 i + [8 wave, 8 wave + 8) <- tile rows 32 blk + [8 wave, 8 wave + 8)
+    // (blk = i unless the tile's 32-row blocks are dealt out to the two wave rows alternately)
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i, int blk) const {
         const uint32_t vo = (k0 + c8 < klim) ? voff : kOobOffset;
-        dma16(rsrc, vo, (uint32_t)i * row_step + (uint32_t)k0 * 2u,
+        dma16(rsrc, vo, (uint32_t)blk * row_step + (uint32_t)k0 * 2u,
               lds_op + (uint32_t)((i * 32 + wave * 8) * 128));
     }
     // piece x = fragment x (rows 32 x ..), k sub-step ks (0..3): chunk 2 ks + lane/32
@@ -142,6 +143,34 @@ struct DirectOperand64 {
             *(const s16x8 *)(lds_op + ((frag0 ^ (uint32_t)(ks << 5)) + (uint32_t)(x * 32 * 128)));
         h[x][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
         h[x][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+    }
+};
+
+// The same operand with its rows gathered: tile row r is the row at byte offset off(r) of a
+// token-major matrix (the dispatch of Sec. 5.4 done by the load addresses).  The eight loads of
+// a lane go to eight different tokens, so their byte offsets are kept per load.
+struct DirectGather64 : DirectOperand64 {
+    uint32_t gvoff[8];   // byte offset of the lane's chunk for load i (>= kOobOffset: row absent)
+
+    // off_of_lane: row offset of tile row 8 wave + (lane & 7) + 32 (lane >> 3), kOobOffset past the rows
+    // dealt: LDS rows 32 i .. hold tile rows 32 blk .., blk = 2 (i % 4) + i / 4 (see the GEMM kernel)
+    __device__ __forceinline__ void init_gather(const bf16 *base, uint32_t bytes, int klim_,
+                                                int lane, int wave, uint32_t off_of_lane, bool dealt) {
+        rsrc = make_rsrc(base, bytes);
+        const int r = wave * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        c8 = c << 3;
+        klim = klim_;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {   // load i covers tile rows 32 blk + 8 wave + lane / 8
+            const int blk = dealt ? 2 * (i & 3) + (i >> 2) : i;
+            gvoff[i] = (uint32_t)__shfl((int)off_of_lane, (lane >> 3) + 8 * blk, kWave) + (uint32_t)c8 * 2u;
+        }
+    }
+    __device__ __forceinline__ void disable_load() { klim = 0; }
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i, int) const {
+        const uint32_t vo = (k0 + c8 < klim) ? gvoff[i] : kOobOffset;
+        dma16(rsrc, vo, (uint32_t)k0 * 2u, lds_op + (uint32_t)((i * 32 + wave * 8) * 128));
     }
 };
 
@@ -196,6 +225,34 @@ struct TransOperand64 {
         typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
         const char *p0 = lds_op + frag_base[x >> 1] + ks * (16 * 512) + (x & 1) * (4 * 512);
         h[x >> 1][x & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
+    }
+};
+
+// The same operand with its k-rows gathered: k-row k of the tile is the row at byte offset
+// off(k) of a token-major matrix; issue_one is handed the offset of the k-row the lane
+// fetches (kOobOffset past the tile's k range: the offset table holds that value in every
+// slot without a token).  (A sum of two absent parts may wrap into the matrix: such a chunk
+// lies in a column past the operand's rows, whose products are never stored.)
+struct TransGather64 : TransOperand64 {
+    uint32_t cvoff[2];   // byte offset of the lane's chunk inside a row, loads with even / odd index
+
+    __device__ __forceinline__ void init_gather(const bf16 *base, uint32_t bytes, int row0,
+                                                int rowlim, int lane, int wave) {
+        rsrc = make_rsrc(base, bytes);
+        const int kk = lane >> 5, pc = lane & 31;
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+            const int kr = wave * 16 + 2 * par + kk;
+            const int c = pc ^ ((kr & 3) << 2);
+            const int row = row0 + (c << 3);
+            cvoff[par] = row < rowlim ? (uint32_t)row * 2u : kOobOffset;
+        }
+    }
+    __device__ __forceinline__ void disable_load() { cvoff[0] = cvoff[1] = kOobOffset; }
+    // load i of eight: k-rows 16 wave + 2 i + {0, 1} of the step; row_off: the lane's k-row
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int wave, int i,
+                                              uint32_t row_off) const {
+        dma16(rsrc, row_off + cvoff[i & 1], 0u, lds_op + (uint32_t)((wave * 16 + 2 * i) * 512));
     }
 };
 

@@ -180,8 +180,9 @@ __global__ __launch_bounds__(256) void ntlb_place_kernel(
     const int32_t *__restrict__ asked, const int32_t *__restrict__ local_rank,
     const int32_t *__restrict__ block_off, const int32_t *__restrict__ free_r,
     const int32_t *__restrict__ base_r, const float *__restrict__ probs,
-    int32_t *__restrict__ tok_slot, int32_t *__restrict__ slot_token, int32_t *__restrict__ idx_ws,
-    float *__restrict__ gate_ws, int32_t *__restrict__ expert_index, float *__restrict__ gate,
+    int32_t *__restrict__ tok_slot, int32_t *__restrict__ slot_token,
+    float *__restrict__ slot_gate, uint32_t *__restrict__ slot_off, uint32_t row_bytes,
+    int32_t *__restrict__ idx_ws, float *__restrict__ gate_ws, int32_t *__restrict__ expert_index, float *__restrict__ gate,
     int32_t *__restrict__ pos_out, uint8_t *__restrict__ dropped_out, int T, int Tg, int nbg, int E,
     int Cg) {
     const int t = blockIdx.x * 256 + threadIdx.x;
@@ -199,6 +200,8 @@ __global__ __launch_bounds__(256) void ntlb_place_kernel(
     const float pr = probs[(size_t)t * E + e];
     tok_slot[t] = slot;
     slot_token[slot] = t;
+    slot_gate[slot] = pr;
+    slot_off[slot] = (uint32_t)t * row_bytes;
     idx_ws[t] = e;
     gate_ws[t] = pr;
     expert_index[t] = e;
@@ -235,7 +238,9 @@ hipError_t launch_ntlb(const Workspace &w, char *ws, const float *logits, int32_
                            (const int32_t *)(ws + w.block_off), (const int32_t *)(ws + w.ntlb_free),
                            (const int32_t *)(ws + w.ntlb_base), (const float *)(ws + w.probs),
                            (int32_t *)(ws + w.tok_slot), (int32_t *)(ws + w.slot_token),
-                           (int32_t *)(ws + w.idx), (float *)(ws + w.gate), expert_index, gate,
+                           (float *)(ws + w.slot_gate), (uint32_t *)(ws + w.slot_off),
+                           (uint32_t)(w.d * w.elt), (int32_t *)(ws + w.idx),
+                           (float *)(ws + w.gate), expert_index, gate,
                            position_in_expert, dropped, (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E,
                            (int)w.Cg);
         hipError_t err = hipGetLastError();

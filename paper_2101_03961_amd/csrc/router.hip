@@ -247,7 +247,11 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
     const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
     int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
     int32_t *__restrict__ counts_g, int32_t *__restrict__ grp_off, int32_t *__restrict__ counts_out,
-    double *__restrict__ loss_part, int nb, int E, int C, int T) {
+    double *__restrict__ loss_part, uint32_t *__restrict__ slot_off, int slot_off_n, int nb, int E,
+    int C, int T) {
+    // every slot starts without a token (the position kernel, which runs next, fills in the rest)
+    for (int i = blockIdx.x * kScanThreads + threadIdx.x; i < slot_off_n; i += gridDim.x * kScanThreads)
+        slot_off[i] = kNoRow;
     __shared__ int32_t part_cnt[kScanThreads];
     __shared__ float part_ps[kScanThreads];
     __shared__ double red[kScanThreads];
@@ -321,10 +325,11 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_groups_kernel(
     const int32_t *__restrict__ block_counts, const float *__restrict__ block_psum,
     int32_t *__restrict__ block_off, int32_t *__restrict__ counts_ws, int32_t *__restrict__ kept_ws,
     int32_t *__restrict__ counts_g, float *__restrict__ psum_g, int32_t *__restrict__ grp_off,
-    int32_t *__restrict__ counts_out, double *__restrict__ loss_part, int n, int nbg, int E, int Cg,
-    int Tg) {
+    int32_t *__restrict__ counts_out, double *__restrict__ loss_part,
+    uint32_t *__restrict__ slot_off, int slot_off_n, int n, int nbg, int E, int Cg, int Tg) {
     __shared__ double red[kScanThreads];
     const int tid = threadIdx.x;
+    for (int i = tid; i < slot_off_n; i += kScanThreads) slot_off[i] = kNoRow;
     for (int pair = tid; pair < n * E; pair += kScanThreads) {
         const int g = pair / E, e = pair - g * E;
         int run = 0;
@@ -795,8 +800,9 @@ hipError_t launch_route_scan(const Workspace &w, char *ws, int32_t *expert_count
                            (const float *)(ws + w.block_psum), (int32_t *)(ws + w.block_off),
                            (int32_t *)(ws + w.counts), (int32_t *)(ws + w.kept),
                            (int32_t *)(ws + w.counts_g), (int32_t *)(ws + w.grp_off),
-                           expert_counts, (double *)(ws + w.loss_part), (int)w.nb, (int)w.E,
-                           (int)w.C, (int)w.T);
+                           expert_counts, (double *)(ws + w.loss_part),
+                           (uint32_t *)(ws + w.slot_off), (int)(w.E * w.C + 128), (int)w.nb,
+                           (int)w.E, (int)w.C, (int)w.T);
     else
         hipLaunchKernelGGL(route_scan_groups_kernel, dim3(1), dim3(kScanThreads), 0, s,
                            (const int32_t *)(ws + w.block_counts),
@@ -804,8 +810,9 @@ hipError_t launch_route_scan(const Workspace &w, char *ws, int32_t *expert_count
                            (int32_t *)(ws + w.counts), (int32_t *)(ws + w.kept),
                            (int32_t *)(ws + w.counts_g), (float *)(ws + w.psum_g),
                            (int32_t *)(ws + w.grp_off), expert_counts,
-                           (double *)(ws + w.loss_part), (int)w.n, (int)w.nbg, (int)w.E,
-                           (int)w.Cg, (int)w.Tg);
+                           (double *)(ws + w.loss_part), (uint32_t *)(ws + w.slot_off),
+                           (int)(w.E * w.C + 128), (int)w.n, (int)w.nbg, (int)w.E, (int)w.Cg,
+                           (int)w.Tg);
     return hipGetLastError();
 }
 

@@ -61,18 +61,18 @@ def test_capacity_and_workspace_host_functions():
     (dict(expert_dropout=1.0), -3), (dict(expert_dropout=-0.1), -3),
     (dict(expert_dropout=float("nan")), -3),
     (dict(jitter_eps=1.0), -3), (dict(jitter_eps=-1e-3), -3), (dict(jitter_eps=float("nan")), -3),
-    (dict(reserved=1), -3),            # the header says "must be 0"
+    (dict(flags=2), -3), (dict(flags=-1), -3),   # only the documented flag bits
 ])
 def test_bad_config_is_refused(kw, status):
     assert ctypes.sizeof(sw.SwitchConfig) == 88       # the header's struct
     base = dict(T=256, d_model=64, d_ff=256, E=4, capacity_factor=1.25, alpha=0.01,
                 act_dtype=sw.SW_BF16, ffn_kind=0, n_groups=1, expert_dropout=0.0, jitter_eps=0.0,
-                seed=0, ntlb_rounds=0, reserved=0)
+                seed=0, ntlb_rounds=0, flags=0)
     base.update(kw)
     cfg = sw.SwitchConfig(*[base[k] for k in ("T", "d_model", "d_ff", "E", "capacity_factor",
                                               "alpha", "act_dtype", "ffn_kind", "n_groups",
                                               "expert_dropout", "jitter_eps", "seed", "ntlb_rounds",
-                                              "reserved")])
+                                              "flags")])
     with pytest.raises(sw.SwitchError) as ei:
         sw.switch_capacity(cfg)
     assert ei.value.status == status

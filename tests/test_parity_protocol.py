@@ -71,3 +71,28 @@ def test_a14_and_boundary_experts():
     assert a14(np.array([[1.5, 7.0]]), nan_ref) == 0.5          # rows not evaluated are skipped
     assert boundary_experts(128) == [0, 15, 16, 31, 32, 47, 48, 63, 64, 79, 80, 95, 96, 111, 112, 127]
     assert boundary_experts(4) == [0, 1, 2, 3] and boundary_experts(1) == [0]
+
+
+def test_router_gradients_compose_over_expert_ranges():
+    """compare_full_by_experts adds up the router's gradients range by range: each range's run
+    minus the run with no token selected (the auxiliary loss's share), plus that share once,
+    is the one-call result (the gradients are linear in the gate gradients)."""
+    s = SwitchShape("t", 600, 32, 48, 8, 1.0, dtype="f32", seed_index=212)
+    npi = _np_inputs(s)
+    args = (npi["x"], npi["W_r"], npi["W_in"], npi["W_out"])
+    fwd = oracle.forward(*args, s.capacity_factor, s.alpha)
+    full = oracle.backward(*args, npi["dy"], fwd, s.alpha, 0.7)
+    aux = oracle.backward(*args, npi["dy"], fwd, s.alpha, 0.7, expert_sel=[], token_sel=[])
+    dW_r, db_r, dlog = aux["dW_r"].copy(), aux["db_r"].copy(), aux["dlogits"].copy()
+    assert np.abs(aux["dW_r"]).max() > 0          # the loss alone reaches the router
+    for c in range(4):
+        sel = [2 * c, 2 * c + 1]
+        part = oracle.backward(*args, npi["dy"], fwd, s.alpha, 0.7, expert_sel=sel)
+        dW_r += part["dW_r"] - aux["dW_r"]
+        db_r += part["db_r"] - aux["db_r"]
+        mask = np.isin(fwd["expert_index"], sel)
+        dlog[mask] = part["dlogits"][mask]
+        np.testing.assert_allclose(part["dx"][mask], full["dx"][mask], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(dW_r, full["dW_r"], rtol=0, atol=1e-13 * np.abs(full["dW_r"]).max())
+    np.testing.assert_allclose(db_r, full["db_r"], rtol=0, atol=1e-13 * np.abs(full["db_r"]).max())
+    np.testing.assert_allclose(dlog, full["dlogits"], rtol=1e-12, atol=1e-18)
