@@ -186,13 +186,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     constexpr bool GQ = (GATHER & GATHER_Q) != 0, GP = (GATHER & GATHER_P) != 0;
     constexpr bool GQ_ROWS = GQ && !Q_TRANS;            // Q's tile rows are gathered (per tile)
     constexpr bool G_STEPS = (GQ && Q_TRANS) || GP;     // an operand's k-rows are gathered (per step)
-    // Ragged row tiles.  Where q runs over an expert's slots (Q_LIMITED, Q stored [row][k]) the
-    // tile's 32-row blocks are dealt out to the two wave rows alternately -- block b goes to wave
-    // row b % 2 as its block b / 2 -- so that a tile with few rows keeps both wave rows busy
-    // and each wave multiplies only its first nj = ceil(rows / 64) blocks: a last tile of 40
-    // rows costs a quarter of the MFMAs of a full one instead of all of them.  LDS row
-    // 128 wq + 32 j + r holds tile row 32 (2 j + wq) + r; blocks without rows are not loaded.
-    constexpr bool DEAL = Q_LIMITED && !Q_TRANS && MODE == MODE_EXPERTS;
     static_assert(!(GP && !P_TRANS), "P is gathered only along k");
     static_assert(!(SCALE && SCATTER), "one per-row table per launch");
     const int tid = threadIdx.x;
@@ -200,11 +193,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave & 1;
     const int wq = wave >> 1;
-    // tile row of row r of block j of wave row w (see DEAL below)
-    auto row_of = [](int w, int j, int r) {
-        return (Q_LIMITED && !Q_TRANS && MODE == MODE_EXPERTS) ? (2 * j + w) * 32 + r
-                                                                : w * 128 + j * 32 + r;
-    };
+    // tile row of row r of 32-row block j of wave row w
+    auto row_of = [](int w, int j, int r) { return w * 128 + j * 32 + r; };
     // LDS address of the ring (the dynamic segment starts the block's allocation)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
 
@@ -229,7 +219,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     oq.init_frag(lane, wq * 128);
     int ld_nk = 0;      // k steps (with data) of the tile the loads are in
     int ld_e = 0;       // its expert
-    int ld_rows = kBQ;  // DEAL: its q rows
     // Values fetched with ordinary loads long before their use, and "pinned" (passed through an
     // empty asm) right after a k step's barrier, where every load of the wave has completed
     // anyway: the wait the compiler puts before their first use then costs nothing, while a
@@ -260,7 +249,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             else
                 op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave);
             if constexpr (GQ_ROWS)
-                oq.init_gather(a.Q, a.gather_bytes, t.klim, lane, wave, off_rows, DEAL);
+                oq.init_gather(a.Q, a.gather_bytes, t.klim, lane, wave, off_rows);
             else if constexpr (GQ)
                 oq.init_gather(a.Q, a.gather_bytes, t.q0, t.qlim, lane, wave);
             else
@@ -268,7 +257,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         }
         ld_nk = steps_of(t);
         ld_e = t.e;
-        ld_rows = t.qlim - t.q0;
     };
     // k offsets (P, Q) of step j of the tile the loads are in; steps past its range read zeros
     int k0p_ = 0, k0q_ = 0;
@@ -321,16 +309,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         const uint32_t st_ = lds0 + (uint32_t)(((GS) & (kStages - 1)) * kStageBytes); \
         if ((G) < 8) {                                                                \
             if constexpr (GP) op.issue_one(st_, wave, (G), off_step[(G)]);            \
-            else if constexpr (P_TRANS) op.issue_one(st_, k0p_, wave, (G));           \
-            else op.issue_one(st_, k0p_, wave, (G), (G));                             \
+            else op.issue_one(st_, k0p_, wave, (G));                                  \
         } else {                                                                      \
-            const int i_ = ((G)-8) & 7;                                               \
-            const int blk_ = DEAL ? 2 * (i_ & 3) + (i_ >> 2) : i_;                    \
             if constexpr (GQ && Q_TRANS)                                              \
-                oq.issue_one(st_ + kOpBytes64, wave, i_, off_step[i_]);               \
-            else if constexpr (Q_TRANS) oq.issue_one(st_ + kOpBytes64, k0q_, wave, i_); \
-            else if (!DEAL || blk_ * 32 < ld_rows)                                    \
-                oq.issue_one(st_ + kOpBytes64, k0q_, wave, i_, blk_);                 \
+                oq.issue_one(st_ + kOpBytes64, wave, (G)-8, off_step[(G)-8]);         \
+            else oq.issue_one(st_ + kOpBytes64, k0q_, wave, (G)-8);                   \
         }                                                                             \
     } while (0)
 // LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of pipeline step GS, sub-step KS into SET
@@ -346,7 +329,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #define SW_MFMA_PAIR(SET, G)                                                          \
     _Pragma("unroll") for (int m_ = 2 * (G); m_ < 2 * (G) + 2; ++m_) {                \
         const int i_ = m_ >> 2, j_ = m_ & 3;                                          \
-        if (DEAL && j_ >= nj) continue;                                               \
         const s16x8 a8_ = __builtin_shufflevector(fa[SET][i_][0], fa[SET][i_][1], 0, 1, 2, 3, 4, 5, 6, 7); \
         const s16x8 b8_ = __builtin_shufflevector(fb[SET][j_][0], fb[SET][j_][1], 0, 1, 2, 3, 4, 5, 6, 7); \
         acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                        \
@@ -398,16 +380,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
         for (int g = 0; g < 16; ++g) SW_ISSUE_ONE(st, g);
     }
-    // (step 0 has landed; with dealt row blocks a step may be fewer than sixteen loads, so all
-    // are awaited rather than all but the last sixteen)
-    if (DEAL) SW_WAIT_VMCNT(0); else SW_WAIT_VMCNT(16);
+    SW_WAIT_VMCNT(16);
     __syncthreads();
 
     int gs = 0;   // pipeline step of the current tile's first k step
     while (true) {
         const int nsteps = steps_of(cur) > 2 ? steps_of(cur) : 2;
-        // DEAL: 32-row blocks with work per wave row (see above)
-        const int nj = DEAL ? (min(cur.qlim - cur.q0, kBQ) + 63) / 64 : 4;
         const bool have_next = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, nxt);
 
         // Per-tile values of the epilogue and of the next tile's loads, asked for here and
@@ -534,7 +512,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (DEAL && j >= nj) continue;   // blocks without rows
                 const int wrow = ln & 31;
                 // expert dropout: the draw of hidden unit p of token t is element t * d_ff + p of
                 // the dropout stream; the lane's accumulators of this round belong to one slot

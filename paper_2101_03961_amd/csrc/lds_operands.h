@@ -129,11 +129,10 @@ struct DirectOperand64 {
         frag0 = (uint32_t)(fr * 128 + (((lane >> 5) ^ ((fr >> 1) & 7)) << 4));
     }
     static constexpr int kPieces = 4;   // LDS reads per k sub-step: one per fragment
-    // load i of eight: LDS rows 32 i + [8 wave, 8 wave + 8) <- tile rows 32 blk + [8 wave, 8 wave + 8)
-    // (blk = i unless the tile's 32-row blocks are dealt out to the two wave rows alternately)
-    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i, int blk) const {
+    // load i of eight: rows 32 i + [8 wave, 8 wave + 8)
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
         const uint32_t vo = (k0 + c8 < klim) ? voff : kOobOffset;
-        dma16(rsrc, vo, (uint32_t)blk * row_step + (uint32_t)k0 * 2u,
+        dma16(rsrc, vo, (uint32_t)i * row_step + (uint32_t)k0 * 2u,
               lds_op + (uint32_t)((i * 32 + wave * 8) * 128));
     }
     // piece x = fragment x (rows 32 x ..), k sub-step ks (0..3): chunk 2 ks + lane/32
@@ -153,22 +152,19 @@ struct DirectGather64 : DirectOperand64 {
     uint32_t gvoff[8];   // byte offset of the lane's chunk for load i (>= kOobOffset: row absent)
 
     // off_of_lane: row offset of tile row 8 wave + (lane & 7) + 32 (lane >> 3), kOobOffset past the rows
-    // dealt: LDS rows 32 i .. hold tile rows 32 blk .., blk = 2 (i % 4) + i / 4 (see the GEMM kernel)
     __device__ __forceinline__ void init_gather(const bf16 *base, uint32_t bytes, int klim_,
-                                                int lane, int wave, uint32_t off_of_lane, bool dealt) {
+                                                int lane, int wave, uint32_t off_of_lane) {
         rsrc = make_rsrc(base, bytes);
         const int r = wave * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ((r >> 1) & 7);
         c8 = c << 3;
         klim = klim_;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {   // load i covers tile rows 32 blk + 8 wave + lane / 8
-            const int blk = dealt ? 2 * (i & 3) + (i >> 2) : i;
-            gvoff[i] = (uint32_t)__shfl((int)off_of_lane, (lane >> 3) + 8 * blk, kWave) + (uint32_t)c8 * 2u;
-        }
+        for (int i = 0; i < 8; ++i)   // load i covers rows 32 i + 8 wave + lane / 8
+            gvoff[i] = (uint32_t)__shfl((int)off_of_lane, (lane >> 3) + 8 * i, kWave) + (uint32_t)c8 * 2u;
     }
     __device__ __forceinline__ void disable_load() { klim = 0; }
-    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i, int) const {
+    __device__ __forceinline__ void issue_one(uint32_t lds_op, int k0, int wave, int i) const {
         const uint32_t vo = (k0 + c8 < klim) ? gvoff[i] : kOobOffset;
         dma16(rsrc, vo, (uint32_t)k0 * 2u, lds_op + (uint32_t)((i * 32 + wave * 8) * 128));
     }
