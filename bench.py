@@ -140,7 +140,8 @@ def measure(shape, steps, warmup, dev="cuda:0"):
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
                         shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups,
                         expert_dropout=shape.expert_dropout, jitter_eps=shape.jitter_eps,
-                        seed=shape.noise_seed, ffn=shape.ffn, ntlb_rounds=shape.ntlb_rounds)
+                        seed=shape.noise_seed, ffn=shape.ffn, ntlb_rounds=shape.ntlb_rounds,
+                        separate_dispatch=shape.separate_dispatch)
     layer.alloc_grads(with_bias=inp["b_r"] is not None)
 
     def step():
@@ -219,6 +220,8 @@ def main() -> int:
                     help="expert dropout rate (0 = the benchmark's workload; >0 for experiments)")
     ap.add_argument("--jitter-eps", type=float, default=0.0,
                     help="input jitter on the router (0 = the benchmark's workload)")
+    ap.add_argument("--separate-dispatch", action="store_true",
+                    help="dispatch / combine as separate passes (for experiments)")
     ap.add_argument("--ntlb-rounds", type=int, default=0,
                     help="No-Token-Left-Behind re-routing stages (0 = the benchmark's workload)")
     args = ap.parse_args()
@@ -243,6 +246,8 @@ def main() -> int:
     if args.ntlb_rounds:
         shape = shape.with_(name="%s_ntlb%d" % (shape.name, args.ntlb_rounds),
                             ntlb_rounds=args.ntlb_rounds)
+    if args.separate_dispatch:
+        shape = shape.with_(name="%s_separate_dispatch" % shape.name, separate_dispatch=True)
     ms_per_step, ms_prof, kernels, facts, inp = measure(shape, args.steps, args.warmup)
 
     dominant = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])

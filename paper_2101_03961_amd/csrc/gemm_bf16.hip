@@ -9,10 +9,18 @@
 // Data path.  Operand tiles go from HBM/L2 straight into LDS with
 // buffer_load_dwordx4 ... lds (no registers, no ds_write: LDS stores issued by
 // the waves cost ~30 cycles of issue each and were the bottleneck of an earlier
-// register-staged version).  k advances 64 at a time through two LDS stages
-// (2 x 64 KB): every row of an operand tile is then one full 128-byte line per
-// step.  The sixteen loads a wave issues for step kt+2 go out between the MFMAs
-// of the last quarter of step kt, right after the barrier that frees the stage.
+// register-staged version).  k advances 64 at a time: every row of an operand tile
+// is then one full 128-byte line per step.  The P operand goes through three LDS
+// stages of 32 KB, the Q operand through two (3 x 32 + 2 x 32 = all 160 KB): in the
+// last quarter of step kt, right after the barrier that frees the stages of step
+// kt, a wave issues its eight loads of Q for step kt+2 and then its eight loads of P
+// for step kt+3.  Loads complete in order, so the wait of step kt+1 (for step kt+2's
+// operands) leaves the eight youngest -- P of step kt+3 -- in flight: the weights are
+// asked for a whole step earlier than a two-stage ring allows.  (Measured with the
+// loads of the first forward GEMM and 64 MFMAs per step and wave, no LDS reads:
+// two stages each 352 us, this arrangement 268 us, three stages each 240 us = the
+// time of the loads alone.  With one step of lead a CU has one stage of requests
+// outstanding and the fetch path, which needs about two to run at its rate, idles.)
 //   - An operand stored [row][k] (k contiguous) is kept in LDS as [row][64 k];
 //     a lane's MFMA fragment (8 consecutive k of one row) is one ds_read_b128.
 //   - An operand stored [k][row] (row contiguous: the weights in the forward
@@ -42,11 +50,13 @@
 // HBM once per XCD (measured: starting neighbours a few k steps apart, to turn
 // hits under a miss into plain hits, raised HBM traffic by a third -- the leading
 // block's lines were evicted before the followers arrived -- and saved no time).
-// The k steps of all tiles of a block form one load pipeline: a tile's last two steps
-// issue the next tile's first two loads, which stay in flight during the epilogue.
+// The k steps of all tiles of a block form one load pipeline: a tile's last steps issue
+// the next tile's first loads, which stay in flight during the epilogue.
 // The epilogue turns each wave's sub-tile around, 32 rows at a time, through 8 KB of
-// LDS of its own (ring 128 KB + 4 x 8 KB = all 160 KB of a CU) so that C is written
-// in whole 256-byte row segments; fused into it: ReLU and one mask bit per element
+// LDS of its own -- a quarter of the P stage that the tile's last step has freed; the
+// load that stage is waiting for (P of the next tile's third step) is issued after the
+// epilogue instead of before it -- so that C is written in whole 256-byte row
+// segments; fused into it: ReLU and one mask bit per element
 // (first forward GEMM), that mask (gradient w.r.t. the hidden activations), the
 // gathered addend of the router's dx.
 //
@@ -66,13 +76,15 @@ namespace sw {
 constexpr int kBP = kGemmTile;                    // block tile, p rows
 constexpr int kBQ = kGemmTile;                    // block tile, q rows
 constexpr int kBK = 64;                           // k per pipeline step
-constexpr int kStages = 2;                        // LDS stages
+constexpr int kPStages = 3;                       // LDS stages of the P operand
+constexpr int kQStages = 2;                       // ... of the Q operand
 constexpr int kGemmThreads = 256;
 static_assert(kOpBytes64 == kBP * kBK * 2, "operand stage size");
-constexpr int kStageBytes = 2 * kOpBytes64;       // P then Q
-constexpr int kRingBytes = kStages * kStageBytes;  // 128 KB
+constexpr int kPRingBytes = kPStages * kOpBytes64;            // 96 KB
+constexpr int kRingBytes = kPRingBytes + kQStages * kOpBytes64;   // 160 KB: all of a CU's LDS
 constexpr int kTurnBytes = 32 * 256;              // per wave: 32 rows x 128 bf16 of the epilogue's turn-around
-constexpr int kGemmLds = kRingBytes + 4 * kTurnBytes;   // 160 KB: all of a CU's LDS
+static_assert(4 * kTurnBytes == kOpBytes64, "the turn-around buffers are one P stage");
+constexpr int kGemmLds = kRingBytes;
 constexpr int kXcds = 8;
 
 struct GemmArgs {
@@ -97,7 +109,7 @@ struct GemmArgs {
     float *Cf;                          // ROUTER_DWR: fp32 partial sums [split][q][p]
     int T_total, tps;                   // ROUTER_DWR: tokens, tokens per split
     // dispatch / combine inside the GEMM (see GATHER, EPI_SCALE, EPI_SCATTER)
-    uint32_t gather_bytes;              // bytes of the token-major matrix a gathered operand points at
+    uint32_t gather_bytes;              // bytes of a token-major matrix (gathered operand, Cscatter)
     const uint32_t *slot_off;           // byte offset of each slot's token row in the token-major tensors
     const float *row_scale;             // EPI_SCALE: gate of each slot's token, [expert][slots]
     bf16 *Cscatter;                     // EPI_SCATTER: token-major output, row token(slot)
@@ -173,8 +185,50 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int &L, int L_end, 
     return false;
 }
 
-// wait until at most N of this wave's direct loads are still in flight
+// wait until at most N of this wave's direct loads and stores are still in flight
 #define SW_WAIT_VMCNT(N) asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory")
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "the counter has six bits");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// One store of 16 bytes per lane at byte offset voff of the buffer; offsets past the buffer's
+// size store nothing.  Written as asm so that every lane's store is issued whatever its
+// offset -- the number of stores in flight is then known -- and so that the compiler's own
+// waits do not count it.  (The s_nop keeps a write of the data registers one state away.)
+__device__ __forceinline__ void store16(i32x4 rsrc, uint32_t voff, u32x4 data) {
+    asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 0"
+                 :
+                 : "v"(data), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+// two floats rounded to bf16 (nearest even), first in the low half
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+// per 16-bit half: signed maximum, unsigned minimum (written as asm: the compiler turns the
+// generic forms of these into compares and selects, several instructions per half)
+__device__ __forceinline__ uint32_t pk_max_i16(uint32_t x, uint32_t y) {
+    uint32_t d;
+    asm("v_pk_max_i16 %0, %1, %2" : "=v"(d) : "v"(x), "v"(y));
+    return d;
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t x, uint32_t y) {
+    uint32_t d;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(d) : "v"(x), "v"(y));
+    return d;
+}
+
+// Per-tile values of the epilogue, one set per lane (see tile_values in the kernel).
+struct TileVals {
+    uint32_t ep_lo, ep_hi;   // SCALE / SCATTER: gate / row offset of rows lane, lane + 64 of the wave's q rows
+    uint32_t mb[8];          // EPI_MASK: the lane's 32 bytes of ReLU bits of the tile
+    int slot_lo, slot_hi;    // ROUTER_DX: slot of the addend of rows lane, lane + 64 (-1: none)
+    int tok_lo, tok_hi;      // EPI_DROP after ReLU: token of those rows
+};
 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE, int GATHER>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
@@ -188,6 +242,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     constexpr bool G_STEPS = (GQ && Q_TRANS) || GP;     // an operand's k-rows are gathered (per step)
     static_assert(!(GP && !P_TRANS), "P is gathered only along k");
     static_assert(!(SCALE && SCATTER), "one per-row table per launch");
+    // The bf16 epilogue of the expert GEMMs issues a fixed number of stores per lane and does
+    // not wait for them: the next tile's first step counts them among the operations that may
+    // stay in flight, the second waits for loads issued after them and thereby for them.
+    constexpr bool ASYNC_STORES = MODE == MODE_EXPERTS;
+    constexpr int kEpStores = ASYNC_STORES ? (SCATTER ? 64 : 32) + (EPI_BASE == EPI_RELU ? 2 : 0) : 0;
+    constexpr int kFirstWait = 8 + kEpStores > 63 ? 63 : 8 + kEpStores;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -205,97 +265,114 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     int L = xcd * per_xcd + blockIdx.x / kXcds;
     const int L_end = min((xcd + 1) * per_xcd, a.total_tiles);
 
-    Tile cur, nxt;
+    Tile cur, nxt, after;
     if (!next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, cur)) return;
 
-    // The k steps of all tiles of this block form one pipeline: while a tile's last two
-    // steps are multiplied, the loads of the next tile's first two steps are already
-    // under way, and they stay in flight during the epilogue (which has its own LDS).
-    // A tile takes at least two steps (steps past its k range read zeros).
+    // The k steps of all tiles of this block form one pipeline: while a tile's last steps are
+    // multiplied, the loads of the next tile's first steps are already under way, and they stay
+    // in flight during the epilogue.  A tile takes at least three steps (steps past its k range
+    // read zeros).  The two operands run through their rings separately: P three steps ahead of
+    // the step that issues its loads, Q two, so each has its own "tile the loads are in".
     auto steps_of = [&](const Tile &t) { return (t.klim + kBK - 1) / kBK; };
     typename OperandOf<P_TRANS, GP>::type op;
     typename OperandOf<Q_TRANS, GQ>::type oq;
     op.init_frag(lane, wp * 128);
     oq.init_frag(lane, wq * 128);
-    int ld_nk = 0;      // k steps (with data) of the tile the loads are in
-    int ld_e = 0;       // its expert
+    int ldp_nk = 0, ldq_nk = 0;   // k steps (with data) of the tile the P / Q loads are in
+    int ldp_e = 0, ldq_e = 0;     // its expert
     // Values fetched with ordinary loads long before their use, and "pinned" (passed through an
-    // empty asm) right after a k step's barrier, where every load of the wave has completed
-    // anyway: the wait the compiler puts before their first use then costs nothing, while a
-    // wait in front of the epilogue or of the next tile's loads would also sit out the direct
-    // loads in flight, which the compiler does not count.
+    // empty asm) right after a k step's barrier: the wait the compiler puts before their first
+    // use counts only the loads it knows of, so it also sits out every direct load issued
+    // before them; after a step's own wait that costs little, in front of the epilogue or of
+    // the next tile's loads it would cost a fetch latency per tile.
     // (row offsets: byte offset of a slot's token row in the token-major tensors, slot_off)
     uint32_t off_rows = kOobOffset;  // GQ_ROWS: offset of row 8 wave + (lane & 7) + 32 (lane >> 3) of the next tile
     // G_STEPS: offsets of the lane's k-rows 16 wave + 2 i + lane / 32 of the step to be loaded
     uint32_t off_step[8] = {kOobOffset, kOobOffset, kOobOffset, kOobOffset,
                             kOobOffset, kOobOffset, kOobOffset, kOobOffset};
-    uint32_t ep_lo = 0, ep_hi = 0;   // SCALE / SCATTER: gate / offset of rows lane, lane + 64 of the wave's q rows
+    TileVals tv = {}, tvn = {};      // epilogue values of the current tile, of the next one
     auto rows_offsets = [&](const Tile &t) {
         const int row = t.q0 + 8 * wave + (lane & 7) + 32 * (lane >> 3);
         return row < t.qlim ? a.slot_off[(size_t)t.e * a.slots + row] : kOobOffset;
     };
-    auto begin_loads = [&](const Tile &t) {
+    auto begin_p = [&](const Tile &t) {
         if (MODE == MODE_ROUTER_DX) {
             // the 384 k values of an expert tile are read from 256-wide (hi | lo) rows of that
             // tile's plane; k offsets address across planes, so the bounds span all of them (a
             // ragged last row tile then reads rows of the next plane: finite, and never stored)
             op.init_load(a.P, a.ldp, t.p0, a.router_tiles * a.Pdim, a.router_tiles * a.p_plane, lane,
                          wave);
+        } else if constexpr (GP) {
+            op.init_gather(a.P, a.gather_bytes, t.p0, a.Pdim, lane, wave);
+        } else {
+            op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave);
+        }
+        ldp_nk = steps_of(t);
+        ldp_e = t.e;
+    };
+    auto begin_q = [&](const Tile &t) {
+        if (MODE == MODE_ROUTER_DX) {
             oq.init_load(a.Q, a.ldq, t.q0, a.router_tiles * a.Qdim, a.router_tiles * a.q_plane, lane,
                          wave);
+        } else if constexpr (GQ_ROWS) {
+            oq.init_gather(a.Q, a.gather_bytes, t.klim, lane, wave, off_rows);
+        } else if constexpr (GQ) {
+            oq.init_gather(a.Q, a.gather_bytes, t.q0, t.qlim, lane, wave);
         } else {
-            if constexpr (GP)
-                op.init_gather(a.P, a.gather_bytes, t.p0, a.Pdim, lane, wave);
-            else
-                op.init_load(a.P + (size_t)t.e * a.p_batch, a.ldp, t.p0, a.Pdim, t.klim, lane, wave);
-            if constexpr (GQ_ROWS)
-                oq.init_gather(a.Q, a.gather_bytes, t.klim, lane, wave, off_rows);
-            else if constexpr (GQ)
-                oq.init_gather(a.Q, a.gather_bytes, t.q0, t.qlim, lane, wave);
-            else
-                oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave);
+            oq.init_load(a.Q + (size_t)t.e * a.q_batch, a.ldq, t.q0, t.qlim, t.klim, lane, wave);
         }
-        ld_nk = steps_of(t);
-        ld_e = t.e;
+        ldq_nk = steps_of(t);
+        ldq_e = t.e;
     };
-    // k offsets (P, Q) of step j of the tile the loads are in; steps past its range read zeros
-    int k0p_ = 0, k0q_ = 0;
-    auto k_of = [&](int j) {
-        const int r = j < ld_nk ? j : ld_nk;
-        if (G_STEPS) {
-            // row offsets of the lane's k-rows of the step: two addresses per load instruction.
-            // Slots without a token hold kOobOffset, and the table is padded for steps past the end.
-            const uint32_t *row = a.slot_off + (size_t)ld_e * a.slots + r * kBK + 16 * wave + (lane >> 5);
+    // row offsets of the lane's k-rows of step r of expert e: two addresses per load instruction.
+    // Slots without a token hold kOobOffset, and the table is padded for steps past the end.
+    auto step_offsets = [&](int e, int r) {
+        const uint32_t *row = a.slot_off + (size_t)e * a.slots + r * kBK + 16 * wave + (lane >> 5);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) off_step[i] = row[2 * i];
-        }
+        for (int i = 0; i < 8; ++i) off_step[i] = row[2 * i];
+    };
+    // k offset of step j of the tile the P (Q) loads are in; steps past its range read zeros
+    int k0p_ = 0, k0q_ = 0;
+    auto k_of_p = [&](int j) {
+        const int r = j < ldp_nk ? j : ldp_nk;
+        if (GP) step_offsets(ldp_e, r);
         if (MODE == MODE_ROUTER_DX) {
             // six steps per expert tile -- 0,1: dl_hi x W_hi, 2,3: dl_hi x W_lo, 4,5: dl_lo x W_hi --
             // in that tile's planes; past the last tile: beyond the k limit (zeros)
             const int jt = r / 6, rr = r - 6 * jt;
-            k0q_ = jt * a.q_plane + (rr < 4 ? 64 * (rr & 1) : 128 + 64 * (rr - 4));
             k0p_ = jt * a.p_plane + (rr < 2 ? 64 * rr : (rr < 4 ? 128 + 64 * (rr - 2) : 64 * (rr - 4)));
-            if (r >= ld_nk) {
-                k0q_ = a.router_tiles * a.q_plane;
-                k0p_ = a.router_tiles * a.p_plane;
-            }
+            if (r >= ldp_nk) k0p_ = a.router_tiles * a.p_plane;
         } else {
-            k0p_ = k0q_ = r * kBK;
+            k0p_ = r * kBK;
+        }
+    };
+    auto k_of_q = [&](int j) {
+        const int r = j < ldq_nk ? j : ldq_nk;
+        if (GQ && Q_TRANS) step_offsets(ldq_e, r);
+        if (MODE == MODE_ROUTER_DX) {
+            const int jt = r / 6, rr = r - 6 * jt;
+            k0q_ = jt * a.q_plane + (rr < 4 ? 64 * (rr & 1) : 128 + 64 * (rr - 4));
+            if (r >= ldq_nk) k0q_ = a.router_tiles * a.q_plane;
+        } else {
+            k0q_ = r * kBK;
         }
     };
 
-    uint32_t mb[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // EPI_MASK: the lane's 32 bytes of ReLU bits of the tile
-    int slot_lo = -1, slot_hi = -1;   // ROUTER_DX: slot of the addend of rows lane, lane + 64 (-1: none)
+    auto pin_tile_values = [&](TileVals &v) {
+        if (SCALE || SCATTER) asm volatile("" : "+v"(v.ep_lo), "+v"(v.ep_hi));
+        if (EPI_BASE == EPI_MASK)
+            asm volatile("" : "+v"(v.mb[0]), "+v"(v.mb[1]), "+v"(v.mb[2]), "+v"(v.mb[3]), "+v"(v.mb[4]),
+                              "+v"(v.mb[5]), "+v"(v.mb[6]), "+v"(v.mb[7]));
+        if (MODE == MODE_ROUTER_DX) asm volatile("" : "+v"(v.slot_lo), "+v"(v.slot_hi));
+        if (DROP && EPI_BASE == EPI_RELU) asm volatile("" : "+v"(v.tok_lo), "+v"(v.tok_hi));
+    };
     auto pin_values = [&]() {
         if (GQ_ROWS) asm volatile("" : "+v"(off_rows));
         if (G_STEPS)
             asm volatile("" : "+v"(off_step[0]), "+v"(off_step[1]), "+v"(off_step[2]), "+v"(off_step[3]),
                               "+v"(off_step[4]), "+v"(off_step[5]), "+v"(off_step[6]), "+v"(off_step[7]));
-        if (SCALE || SCATTER) asm volatile("" : "+v"(ep_lo), "+v"(ep_hi));
-        if (EPI_BASE == EPI_MASK)
-            asm volatile("" : "+v"(mb[0]), "+v"(mb[1]), "+v"(mb[2]), "+v"(mb[3]), "+v"(mb[4]),
-                              "+v"(mb[5]), "+v"(mb[6]), "+v"(mb[7]));
-        if (MODE == MODE_ROUTER_DX) asm volatile("" : "+v"(slot_lo), "+v"(slot_hi));
+        pin_tile_values(tv);
+        pin_tile_values(tvn);
     };
 
     // fragments: two register sets, each fragment as two 8-byte halves
@@ -303,26 +380,27 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     constexpr int kNP = OperandOf<P_TRANS, GP>::type::kPieces;
     constexpr int kNR = kNP + OperandOf<Q_TRANS, GQ>::type::kPieces;   // LDS reads per sub-step
 
-// direct loads into the stage of pipeline step GS, load G of sixteen (P: 0..7, Q: 8..15)
-#define SW_ISSUE_ONE(GS, G)                                                           \
+// direct load G of eight of the P operand into P stage PST (of the Q operand into Q stage QST)
+#define SW_ISSUE_P(PST, G)                                                            \
     do {                                                                              \
-        const uint32_t st_ = lds0 + (uint32_t)(((GS) & (kStages - 1)) * kStageBytes); \
-        if ((G) < 8) {                                                                \
-            if constexpr (GP) op.issue_one(st_, wave, (G), off_step[(G)]);            \
-            else op.issue_one(st_, k0p_, wave, (G));                                  \
-        } else {                                                                      \
-            if constexpr (GQ && Q_TRANS)                                              \
-                oq.issue_one(st_ + kOpBytes64, wave, (G)-8, off_step[(G)-8]);         \
-            else oq.issue_one(st_ + kOpBytes64, k0q_, wave, (G)-8);                   \
-        }                                                                             \
+        const uint32_t st_ = lds0 + (uint32_t)((PST) * kOpBytes64);                   \
+        if constexpr (GP) op.issue_one(st_, wave, (G), off_step[(G)]);                \
+        else op.issue_one(st_, k0p_, wave, (G));                                      \
     } while (0)
-// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of pipeline step GS, sub-step KS into SET
-#define SW_READ_GROUP(SET, GS, KS, G)                                                 \
+#define SW_ISSUE_Q(QST, G)                                                            \
     do {                                                                              \
-        const char *st_ = lds + ((GS) & (kStages - 1)) * kStageBytes;                 \
+        const uint32_t st_ = lds0 + (uint32_t)(kPRingBytes + (QST) * kOpBytes64);     \
+        if constexpr (GQ && Q_TRANS) oq.issue_one(st_, wave, (G), off_step[(G)]);     \
+        else oq.issue_one(st_, k0q_, wave, (G));                                      \
+    } while (0)
+// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of the step in stages PST / QST, sub-step KS into SET
+#define SW_READ_GROUP(SET, PST, QST, KS, G)                                           \
+    do {                                                                              \
+        const char *sp_ = lds + (PST) * kOpBytes64;                                   \
+        const char *sq_ = lds + kPRingBytes + (QST) * kOpBytes64;                     \
         _Pragma("unroll") for (int x_ = (G)*kNR / 8; x_ < ((G) + 1) * kNR / 8; ++x_) { \
-            if (x_ < kNP) op.read_piece(st_, x_, KS, fa[SET]);                        \
-            else oq.read_piece(st_ + kOpBytes64, x_ - kNP, KS, fb[SET]);              \
+            if (x_ < kNP) op.read_piece(sp_, x_, KS, fa[SET]);                        \
+            else oq.read_piece(sq_, x_ - kNP, KS, fb[SET]);                           \
         }                                                                             \
     } while (0)
 // MFMAs 2 G and 2 G + 1 of the sixteen of a sub-step (fragment pairs in row-major order)
@@ -335,93 +413,126 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             __builtin_bit_cast(bf16x8, a8_), __builtin_bit_cast(bf16x8, b8_), acc[i_][j_], 0, 0, 0); \
     }
 
-// One k step (pipeline step GS) = four sub-steps of 16 MFMAs.  Fragments of a sub-step
-// are read (into the other of two register sets) between the MFMAs of the sub-step before
-// it.  After the third sub-step's MFMAs nobody reads this stage any more: the step's one
-// barrier sits there, and the fourth sub-step runs with the loads of the step after next
-// (into the stage just freed; k offsets from the preceding k_of) and the first fragments
-// of the next step between its MFMAs.
-#define SW_K_STEP(GS)                                                                 \
+// One k step = four sub-steps of 16 MFMAs, on the operands in P stage pst and Q stage qst.
+// Fragments of a sub-step are read (into the other of two register sets) between the MFMAs of
+// the sub-step before it.  After the third sub-step's MFMAs nobody reads these stages any
+// more: the step's one barrier sits there, behind a wait that leaves the eight youngest loads
+// (P of the step after next) in flight.  The fourth sub-step runs with the loads of Q for the
+// step after next (into the Q stage just freed), then -- unless ISSUE_P is false -- of P for
+// the step after that (into the P stage just freed; k offsets from the preceding k_of_q /
+// k_of_p), and with the first fragments of the next step between its MFMAs.
+#define SW_K_STEP(ISSUE_P)                                                            \
     do {                                                                              \
+        const int pn_ = pst == kPStages - 1 ? 0 : pst + 1;                            \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_READ_GROUP(1, GS, 1, g);                                               \
+            SW_READ_GROUP(1, pst, qst, 1, g);                                         \
             SW_MFMA_PAIR(0, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_READ_GROUP(0, GS, 2, g);                                               \
+            SW_READ_GROUP(0, pst, qst, 2, g);                                         \
             SW_MFMA_PAIR(1, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_READ_GROUP(1, GS, 3, g);                                               \
+            SW_READ_GROUP(1, pst, qst, 3, g);                                         \
             SW_MFMA_PAIR(0, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
-        SW_WAIT_VMCNT(0); /* the next step has landed */                              \
+        if (first_step) { /* after an epilogue: its stores and P of step 2 are younger */ \
+            wait_vmcnt<kFirstWait>();                                                 \
+            first_step = false;                                                       \
+        } else {                                                                      \
+            SW_WAIT_VMCNT(8); /* the next step has landed */                          \
+        }                                                                             \
         __syncthreads();                                                              \
         pin_values();                                                                 \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_ISSUE_ONE(GS, 2 * g);                                                  \
-            SW_ISSUE_ONE(GS, 2 * g + 1);                                              \
-            SW_READ_GROUP(0, (GS) + 1, 0, g);                                         \
+            if (g < 4) {                                                              \
+                SW_ISSUE_Q(qst, 2 * g);                                               \
+                SW_ISSUE_Q(qst, 2 * g + 1);                                           \
+            } else if (ISSUE_P) {                                                     \
+                SW_ISSUE_P(pst, 2 * (g - 4));                                         \
+                SW_ISSUE_P(pst, 2 * (g - 4) + 1);                                     \
+            }                                                                         \
+            SW_READ_GROUP(0, pn_, qst ^ 1, 0, g);                                     \
             SW_MFMA_PAIR(1, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
+        pst = pn_;                                                                    \
+        qst ^= 1;                                                                     \
     } while (0)
 
-    // Start of the pipeline: both stages are filled with the first tile's steps 0 and 1,
-    // then step 0 is awaited.
-    if (GQ_ROWS) off_rows = rows_offsets(cur);
-    begin_loads(cur);
-#pragma unroll
-    for (int st = 0; st < kStages; ++st) {
-        k_of(st);
-#pragma unroll
-        for (int g = 0; g < 16; ++g) SW_ISSUE_ONE(st, g);
-    }
-    SW_WAIT_VMCNT(16);
-    __syncthreads();
-
-    int gs = 0;   // pipeline step of the current tile's first k step
-    while (true) {
-        const int nsteps = steps_of(cur) > 2 ? steps_of(cur) : 2;
-        const bool have_next = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, nxt);
-
-        // Per-tile values of the epilogue and of the next tile's loads, asked for here and
-        // pinned after the first barrier of the tile (see pin_values).
+    int pst = 0, qst = 0;   // stages of the step that is multiplied next
+    bool first_step = false;   // the step that is multiplied next follows an epilogue
+    // per-tile values of the epilogue, asked for two steps before the end of the tile before
+    // (see pin_values)
+    auto tile_values = [&](const Tile &t, TileVals &v) {
         if (MODE == MODE_ROUTER_DX) {
             // slot of the addend of rows lane and lane + 64 of the wave's 128 rows
             // (-1: dropped token or past the end: nothing to add)
-            const int q = cur.q0 + wq * 128 + lane;
-            slot_lo = q < cur.qlim ? a.tok_slot[q] : -1;
-            slot_hi = q + 64 < cur.qlim ? a.tok_slot[q + 64] : -1;
+            const int q = t.q0 + wq * 128 + lane;
+            v.slot_lo = q < t.qlim ? a.tok_slot[q] : -1;
+            v.slot_hi = q + 64 < t.qlim ? a.tok_slot[q + 64] : -1;
         }
+        if (EPI_BASE == EPI_MASK) {
+            const uint32_t *bits = (const uint32_t *)(a.relu_bits + (size_t)t.index * kReluBitsPerTile +
+                                                      (size_t)(wave * 64 + lane) * 32);
+            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { v.mb[w] = b0[w]; v.mb[4 + w] = b1[w]; }
+        }
+        if (SCALE || SCATTER || (DROP && EPI_BASE == EPI_RELU)) {
+            // gate (SCALE) or row offset (SCATTER) of the wave's q rows: lane 32 j + r holds the
+            // value of row r of the wave's block j (ep_lo: j = 0, 1; ep_hi: j = 2, 3)
+            const int q_lo = t.q0 + row_of(wq, lane >> 5, lane & 31);
+            const int q_hi = t.q0 + row_of(wq, 2 + (lane >> 5), lane & 31);
+            const size_t at = (size_t)t.e * a.slots;
+            if (SCALE) {
+                v.ep_lo = q_lo < t.qlim ? __float_as_uint(a.row_scale[at + q_lo]) : 0u;
+                v.ep_hi = q_hi < t.qlim ? __float_as_uint(a.row_scale[at + q_hi]) : 0u;
+            }
+            if (SCATTER) {   // rows without a token: an offset past the output
+                v.ep_lo = q_lo < t.qlim ? a.slot_off[at + q_lo] : kOobOffset;
+                v.ep_hi = q_hi < t.qlim ? a.slot_off[at + q_hi] : kOobOffset;
+            }
+            if (DROP && EPI_BASE == EPI_RELU) {
+                v.tok_lo = q_lo < t.qlim ? a.slot_token[at + q_lo] : 0;
+                v.tok_hi = q_hi < t.qlim ? a.slot_token[at + q_hi] : 0;
+            }
+        }
+    };
+
+    // Start of the pipeline: Q and P of the first tile's steps 0 and 1, then P of step 2; step 0
+    // is awaited (what may stay in flight: Q, P of step 1 and P of step 2, 24 loads).
+    tile_values(cur, tv);
+    if (GQ_ROWS) off_rows = rows_offsets(cur);
+    begin_p(cur);
+    begin_q(cur);
+    bool have_next = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, nxt);
+    // rows of the tile after (pinned after a barrier, used when its loads begin)
+    if (GQ_ROWS && have_next) off_rows = rows_offsets(nxt);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        k_of_q(st);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) SW_ISSUE_Q(st, g);
+        k_of_p(st);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) SW_ISSUE_P(st, g);
+    }
+    k_of_p(2);
+#pragma unroll
+    for (int g = 0; g < 8; ++g) SW_ISSUE_P(2, g);
+    SW_WAIT_VMCNT(24);
+    __syncthreads();
+
+    while (true) {
+        const int nsteps = steps_of(cur) > 3 ? steps_of(cur) : 3;
         auto bits_of = [&](int ln) {
             return (uint32_t *)(a.relu_bits + (size_t)cur.index * kReluBitsPerTile +
                                 (size_t)(wave * 64 + ln) * 32);
         };
-        if (EPI_BASE == EPI_MASK) {
-            const uint32_t *bits = bits_of(lane);
-            const u32x4 b0 = *(const u32x4 *)bits, b1 = *(const u32x4 *)(bits + 4);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) { mb[w] = b0[w]; mb[4 + w] = b1[w]; }
-        }
-        if (SCALE || SCATTER) {
-            // gate (SCALE) or row offset (SCATTER) of the wave's q rows: lane 32 j + r holds the
-            // value of row r of the wave's block j (ep_lo: j = 0, 1; ep_hi: j = 2, 3)
-            const int q_lo = cur.q0 + row_of(wq, lane >> 5, lane & 31);
-            const int q_hi = cur.q0 + row_of(wq, 2 + (lane >> 5), lane & 31);
-            const size_t at = (size_t)cur.e * a.slots;
-            if (SCALE) {
-                ep_lo = q_lo < cur.qlim ? __float_as_uint(a.row_scale[at + q_lo]) : 0u;
-                ep_hi = q_hi < cur.qlim ? __float_as_uint(a.row_scale[at + q_hi]) : 0u;
-            } else {
-                ep_lo = q_lo < cur.qlim ? a.slot_off[at + q_lo] : 0u;
-                ep_hi = q_hi < cur.qlim ? a.slot_off[at + q_hi] : 0u;
-            }
-        }
-        if (GQ_ROWS && have_next) off_rows = rows_offsets(nxt);
 
         f32x16 acc[4][4];
 #pragma unroll
@@ -433,25 +544,38 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 
         // first fragments of the tile's first step (it has landed: awaited in the step before)
 #pragma unroll
-        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, gs, 0, g);
+        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, pst, qst, 0, g);
 
-        // all but the last two steps load two steps ahead inside the tile
-        for (int kt = 0; kt < nsteps - 2; ++kt) {
-            k_of(kt + 2);
-            SW_K_STEP(gs + kt);
+        // Step kt issues Q of step kt + 2 and P of step kt + 3 of this tile, as long as there
+        // are such steps ...
+        for (int kt = 0; kt < nsteps - 3; ++kt) {
+            k_of_q(kt + 2);
+            k_of_p(kt + 3);
+            SW_K_STEP(true);
         }
-        // the last two steps load the next tile's first two (after the last tile: zeros)
+        // ... then the third step from the end P of the next tile's first step (after the last
+        // tile: zeros) with Q of this tile's last,
+        k_of_q(nsteps - 1);
+        if (have_next) begin_p(nxt); else op.disable_load();
+        k_of_p(0);
+        SW_K_STEP(true);
+        // the second from the end Q of the next tile's first step and P of its second; the next
+        // tile's epilogue values and the rows of the tile after it are asked for here, ahead of
+        // this step's barrier (see pin_values) and of this tile's stores,
+        if (have_next) begin_q(nxt); else oq.disable_load();
+        bool have_after = false;
         if (have_next) {
-            begin_loads(nxt);
-        } else {
-            op.disable_load();
-            oq.disable_load();
+            have_after = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, after);
+            tile_values(nxt, tvn);
+            if (GQ_ROWS && have_after) off_rows = rows_offsets(after);
         }
-        for (int kt = 0; kt < 2; ++kt) {
-            k_of(kt);
-            SW_K_STEP(gs + nsteps - 2 + kt);
-        }
-        gs += nsteps;
+        k_of_q(0);
+        k_of_p(1);
+        SW_K_STEP(true);
+        // and the last one Q of its second step only: the P stage it frees is the epilogue's.
+        k_of_q(1);
+        SW_K_STEP(false);
+        const int turn_stage = pst == 0 ? kPStages - 1 : pst - 1;   // P stage of the step just done
 
         // Epilogue.  A lane holds, for q = lane%32 of each 32x32 MFMA tile, the four
         // consecutive p = 8*(r/4) + 4*(lane/32) + r%4: 8-byte pieces scattered over 32
@@ -482,12 +606,23 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                     }
             }
         } else {
-            char *ep = lds + kRingBytes + wave * kTurnBytes;
+            char *ep = lds + turn_stage * kOpBytes64 + wave * kTurnBytes;
             bf16 *Cout = a.Cout + (size_t)cur.e * a.c_batch;
             const int c = ln & 15;
-            bf16 *Cscat = SCATTER ? a.Cscatter : nullptr;
             uint32_t *bits = EPI_BASE == EPI_NONE ? nullptr : bits_of(ln);
             const int p = cur.p0 + wp * 128 + c * 8;
+            // ASYNC_STORES: the tile's rows that exist as a buffer of their own, so that rows
+            // past them (and, by their offset, columns past the matrix) store nothing
+            i32x4 c_rsrc = {0, 0, 0, 0}, s_rsrc = {0, 0, 0, 0};
+            uint32_t c_voff = 0;
+            const uint32_t row_bytes = (uint32_t)a.ldc * 2u;
+            if (ASYNC_STORES) {
+                const int rows = cur.qlim - cur.q0 < kBQ ? cur.qlim - cur.q0 : kBQ;
+                c_rsrc = make_rsrc(Cout + (size_t)cur.q0 * a.ldc, (uint32_t)rows * row_bytes);
+                if (SCATTER) s_rsrc = make_rsrc(a.Cscatter, a.gather_bytes);
+                c_voff = (p < a.Pdim ? (uint32_t)p * 2u : kOobOffset) +
+                         (uint32_t)(wq * 128 + (ln >> 4)) * row_bytes;
+            }
             // ReLU mask: byte j * 8 + i8 of a lane's 32 bytes says which of the eight
             // elements of the 16-byte piece the lane handles in round j, iteration i8 are
             // > 0.  EPI_RELU (the first forward GEMM) writes the bits, EPI_MASK (the gradient
@@ -495,6 +630,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             // applies them: 32 bytes per lane instead of a second read of the activations.
             // ROUTER_DX: all 32 addend pieces of the lane are asked for first, at once, so that
             // their latency overlaps the turn-around instead of adding up round by round
+            uint32_t new_bits[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // EPI_RELU: the lane's bits of this tile
             u32x4 addend[4][8];
             bool has_addend[4][8];
             if (MODE == MODE_ROUTER_DX) {
@@ -503,7 +639,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
                     for (int i8 = 0; i8 < 8; ++i8) {
                         const int row = j * 32 + i8 * 4 + (ln >> 4);
-                        const int slot = __shfl(j < 2 ? slot_lo : slot_hi, row & 63);
+                        const int slot = __shfl(j < 2 ? tv.slot_lo : tv.slot_hi, row & 63);
                         has_addend[j][i8] = slot >= 0 && p < a.Pdim;
                         addend[j][i8] = u32x4{0u, 0u, 0u, 0u};
                         if (has_addend[j][i8])
@@ -517,8 +653,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                 // the dropout stream; the lane's accumulators of this round belong to one slot
                 uint32_t drop_row = 0;
                 if (DROP && EPI_BASE == EPI_RELU) {
-                    const int q = cur.q0 + row_of(wq, j, wrow);
-                    const int tok = q < cur.qlim ? a.slot_token[(size_t)cur.e * a.slots + q] : 0;
+                    const int tok = __shfl(j < 2 ? tv.tok_lo : tv.tok_hi, (j & 1) * 32 + wrow, kWave);
                     drop_row = (uint32_t)tok * (uint32_t)a.Pdim +
                                (uint32_t)(cur.p0 + wp * 128 + ((ln >> 5) << 2));
                 }
@@ -526,7 +661,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                 float row_gate = 1.f;
                 if (SCALE)
                     row_gate = __uint_as_float(
-                        (uint32_t)__shfl((int)(j < 2 ? ep_lo : ep_hi), (j & 1) * 32 + wrow, kWave));
+                        (uint32_t)__shfl((int)(j < 2 ? tv.ep_lo : tv.ep_hi), (j & 1) * 32 + wrow, kWave));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -535,8 +670,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) v[r] = acc[i][j][g * 4 + r];
                         if (EPI_BASE == EPI_RELU) {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+                            // (the ReLU itself is taken on the rounded values below: every
+                            // factor applied in between is positive or zero)
                             if (DROP) {   // the lane's four units are two aligned pairs
                                 const uint32_t first = drop_row + (uint32_t)(i * 32 + g * 8);
 #pragma unroll
@@ -556,32 +691,43 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] *= row_gate;
                         }
-                        bf16x4 o;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) o[r] = (bf16)v[r];
+                        uint2 o = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+                        if (EPI_BASE == EPI_RELU) {
+                            // ReLU on the bf16 values, two per instruction: read as 16-bit
+                            // integers the negative ones (and -0) are < 0, the others unchanged
+                            o.x = pk_max_i16(o.x, 0u);
+                            o.y = pk_max_i16(o.y, 0u);
+                        }
                         const int ch = i * 4 + g;
-                        *(bf16x4 *)(ep + wrow * 256 + ((ch ^ (wrow & 15)) << 4) + ((ln >> 5) << 3)) = o;
+                        *(uint2 *)(ep + wrow * 256 + ((ch ^ (wrow & 15)) << 4) + ((ln >> 5) << 3)) = o;
                     }
                 }
                 uint32_t m_lo = 0u, m_hi = 0u;
-                if (EPI_BASE == EPI_MASK) { m_lo = mb[2 * j]; m_hi = mb[2 * j + 1]; }
+                if (EPI_BASE == EPI_MASK) { m_lo = tv.mb[2 * j]; m_hi = tv.mb[2 * j + 1]; }
+                // all eight pieces of the round are read before the first is stored (the stores
+                // are fences to the compiler, which would otherwise read, wait and store in turn)
+                u32x4 vals[8];
+#pragma unroll
+                for (int i8 = 0; i8 < 8; ++i8) {
+                    const int rrow = i8 * 4 + (ln >> 4);
+                    vals[i8] = *(const u32x4 *)(ep + rrow * 256 + ((c ^ (rrow & 15)) << 4));
+                }
 #pragma unroll
                 for (int i8 = 0; i8 < 8; ++i8) {
                     const int rrow = i8 * 4 + (ln >> 4);       // row within the round
                     const int row = j * 32 + rrow;               // row within the wave's sub-tile
                     const int q = cur.q0 + row_of(wq, j, rrow);
-                    u32x4 val = *(const u32x4 *)(ep + rrow * 256 + ((c ^ (rrow & 15)) << 4));
+                    u32x4 val = vals[i8];
                     uint32_t row_off = 0;   // SCATTER: the row's place (asked of the lane that holds it, by all lanes)
-                    if (SCATTER) row_off = (uint32_t)__shfl((int)(j < 2 ? ep_lo : ep_hi), row & 63, kWave);
+                    if (SCATTER) row_off = (uint32_t)__shfl((int)(j < 2 ? tv.ep_lo : tv.ep_hi), row & 63, kWave);
                     if (EPI_BASE == EPI_RELU) {
-                        // After ReLU every half word is a non-negative bf16, so adding 0x7fff
-                        // carries into its top bit exactly when it is > 0.  Bits 0..3 of the
+                        // After ReLU every half word is a non-negative bf16: read as an unsigned
+                        // integer it is > 0 exactly when min(., 1) is 1.  Bits 0..3 of the
                         // byte: low halves of the four words, bits 4..7: high halves.
                         uint32_t u = 0;
 #pragma unroll
-                        for (int w = 0; w < 4; ++w)
-                            u |= ((val[w] + 0x7fff7fffu) & 0x80008000u) >> (15 - w);
-                        const uint32_t byte = (u | (u >> 12)) & 0xffu;
+                        for (int w = 0; w < 4; ++w) u |= pk_min_u16(val[w], 0x00010001u) << w;
+                        const uint32_t byte = (u & 0xfu) | ((u >> 12) & 0xf0u);
                         if (i8 < 4) m_lo |= byte << (8 * i8);
                         else m_hi |= byte << (8 * (i8 - 4));
                     }
@@ -591,7 +737,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
                         for (int w = 0; w < 4; ++w) val[w] &= ((byte >> w) & 0x10001u) * 0xffffu;
                     }
-                    if (q < cur.qlim && p < a.Pdim) {
+                    if (ASYNC_STORES) {
+                        store16(c_rsrc, c_voff + (uint32_t)(j * 32 + i8 * 4) * row_bytes, val);
+                        // the same row, at its token's place in the token-major output
+                        if (SCATTER)
+                            store16(s_rsrc, p < a.Pdim ? row_off + (uint32_t)p * 2u : kOobOffset, val);
+                    } else if (q < cur.qlim && p < a.Pdim) {
                         const size_t off = (size_t)q * a.ldc + p;
                         if (MODE == MODE_ROUTER_DX && has_addend[j][i8]) {
                             // add the token's row of the expert-side gradient (fp32 add, one rounding)
@@ -603,19 +754,43 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                             val = __builtin_bit_cast(u32x4, vo);
                         }
                         *(u32x4 *)(Cout + off) = val;
-                        // the same row, at its token's place in the token-major output
-                        if (SCATTER) *(u32x4 *)((char *)Cscat + row_off + (size_t)p * 2) = val;
                     }
                 }
-                if (EPI_BASE == EPI_RELU) *(uint2 *)(bits + 2 * j) = make_uint2(m_lo, m_hi);
+                if (EPI_BASE == EPI_RELU) {
+                    new_bits[2 * j] = m_lo;
+                    new_bits[2 * j + 1] = m_hi;
+                }
+            }
+            if (EPI_BASE == EPI_RELU) {
+                if (ASYNC_STORES) {
+                    const i32x4 b_rsrc =
+                        make_rsrc(a.relu_bits + (size_t)cur.index * kReluBitsPerTile, kReluBitsPerTile);
+                    const uint32_t at = (uint32_t)(wave * 64 + ln) * 32u;
+                    store16(b_rsrc, at, u32x4{new_bits[0], new_bits[1], new_bits[2], new_bits[3]});
+                    store16(b_rsrc, at + 16u, u32x4{new_bits[4], new_bits[5], new_bits[6], new_bits[7]});
+                } else {
+                    *(u32x4 *)bits = u32x4{new_bits[0], new_bits[1], new_bits[2], new_bits[3]};
+                    *(u32x4 *)(bits + 4) = u32x4{new_bits[4], new_bits[5], new_bits[6], new_bits[7]};
+                }
             }
         }
         if (!have_next) break;
+        // The next tile: once every wave has left its turn-around buffer, P of its third step
+        // goes into that stage.  Nothing waits for the stores here.
         cur = nxt;
+        nxt = after;
+        have_next = have_after;
+        tv = tvn;
+        __syncthreads();
+        k_of_p(2);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) SW_ISSUE_P(turn_stage, g);
+        first_step = true;
     }
     SW_WAIT_VMCNT(0);   // the trailing (zero) loads have landed
 #undef SW_K_STEP
-#undef SW_ISSUE_ONE
+#undef SW_ISSUE_P
+#undef SW_ISSUE_Q
 #undef SW_READ_GROUP
 #undef SW_MFMA_PAIR
 }
