@@ -239,7 +239,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     constexpr bool SCATTER = (EPI & EPI_SCATTER) != 0;
     constexpr bool GQ = (GATHER & GATHER_Q) != 0, GP = (GATHER & GATHER_P) != 0;
     constexpr bool GQ_ROWS = GQ && !Q_TRANS;            // Q's tile rows are gathered (per tile)
-    constexpr bool G_STEPS = (GQ && Q_TRANS) || GP;     // an operand's k-rows are gathered (per step)
     static_assert(!(GP && !P_TRANS), "P is gathered only along k");
     static_assert(!(SCALE && SCATTER), "one per-row table per launch");
     // The bf16 epilogue of the expert GEMMs issues a fixed number of stores per lane and does
@@ -287,9 +286,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     // the next tile's loads it would cost a fetch latency per tile.
     // (row offsets: byte offset of a slot's token row in the token-major tensors, slot_off)
     uint32_t off_rows = kOobOffset;  // GQ_ROWS: offset of row 8 wave + (lane & 7) + 32 (lane >> 3) of the next tile
-    // G_STEPS: offsets of the lane's k-rows 16 wave + 2 i + lane / 32 of the step to be loaded
-    uint32_t off_step[8] = {kOobOffset, kOobOffset, kOobOffset, kOobOffset,
-                            kOobOffset, kOobOffset, kOobOffset, kOobOffset};
+    // k-rows gathered: offsets of the wave's sixteen k-rows 16 wave .. of the step to be loaded; they are
+    // the same for all lanes of a half wave, so they are fetched by scalar loads, which the
+    // counter of the direct loads does not see
+    uint32_t off_step[16] = {kOobOffset, kOobOffset, kOobOffset, kOobOffset, kOobOffset, kOobOffset,
+                             kOobOffset, kOobOffset, kOobOffset, kOobOffset, kOobOffset, kOobOffset,
+                             kOobOffset, kOobOffset, kOobOffset, kOobOffset};
     TileVals tv = {}, tvn = {};      // epilogue values of the current tile, of the next one
     auto rows_offsets = [&](const Tile &t) {
         const int row = t.q0 + 8 * wave + (lane & 7) + 32 * (lane >> 3);
@@ -324,13 +326,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         ldq_nk = steps_of(t);
         ldq_e = t.e;
     };
-    // row offsets of the lane's k-rows of step r of expert e: two addresses per load instruction.
-    // Slots without a token hold kOobOffset, and the table is padded for steps past the end.
+    // row offsets of the k-rows of step r of expert e.  Slots without a token hold kOobOffset,
+    // and the table is padded for steps past the end.  (Read through the constant address
+    // space: the table was written by an earlier kernel.)
     auto step_offsets = [&](int e, int r) {
-        const uint32_t *row = a.slot_off + (size_t)e * a.slots + r * kBK + 16 * wave + (lane >> 5);
+        typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;
+        const_u32_ptr row = (const_u32_ptr)(uintptr_t)(a.slot_off + (size_t)e * a.slots + r * kBK + 16 * wave);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) off_step[i] = row[2 * i];
+        for (int i = 0; i < 16; ++i) off_step[i] = row[i];
     };
+    // load i of a lane fetches k-row 16 wave + 2 i + lane / 32
+    auto step_offset_of = [&](int i) { return lane < 32 ? off_step[2 * i] : off_step[2 * i + 1]; };
     // k offset of step j of the tile the P (Q) loads are in; steps past its range read zeros
     int k0p_ = 0, k0q_ = 0;
     auto k_of_p = [&](int j) {
@@ -368,9 +374,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     };
     auto pin_values = [&]() {
         if (GQ_ROWS) asm volatile("" : "+v"(off_rows));
-        if (G_STEPS)
-            asm volatile("" : "+v"(off_step[0]), "+v"(off_step[1]), "+v"(off_step[2]), "+v"(off_step[3]),
-                              "+v"(off_step[4]), "+v"(off_step[5]), "+v"(off_step[6]), "+v"(off_step[7]));
         pin_tile_values(tv);
         pin_tile_values(tvn);
     };
@@ -384,13 +387,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 #define SW_ISSUE_P(PST, G)                                                            \
     do {                                                                              \
         const uint32_t st_ = lds0 + (uint32_t)((PST) * kOpBytes64);                   \
-        if constexpr (GP) op.issue_one(st_, wave, (G), off_step[(G)]);                \
+        if constexpr (GP) op.issue_one(st_, wave, (G), step_offset_of(G));            \
         else op.issue_one(st_, k0p_, wave, (G));                                      \
     } while (0)
 #define SW_ISSUE_Q(QST, G)                                                            \
     do {                                                                              \
         const uint32_t st_ = lds0 + (uint32_t)(kPRingBytes + (QST) * kOpBytes64);     \
-        if constexpr (GQ && Q_TRANS) oq.issue_one(st_, wave, (G), off_step[(G)]);     \
+        if constexpr (GQ && Q_TRANS) oq.issue_one(st_, wave, (G), step_offset_of(G)); \
         else oq.issue_one(st_, k0q_, wave, (G));                                      \
     } while (0)
 // LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of the step in stages PST / QST, sub-step KS into SET

@@ -309,39 +309,56 @@ def compare_full(shape, inp, d_aux=1.0):
     return errs, gpu, fwd, bwd
 
 
-def compare_full_by_experts(shape, inp, n_chunks=8, d_aux=1.0, progress=print):
+class FullByExperts:
     """compare_full for layers where one oracle call would run for minutes: the same complete
     comparison -- every token's rows of y and dx, every expert's weight gradients, the router's --
     with the oracle evaluated for one range of experts at a time (its partial evaluation is
-    pinned against the full run by the CPU tests) and a progress line after each.  The router's
-    gradients are linear in the gate gradients: each range contributes its tokens' share on top
-    of the auxiliary loss's, which a run with no token selected gives alone."""
-    tol = shape.dtype
-    npi = np_inputs(inp)
-    _, gpu = run_gpu(shape, inp, d_aux)
-    for k in DENSE:
-        assert np.all(np.isfinite(gpu[k])), k + " has non-finite values"
-    fwd, flips = check_routing(shape, npi, gpu)
-    check_dropped_rows_are_zero(gpu, shape.dtype)
-    args = (npi["x"], npi["W_r"], npi["W_in"], npi["W_out"])
-    aux = oracle.backward(*args, npi["dy"], fwd, shape.alpha, d_aux, expert_sel=[], token_sel=[])
-    dW_r, db_r, dlog = aux["dW_r"].copy(), aux["db_r"].copy(), aux["dlogits"].copy()
-    y_ref = np.full(gpu["y"].shape, np.nan)
-    errs = {"flips": flips, "relu_ties": 0, "y": 0.0, "dx": 0.0, "dW_in": 0.0, "dW_out": 0.0}
-    worst = {k: 0.0 for k in ("y", "dx", "dW_in", "dW_out")}
-    progress("[by experts] routing checked on all %d tokens" % shape.T)
-    for c in range(n_chunks):
-        sel = list(range(c * shape.E // n_chunks, (c + 1) * shape.E // n_chunks))
+    pinned against the full run by the CPU tests), so that a caller can report after each range.
+    The router's gradients are linear in the gate gradients: each range contributes its tokens'
+    share on top of the auxiliary loss's, which a run with no token selected gives alone.
+    Use: the constructor (GPU run, routing on all tokens), ranges 0 .. n_chunks - 1 in any order,
+    then router()."""
+
+    def __init__(self, shape, inp, n_chunks=8, d_aux=1.0):
+        self.shape, self.n_chunks, self.d_aux = shape, n_chunks, d_aux
+        self.npi = np_inputs(inp)
+        _, self.gpu = run_gpu(shape, inp, d_aux)
+        for k in DENSE:
+            assert np.all(np.isfinite(self.gpu[k])), k + " has non-finite values"
+        self.fwd, flips = check_routing(shape, self.npi, self.gpu)
+        check_dropped_rows_are_zero(self.gpu, shape.dtype)
+        npi = self.npi
+        self.args = (npi["x"], npi["W_r"], npi["W_in"], npi["W_out"])
+        self.aux = oracle.backward(*self.args, npi["dy"], self.fwd, shape.alpha, d_aux,
+                                   expert_sel=[], token_sel=[])
+        self.dW_r, self.db_r = self.aux["dW_r"].copy(), self.aux["db_r"].copy()
+        self.dlog = self.aux["dlogits"].copy()
+        self.y_ref = np.full(self.gpu["y"].shape, np.nan)
+        self.errs = {"flips": flips, "relu_ties": 0, "y": 0.0, "dx": 0.0, "dW_in": 0.0, "dW_out": 0.0}
+        self.worst = {k: 0.0 for k in ("y", "dx", "dW_in", "dW_out")}
+        self.done = set()
+
+    def experts_of(self, c):
+        E = self.shape.E
+        return list(range(c * E // self.n_chunks, (c + 1) * E // self.n_chunks))
+
+    def chunk(self, c):
+        """Range c against the oracle; returns a progress line."""
+        shape, npi, gpu, fwd, errs, worst = self.shape, self.npi, self.gpu, self.fwd, self.errs, self.worst
+        tol = shape.dtype
+        sel = self.experts_of(c)
+        assert c not in self.done
+        self.done.add(c)
         if not sel:
-            continue
+            return "[by experts] range %d is empty" % c
         tmask = np.isin(fwd["expert_index"], sel)
         y_c = oracle.expert_ffn(npi["x"], npi["W_in"], npi["W_out"], fwd["expert_index"],
                                 fwd["dropped"], fwd["gate"], expert_sel=sel, noise=noise_of(shape),
                                 ffn=shape.ffn)
         errs["y"] = max(errs["y"], assert_close("y[experts %d..]" % sel[0], gpu["y"][tmask], y_c[tmask], tol))
-        ties = resolve_relu_ties(shape, npi, fwd, gpu["dx"], d_aux, expert_sel=sel)
+        ties = resolve_relu_ties(shape, npi, fwd, gpu["dx"], self.d_aux, expert_sel=sel)
         errs["relu_ties"] += len(ties)
-        bwd = oracle.backward(*args, npi["dy"], fwd, shape.alpha, d_aux, expert_sel=sel,
+        bwd = oracle.backward(*self.args, npi["dy"], fwd, shape.alpha, self.d_aux, expert_sel=sel,
                               relu_flips=ties)
         errs["dx"] = max(errs["dx"], assert_close("dx[experts %d..]" % sel[0], gpu["dx"][tmask],
                                                   bwd["dx"][tmask], tol))
@@ -353,19 +370,34 @@ def compare_full_by_experts(shape, inp, n_chunks=8, d_aux=1.0, progress=print):
         worst["dx"] = max(worst["dx"], a14(gpu["dx"][tmask], bwd["dx"][tmask]))
         worst["dW_in"] = max(worst["dW_in"], a14(gpu["dW_in"][sel], bwd["dW_in"]))
         worst["dW_out"] = max(worst["dW_out"], a14(gpu["dW_out"][sel], bwd["dW_out"]))
-        dW_r += bwd["dW_r"] - aux["dW_r"]
-        db_r += bwd["db_r"] - aux["db_r"]
-        dlog[tmask] = bwd["dlogits"][tmask]
-        y_ref[tmask] = y_c[tmask]
-        progress("[by experts] experts %d..%d: %d tokens, block errors y %.2e dx %.2e dW_in %.2e dW_out %.2e"
-                 % (sel[0], sel[-1], int(tmask.sum()), errs["y"], errs["dx"], errs["dW_in"], errs["dW_out"]))
-    assert not np.isnan(y_ref).any()          # every token belonged to a range
-    wr_scale, br_scale = router_grad_scales(npi, fwd, y_ref, dlog)
-    errs["dW_r"] = assert_close("dW_r", gpu["dW_r"], dW_r, tol, scale=wr_scale)
-    errs["db_r"] = assert_close("db_r", gpu["db_r"], db_r, tol, scale=br_scale)
-    worst["dW_r"], worst["db_r"] = a14(gpu["dW_r"], dW_r), a14(gpu["db_r"], db_r)
-    errs["a14"] = {k: float("%.2e" % v) for k, v in worst.items()}
-    return errs, gpu, fwd
+        self.dW_r += bwd["dW_r"] - self.aux["dW_r"]
+        self.db_r += bwd["db_r"] - self.aux["db_r"]
+        self.dlog[tmask] = bwd["dlogits"][tmask]
+        self.y_ref[tmask] = y_c[tmask]
+        return ("[by experts] experts %d..%d: %d tokens, block errors y %.2e dx %.2e dW_in %.2e dW_out %.2e"
+                % (sel[0], sel[-1], int(tmask.sum()), errs["y"], errs["dx"], errs["dW_in"], errs["dW_out"]))
+
+    def router(self):
+        """The router's gradients, once every range has added its share; returns all errors."""
+        assert self.done == set(range(self.n_chunks)), "ranges not compared: %s" % (
+            sorted(set(range(self.n_chunks)) - self.done),)
+        assert not np.isnan(self.y_ref).any()          # every token belonged to a range
+        gpu, errs, worst, tol = self.gpu, self.errs, self.worst, self.shape.dtype
+        wr_scale, br_scale = router_grad_scales(self.npi, self.fwd, self.y_ref, self.dlog)
+        errs["dW_r"] = assert_close("dW_r", gpu["dW_r"], self.dW_r, tol, scale=wr_scale)
+        errs["db_r"] = assert_close("db_r", gpu["db_r"], self.db_r, tol, scale=br_scale)
+        worst["dW_r"], worst["db_r"] = a14(gpu["dW_r"], self.dW_r), a14(gpu["db_r"], self.db_r)
+        errs["a14"] = {k: float("%.2e" % v) for k, v in worst.items()}
+        return errs
+
+
+def compare_full_by_experts(shape, inp, n_chunks=8, d_aux=1.0, progress=print):
+    """FullByExperts in one call, a progress line after each range."""
+    run = FullByExperts(shape, inp, n_chunks, d_aux)
+    progress("[by experts] routing checked on all %d tokens" % shape.T)
+    for c in range(n_chunks):
+        progress(run.chunk(c))
+    return run.router(), run.gpu, run.fwd
 
 
 def boundary_experts(E: int, ranges: int = 8):

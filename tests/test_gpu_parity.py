@@ -588,19 +588,37 @@ def test_no_token_left_behind_full_size():
 
 
 # ------------------------------------------- full sizes
-def test_switch_base_full_oracle_parity():
-    """The metric's own workload (Switch-Base, capacity factor 1.0: 65 536 tokens, 128 experts)
-    against the complete fp64 oracle, forward and backward: every row of y and dx, every
-    expert's weight gradients, the router's.  The oracle takes the experts sixteen at a time
-    (the GEMMs' eight tile ranges) and reports after each; a few minutes of host time."""
-    from parity import compare_full_by_experts
-    s = CONFIGS["base_cf1.0"]
-    inp = make_inputs(s, _dev())
-    say = lambda msg: print(msg, flush=True)
-    say("\n[full oracle] base_cf1.0: forward + backward on all %d tokens" % s.T)
-    errs, gpu, fwd = compare_full_by_experts(s, inp, n_chunks=8, d_aux=1.0, progress=say)
+# The metric's own workload (Switch-Base, capacity factor 1.0: 65 536 tokens, 128 experts)
+# against the complete fp64 oracle, forward and backward: every row of y and dx, every expert's
+# weight gradients, the router's.  The oracle takes the experts sixteen at a time (the GEMMs'
+# eight tile ranges); each range is a test of its own, so that the run reports every twenty
+# seconds instead of staying silent for minutes, and the router's gradients, which need every
+# range, come last.
+_BASE_FULL = {}
+
+
+def _base_full():
+    from parity import FullByExperts
+    if "run" not in _BASE_FULL:
+        s = CONFIGS["base_cf1.0"]
+        _BASE_FULL["run"] = FullByExperts(s, make_inputs(s, _dev()), n_chunks=8, d_aux=1.0)
+    return _BASE_FULL["run"]
+
+
+@pytest.mark.parametrize("c", range(8))
+def test_switch_base_full_oracle_parity_experts(c):
+    run = _base_full()
+    print("\n" + run.chunk(c), flush=True)
+    assert run.fwd["capacity"] == 512 and int(run.fwd["dropped"].sum()) > 0
+
+
+def test_switch_base_full_oracle_parity_router():
+    run = _base_full()
+    if len(run.done) < run.n_chunks:
+        pytest.skip("needs every expert range of test_switch_base_full_oracle_parity_experts")
+    errs = run.router()
+    _BASE_FULL.clear()          # the tensors are large
     _report("base_cf1.0, full oracle", errs)
-    assert fwd["capacity"] == 512 and int(fwd["dropped"].sum()) > 0
 
 
 @pytest.mark.parametrize("name,n_experts", [
