@@ -631,27 +631,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             // > 0.  EPI_RELU (the first forward GEMM) writes the bits, EPI_MASK (the gradient
             // w.r.t. the hidden activations, same tiling and same lane-to-element map)
             // applies them: 32 bytes per lane instead of a second read of the activations.
-            // ROUTER_DX: all 32 addend pieces of the lane are asked for first, at once, so that
-            // their latency overlaps the turn-around instead of adding up round by round
             uint32_t new_bits[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // EPI_RELU: the lane's bits of this tile
-            u32x4 addend[4][8];
-            bool has_addend[4][8];
-            if (MODE == MODE_ROUTER_DX) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j) {
+                const int wrow = ln & 31;
+                // ROUTER_DX: the round's eight addend pieces are asked for first, so that their
+                // latency overlaps the turn-around
+                u32x4 addend[8];
+                bool has_addend[8];
+                if (MODE == MODE_ROUTER_DX) {
 #pragma unroll
                     for (int i8 = 0; i8 < 8; ++i8) {
                         const int row = j * 32 + i8 * 4 + (ln >> 4);
                         const int slot = __shfl(j < 2 ? tv.slot_lo : tv.slot_hi, row & 63);
-                        has_addend[j][i8] = slot >= 0 && p < a.Pdim;
-                        addend[j][i8] = u32x4{0u, 0u, 0u, 0u};
-                        if (has_addend[j][i8])
-                            addend[j][i8] = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
+                        has_addend[i8] = slot >= 0 && p < a.Pdim;
+                        addend[i8] = u32x4{0u, 0u, 0u, 0u};
+                        if (has_addend[i8]) addend[i8] = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
                     }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int wrow = ln & 31;
+                }
                 // expert dropout: the draw of hidden unit p of token t is element t * d_ff + p of
                 // the dropout stream; the lane's accumulators of this round belong to one slot
                 uint32_t drop_row = 0;
@@ -747,10 +744,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                             store16(s_rsrc, p < a.Pdim ? row_off + (uint32_t)p * 2u : kOobOffset, val);
                     } else if (q < cur.qlim && p < a.Pdim) {
                         const size_t off = (size_t)q * a.ldc + p;
-                        if (MODE == MODE_ROUTER_DX && has_addend[j][i8]) {
+                        if (MODE == MODE_ROUTER_DX && has_addend[i8]) {
                             // add the token's row of the expert-side gradient (fp32 add, one rounding)
                             const bf16x8 va = __builtin_bit_cast(bf16x8, val);
-                            const bf16x8 vb = __builtin_bit_cast(bf16x8, addend[j][i8]);
+                            const bf16x8 vb = __builtin_bit_cast(bf16x8, addend[i8]);
                             bf16x8 vo;
 #pragma unroll
                             for (int w = 0; w < 8; ++w) vo[w] = (bf16)((float)va[w] + (float)vb[w]);
