@@ -264,7 +264,7 @@ def main() -> int:
         with open(traffic_file) as fh:
             for ln in fh:
                 parts = ln.split("#")[0].split()
-                if len(parts) == 3 and parts[0] == args.config and parts[1] == dominant:
+                if len(parts) == 3 and parts[0] == shape.name and parts[1] == dominant:
                     roofline["traffic"] = float(parts[2])
                     roofline["traffic_source"] = ("profiles/hbm_traffic.txt: rocprofv3 FETCH_SIZE + "
                                                   "WRITE_SIZE of an earlier run of this command, "
