@@ -58,7 +58,12 @@
 // epilogue instead of before it -- so that C is written in whole 256-byte row
 // segments; fused into it: ReLU and one mask bit per element
 // (first forward GEMM), that mask (gradient w.r.t. the hidden activations), the
-// gathered addend of the router's dx.
+// gathered addend of the router's dx.  The expert GEMMs' stores are buffer stores of a
+// fixed number per lane (rows and columns that do not exist fall outside the descriptor),
+// and nothing waits for them: loads and stores retire in order, so the next tile's first
+// step simply counts them among the operations that may stay in flight.  (Measured: the
+// k loops alone run 229-267 us per launch at Switch-Base, the epilogue's instructions cost
+// 10-45 us, the writes to HBM themselves another 30-60 us whether or not they are waited for.)
 //
 // Dispatch and combine (Sec. 5.4) without a pass of their own.  With GATHER set an operand's
 // rows are fetched from the token-major tensors by the slot -> token table: the first forward
@@ -632,23 +637,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             // w.r.t. the hidden activations, same tiling and same lane-to-element map)
             // applies them: 32 bytes per lane instead of a second read of the activations.
             uint32_t new_bits[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // EPI_RELU: the lane's bits of this tile
+            const int wrow = ln & 31;
+            // ROUTER_DX: the round's eight addend pieces, asked for before the round is turned
+            // around so that their latency overlaps it
+            u32x4 addend[8];
+            bool has_addend[8];
+            auto ask_addend = [&](int j) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int wrow = ln & 31;
-                // ROUTER_DX: the round's eight addend pieces are asked for first, so that their
-                // latency overlaps the turn-around
-                u32x4 addend[8];
-                bool has_addend[8];
-                if (MODE == MODE_ROUTER_DX) {
-#pragma unroll
-                    for (int i8 = 0; i8 < 8; ++i8) {
-                        const int row = j * 32 + i8 * 4 + (ln >> 4);
-                        const int slot = __shfl(j < 2 ? tv.slot_lo : tv.slot_hi, row & 63);
-                        has_addend[i8] = slot >= 0 && p < a.Pdim;
-                        addend[i8] = u32x4{0u, 0u, 0u, 0u};
-                        if (has_addend[i8]) addend[i8] = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
-                    }
+                for (int i8 = 0; i8 < 8; ++i8) {
+                    const int row = j * 32 + i8 * 4 + (ln >> 4);
+                    const int slot = __shfl(j < 2 ? tv.slot_lo : tv.slot_hi, row & 63);
+                    has_addend[i8] = slot >= 0 && p < a.Pdim;
+                    addend[i8] = u32x4{0u, 0u, 0u, 0u};
+                    if (has_addend[i8]) addend[i8] = *(const u32x4 *)(a.mask + (size_t)slot * a.ldc + p);
                 }
+            };
+            // round j, first half: the lane's accumulators of rows 32 j .. of the wave's sub-tile,
+            // converted, into the turn-around buffer
+            auto turn_in = [&](int j) {
                 // expert dropout: the draw of hidden unit p of token t is element t * d_ff + p of
                 // the dropout stream; the lane's accumulators of this round belong to one slot
                 uint32_t drop_row = 0;
@@ -702,16 +708,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                         *(uint2 *)(ep + wrow * 256 + ((ch ^ (wrow & 15)) << 4) + ((ln >> 5) << 3)) = o;
                     }
                 }
-                uint32_t m_lo = 0u, m_hi = 0u;
-                if (EPI_BASE == EPI_MASK) { m_lo = tv.mb[2 * j]; m_hi = tv.mb[2 * j + 1]; }
-                // all eight pieces of the round are read before the first is stored (the stores
-                // are fences to the compiler, which would otherwise read, wait and store in turn)
-                u32x4 vals[8];
+            };
+            // second half: the round's rows read back as 16-byte pieces of 256-byte segments.  All
+            // eight are read before the first is stored (the stores are fences to the compiler,
+            // which would otherwise read, wait and store in turn).
+            u32x4 vals[8];
+            auto turn_out = [&]() {
 #pragma unroll
                 for (int i8 = 0; i8 < 8; ++i8) {
                     const int rrow = i8 * 4 + (ln >> 4);
                     vals[i8] = *(const u32x4 *)(ep + rrow * 256 + ((c ^ (rrow & 15)) << 4));
                 }
+            };
+            // third: what is left to do on the pieces, and their stores
+            auto store_round = [&](int j) {
+                uint32_t m_lo = 0u, m_hi = 0u;
+                if (EPI_BASE == EPI_MASK) { m_lo = tv.mb[2 * j]; m_hi = tv.mb[2 * j + 1]; }
 #pragma unroll
                 for (int i8 = 0; i8 < 8; ++i8) {
                     const int rrow = i8 * 4 + (ln >> 4);       // row within the round
@@ -760,6 +772,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
                     new_bits[2 * j] = m_lo;
                     new_bits[2 * j + 1] = m_hi;
                 }
+            };
+            if (MODE == MODE_ROUTER_DX) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    ask_addend(j);
+                    turn_in(j);
+                    turn_out();
+                    store_round(j);
+                }
+            } else {
+                // The rounds overlap: round j + 1 is converted and written into the buffer (behind
+                // round j's reads, which the LDS executes in order) before round j's pieces are
+                // waited for and stored, so that the conversions cover the reads' latency.
+                turn_in(0);
+                turn_out();
+#pragma unroll
+                for (int j = 1; j < 4; ++j) {
+                    turn_in(j);
+                    store_round(j - 1);
+                    turn_out();
+                }
+                store_round(3);
             }
             if (EPI_BASE == EPI_RELU) {
                 if (ASYNC_STORES) {
