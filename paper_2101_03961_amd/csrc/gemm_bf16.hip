@@ -11,7 +11,8 @@
 // the waves cost ~30 cycles of issue each and were the bottleneck of an earlier
 // register-staged version).  k advances 64 at a time: every row of an operand tile
 // is then one full 128-byte line per step.  The P operand goes through three LDS
-// stages of 32 KB, the Q operand through two (3 x 32 + 2 x 32 = all 160 KB): in the
+// stages of 32 KB, the Q operand through two (3 x 32 + 2 x 32 = all 160 KB; with DEEP_Q
+// the other way round, for the one GEMM whose Q is the operand that comes from HBM): in the
 // last quarter of step kt, right after the barrier that frees the stages of step
 // kt, a wave issues its eight loads of Q for step kt+2 and then its eight loads of P
 // for step kt+3.  Loads complete in order, so the wait of step kt+1 (for step kt+2's
@@ -81,12 +82,12 @@ namespace sw {
 constexpr int kBP = kGemmTile;                    // block tile, p rows
 constexpr int kBQ = kGemmTile;                    // block tile, q rows
 constexpr int kBK = 64;                           // k per pipeline step
-constexpr int kPStages = 3;                       // LDS stages of the P operand
-constexpr int kQStages = 2;                       // ... of the Q operand
+constexpr int kDeepStages = 3;                    // LDS stages of the operand that mostly comes from HBM
+constexpr int kShallowStages = 2;                 // ... of the other operand
 constexpr int kGemmThreads = 256;
 static_assert(kOpBytes64 == kBP * kBK * 2, "operand stage size");
-constexpr int kPRingBytes = kPStages * kOpBytes64;            // 96 KB
-constexpr int kRingBytes = kPRingBytes + kQStages * kOpBytes64;   // 160 KB: all of a CU's LDS
+constexpr int kDeepRingBytes = kDeepStages * kOpBytes64;      // 96 KB
+constexpr int kRingBytes = kDeepRingBytes + kShallowStages * kOpBytes64;   // 160 KB: all of a CU's LDS
 constexpr int kTurnBytes = 32 * 256;              // per wave: 32 rows x 128 bf16 of the epilogue's turn-around
 static_assert(4 * kTurnBytes == kOpBytes64, "the turn-around buffers are one P stage");
 constexpr int kGemmLds = kRingBytes;
@@ -200,9 +201,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // One store of 16 bytes per lane at byte offset voff of the buffer; offsets past the buffer's
 // size store nothing.  Written as asm so that every lane's store is issued whatever its
 // offset -- the number of stores in flight is then known -- and so that the compiler's own
-// waits do not count it.  (The s_nop keeps a write of the data registers one state away.)
+// waits do not count it.  The compiler does not look into asm for hazards: the leading s_nop
+// keeps five states between a descriptor word it may just have reloaded from a spill lane
+// (v_readlane) and the store that reads it, the trailing one keeps a write of the data
+// registers one state away.
 __device__ __forceinline__ void store16(i32x4 rsrc, uint32_t voff, u32x4 data) {
-    asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 0"
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, 0 offen\n\ts_nop 0"
                  :
                  : "v"(data), "v"(voff), "s"(rsrc)
                  : "memory");
@@ -235,7 +239,8 @@ struct TileVals {
     int tok_lo, tok_hi;      // EPI_DROP after ReLU: token of those rows
 };
 
-template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE, int GATHER>
+template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED, int MODE, int GATHER,
+          bool DEEP_Q>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int EPI_BASE = EPI & 3;
@@ -388,24 +393,43 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     constexpr int kNP = OperandOf<P_TRANS, GP>::type::kPieces;
     constexpr int kNR = kNP + OperandOf<Q_TRANS, GQ>::type::kPieces;   // LDS reads per sub-step
 
-// direct load G of eight of the P operand into P stage PST (of the Q operand into Q stage QST)
-#define SW_ISSUE_P(PST, G)                                                            \
+// The two rings: the deep one (three stages, the first 96 KB) carries the operand that mostly
+// comes from HBM -- P, or with DEEP_Q Q (the second-layer weight gradient, whose Q is the
+// hidden activations and whose P is dy) -- the shallow one (two stages) the other.
+// Byte offsets of stage DST of the deep ring, SST of the shallow ring, of the stages that hold P / Q:
+#define SW_DEEP_AT(DST) ((DST) * kOpBytes64)
+#define SW_SHALLOW_AT(SST) (kDeepRingBytes + (SST) * kOpBytes64)
+#define SW_P_AT(DST, SST) (DEEP_Q ? SW_SHALLOW_AT(SST) : SW_DEEP_AT(DST))
+#define SW_Q_AT(DST, SST) (DEEP_Q ? SW_DEEP_AT(DST) : SW_SHALLOW_AT(SST))
+// direct load G of eight of the P (Q) operand into the stage at byte offset AT
+#define SW_ISSUE_P_AT(AT, G)                                                          \
     do {                                                                              \
-        const uint32_t st_ = lds0 + (uint32_t)((PST) * kOpBytes64);                   \
+        const uint32_t st_ = lds0 + (uint32_t)(AT);                                   \
         if constexpr (GP) op.issue_one(st_, wave, (G), step_offset_of(G));            \
         else op.issue_one(st_, k0p_, wave, (G));                                      \
     } while (0)
-#define SW_ISSUE_Q(QST, G)                                                            \
+#define SW_ISSUE_Q_AT(AT, G)                                                          \
     do {                                                                              \
-        const uint32_t st_ = lds0 + (uint32_t)(kPRingBytes + (QST) * kOpBytes64);     \
+        const uint32_t st_ = lds0 + (uint32_t)(AT);                                   \
         if constexpr (GQ && Q_TRANS) oq.issue_one(st_, wave, (G), step_offset_of(G)); \
         else oq.issue_one(st_, k0q_, wave, (G));                                      \
     } while (0)
-// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of the step in stages PST / QST, sub-step KS into SET
-#define SW_READ_GROUP(SET, PST, QST, KS, G)                                           \
+// ... of the deep (shallow) operand into stage DST (SST) of its ring
+#define SW_ISSUE_DEEP(DST, G)                                                         \
     do {                                                                              \
-        const char *sp_ = lds + (PST) * kOpBytes64;                                   \
-        const char *sq_ = lds + kPRingBytes + (QST) * kOpBytes64;                     \
+        if constexpr (DEEP_Q) SW_ISSUE_Q_AT(SW_DEEP_AT(DST), G);                      \
+        else SW_ISSUE_P_AT(SW_DEEP_AT(DST), G);                                       \
+    } while (0)
+#define SW_ISSUE_SHALLOW(SST, G)                                                      \
+    do {                                                                              \
+        if constexpr (DEEP_Q) SW_ISSUE_P_AT(SW_SHALLOW_AT(SST), G);                   \
+        else SW_ISSUE_Q_AT(SW_SHALLOW_AT(SST), G);                                    \
+    } while (0)
+// LDS reads [G kNR/8, (G+1) kNR/8) of the fragments of the step in stages DST / SST, sub-step KS into SET
+#define SW_READ_GROUP(SET, DST, SST, KS, G)                                           \
+    do {                                                                              \
+        const char *sp_ = lds + SW_P_AT(DST, SST);                                    \
+        const char *sq_ = lds + SW_Q_AT(DST, SST);                                    \
         _Pragma("unroll") for (int x_ = (G)*kNR / 8; x_ < ((G) + 1) * kNR / 8; ++x_) { \
             if (x_ < kNP) op.read_piece(sp_, x_, KS, fa[SET]);                        \
             else oq.read_piece(sq_, x_ - kNP, KS, fb[SET]);                           \
@@ -421,33 +445,34 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             __builtin_bit_cast(bf16x8, a8_), __builtin_bit_cast(bf16x8, b8_), acc[i_][j_], 0, 0, 0); \
     }
 
-// One k step = four sub-steps of 16 MFMAs, on the operands in P stage pst and Q stage qst.
-// Fragments of a sub-step are read (into the other of two register sets) between the MFMAs of
-// the sub-step before it.  After the third sub-step's MFMAs nobody reads these stages any
+// One k step = four sub-steps of 16 MFMAs, on the operands in deep stage dst and shallow stage
+// sst.  Fragments of a sub-step are read (into the other of two register sets) between the MFMAs
+// of the sub-step before it.  After the third sub-step's MFMAs nobody reads these stages any
 // more: the step's one barrier sits there, behind a wait that leaves the eight youngest loads
-// (P of the step after next) in flight.  The fourth sub-step runs with the loads of Q for the
-// step after next (into the Q stage just freed), then -- unless ISSUE_P is false -- of P for
-// the step after that (into the P stage just freed; k offsets from the preceding k_of_q /
-// k_of_p), and with the first fragments of the next step between its MFMAs.
-#define SW_K_STEP(ISSUE_P)                                                            \
+// (the deep operand of the step after next) in flight.  The fourth sub-step runs with the loads
+// of the shallow operand for the step after next (into the shallow stage just freed), then --
+// unless ISSUE_DEEP is false -- of the deep operand for the step after that (into the deep stage
+// just freed; k offsets from the preceding k_of_shallow / k_of_deep), and with the first
+// fragments of the next step between its MFMAs.
+#define SW_K_STEP(ISSUE_DEEP)                                                         \
     do {                                                                              \
-        const int pn_ = pst == kPStages - 1 ? 0 : pst + 1;                            \
+        const int dn_ = dst == kDeepStages - 1 ? 0 : dst + 1;                         \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_READ_GROUP(1, pst, qst, 1, g);                                         \
+            SW_READ_GROUP(1, dst, sst, 1, g);                                         \
             SW_MFMA_PAIR(0, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_READ_GROUP(0, pst, qst, 2, g);                                         \
+            SW_READ_GROUP(0, dst, sst, 2, g);                                         \
             SW_MFMA_PAIR(1, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
-            SW_READ_GROUP(1, pst, qst, 3, g);                                         \
+            SW_READ_GROUP(1, dst, sst, 3, g);                                         \
             SW_MFMA_PAIR(0, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
-        if (first_step) { /* after an epilogue: its stores and P of step 2 are younger */ \
+        if (first_step) { /* after an epilogue: its stores and the deep operand of step 2 are younger */ \
             wait_vmcnt<kFirstWait>();                                                 \
             first_step = false;                                                       \
         } else {                                                                      \
@@ -457,21 +482,29 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         pin_values();                                                                 \
         _Pragma("unroll") for (int g = 0; g < 8; ++g) {                               \
             if (g < 4) {                                                              \
-                SW_ISSUE_Q(qst, 2 * g);                                               \
-                SW_ISSUE_Q(qst, 2 * g + 1);                                           \
-            } else if (ISSUE_P) {                                                     \
-                SW_ISSUE_P(pst, 2 * (g - 4));                                         \
-                SW_ISSUE_P(pst, 2 * (g - 4) + 1);                                     \
+                SW_ISSUE_SHALLOW(sst, 2 * g);                                         \
+                SW_ISSUE_SHALLOW(sst, 2 * g + 1);                                     \
+            } else if (ISSUE_DEEP) {                                                  \
+                SW_ISSUE_DEEP(dst, 2 * (g - 4));                                      \
+                SW_ISSUE_DEEP(dst, 2 * (g - 4) + 1);                                  \
             }                                                                         \
-            SW_READ_GROUP(0, pn_, qst ^ 1, 0, g);                                     \
+            SW_READ_GROUP(0, dn_, sst ^ 1, 0, g);                                     \
             SW_MFMA_PAIR(1, g)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                        \
         }                                                                             \
-        pst = pn_;                                                                    \
-        qst ^= 1;                                                                     \
+        dst = dn_;                                                                    \
+        sst ^= 1;                                                                     \
     } while (0)
 
-    int pst = 0, qst = 0;   // stages of the step that is multiplied next
+    // the operand in the deep ring and the one in the shallow ring
+    auto begin_deep = [&](const Tile &t) { if constexpr (DEEP_Q) begin_q(t); else begin_p(t); };
+    auto begin_shallow = [&](const Tile &t) { if constexpr (DEEP_Q) begin_p(t); else begin_q(t); };
+    auto k_of_deep = [&](int j) { if constexpr (DEEP_Q) k_of_q(j); else k_of_p(j); };
+    auto k_of_shallow = [&](int j) { if constexpr (DEEP_Q) k_of_p(j); else k_of_q(j); };
+    auto disable_deep = [&]() { if constexpr (DEEP_Q) oq.disable_load(); else op.disable_load(); };
+    auto disable_shallow = [&]() { if constexpr (DEEP_Q) op.disable_load(); else oq.disable_load(); };
+
+    int dst = 0, sst = 0;   // stages of the step that is multiplied next
     bool first_step = false;   // the step that is multiplied next follows an epilogue
     // per-tile values of the epilogue, asked for two steps before the end of the tile before
     // (see pin_values)
@@ -511,8 +544,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
         }
     };
 
-    // Start of the pipeline: Q and P of the first tile's steps 0 and 1, then P of step 2; step 0
-    // is awaited (what may stay in flight: Q, P of step 1 and P of step 2, 24 loads).
+    // Start of the pipeline: both operands of the first tile's steps 0 and 1, then the deep one
+    // of step 2; step 0 is awaited (what may stay in flight: both of step 1 and the deep one of
+    // step 2, 24 loads).
     tile_values(cur, tv);
     if (GQ_ROWS) off_rows = rows_offsets(cur);
     begin_p(cur);
@@ -522,16 +556,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
     if (GQ_ROWS && have_next) off_rows = rows_offsets(nxt);
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
-        k_of_q(st);
+        k_of_shallow(st);
 #pragma unroll
-        for (int g = 0; g < 8; ++g) SW_ISSUE_Q(st, g);
-        k_of_p(st);
+        for (int g = 0; g < 8; ++g) SW_ISSUE_SHALLOW(st, g);
+        k_of_deep(st);
 #pragma unroll
-        for (int g = 0; g < 8; ++g) SW_ISSUE_P(st, g);
+        for (int g = 0; g < 8; ++g) SW_ISSUE_DEEP(st, g);
     }
-    k_of_p(2);
+    k_of_deep(2);
 #pragma unroll
-    for (int g = 0; g < 8; ++g) SW_ISSUE_P(2, g);
+    for (int g = 0; g < 8; ++g) SW_ISSUE_DEEP(2, g);
     SW_WAIT_VMCNT(24);
     __syncthreads();
 
@@ -552,38 +586,40 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
 
         // first fragments of the tile's first step (it has landed: awaited in the step before)
 #pragma unroll
-        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, pst, qst, 0, g);
+        for (int g = 0; g < 8; ++g) SW_READ_GROUP(0, dst, sst, 0, g);
 
-        // Step kt issues Q of step kt + 2 and P of step kt + 3 of this tile, as long as there
-        // are such steps ...
+        // Step kt issues the shallow operand of step kt + 2 and the deep one of step kt + 3 of
+        // this tile, as long as there are such steps ...
         for (int kt = 0; kt < nsteps - 3; ++kt) {
-            k_of_q(kt + 2);
-            k_of_p(kt + 3);
+            k_of_shallow(kt + 2);
+            k_of_deep(kt + 3);
             SW_K_STEP(true);
         }
-        // ... then the third step from the end P of the next tile's first step (after the last
-        // tile: zeros) with Q of this tile's last,
-        k_of_q(nsteps - 1);
-        if (have_next) begin_p(nxt); else op.disable_load();
-        k_of_p(0);
+        // ... then the third step from the end the deep operand of the next tile's first step
+        // (after the last tile: zeros) with the shallow one of this tile's last,
+        k_of_shallow(nsteps - 1);
+        if (have_next) begin_deep(nxt); else disable_deep();
+        k_of_deep(0);
         SW_K_STEP(true);
-        // the second from the end Q of the next tile's first step and P of its second; the next
-        // tile's epilogue values and the rows of the tile after it are asked for here, ahead of
-        // this step's barrier (see pin_values) and of this tile's stores,
-        if (have_next) begin_q(nxt); else oq.disable_load();
+        // the second from the end the shallow operand of the next tile's first step and the deep
+        // one of its second; the next tile's epilogue values and the rows of the tile after it
+        // are asked for here, ahead of this step's barrier (see pin_values) and of this tile's
+        // stores,
+        if (have_next) begin_shallow(nxt); else disable_shallow();
         bool have_after = false;
         if (have_next) {
             have_after = next_tile<Q_LIMITED, K_LIMITED, MODE>(a, L, L_end, stride, after);
             tile_values(nxt, tvn);
             if (GQ_ROWS && have_after) off_rows = rows_offsets(after);
         }
-        k_of_q(0);
-        k_of_p(1);
+        k_of_shallow(0);
+        k_of_deep(1);
         SW_K_STEP(true);
-        // and the last one Q of its second step only: the P stage it frees is the epilogue's.
-        k_of_q(1);
+        // and the last one the shallow operand of its second step only: the deep stage it frees
+        // is the epilogue's.
+        k_of_shallow(1);
         SW_K_STEP(false);
-        const int turn_stage = pst == 0 ? kPStages - 1 : pst - 1;   // P stage of the step just done
+        const int turn_stage = dst == 0 ? kDeepStages - 1 : dst - 1;   // deep stage of the step just done
 
         // Epilogue.  A lane holds, for q = lane%32 of each 32x32 MFMA tile, the four
         // consecutive p = 8*(r/4) + 4*(lane/32) + r%4: 8-byte pieces scattered over 32
@@ -809,22 +845,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs a) {
             }
         }
         if (!have_next) break;
-        // The next tile: once every wave has left its turn-around buffer, P of its third step
-        // goes into that stage.  Nothing waits for the stores here.
+        // The next tile: once every wave has left its turn-around buffer, the deep operand of its
+        // third step goes into that stage.  Nothing waits for the stores here.
         cur = nxt;
         nxt = after;
         have_next = have_after;
         tv = tvn;
         __syncthreads();
-        k_of_p(2);
+        k_of_deep(2);
 #pragma unroll
-        for (int g = 0; g < 8; ++g) SW_ISSUE_P(turn_stage, g);
+        for (int g = 0; g < 8; ++g) SW_ISSUE_DEEP(turn_stage, g);
         first_step = true;
     }
     SW_WAIT_VMCNT(0);   // the trailing (zero) loads have landed
 #undef SW_K_STEP
-#undef SW_ISSUE_P
-#undef SW_ISSUE_Q
+#undef SW_ISSUE_DEEP
+#undef SW_ISSUE_SHALLOW
+#undef SW_ISSUE_P_AT
+#undef SW_ISSUE_Q_AT
+#undef SW_P_AT
+#undef SW_Q_AT
+#undef SW_DEEP_AT
+#undef SW_SHALLOW_AT
 #undef SW_READ_GROUP
 #undef SW_MFMA_PAIR
 }
@@ -848,9 +890,9 @@ static int persistent_blocks() {
 }
 
 template <bool Q_TRANS, bool P_TRANS, int EPI, bool Q_LIMITED, bool K_LIMITED,
-          int MODE = MODE_EXPERTS, int GATHER = GATHER_NONE>
+          int MODE = MODE_EXPERTS, int GATHER = GATHER_NONE, bool DEEP_Q = false>
 static hipError_t gemm_launch(const GemmArgs &a, hipStream_t s) {
-    auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED, MODE, GATHER>;
+    auto kern = gemm_bf16_kernel<Q_TRANS, P_TRANS, EPI, Q_LIMITED, K_LIMITED, MODE, GATHER, DEEP_Q>;
     static PerDeviceOnce once;   // one per template instantiation
     hipError_t attr_err = once_per_device(once, [&] {
         return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -977,8 +1019,8 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
         finish(f, d, C);
         ProfScope ps("gemm2_wgrad", s);
         if (fused)
-            return gemm_launch<true, true, EPI_NONE, false, true, MODE_EXPERTS, GATHER_P>(a, s);
-        return gemm_launch<true, true, EPI_NONE, false, true>(a, s);
+            return gemm_launch<true, true, EPI_NONE, false, true, MODE_EXPERTS, GATHER_P, true>(a, s);
+        return gemm_launch<true, true, EPI_NONE, false, true, MODE_EXPERTS, GATHER_NONE, true>(a, s);
     }
     case GEMM_WGRAD1: {
         a.Q = fused ? (const bf16 *)tm.x : Xd;              // [k = slot][q = d]

@@ -32,10 +32,13 @@ __device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes) {
 }
 
 // One direct global -> LDS load of 16 bytes per lane: lane l's bytes land at
-// LDS offset lds_base + 16 l.  lds_base and soff are wave-uniform.
+// LDS offset lds_base + 16 l.  lds_base and soff are wave-uniform.  The s_nop covers two
+// hazards the compiler does not see inside asm: m0 written one state before the load, and a
+// descriptor or offset register reloaded from a spill lane (v_readlane) fewer than five
+// states before it.
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\t"
-                 "s_nop 0\n\t"
+                 "s_nop 3\n\t"
                  "buffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
