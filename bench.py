@@ -55,6 +55,8 @@ def kernel_work(shape, kept, elt):
         "gemm1_wgrad": (gemm_in, w_in_bytes + kept * (d + f1) * elt, "mfma"),
     } if shape.ffn == "geglu" else {}
     jit = shape.jitter_eps > 0
+    zero_with_positions = (shape.dtype == "bf16" and shape.fused_dispatch and
+                           shape.ntlb_rounds == 0)
     dpad = -(-d // 32) * 32
     x_router = T * 3 * dpad * 2 if jit else T * d * elt     # bytes of the router's input operand
     return {**{
@@ -65,7 +67,10 @@ def kernel_work(shape, kept, elt):
         "router_logits": (2.0 * T * d * E, T * d * elt + T * E * 4 + d * E * 4, "hbm"),
         "router_softmax_top1": (0.0, 2.0 * T * E * 4 + T * 8, "hbm"),
         "route_scan_aux": (0.0, 3.0 * (T / 256.0) * E * 4, "hbm"),
-        "positions": (0.0, T * (4 + 4 + 4 + 4 + 1 + 4 + 1), "hbm"),
+        # (with dispatch / combine inside the GEMMs and no re-routing stages it also clears the
+        # rows of y of the tokens without a slot)
+        "positions": (0.0, T * (4 + 4 + 4 + 4 + 1 + 4 + 1) +
+                      ((T - kept) * d * elt if zero_with_positions else 0), "hbm"),
         "dispatch_gather": (0.0, 2.0 * kept * d * elt, "hbm"),
         # dispatch / combine inside the GEMMs: what is left of the two passes
         "zero_dropped": (0.0, T * 4.0 + (T - kept) * d * elt, "hbm"),
@@ -141,7 +146,7 @@ def measure(shape, steps, warmup, dev="cuda:0"):
                         shape.alpha, shape.dtype, device=dev, n_groups=shape.n_groups,
                         expert_dropout=shape.expert_dropout, jitter_eps=shape.jitter_eps,
                         seed=shape.noise_seed, ffn=shape.ffn, ntlb_rounds=shape.ntlb_rounds,
-                        separate_dispatch=shape.separate_dispatch)
+                        fused_dispatch=shape.fused_dispatch)
     layer.alloc_grads(with_bias=inp["b_r"] is not None)
 
     def step():
@@ -220,8 +225,8 @@ def main() -> int:
                     help="expert dropout rate (0 = the benchmark's workload; >0 for experiments)")
     ap.add_argument("--jitter-eps", type=float, default=0.0,
                     help="input jitter on the router (0 = the benchmark's workload)")
-    ap.add_argument("--separate-dispatch", action="store_true",
-                    help="dispatch / combine as separate passes (for experiments)")
+    ap.add_argument("--fused-dispatch", action="store_true",
+                    help="dispatch / combine inside the expert GEMMs (for experiments)")
     ap.add_argument("--ntlb-rounds", type=int, default=0,
                     help="No-Token-Left-Behind re-routing stages (0 = the benchmark's workload)")
     args = ap.parse_args()
@@ -246,8 +251,8 @@ def main() -> int:
     if args.ntlb_rounds:
         shape = shape.with_(name="%s_ntlb%d" % (shape.name, args.ntlb_rounds),
                             ntlb_rounds=args.ntlb_rounds)
-    if args.separate_dispatch:
-        shape = shape.with_(name="%s_separate_dispatch" % shape.name, separate_dispatch=True)
+    if args.fused_dispatch:
+        shape = shape.with_(name="%s_fused_dispatch" % shape.name, fused_dispatch=True)
     ms_per_step, ms_prof, kernels, facts, inp = measure(shape, args.steps, args.warmup)
 
     dominant = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])

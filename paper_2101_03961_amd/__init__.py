@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     SW_F32,
     SW_FFN_GEGLU,
     SW_FFN_RELU,
-    SW_FLAG_SEPARATE_DISPATCH,
+    SW_FLAG_FUSED_DISPATCH,
     SwitchConfig,
     SwitchError,
     library_path,

@@ -10,7 +10,7 @@ _LIB_PATH = os.path.join(HERE, "libswitchffn.so")
 
 SW_F32, SW_BF16 = 0, 1
 SW_FFN_RELU, SW_FFN_GEGLU = 0, 1
-SW_FLAG_SEPARATE_DISPATCH = 1
+SW_FLAG_FUSED_DISPATCH = 1
 
 
 class SwitchError(RuntimeError):

@@ -27,7 +27,7 @@ int check_config(const switch_config *cfg) {
     if (!(cfg->expert_dropout >= 0.f && cfg->expert_dropout < 1.f)) return SW_ERR_VALUE;
     if (!(cfg->jitter_eps >= 0.f && cfg->jitter_eps < 1.f)) return SW_ERR_VALUE;
     if (cfg->ntlb_rounds < 0 || cfg->ntlb_rounds > 16) return SW_ERR_VALUE;
-    if (cfg->flags & ~SW_FLAG_SEPARATE_DISPATCH) return SW_ERR_VALUE;
+    if (cfg->flags & ~SW_FLAG_FUSED_DISPATCH) return SW_ERR_VALUE;
     // slot indices (expert * slots per expert + position) are kept in 32 bits
     const double n = cfg->n_groups > 1 ? (double)cfg->n_groups : 1.0;
     const double c = floor((double)cfg->T / n / (double)cfg->E * cfg->capacity_factor);
@@ -83,7 +83,7 @@ Workspace layout_workspace(const switch_config *cfg) {
     w.slot_off = take((E * C + 128) * 4);
     // dispatch and combine inside the GEMMs: bf16, and x / dy / y addressed through one buffer
     // descriptor with 32-bit byte offsets
-    w.fused = cfg->act_dtype == SW_BF16 && !(cfg->flags & SW_FLAG_SEPARATE_DISPATCH) &&
+    w.fused = cfg->act_dtype == SW_BF16 && (cfg->flags & SW_FLAG_FUSED_DISPATCH) &&
               (double)T * (double)d * 2.0 < 2147483647.0;
     w.tok_slot = take(T * 4);
     w.Xd = take(E * C * d * w.elt);
@@ -273,11 +273,14 @@ static int forward_on(const switch_config *cfg, const Workspace &w, const void *
     if (st) return st;
     if ((st = status_of(launch_route_scan(w, ws, expert_counts, s)))) return st;
     if ((st = status_of(launch_dispatch(w, dt, cfg->alpha, x, ws, position_in_expert, dropped,
-                                        aux_loss, router_logits, expert_index, gate, s))))
+                                        aux_loss, router_logits, expert_index, gate, y, s))))
         return st;
     const TokenMajor tm{x, nullptr, y};
-    // fused: rows of tokens without a slot are +0, all others are written by the second GEMM
-    if (w.fused && (st = status_of(launch_zero_dropped(w, ws, y, s)))) return st;
+    // fused: rows of tokens without a slot are +0 (cleared above, or here once the re-routing
+    // stages have run), all others are written by the second GEMM
+    if (w.fused && !zero_rows_with_positions(w) &&
+        (st = status_of(launch_zero_dropped(w, ws, y, s))))
+        return st;
     if ((st = status_of(gemm(GEMM_FWD1, w, ws, W_in, W_out, nullptr, nullptr, tm, s)))) return st;
     if (w.geglu && (st = status_of(launch_geglu_fwd(w, dt, ws, s)))) return st;
     if ((st = status_of(gemm(GEMM_FWD2, w, ws, W_in, W_out, nullptr, nullptr, tm, s)))) return st;

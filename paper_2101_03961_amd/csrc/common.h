@@ -220,7 +220,7 @@ int route_scan_blocks(const Workspace &w);
 // expert_index and gate of the tokens they place.
 hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
-                           const float *logits, int32_t *expert_index, float *gate,
+                           const float *logits, int32_t *expert_index, float *gate, void *y,
                            hipStream_t s);
 hipError_t launch_ntlb(const Workspace &w, char *ws, const float *logits, int32_t *expert_index,
                        float *gate, int32_t *position_in_expert, uint8_t *dropped,
@@ -265,6 +265,10 @@ hipError_t launch_gemm_bf16(GemmKind kind, const Workspace &w, char *ws, const v
 hipError_t launch_gemm_f32(GemmKind kind, const Workspace &w, char *ws, const void *W_in,
                            const void *W_out, void *dW_in, void *dW_out, const TokenMajor &tm,
                            hipStream_t s);
+// Dispatch and combine inside the GEMMs: the rows of y of tokens without a slot are cleared by
+// the kernel that assigns the slots (launch_dispatch) -- unless re-routing stages follow it and
+// hand some of those tokens a slot after all; then launch_zero_dropped runs behind them.
+inline bool zero_rows_with_positions(const Workspace &w) { return w.fused && w.ntlb_rounds == 0; }
 // fused path: +0 rows of y for the tokens without a slot; gate gradient from the saved outputs
 hipError_t launch_zero_dropped(const Workspace &w, char *ws, void *y, hipStream_t s);
 hipError_t launch_gate_grad(const Workspace &w, const void *dy, char *ws, hipStream_t s);

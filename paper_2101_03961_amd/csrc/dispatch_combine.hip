@@ -60,26 +60,40 @@ __global__ __launch_bounds__(256) void positions_kernel(
     uint32_t row_bytes, int32_t *__restrict__ tok_slot, const double *__restrict__ loss_part,
     int loss_parts,
     double loss_scale /* alpha E / n */, float *__restrict__ aux_out, int T, int Tg, int nbg, int E,
-    int C, int Cg) {
+    int C, int Cg, Chunk16 *__restrict__ y_zero /* or null */, int cpr) {
+    __shared__ int32_t dropped_tokens[256];
+    __shared__ int n_dropped;
     const int t = blockIdx.x * 256 + threadIdx.x;
+    if (threadIdx.x == 0) n_dropped = 0;
     if (t == 0) {   // Eqs. 4-6 from the scan kernel's parts, in block order
         double sum = 0.0;
         for (int i = 0; i < loss_parts; ++i) sum += loss_part[i];
         aux_out[0] = (float)(loss_scale * sum);
     }
-    if (t >= T) return;
-    const int e = idx[t];
-    const int p = block_off[(size_t)block_of_token(t, nbg, Tg) * E + e] + local_rank[t];
-    const uint8_t dr = p >= Cg;
-    pos_out[t] = p;
-    dropped_out[t] = dr;
-    const int slot = e * C + grp_off[(size_t)(t / Tg) * E + e] + p;
-    if (!dr) {
-        slot_token[slot] = t;
-        slot_gate[slot] = gate[t];
-        slot_off[slot] = (uint32_t)t * row_bytes;   // used only where it cannot overflow
+    __syncthreads();
+    if (t < T) {
+        const int e = idx[t];
+        const int p = block_off[(size_t)block_of_token(t, nbg, Tg) * E + e] + local_rank[t];
+        const uint8_t dr = p >= Cg;
+        pos_out[t] = p;
+        dropped_out[t] = dr;
+        const int slot = e * C + grp_off[(size_t)(t / Tg) * E + e] + p;
+        if (!dr) {
+            slot_token[slot] = t;
+            slot_gate[slot] = gate[t];
+            slot_off[slot] = (uint32_t)t * row_bytes;   // used only where it cannot overflow
+        }
+        tok_slot[t] = dr ? -1 : slot;
+        if (dr && y_zero) dropped_tokens[atomicAdd(&n_dropped, 1)] = t;   // any order
     }
-    tok_slot[t] = dr ? -1 : slot;
+    if (!y_zero) return;
+    // the block's tokens without a slot get their rows of y: +0, written by all 256 threads
+    __syncthreads();
+    const Chunk16 zero = {{0u, 0u, 0u, 0u}};
+    for (int i = threadIdx.x; i < n_dropped * cpr; i += 256) {
+        const int k = i / cpr;
+        y_zero[(size_t)dropped_tokens[k] * cpr + (i - k * cpr)] = zero;
+    }
 }
 
 // -----------------------------------------------------------------------------
@@ -241,7 +255,7 @@ hipError_t launch_gate_grad(const Workspace &w, const void *dy, char *ws, hipStr
 
 hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const void *x, char *ws,
                            int32_t *position_in_expert, uint8_t *dropped, float *aux_loss,
-                           const float *logits, int32_t *expert_index, float *gate,
+                           const float *logits, int32_t *expert_index, float *gate, void *y,
                            hipStream_t s) {
     hipError_t err;
     {
@@ -255,7 +269,8 @@ hipError_t launch_dispatch(const Workspace &w, int dtype, float alpha, const voi
                            (int32_t *)(ws + w.tok_slot), (const double *)(ws + w.loss_part),
                            route_scan_blocks(w), (double)alpha * (double)w.E / (double)w.n,
                            aux_loss, (int)w.T, (int)w.Tg, (int)w.nbg, (int)w.E, (int)w.C,
-                           (int)w.Cg);
+                           (int)w.Cg, (Chunk16 *)(zero_rows_with_positions(w) ? y : nullptr),
+                           (int)(w.d * w.elt / 16));
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (w.C == 0) return hipSuccess;

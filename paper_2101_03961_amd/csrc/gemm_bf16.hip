@@ -66,7 +66,8 @@
 // k loops alone run 229-267 us per launch at Switch-Base, the epilogue's instructions cost
 // 10-45 us, the writes to HBM themselves another 30-60 us whether or not they are waited for.)
 //
-// Dispatch and combine (Sec. 5.4) without a pass of their own.  With GATHER set an operand's
+// Dispatch and combine (Sec. 5.4) without a pass of their own (on request: at the Switch-Base
+// shape the gathers below cost a little more than the passes they replace).  With GATHER set an operand's
 // rows are fetched from the token-major tensors by the slot -> token table: the first forward
 // GEMM and the first-layer weight gradient read x, the second-layer data and weight gradients
 // read dy.  The first GEMM's epilogue scales each hidden row by its token's gate (EPI_SCALE) so

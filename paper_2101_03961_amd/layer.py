@@ -18,7 +18,7 @@ class SwitchLayer:
                  alpha: float = 0.01, dtype: str = "bf16", device: str = "cuda:0",
                  want_logits: bool = False, n_groups: int = 1, expert_dropout: float = 0.0,
                  jitter_eps: float = 0.0, seed: int = 0, ffn: str = "relu",
-                 ntlb_rounds: int = 0, separate_dispatch: bool = False):
+                 ntlb_rounds: int = 0, fused_dispatch: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("SwitchLayer needs a GPU: the layer runs only in the HIP library")
         self.cfg = B.SwitchConfig(T, d_model, d_ff, E, float(capacity_factor), float(alpha),
@@ -27,7 +27,7 @@ class SwitchLayer:
                                   int(n_groups),
                                   float(expert_dropout), float(jitter_eps), int(seed),
                                   int(ntlb_rounds),
-                                  B.SW_FLAG_SEPARATE_DISPATCH if separate_dispatch else 0)
+                                  B.SW_FLAG_FUSED_DISPATCH if fused_dispatch else 0)
         self.d_in = d_ff * (2 if ffn == "geglu" else 1)   # columns of W_in
         self.device = torch.device(device)
         self.act = torch.bfloat16 if dtype == "bf16" else torch.float32

@@ -51,7 +51,7 @@ class SwitchShape:
     noise_seed: int = 0          # seed of both
     ntlb_rounds: int = 0         # No-Token-Left-Behind re-routing stages
     ffn: str = "relu"            # expert FFN: "relu", or "geglu" (W_in = [W_g | W_l], [E, d, 2 d_ff])
-    separate_dispatch: bool = False   # bf16: dispatch / combine as separate passes, not inside the GEMMs
+    fused_dispatch: bool = False      # bf16: dispatch / combine inside the GEMMs, not as separate passes
 
     def with_(self, **kw) -> "SwitchShape":
         return replace(self, **kw)

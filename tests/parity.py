@@ -178,7 +178,7 @@ def run_gpu(shape, inp, d_aux=1.0, backward=True, dy=None):
                         shape.alpha, shape.dtype, device=str(inp["x"].device), want_logits=True,
                         n_groups=shape.n_groups, expert_dropout=shape.expert_dropout,
                         jitter_eps=shape.jitter_eps, seed=shape.noise_seed, ffn=shape.ffn,
-                        ntlb_rounds=shape.ntlb_rounds, separate_dispatch=shape.separate_dispatch)
+                        ntlb_rounds=shape.ntlb_rounds, fused_dispatch=shape.fused_dispatch)
     out = layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"])
     res = {k: to_np(v) for k, v in out.items() if v is not None}
     if backward:

@@ -54,12 +54,14 @@ def test_fp32_shapes_full_parity(T, d, f, E, cf, bias):
     (777, 72, 136, 7, 0.5, False),     # heavy dropping, odd sizes
     (3000, 512, 768, 4, 1.25, False),  # several k steps and 3 x 2 p tiles
 ])
-def test_bf16_shapes_full_parity(T, d, f, E, cf, bias):
+@pytest.mark.parametrize("in_gemm", [False, True])   # dispatch / combine as passes, or inside the GEMMs
+def test_bf16_shapes_full_parity(T, d, f, E, cf, bias, in_gemm):
     from parity import compare_full
-    s = SwitchShape("t", T, d, f, E, cf, dtype="bf16", zipf_bias=bias, seed_index=41)
+    s = SwitchShape("t", T, d, f, E, cf, dtype="bf16", zipf_bias=bias, seed_index=41,
+                    fused_dispatch=in_gemm)
     inp = make_inputs(s, _dev())
     errs, gpu, fwd, _ = compare_full(s, inp, d_aux=1.0)
-    _report("bf16 %s" % ((T, d, f, E, cf, bias),), errs)
+    _report("bf16 %s%s" % ((T, d, f, E, cf, bias), ", in the GEMMs" if in_gemm else ""), errs)
     if bias:
         assert fwd["dropped"].sum() > 0 and (fwd["expert_counts"] == 0).any()
 
@@ -69,17 +71,17 @@ def test_bf16_shapes_full_parity(T, d, f, E, cf, bias):
     (4096, 128, 256, 16, 1.0, 2, True, "relu", 0.1, 1),    # groups, skew, dropout, re-routing
     (3000, 512, 768, 4, 1.25, 1, False, "geglu", 0.0, 0),  # gated-GELU experts
 ])
-def test_bf16_separate_dispatch_passes(T, d, f, E, cf, n, bias, ffn, rate, rounds):
-    """bf16 layers run dispatch and combine inside the GEMMs; the separate passes (taken when x
-    reaches 2 GB, or on request) stay tested, and both give the same result to rounding."""
+def test_bf16_dispatch_inside_the_gemms_agrees_with_the_passes(T, d, f, E, cf, n, bias, ffn, rate, rounds):
+    """Dispatch and combine as passes of their own (the default) and inside the GEMMs (on
+    request): each against the oracle, and against each other to rounding."""
     from parity import compare_full
     s = SwitchShape("t", T, d, f, E, cf, dtype="bf16", zipf_bias=bias, seed_index=43, n_groups=n,
-                    ffn=ffn, expert_dropout=rate, noise_seed=5, ntlb_rounds=rounds,
-                    separate_dispatch=True)
+                    ffn=ffn, expert_dropout=rate, noise_seed=5, ntlb_rounds=rounds)
     inp = make_inputs(s, _dev())
     errs, sep, _, _ = compare_full(s, inp, d_aux=0.9)
     _report("bf16 separate passes %s" % ((T, d, f, E, cf, n, ffn),), errs)
-    _, fused, _, _ = compare_full(s.with_(separate_dispatch=False), inp, d_aux=0.9)
+    errs, fused, _, _ = compare_full(s.with_(fused_dispatch=True), inp, d_aux=0.9)
+    _report("bf16 inside the GEMMs %s" % ((T, d, f, E, cf, n, ffn),), errs)
     for k in ("expert_index", "gate", "position_in_expert", "dropped", "expert_counts", "aux_loss",
               "router_logits"):
         assert np.array_equal(sep[k], fused[k]), k
@@ -146,6 +148,9 @@ def test_routing_groups(dtype, T, d, f, E, cf, n):
     from parity import compare_full
     s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=57, n_groups=n)
     inp = make_inputs(s, _dev())
+    if dtype == "bf16":   # also with dispatch / combine inside the GEMMs
+        errs = compare_full(s.with_(fused_dispatch=True), inp, d_aux=0.8)[0]
+        _report("groups %s, in the GEMMs" % ((dtype, T, E, cf, n),), errs)
     errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.8)
     _report("groups %s" % ((dtype, T, E, cf, n),), errs)
     assert fwd["capacity"] == int(np.floor(T / n / E * cf))
@@ -206,9 +211,10 @@ def test_exact_ties_go_to_expert_zero():
     assert abs(float(gpu["aux_loss"][0]) - 0.01) < 1e-7      # P uniform => loss = alpha
 
 
-def test_run_to_run_determinism():
+@pytest.mark.parametrize("in_gemm", [False, True])
+def test_run_to_run_determinism(in_gemm):
     from parity import run_gpu
-    s = SwitchShape("t", 5000, 256, 512, 12, 1.0, dtype="bf16", seed_index=53)
+    s = SwitchShape("t", 5000, 256, 512, 12, 1.0, dtype="bf16", seed_index=53, fused_dispatch=in_gemm)
     inp = make_inputs(s, _dev())
     _, a = run_gpu(s, inp)
     _, b = run_gpu(s, inp)
@@ -216,14 +222,14 @@ def test_run_to_run_determinism():
         assert np.array_equal(a[k], b[k]), k
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_scaling_and_expert_permutation_properties(dtype):
+@pytest.mark.parametrize("dtype,in_gemm", [("f32", False), ("bf16", False), ("bf16", True)])
+def test_scaling_and_expert_permutation_properties(dtype, in_gemm):
     """Properties of the GPU path alone.  Doubling W_out doubles y exactly (a power of two
     changes no rounding).  Renumbering the experts (columns of W_r, blocks of W_in / W_out)
     renumbers expert_index and the counts and leaves every token's slot; gate and output move
     only by the rounding of the softmax sum taken in another order (and what follows from it)."""
     from parity import run_gpu
-    s = SwitchShape("t", 3000, 128, 264, 12, 1.0, dtype=dtype, seed_index=92)
+    s = SwitchShape("t", 3000, 128, 264, 12, 1.0, dtype=dtype, seed_index=92, fused_dispatch=in_gemm)
     inp = make_inputs(s, _dev())
     _, a = run_gpu(s, inp, backward=False)
     doubled = dict(inp, W_out=inp["W_out"] * 2)
@@ -241,12 +247,12 @@ def test_scaling_and_expert_permutation_properties(dtype):
     for k in ("dropped", "position_in_expert"):
         assert np.array_equal(a[k], c[k]), k
     np.testing.assert_allclose(c["gate"], a["gate"], rtol=5e-7, atol=0)
-    # one rounding step of the storage type; bf16 also: the gate scales the hidden activations
-    # before they are rounded (combine inside the GEMMs), so a gate that moves by one fp32 ulp
+    # one rounding step of the storage type; with the combine inside the GEMMs also: the gate
+    # scales the hidden activations before they are rounded, so a gate that moves by one fp32 ulp
     # flips the rounding of a few of them: a row may move by a small share of its RMS
     ulp = 2.0 ** -7 if dtype == "bf16" else 1e-6
     rms = np.sqrt(np.mean(a["y"].astype(np.float64) ** 2, axis=1, keepdims=True))
-    floor = 2.0 ** -9 * rms if dtype == "bf16" else 1e-30
+    floor = 2.0 ** -9 * rms if in_gemm else 1e-30
     assert np.all(np.abs(c["y"].astype(np.float64) - a["y"]) <= ulp * np.abs(a["y"]) + floor)
     assert abs(float(a["aux_loss"][0]) - float(c["aux_loss"][0])) <= 1e-6 * abs(float(a["aux_loss"][0]))
 
@@ -306,9 +312,11 @@ def test_random_shapes():
         d = int(rng.integers(32 // mult, hi_d // mult)) * mult
         f = int(rng.integers(32 // mult, hi_f // mult)) * mult
         cf = float(rng.choice([0.7, 1.0, 1.25, 2.0, 8.0]))
-        s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=300 + case, n_groups=n)
-        print("[random shape %d] %s T=%d d=%d f=%d E=%d cf=%g groups=%d" %
-              (case, dtype, T, d, f, E, cf, n), flush=True)
+        in_gemm = dtype == "bf16" and case % 2 == 1
+        s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=300 + case, n_groups=n,
+                        fused_dispatch=in_gemm)
+        print("[random shape %d] %s T=%d d=%d f=%d E=%d cf=%g groups=%d in_gemm=%d" %
+              (case, dtype, T, d, f, E, cf, n, in_gemm), flush=True)
         inp = make_inputs(s, _dev())
         compare_full(s, inp, d_aux=0.5)
 
@@ -335,10 +343,11 @@ def test_random_shapes_with_options():
         bias = bool(rng.random() < 0.4)
         s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=400 + case, n_groups=n,
                         ffn=ffn, expert_dropout=rate, jitter_eps=eps,
-                        noise_seed=int(rng.integers(0, 2 ** 62)), ntlb_rounds=rounds, zipf_bias=bias)
+                        noise_seed=int(rng.integers(0, 2 ** 62)), ntlb_rounds=rounds, zipf_bias=bias,
+                        fused_dispatch=dtype == "bf16" and case % 2 == 0)
         print("[random options %d] %s T=%d d=%d f=%d E=%d cf=%g groups=%d %s drop=%g jitter=%g "
-              "stages=%d bias=%d" % (case, dtype, T, d, f, E, cf, n, ffn, rate, eps, rounds, bias),
-              flush=True)
+              "stages=%d bias=%d in_gemm=%d" % (case, dtype, T, d, f, E, cf, n, ffn, rate, eps, rounds,
+                                                bias, s.fused_dispatch), flush=True)
         inp = make_inputs(s, _dev())
         compare_full(s, inp, d_aux=0.5)
 
@@ -361,7 +370,10 @@ def test_relu_decision_at_a_zero_preactivation():
 
 @pytest.mark.parametrize("options", [
     {},
+    dict(fused_dispatch=True),
     dict(ffn="geglu", expert_dropout=0.1, jitter_eps=0.01, noise_seed=3, ntlb_rounds=2),
+    dict(ffn="geglu", expert_dropout=0.1, jitter_eps=0.01, noise_seed=3, ntlb_rounds=2,
+         fused_dispatch=True),
 ])
 def test_step_can_be_captured_in_a_graph(options):
     """Forward + backward recorded once and replayed: every replay, with eager work and
@@ -375,7 +387,7 @@ def test_step_can_be_captured_in_a_graph(options):
     layer = SwitchLayer(s.T, s.d_model, s.d_ff, s.E, s.capacity_factor, s.alpha, s.dtype,
                         device=_dev(), n_groups=s.n_groups, ffn=s.ffn,
                         expert_dropout=s.expert_dropout, jitter_eps=s.jitter_eps,
-                        seed=s.noise_seed, ntlb_rounds=s.ntlb_rounds)
+                        seed=s.noise_seed, ntlb_rounds=s.ntlb_rounds, fused_dispatch=s.fused_dispatch)
     layer.alloc_grads(with_bias=False)
     names = ("y", "dx", "dW_r", "dW_in", "dW_out", "aux_loss", "expert_counts", "gate", "dropped")
 
@@ -420,6 +432,9 @@ def test_training_noise(dtype, T, d, f, E, cf, n, bias, rate, eps, seed):
     s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=70, n_groups=n, zipf_bias=bias,
                     expert_dropout=rate, jitter_eps=eps, noise_seed=seed)
     inp = make_inputs(s, _dev())
+    if dtype == "bf16":   # also with dispatch / combine inside the GEMMs
+        errs = compare_full(s.with_(fused_dispatch=True), inp, d_aux=0.8)[0]
+        _report("noise %s rate %.2f eps %.2f, in the GEMMs" % (dtype, rate, eps), errs)
     errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.8)
     _report("noise %s rate %.2f eps %.2f" % (dtype, rate, eps), errs)
     # the noise did something: outputs differ from the noise-free layer's
@@ -487,6 +502,9 @@ def test_geglu_experts(dtype, T, d, f, E, cf, n, rate, eps):
                     expert_dropout=rate, jitter_eps=eps, noise_seed=31)
     inp = make_inputs(s, _dev())
     assert inp["W_in"].shape == (E, d, 2 * f)
+    if dtype == "bf16":   # also with dispatch / combine inside the GEMMs
+        errs = compare_full(s.with_(fused_dispatch=True), inp, d_aux=0.8)[0]
+        _report("geglu %s f=%d, in the GEMMs" % (dtype, f), errs)
     errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.8)
     assert gpu["dW_in"].shape == (E, d, 2 * f)
     _report("geglu %s f=%d" % (dtype, f), errs)
@@ -546,6 +564,9 @@ def test_no_token_left_behind(dtype, T, d, f, E, cf, n, bias, rounds, ffn):
     s = SwitchShape("t", T, d, f, E, cf, dtype=dtype, seed_index=90, n_groups=n, zipf_bias=bias,
                     ntlb_rounds=rounds, ffn=ffn)
     inp = make_inputs(s, _dev())
+    if dtype == "bf16":   # also with dispatch / combine inside the GEMMs
+        errs = compare_full(s.with_(fused_dispatch=True), inp, d_aux=0.7)[0]
+        _report("ntlb %s E=%d rounds=%d, in the GEMMs" % (dtype, E, rounds), errs)
     errs, gpu, fwd, _ = compare_full(s, inp, d_aux=0.7)
     _, plain = run_gpu(s.with_(ntlb_rounds=0), inp, backward=False)
     rescued = int(plain["dropped"].sum()) - int(gpu["dropped"].sum())
@@ -633,6 +654,17 @@ def test_full_size_sampled_parity(name, n_experts):
     inp = make_inputs(s, _dev())
     errs = compare_sampled(s, inp, n_experts=n_experts, n_tokens=24)
     _report(name, errs)
+
+
+@pytest.mark.parametrize("name,n_experts", [("base_cf1.0", 18), ("base_cf1.25", 18), ("large", 12)])
+def test_full_size_sampled_parity_inside_the_gemms(name, n_experts):
+    """The full-size workloads with dispatch and combine inside the GEMMs (gathered operand
+    loads, scattered output rows, at 3072+ tiles per launch): same checks as above."""
+    from parity import compare_sampled
+    s = CONFIGS[name].with_(fused_dispatch=True)
+    inp = make_inputs(s, _dev())
+    errs = compare_sampled(s, inp, n_experts=n_experts, n_tokens=24)
+    _report(name + ", in the GEMMs", errs)
 
 
 def test_xxl_sampled_parity():

@@ -20,7 +20,8 @@ def _both_ways(shape, dev):
     inp = make_inputs(shape, dev)
     layer = SwitchLayer(shape.T, shape.d_model, shape.d_ff, shape.E, shape.capacity_factor,
                         shape.alpha, shape.dtype, device=dev, want_logits=True,
-                        n_groups=shape.n_groups, ffn=shape.ffn, ntlb_rounds=shape.ntlb_rounds)
+                        n_groups=shape.n_groups, ffn=shape.ffn, ntlb_rounds=shape.ntlb_rounds,
+                        fused_dispatch=shape.fused_dispatch)
     assert layer.workspace_bytes <= sw.SW_STATIC_SCRATCH_BYTES
     ref = {k: v.clone() for k, v in
            layer.forward(inp["x"], inp["W_r"], inp["W_in"], inp["W_out"], inp["b_r"]).items()}
@@ -55,6 +56,10 @@ def test_static_scratch_forward_matches_workspace_forward():
     third = SwitchShape("static_third", 300, 64, 72, 4, 0.75, dtype="bf16", seed_index=122,
                         ffn="geglu")
     _both_ways(third, dev)
+    # and one with dispatch and combine inside the GEMMs
+    fourth = SwitchShape("static_fourth", 280, 72, 136, 5, 1.0, dtype="bf16", seed_index=123,
+                         fused_dispatch=True)
+    _both_ways(fourth, dev)
 
 
 def test_static_scratch_forward_against_the_oracle():
