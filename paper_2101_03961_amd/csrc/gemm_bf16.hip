@@ -10,9 +10,10 @@
 // buffer_load_dwordx4 ... lds (no registers, no ds_write: LDS stores issued by
 // the waves cost ~30 cycles of issue each and were the bottleneck of an earlier
 // register-staged version).  k advances 64 at a time: every row of an operand tile
-// is then one full 128-byte line per step.  The P operand goes through three LDS
-// stages of 32 KB, the Q operand through two (3 x 32 + 2 x 32 = all 160 KB; with DEEP_Q
-// the other way round, for the one GEMM whose Q is the operand that comes from HBM): in the
+// is then one full 128-byte line per step.  One operand goes through three LDS stages of
+// 32 KB (the "deep" ring), the other through two (3 x 32 + 2 x 32 = all 160 KB).  The deep
+// one is P unless DEEP_Q is set; which is better was measured per GEMM (see
+// launch_gemm_bf16), the wrong choice costs 4-11 %.  Below, P is the deep one.  In the
 // last quarter of step kt, right after the barrier that frees the stages of step
 // kt, a wave issues its eight loads of Q for step kt+2 and then its eight loads of P
 // for step kt+3.  Loads complete in order, so the wait of step kt+1 (for step kt+2's
@@ -54,8 +55,8 @@
 // The k steps of all tiles of a block form one load pipeline: a tile's last steps issue
 // the next tile's first loads, which stay in flight during the epilogue.
 // The epilogue turns each wave's sub-tile around, 32 rows at a time, through 8 KB of
-// LDS of its own -- a quarter of the P stage that the tile's last step has freed; the
-// load that stage is waiting for (P of the next tile's third step) is issued after the
+// LDS of its own -- a quarter of the deep ring's stage that the tile's last step has freed; the
+// load that stage is waiting for (the deep operand of the next tile's third step) is issued after the
 // epilogue instead of before it -- so that C is written in whole 256-byte row
 // segments; fused into it: ReLU and one mask bit per element
 // (first forward GEMM), that mask (gradient w.r.t. the hidden activations), the
@@ -90,7 +91,7 @@ static_assert(kOpBytes64 == kBP * kBK * 2, "operand stage size");
 constexpr int kDeepRingBytes = kDeepStages * kOpBytes64;      // 96 KB
 constexpr int kRingBytes = kDeepRingBytes + kShallowStages * kOpBytes64;   // 160 KB: all of a CU's LDS
 constexpr int kTurnBytes = 32 * 256;              // per wave: 32 rows x 128 bf16 of the epilogue's turn-around
-static_assert(4 * kTurnBytes == kOpBytes64, "the turn-around buffers are one P stage");
+static_assert(4 * kTurnBytes == kOpBytes64, "the turn-around buffers are one stage of the deep ring");
 constexpr int kGemmLds = kRingBytes;
 constexpr int kXcds = 8;
 
