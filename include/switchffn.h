@@ -21,11 +21,11 @@
  *     detected on the host before anything is launched; nothing is thrown
  *     across the ABI.  Inputs must be finite (NaN/Inf behaviour unspecified).
  *   - Gradients are overwritten, not accumulated.
- *   - The library keeps no state between calls apart from what the workspace holds (and
- *     one-time kernel attributes, set under std::call_once); with profiling off, calls from
- *     several host threads may run at once if each has its own workspace, outputs and
- *     stream.  One device per process is assumed for switch_forward / switch_backward (the
- *     launch width is taken from the device that is current at the first call).
+ *   - The library keeps no state between calls apart from what the workspace holds and a
+ *     few values it looks up once per device (std::call_once: kernel attributes, the number of
+ *     compute units, the address of the static scratch array); with profiling off, calls
+ *     from several host threads may run at once if each has its own workspace, outputs and
+ *     stream.  Work runs on the device that is current when the call is made.
  *   - An empty batch (T = 0) is legal: forward writes expert_counts = 0 and
  *     aux_loss = 0 (both fractions of Eq. 4 are empty sums), backward writes
  *     zeros to dW_r, db_r, dW_in, dW_out; the per-token arguments and the
