@@ -1,7 +1,7 @@
 """switch_forward_static -- the forward pass on the library's own fixed scratch array, for
 callers that cannot allocate -- against switch_forward with a caller workspace: same kernels,
-so every output must agree bit for bit, on two calls in a row, the second with a smaller
-input (the array then still holds the first call's tables)."""
+so every output must agree bit for bit, on several calls in a row, each with a smaller input
+than the one before (the array then still holds the earlier calls' tables)."""
 import numpy as np
 import pytest
 import torch
